@@ -1,0 +1,165 @@
+/*
+ * eet.h -- C ABI of the MI355X-native decoder-layer hot path of EET (arXiv 2104.12470).
+ *
+ * The library implements one pre-LN GPT-2 style decoder layer with mask fusion (Section 2.1,
+ * Algorithm 1): no attention-mask or padding-mask tensor is ever built; causality is an index
+ * comparison between query and key position, and padding tokens are skipped, not masked.
+ * Prompts are processed whole (Section 4.1: every sequence at its own length, the batch at the
+ * maximum length); generation is incremental over a K/V cache that is sized once for the
+ * maximum batch and sequence length (Section 3.1).  Row-wise kernels (softmax, LayerNorm,
+ * add-bias/GELU/residual) handle rows of any width (the goal of Section 2.2).
+ *
+ * Conventions
+ *   - All tensors are fp16 (IEEE binary16) in DEVICE memory unless a parameter says HOST.
+ *     Accumulation and statistics are fp32.  Row-major, innermost dimension contiguous,
+ *     base pointers 16-byte aligned.
+ *   - Sequences are right-padded: sequence b has q_lens[b] valid rows [0, q_lens[b]) out of
+ *     padded_len; the paper's per-sequence padding length is padded_len - q_lens[b].
+ *   - The library never allocates, frees or synchronises device memory: workspace, K/V cache,
+ *     weights, inputs and outputs are the caller's.  Every call only enqueues work on the
+ *     given hipStream_t (passed as void*; NULL = default stream), except eet_cache_lens.
+ *   - Return value: EET_OK or a negative error code.  On error nothing has been enqueued and
+ *     no state has changed; eet_last_error() describes the failure (thread-local storage).
+ *   - Calls on one layer handle must not overlap in time (one stream at a time).
+ */
+#ifndef EET_H
+#define EET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EET_OK                      0
+#define EET_ERR_INVALID_ARG        (-1)  /* null pointer, non-positive size, length out of range   */
+#define EET_ERR_UNSUPPORTED_SHAPE  (-2)  /* head size not 64/128, width not a multiple of 64, ...   */
+#define EET_ERR_CAPACITY           (-3)  /* batch/prompt/sequence exceeds what the layer was sized for */
+#define EET_ERR_STATE              (-4)  /* decode before prefill, batch mismatch                  */
+#define EET_ERR_HIP                (-5)  /* a HIP runtime call failed                              */
+
+#define EET_MAX_BATCH 128                /* per-sequence lengths travel as kernel arguments        */
+
+typedef struct eet_layer eet_layer_t;    /* opaque, host memory owned by the library               */
+
+/* Layer shape and capacity: the paper's h, n, and maximum b, p, s (Section 3.1 notation). */
+typedef struct {
+    int32_t hidden;       /* h: model width; hidden = heads * d with d in {64, 128}              */
+    int32_t heads;        /* n                                                                    */
+    int32_t ffn;          /* feed-forward width, multiple of 64                                   */
+    int32_t max_batch;    /* b, 1..EET_MAX_BATCH                                                  */
+    int32_t max_prompt;   /* p: largest padded prompt length                                      */
+    int32_t max_seq;      /* s: K/V cache capacity per sequence (prompt + generated), >= max_prompt */
+    float   ln_eps;       /* LayerNorm epsilon (1e-5 for GPT-2)                                   */
+} eet_layer_config;
+
+/* DEVICE fp16 parameters, BORROWED for the life of the layer.  Linear weights are row-major
+ * [out, in].  w_qkv is [3*hidden, hidden]: rows [0,h) produce Q, [h,2h) K, [2h,3h) V; head g
+ * owns rows g*d .. (g+1)*d-1 of each block. */
+typedef struct {
+    const void *ln1_g, *ln1_b;      /* [hidden]                 */
+    const void *w_qkv, *b_qkv;      /* [3*hidden, hidden], [3*hidden] */
+    const void *w_o,   *b_o;        /* [hidden, hidden], [hidden]     */
+    const void *ln2_g, *ln2_b;      /* [hidden]                 */
+    const void *w_fc1, *b_fc1;      /* [ffn, hidden], [ffn]     */
+    const void *w_fc2, *b_fc2;      /* [hidden, ffn], [hidden]  */
+} eet_layer_weights;
+
+/* Bytes of one layer's K/V cache: 2 * max_batch * hidden * max_seq fp16 elements (Section 3.1,
+ * the K/V cache size formula with l = 1).  Layout: [2 (K,V)][max_batch][heads][max_seq][d];
+ * slot t of sequence b holds token t of that sequence.  Returns 0 on a bad config. */
+size_t eet_kv_cache_bytes(const eet_layer_config *cfg);
+
+/* Bytes of caller-provided workspace a layer needs (activation buffers for max_batch*max_prompt
+ * packed tokens, split-attention partials, per-sequence lengths; the pre-sized buffers of
+ * Section 3).  Returns 0 on a bad config. */
+size_t eet_workspace_bytes(const eet_layer_config *cfg);
+
+/* Create a layer.  `workspace` is DEVICE memory of eet_workspace_bytes(cfg), 256-byte aligned,
+ * owned by the caller and used exclusively by this layer until eet_layer_destroy.  Nothing is
+ * enqueued.  Errors: INVALID_ARG (null), UNSUPPORTED_SHAPE. */
+int eet_layer_create(const eet_layer_config *cfg, const eet_layer_weights *weights,
+                     void *workspace, eet_layer_t **out_layer);
+
+/* Prefill (whole-prompt pass; Sections 2.1 and 4.1).
+ *   q_lens     HOST int32[batch], 1 <= q_lens[b] <= padded_len (read before the call returns)
+ *   tokens     DEVICE fp16 [batch, padded_len, hidden] input hidden states; pad rows are never read
+ *   out        DEVICE fp16 [batch, padded_len, hidden]; valid rows = layer output, pad rows = 0
+ *   kv_cache   DEVICE, eet_kv_cache_bytes(cfg); slots [0, q_lens[b]) of sequence b are written,
+ *              all other bytes are left untouched
+ * Afterwards the cache length of sequence b is q_lens[b].
+ * Errors: INVALID_ARG, CAPACITY (batch > max_batch or padded_len > max_prompt). */
+int eet_prefill(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                const void *tokens, void *out, void *kv_cache, void *hip_stream);
+
+/* One incremental decoding step for every sequence of the last prefill (Section 3.1: keys and
+ * values of each step are kept for the next).
+ *   tokens     DEVICE fp16 [batch, hidden]; out DEVICE fp16 [batch, hidden]
+ * The token of sequence b is written to cache slot n_b, attends to slots 0..n_b, and n_b
+ * becomes n_b + 1 (the lengths live in device memory and are advanced on the stream, so a
+ * step has no host-varying argument).
+ * Errors: STATE (no prefill yet), CAPACITY (some n_b + 1 > max_seq). */
+int eet_decode_step(eet_layer_t *layer, const void *tokens, void *out, void *kv_cache,
+                    void *hip_stream);
+
+/* Copy the device-side cache lengths n_b of the current batch to HOST int32[batch].
+ * Synchronises the stream.  Errors: STATE, HIP. */
+int eet_cache_lens(eet_layer_t *layer, int32_t *out_host, void *hip_stream);
+
+/* Release the handle (host memory only). */
+int eet_layer_destroy(eet_layer_t *layer);
+
+/* Message for the last error on this thread ("" if none). */
+const char *eet_last_error(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Operator-level entry points: the individual kernels of the layer, for parity tests and
+ * profiling (the paper exposes an operator-level API as well, Section 5).
+ * ------------------------------------------------------------------------------------------- */
+
+/* LayerNorm over rows (Section 2.2 kernel family): y = (x-mean)/sqrt(var+eps)*gamma+beta,
+ * biased variance, fp32 statistics.  x, y [rows, width]; any width >= 1. */
+int eet_op_layernorm(const void *x, const void *gamma, const void *beta, void *y,
+                     int64_t rows, int32_t width, float eps, void *hip_stream);
+
+/* Mask-free softmax, Algorithm 1 as an operator, in place on scores [batch, heads, S, S] with
+ * S = padded_len: for row i < q_lens[b], entries j <= i become softmax(scale * score) over that
+ * window and entries j > i become 0; rows i >= q_lens[b] are not touched.  q_lens is HOST. */
+int eet_op_softmax_maskfree(void *scores, const int32_t *q_lens, int32_t batch, int32_t heads,
+                            int32_t padded_len, float scale, void *hip_stream);
+
+/* y = gelu_tanh(x + bias); x, y [rows, width], bias [width]. */
+int eet_op_bias_gelu(const void *x, const void *bias, void *y, int64_t rows, int32_t width,
+                     void *hip_stream);
+
+/* y = x + bias + residual; x, residual, y [rows, width], bias [width]. */
+int eet_op_bias_residual(const void *x, const void *bias, const void *residual, void *y,
+                         int64_t rows, int32_t width, void *hip_stream);
+
+/* Dense projection y = act(x W^T + bias) (+ residual): x [rows, in], W [out, in], y [rows, out];
+ * in and out multiples of 64.  act: 0 = identity, 1 = gelu_tanh.  residual may be NULL.
+ * rows <= 16 takes the weight-streaming path used by decode, otherwise the MFMA tile path. */
+int eet_op_linear(const void *x, const void *w, const void *bias, const void *residual, void *y,
+                  int64_t rows, int32_t in, int32_t out, int32_t act, void *hip_stream);
+
+/* Causal, padding-skipping attention over whole prompts (mask fusion inside the contraction).
+ *   q, ctx     [batch, padded_len, heads*d]; only valid rows are read / written
+ *   k_cache, v_cache   [batch, heads, capacity, d]
+ * Row i of sequence b attends to slots 0..i.  q_lens is HOST int32[batch]. */
+int eet_op_attention_prefill(const void *q, const void *k_cache, const void *v_cache, void *ctx,
+                             const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                             int32_t heads, int32_t d, int32_t capacity, void *hip_stream);
+
+/* Incremental attention: q, ctx [batch, heads*d]; sequence b attends to slots 0..n_keys[b]-1.
+ * n_keys is DEVICE int32[batch], each 1..capacity.  scratch: DEVICE, at least
+ * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes. */
+size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity);
+int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_cache, void *ctx,
+                            const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,
+                            int32_t capacity, void *scratch, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EET_H */

@@ -1,0 +1,407 @@
+// C ABI of the library (declared in include/eet.h): argument validation, workspace carve-up,
+// launch sequencing.  No device allocation, no synchronisation except eet_cache_lens.
+#include "../../include/eet.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+
+using namespace eet;
+
+static_assert(EET_MAX_BATCH == kMaxBatch, "header and kernels disagree on the batch limit");
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(EET_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Byte offsets of the pieces of a layer's workspace.
+struct WorkspaceLayout {
+    size_t lens, cu, row_map, buf_a, buf_b, buf_y, buf_f, part, total;
+    int splits;
+};
+
+const char* config_problem(const eet_layer_config* c) {
+    if (!c) return "config is null";
+    if (c->hidden <= 0 || c->heads <= 0 || c->ffn <= 0) return "hidden, heads and ffn must be positive";
+    if (c->hidden % c->heads != 0) return "hidden must be a multiple of heads";
+    if (c->max_batch < 1 || c->max_prompt < 1 || c->max_seq < 1) return "capacities must be positive";
+    if (!(c->ln_eps > 0.f)) return "ln_eps must be positive";
+    return nullptr;
+}
+
+const char* shape_problem(const eet_layer_config* c) {
+    const int d = c->hidden / c->heads;
+    if (d != 64 && d != 128) return "head size must be 64 or 128";
+    if (c->ffn % 64 != 0) return "ffn must be a multiple of 64";
+    if (c->max_batch > EET_MAX_BATCH) return "max_batch exceeds EET_MAX_BATCH";
+    if (c->max_seq < c->max_prompt) return "max_seq must be at least max_prompt";
+    if ((int64_t)c->max_batch * c->max_prompt > (int64_t)1 << 30) return "max_batch*max_prompt too large";
+    return nullptr;
+}
+
+WorkspaceLayout layout_of(const eet_layer_config* c) {
+    WorkspaceLayout w{};
+    const size_t T = (size_t)c->max_batch * c->max_prompt, H = c->hidden, F = c->ffn;
+    size_t off = 0;
+    w.lens = off;    off = align_up(off + sizeof(int32_t) * EET_MAX_BATCH, 256);
+    w.cu = off;      off = align_up(off + sizeof(int32_t) * (EET_MAX_BATCH + 1), 256);
+    w.row_map = off; off = align_up(off + sizeof(int32_t) * T, 256);
+    w.buf_a = off;   off = align_up(off + 2 * T * H, 256);
+    w.buf_b = off;   off = align_up(off + 2 * T * H, 256);
+    w.buf_y = off;   off = align_up(off + 2 * T * H, 256);
+    w.buf_f = off;   off = align_up(off + 2 * T * F, 256);
+    w.splits = attention_decode_splits(c->max_batch, c->heads, c->max_seq);
+    w.part = off;
+    // sized for the split count of any batch <= max_batch (fewer sequences -> more splits)
+    size_t part = 0;
+    for (int b = 1; b <= c->max_batch; ++b) {
+        const size_t p = attention_decode_scratch_bytes(b, c->heads, H / c->heads,
+                                                        attention_decode_splits(b, c->heads, c->max_seq));
+        part = p > part ? p : part;
+    }
+    off = align_up(off + part, 256);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+struct eet_layer {
+    eet_layer_config cfg;
+    eet_layer_weights w;
+    WorkspaceLayout lay;
+    char* ws;
+    int d;
+    int batch;                         // batch of the last prefill, 0 = none yet
+    int32_t host_lens[EET_MAX_BATCH];  // host mirror of the device cache lengths (capacity checks only)
+};
+
+extern "C" {
+
+const char* eet_last_error(void) { return g_err; }
+
+size_t eet_kv_cache_bytes(const eet_layer_config* cfg) {
+    if (config_problem(cfg)) return 0;
+    return (size_t)2 * cfg->max_batch * cfg->hidden * cfg->max_seq * sizeof(half_t);
+}
+
+size_t eet_workspace_bytes(const eet_layer_config* cfg) {
+    if (config_problem(cfg) || shape_problem(cfg)) return 0;
+    return layout_of(cfg).total;
+}
+
+int eet_layer_create(const eet_layer_config* cfg, const eet_layer_weights* weights, void* workspace,
+                     eet_layer_t** out_layer) {
+    if (!out_layer) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: out_layer is null");
+    *out_layer = nullptr;
+    if (const char* p = config_problem(cfg)) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: %s", p);
+    if (const char* p = shape_problem(cfg)) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_layer_create: %s", p);
+    if (!weights || !workspace) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: weights or workspace is null");
+    const void* const* wp = reinterpret_cast<const void* const*>(weights);
+    for (size_t i = 0; i < sizeof(eet_layer_weights) / sizeof(void*); ++i) {
+        if (!wp[i]) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: weight pointer %zu is null", i);
+        if (!aligned16(wp[i])) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: weight pointer %zu is not 16-byte aligned", i);
+    }
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+        return fail(EET_ERR_INVALID_ARG, "eet_layer_create: workspace is not 256-byte aligned");
+    eet_layer* L = new (std::nothrow) eet_layer();
+    if (!L) return fail(EET_ERR_INVALID_ARG, "eet_layer_create: out of host memory");
+    L->cfg = *cfg;
+    L->w = *weights;
+    L->lay = layout_of(cfg);
+    L->ws = static_cast<char*>(workspace);
+    L->d = cfg->hidden / cfg->heads;
+    L->batch = 0;
+    std::memset(L->host_lens, 0, sizeof(L->host_lens));
+    *out_layer = L;
+    g_err[0] = 0;
+    return EET_OK;
+}
+
+int eet_layer_destroy(eet_layer_t* layer) {
+    delete layer;
+    return EET_OK;
+}
+
+#define EET_LAUNCH(expr, what)                        \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) return hip_fail(e_, what); \
+    } while (0)
+
+int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                void* out, void* kv_cache, void* hip_stream) {
+    if (!L || !q_lens || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_prefill: null argument");
+    if (batch < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "eet_prefill: batch and padded_len must be >= 1");
+    if (batch > L->cfg.max_batch) return fail(EET_ERR_CAPACITY, "eet_prefill: batch %d > max_batch %d", batch, L->cfg.max_batch);
+    if (padded_len > L->cfg.max_prompt)
+        return fail(EET_ERR_CAPACITY, "eet_prefill: padded_len %d > max_prompt %d", padded_len, L->cfg.max_prompt);
+    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(EET_ERR_INVALID_ARG, "eet_prefill: tokens/out/kv_cache must be 16-byte aligned");
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    int64_t T = 0;
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "eet_prefill: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+        T += q_lens[b];
+        max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const eet_layer_config& c = L->cfg;
+    const int H = c.hidden, F = c.ffn;
+    int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
+    int32_t* d_cu = reinterpret_cast<int32_t*>(L->ws + L->lay.cu);
+    int32_t* d_map = reinterpret_cast<int32_t*>(L->ws + L->lay.row_map);
+    half_t* bufA = reinterpret_cast<half_t*>(L->ws + L->lay.buf_a);
+    half_t* bufB = reinterpret_cast<half_t*>(L->ws + L->lay.buf_b);
+    half_t* bufY = reinterpret_cast<half_t*>(L->ws + L->lay.buf_y);
+    half_t* bufF = reinterpret_cast<half_t*>(L->ws + L->lay.buf_f);
+    const half_t* x = static_cast<const half_t*>(tokens);
+    half_t* kc = static_cast<half_t*>(kv_cache);
+    half_t* vc = kc + (size_t)c.max_batch * H * c.max_seq;
+
+    // a1: padding offsets -> integers on the device; pad rows of `out` zeroed
+    EET_LAUNCH(launch_prefill_setup(lens, batch, padded_len, H, d_lens, d_cu, d_map, static_cast<half_t*>(out), s),
+               "prefill_setup");
+    // a2: LN1 over valid rows only (gathered into the packed layout)
+    EET_LAUNCH(launch_layernorm(x, d_map, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, T, H, c.ln_eps,
+                                nullptr, 0, s), "layernorm 1");
+    // a3: QKV projection; K and V rows land directly in their cache slots
+    GemmArgs g{};
+    g.x = bufA; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
+    g.M = (int)T; g.N = 3 * H; g.K = H;
+    g.k_cache = kc; g.v_cache = vc; g.tok_row_map = d_map; g.lens = nullptr;
+    g.S = padded_len; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
+    EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
+    // a4: mask-free causal attention over the cache
+    AttnPrefillArgs at{};
+    at.q = bufB; at.ctx = bufA; at.k_cache = kc; at.v_cache = vc;
+    at.batch = batch; at.heads = c.heads; at.d = L->d; at.capacity = c.max_seq; at.hidden = H;
+    at.packed = 1; at.S = padded_len; at.max_len = max_len;
+    EET_LAUNCH(launch_attention_prefill(at, lens, s), "prefill attention");
+    // a6: output projection + bias + residual (residual gathered from the padded input)
+    GemmArgs o{};
+    o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
+    o.M = (int)T; o.N = H; o.K = H; o.res = x; o.res_row_map = d_map;
+    EET_LAUNCH(launch_gemm(o, EPI_BIAS_RES, s), "output projection");
+    // a7: LN2
+    EET_LAUNCH(launch_layernorm(bufY, nullptr, (const half_t*)L->w.ln2_g, (const half_t*)L->w.ln2_b, bufB, T, H,
+                                c.ln_eps, nullptr, 0, s), "layernorm 2");
+    // a8: FFN1 + bias + GELU
+    GemmArgs f1{};
+    f1.x = bufB; f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
+    f1.M = (int)T; f1.N = F; f1.K = H;
+    EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
+    // a9: FFN2 + bias + residual, scattered back to the padded layout
+    GemmArgs f2{};
+    f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
+    f2.M = (int)T; f2.N = H; f2.K = F; f2.res = bufY; f2.res_row_map = nullptr; f2.out_row_map = d_map;
+    EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
+
+    L->batch = batch;
+    for (int b = 0; b < batch; ++b) L->host_lens[b] = q_lens[b];
+    return EET_OK;
+}
+
+int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
+    if (!L || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_decode_step: null argument");
+    if (L->batch == 0) return fail(EET_ERR_STATE, "eet_decode_step: no prefill has been run on this layer");
+    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(EET_ERR_INVALID_ARG, "eet_decode_step: tokens/out/kv_cache must be 16-byte aligned");
+    const eet_layer_config& c = L->cfg;
+    const int B = L->batch, H = c.hidden, F = c.ffn;
+    for (int b = 0; b < B; ++b)
+        if (L->host_lens[b] + 1 > c.max_seq)
+            return fail(EET_ERR_CAPACITY, "eet_decode_step: sequence %d is at the cache capacity %d", b, c.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
+    half_t* bufA = reinterpret_cast<half_t*>(L->ws + L->lay.buf_a);
+    half_t* bufB = reinterpret_cast<half_t*>(L->ws + L->lay.buf_b);
+    half_t* bufY = reinterpret_cast<half_t*>(L->ws + L->lay.buf_y);
+    half_t* bufF = reinterpret_cast<half_t*>(L->ws + L->lay.buf_f);
+    const half_t* x = static_cast<const half_t*>(tokens);
+    half_t* kc = static_cast<half_t*>(kv_cache);
+    half_t* vc = kc + (size_t)c.max_batch * H * c.max_seq;
+
+    EET_LAUNCH(launch_layernorm(x, nullptr, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, B, H, c.ln_eps,
+                                nullptr, 0, s), "layernorm 1");
+    GemmArgs g{};
+    g.x = bufA; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
+    g.M = B; g.N = 3 * H; g.K = H;
+    g.k_cache = kc; g.v_cache = vc; g.tok_row_map = nullptr; g.lens = d_lens;   // new token -> slot n_b
+    g.S = 1; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
+    EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
+    AttnDecodeArgs at{};
+    at.q = bufB; at.ctx = bufA; at.k_cache = kc; at.v_cache = vc; at.lens = d_lens; at.len_bias = 1;
+    at.batch = B; at.heads = c.heads; at.d = L->d; at.capacity = c.max_seq;
+    at.splits = attention_decode_splits(B, c.heads, c.max_seq);
+    at.part_acc = reinterpret_cast<float*>(L->ws + L->lay.part);
+    at.part_ml = at.part_acc + (size_t)B * c.heads * at.splits * L->d;
+    EET_LAUNCH(launch_attention_decode(at, s), "decode attention");
+    GemmArgs o{};
+    o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
+    o.M = B; o.N = H; o.K = H; o.res = x;
+    EET_LAUNCH(launch_gemm(o, EPI_BIAS_RES, s), "output projection");
+    // LN2; its row blocks also advance n_b: every reader of n_b in this step is already enqueued
+    EET_LAUNCH(launch_layernorm(bufY, nullptr, (const half_t*)L->w.ln2_g, (const half_t*)L->w.ln2_b, bufB, B, H,
+                                c.ln_eps, d_lens, B, s), "layernorm 2");
+    GemmArgs f1{};
+    f1.x = bufB; f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
+    f1.M = B; f1.N = F; f1.K = H;
+    EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
+    GemmArgs f2{};
+    f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
+    f2.M = B; f2.N = H; f2.K = F; f2.res = bufY;
+    EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
+    for (int b = 0; b < B; ++b) L->host_lens[b] += 1;
+    return EET_OK;
+}
+
+int eet_cache_lens(eet_layer_t* L, int32_t* out_host, void* hip_stream) {
+    if (!L || !out_host) return fail(EET_ERR_INVALID_ARG, "eet_cache_lens: null argument");
+    if (L->batch == 0) return fail(EET_ERR_STATE, "eet_cache_lens: no prefill has been run on this layer");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    EET_LAUNCH(hipMemcpyAsync(out_host, L->ws + L->lay.lens, sizeof(int32_t) * L->batch, hipMemcpyDeviceToHost, s),
+               "copy of cache lengths");
+    EET_LAUNCH(hipStreamSynchronize(s), "stream synchronise");
+    return EET_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// operator-level entry points
+// ------------------------------------------------------------------------------------------------
+int eet_op_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int32_t width,
+                     float eps, void* hip_stream) {
+    if (!x || !gamma || !beta || !y) return fail(EET_ERR_INVALID_ARG, "eet_op_layernorm: null argument");
+    if (rows < 0 || width < 1 || !(eps > 0.f)) return fail(EET_ERR_INVALID_ARG, "eet_op_layernorm: bad size or eps");
+    if (rows > 0x7fffffff) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_layernorm: more than 2^31-1 rows");
+    EET_LAUNCH(launch_layernorm((const half_t*)x, nullptr, (const half_t*)gamma, (const half_t*)beta, (half_t*)y, rows,
+                                width, eps, nullptr, 0, (hipStream_t)hip_stream), "layernorm");
+    return EET_OK;
+}
+
+int eet_op_softmax_maskfree(void* scores, const int32_t* q_lens, int32_t batch, int32_t heads, int32_t padded_len,
+                            float scale, void* hip_stream) {
+    if (!scores || !q_lens) return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: null argument");
+    if (batch < 1 || heads < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: bad size");
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "eet_op_softmax_maskfree: batch > EET_MAX_BATCH");
+    if ((int64_t)batch * heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_softmax_maskfree: batch*heads > 65535");
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+    }
+    EET_LAUNCH(launch_softmax_maskfree((half_t*)scores, lens, batch, heads, padded_len, scale, (hipStream_t)hip_stream),
+               "softmax");
+    return EET_OK;
+}
+
+int eet_op_bias_gelu(const void* x, const void* bias, void* y, int64_t rows, int32_t width, void* hip_stream) {
+    if (!x || !bias || !y) return fail(EET_ERR_INVALID_ARG, "eet_op_bias_gelu: null argument");
+    if (rows < 0 || width < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_bias_gelu: bad size");
+    EET_LAUNCH(launch_bias_gelu((const half_t*)x, (const half_t*)bias, (half_t*)y, rows, width, (hipStream_t)hip_stream),
+               "bias_gelu");
+    return EET_OK;
+}
+
+int eet_op_bias_residual(const void* x, const void* bias, const void* residual, void* y, int64_t rows, int32_t width,
+                         void* hip_stream) {
+    if (!x || !bias || !residual || !y) return fail(EET_ERR_INVALID_ARG, "eet_op_bias_residual: null argument");
+    if (rows < 0 || width < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_bias_residual: bad size");
+    EET_LAUNCH(launch_bias_residual((const half_t*)x, (const half_t*)bias, (const half_t*)residual, (half_t*)y, rows,
+                                    width, (hipStream_t)hip_stream), "bias_residual");
+    return EET_OK;
+}
+
+int eet_op_linear(const void* x, const void* w, const void* bias, const void* residual, void* y, int64_t rows,
+                  int32_t in, int32_t out, int32_t act, void* hip_stream) {
+    if (!x || !w || !bias || !y) return fail(EET_ERR_INVALID_ARG, "eet_op_linear: null argument");
+    if (rows < 0 || in < 1 || out < 1 || (act != 0 && act != 1)) return fail(EET_ERR_INVALID_ARG, "eet_op_linear: bad size or act");
+    if (in % 64 != 0 || out % 64 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear: in and out must be multiples of 64");
+    if (rows > 0x7fffffff) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear: more than 2^31-1 rows");
+    if (act == 1 && residual) return fail(EET_ERR_INVALID_ARG, "eet_op_linear: gelu and residual together are not a layer step");
+    if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(y) || !aligned16(residual))
+        return fail(EET_ERR_INVALID_ARG, "eet_op_linear: pointers must be 16-byte aligned");
+    GemmArgs g{};
+    g.x = (const half_t*)x; g.w = (const half_t*)w; g.bias = (const half_t*)bias; g.y = (half_t*)y;
+    g.M = (int)rows; g.N = out; g.K = in; g.res = (const half_t*)residual;
+    EET_LAUNCH(launch_gemm(g, residual ? EPI_BIAS_RES : (act ? EPI_BIAS_GELU : EPI_BIAS), (hipStream_t)hip_stream), "linear");
+    return EET_OK;
+}
+
+int eet_op_attention_prefill(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* q_lens,
+                             int32_t batch, int32_t padded_len, int32_t heads, int32_t d, int32_t capacity,
+                             void* hip_stream) {
+    if (!q || !k_cache || !v_cache || !ctx || !q_lens) return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: null argument");
+    if (batch < 1 || padded_len < 1 || heads < 1 || capacity < padded_len)
+        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: bad size");
+    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_prefill: head size must be 64 or 128");
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "eet_op_attention_prefill: batch > EET_MAX_BATCH");
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx))
+        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: pointers must be 16-byte aligned");
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+        max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
+    }
+    AttnPrefillArgs a{};
+    a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
+    a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity; a.hidden = heads * d;
+    a.packed = 0; a.S = padded_len; a.max_len = max_len;
+    EET_LAUNCH(launch_attention_prefill(a, lens, (hipStream_t)hip_stream), "prefill attention");
+    return EET_OK;
+}
+
+size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity) {
+    if (batch < 1 || heads < 1 || d < 1 || capacity < 1) return 0;
+    const size_t n = attention_decode_scratch_bytes(batch, heads, d, attention_decode_splits(batch, heads, capacity));
+    return n ? n : 256;
+}
+
+int eet_op_attention_decode(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* n_keys,
+                            int32_t batch, int32_t heads, int32_t d, int32_t capacity, void* scratch, void* hip_stream) {
+    if (!q || !k_cache || !v_cache || !ctx || !n_keys || !scratch)
+        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: null argument");
+    if (batch < 1 || heads < 1 || capacity < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: bad size");
+    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_decode: head size must be 64 or 128");
+    if (batch > 65535 || heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_decode: batch or heads > 65535");
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx) || !aligned16(scratch))
+        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: pointers must be 16-byte aligned");
+    AttnDecodeArgs a{};
+    a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
+    a.lens = n_keys; a.len_bias = 0; a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity;
+    a.splits = attention_decode_splits(batch, heads, capacity);
+    a.part_acc = (float*)scratch;
+    a.part_ml = a.part_acc + (size_t)batch * heads * a.splits * d;
+    EET_LAUNCH(launch_attention_decode(a, (hipStream_t)hip_stream), "decode attention");
+    return EET_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Host-side launchers of the gfx950 kernels.  Each launcher validates nothing: the C-ABI
+// layer in eet_api.hip checks shapes and pointers before any launch.
+#pragma once
+
+#include "common.hpp"
+
+namespace eet {
+
+// ---- row-wise kernels (rowops.hip) ---------------------------------------------------------
+// LayerNorm of `rows` rows.  Row r is read from x[in_row_map ? in_row_map[r] : r] and written
+// to y[r].  If bump_lens != nullptr, the block of row r < bump_count also does bump_lens[r] += 1
+// (advances the per-sequence cache length after all readers of this step were enqueued).
+hipError_t launch_layernorm(const half_t* x, const int32_t* in_row_map, const half_t* gamma,
+                            const half_t* beta, half_t* y, int64_t rows, int width, float eps,
+                            int32_t* bump_lens, int bump_count, hipStream_t s);
+hipError_t launch_bias_gelu(const half_t* x, const half_t* bias, half_t* y, int64_t rows, int width,
+                            hipStream_t s);
+hipError_t launch_bias_residual(const half_t* x, const half_t* bias, const half_t* res, half_t* y,
+                                int64_t rows, int width, hipStream_t s);
+hipError_t launch_softmax_maskfree(half_t* scores, const SeqLens& lens, int batch, int heads, int S,
+                                   float scale, hipStream_t s);
+// Index set-up of a prefill: device copies of the lengths, prefix sums, packed->padded row map,
+// and zero fill of the pad rows of `out` ([batch, S, width]).
+hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width, int32_t* cache_lens,
+                                int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s);
+
+// ---- dense projections (gemm.hip) ------------------------------------------------------------
+enum Epilogue : int { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES = 2, EPI_QKV = 3 };
+
+struct GemmArgs {
+    const half_t* x;        // [M, K] activations, row-major
+    const half_t* w;        // [N, K] weights, row-major
+    const half_t* bias;     // [N]
+    half_t* y;              // output [*, N] (EPI_QKV: the Q rows, [M, hidden])
+    int M, N, K;
+    // EPI_BIAS_RES: residual row of output row m is res[res_row_map ? res_row_map[m] : m]
+    const half_t* res;
+    const int32_t* res_row_map;
+    // output row of m is out_row_map ? out_row_map[m] : m   (scatter back to the padded layout)
+    const int32_t* out_row_map;
+    // EPI_QKV: columns [0,hidden) -> y, [hidden,2*hidden) -> K cache, [2*hidden,3*hidden) -> V cache.
+    // Row m belongs to (b, pos): prefill: (row_map[m] / S, row_map[m] % S); decode: (m, lens[m]).
+    half_t* k_cache;
+    half_t* v_cache;
+    const int32_t* tok_row_map;   // prefill: packed row -> b*S + pos ; nullptr in decode
+    const int32_t* lens;          // decode: device cache lengths
+    int S, hidden, heads, d, max_seq;
+};
+
+// M > 16: MFMA tile kernel.  M <= 16 (decode): weight-streaming kernel.
+hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
+
+// ---- attention (attention.hip) -------------------------------------------------------------------
+// Prefill: q rows of sequence b start at q_row0 + b*q_seq_stride (+ prefix sum of lens if packed).
+struct AttnPrefillArgs {
+    const half_t* q;        // row r, head g at q[r*hidden + g*d]
+    half_t* ctx;            // same addressing as q
+    const half_t* k_cache;  // [batch, heads, capacity, d]
+    const half_t* v_cache;
+    int batch, heads, d, capacity, hidden;
+    int packed;             // 1: rows of sequence b start at sum(len[0..b)); 0: at b*S
+    int S;                  // padded length (row stride between sequences when not packed)
+    int max_len;            // max over lens (sizes the grid)
+};
+hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s);
+
+struct AttnDecodeArgs {
+    const half_t* q;        // [batch, heads*d]
+    half_t* ctx;            // [batch, heads*d]
+    const half_t* k_cache;
+    const half_t* v_cache;
+    const int32_t* lens;    // DEVICE: number of visible keys minus `len_bias`
+    int len_bias;           // keys visible = lens[b] + len_bias (1 inside a decode step: the new token)
+    int batch, heads, d, capacity;
+    int splits;             // key-range splits per (sequence, head)
+    float* part_acc;        // [batch*heads*splits, d]   (splits > 1)
+    float* part_ml;         // [batch*heads*splits, 2]
+};
+int attention_decode_splits(int batch, int heads, int capacity);
+size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits);
+hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s);
+
+}  // namespace eet

@@ -1,0 +1,236 @@
+"""Thin ctypes binding over libeet.so (the C ABI declared in include/eet.h).
+
+Argument marshalling only: every computation runs in the HIP kernels of the library.  torch is
+used for device memory and streams.  There is no fallback: if the library has not been built
+(`python -m paper_2104_12470_amd.build`), loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libeet.so")
+
+EET_OK = 0
+EET_ERR_INVALID_ARG = -1
+EET_ERR_UNSUPPORTED_SHAPE = -2
+EET_ERR_CAPACITY = -3
+EET_ERR_STATE = -4
+EET_ERR_HIP = -5
+EET_MAX_BATCH = 128
+
+WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class LayerConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
+                ("max_batch", C.c_int32), ("max_prompt", C.c_int32), ("max_seq", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class EETError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"eet error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2104_12470_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+        cfgp, i32p = C.POINTER(LayerConfig), C.POINTER(C.c_int32)
+        sig = {
+            "eet_kv_cache_bytes": (sz, [cfgp]),
+            "eet_workspace_bytes": (sz, [cfgp]),
+            "eet_layer_create": (i32, [cfgp, C.POINTER(LayerWeights), vp, C.POINTER(vp)]),
+            "eet_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_decode_step": (i32, [vp, vp, vp, vp, vp]),
+            "eet_cache_lens": (i32, [vp, i32p, vp]),
+            "eet_layer_destroy": (i32, [vp]),
+            "eet_last_error": (C.c_char_p, []),
+            "eet_op_layernorm": (i32, [vp, vp, vp, vp, i64, i32, f32, vp]),
+            "eet_op_softmax_maskfree": (i32, [vp, i32p, i32, i32, i32, f32, vp]),
+            "eet_op_bias_gelu": (i32, [vp, vp, vp, i64, i32, vp]),
+            "eet_op_bias_residual": (i32, [vp, vp, vp, vp, i64, i32, vp]),
+            "eet_op_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
+            "eet_op_attention_prefill": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
+            "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
+            "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_decode_step",
+           "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_op_layernorm", "eet_op_softmax_maskfree",
+           "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill",
+           "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode")
+
+
+def _check(code: int) -> None:
+    if code != EET_OK:
+        raise EETError(code, lib().eet_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _lens_array(q_lens: Sequence[int]):
+    return (C.c_int32 * len(q_lens))(*[int(v) for v in q_lens])
+
+
+def make_config(hidden, heads, ffn, max_batch, max_prompt, max_seq, ln_eps=1e-5) -> LayerConfig:
+    return LayerConfig(hidden, heads, ffn, max_batch, max_prompt, max_seq, ln_eps)
+
+
+# ---- C ABI, same names --------------------------------------------------------------------
+def eet_kv_cache_bytes(cfg: LayerConfig) -> int:
+    return lib().eet_kv_cache_bytes(C.byref(cfg))
+
+
+def eet_workspace_bytes(cfg: LayerConfig) -> int:
+    return lib().eet_workspace_bytes(C.byref(cfg))
+
+
+def eet_layer_create(cfg: LayerConfig, weights: Dict[str, torch.Tensor], workspace: torch.Tensor) -> int:
+    w = LayerWeights(*[_ptr(weights[n]) for n in WEIGHT_FIELDS])
+    handle = C.c_void_p()
+    _check(lib().eet_layer_create(C.byref(cfg), C.byref(w), _ptr(workspace), C.byref(handle)))
+    return handle.value
+
+
+def eet_prefill(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens: torch.Tensor,
+                out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
+    _check(lib().eet_prefill(layer, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
+                             _ptr(kv_cache), _stream(stream)))
+
+
+def eet_decode_step(layer: int, tokens: torch.Tensor, out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
+    _check(lib().eet_decode_step(layer, _ptr(tokens), _ptr(out), _ptr(kv_cache), _stream(stream)))
+
+
+def eet_cache_lens(layer: int, batch: int, stream=None):
+    out = (C.c_int32 * batch)()
+    _check(lib().eet_cache_lens(layer, out, _stream(stream)))
+    return list(out)
+
+
+def eet_layer_destroy(layer: int) -> None:
+    _check(lib().eet_layer_destroy(layer))
+
+
+def eet_op_layernorm(x, gamma, beta, y, eps=1e-5, stream=None) -> None:
+    rows, width = x.numel() // x.shape[-1], x.shape[-1]
+    _check(lib().eet_op_layernorm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), rows, width, eps, _stream(stream)))
+
+
+def eet_op_softmax_maskfree(scores, q_lens, scale=1.0, stream=None) -> None:
+    B, nh, S, S2 = scores.shape
+    assert S == S2
+    _check(lib().eet_op_softmax_maskfree(_ptr(scores), _lens_array(q_lens), B, nh, S, scale, _stream(stream)))
+
+
+def eet_op_bias_gelu(x, bias, y, stream=None) -> None:
+    _check(lib().eet_op_bias_gelu(_ptr(x), _ptr(bias), _ptr(y), x.numel() // x.shape[-1], x.shape[-1], _stream(stream)))
+
+
+def eet_op_bias_residual(x, bias, residual, y, stream=None) -> None:
+    _check(lib().eet_op_bias_residual(_ptr(x), _ptr(bias), _ptr(residual), _ptr(y), x.numel() // x.shape[-1],
+                                      x.shape[-1], _stream(stream)))
+
+
+def eet_op_linear(x, w, bias, y, residual=None, act=0, stream=None) -> None:
+    rows, k = x.numel() // x.shape[-1], x.shape[-1]
+    assert w.shape[1] == k
+    _check(lib().eet_op_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), rows, k, w.shape[0], act,
+                               _stream(stream)))
+
+
+def eet_op_attention_prefill(q, k_cache, v_cache, ctx, q_lens, heads, stream=None) -> None:
+    B, S, H = q.shape
+    _, nh, cap, d = k_cache.shape
+    assert nh == heads and nh * d == H
+    _check(lib().eet_op_attention_prefill(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _lens_array(q_lens),
+                                          B, S, heads, d, cap, _stream(stream)))
+
+
+def eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) -> int:
+    return lib().eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity)
+
+
+def eet_op_attention_decode(q, k_cache, v_cache, ctx, n_keys, scratch, stream=None) -> None:
+    B, nh, cap, d = k_cache.shape
+    assert n_keys.dtype == torch.int32 and n_keys.is_cuda
+    _check(lib().eet_op_attention_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _ptr(n_keys), B, nh, d,
+                                         cap, _ptr(scratch), _stream(stream)))
+
+
+# ---- convenience holder: allocates workspace and cache with torch, keeps tensors alive -------------
+class DecoderLayer:
+    """Owns the torch buffers a layer handle borrows.  No arithmetic here."""
+
+    def __init__(self, cfg: LayerConfig, weights: Dict[str, torch.Tensor], device="cuda:0", cache_fill: float = 0.0):
+        self.cfg = cfg
+        self.weights = {n: weights[n].to(device=device, dtype=torch.float16).contiguous() for n in WEIGHT_FIELDS}
+        self.workspace = torch.empty(eet_workspace_bytes(cfg), dtype=torch.uint8, device=device)
+        self.kv_cache = torch.full((eet_kv_cache_bytes(cfg) // 2,), cache_fill, dtype=torch.float16, device=device)
+        self.handle = eet_layer_create(cfg, self.weights, self.workspace)
+
+    def cache_views(self):
+        c = self.cfg
+        kv = self.kv_cache.view(2, c.max_batch, c.heads, c.max_seq, c.hidden // c.heads)
+        return kv[0], kv[1]
+
+    def prefill(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_prefill(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
+    def decode_step(self, tokens: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):
+        out = torch.empty_like(tokens) if out is None else out
+        eet_decode_step(self.handle, tokens, out, self.kv_cache, stream)
+        return out
+
+    def cache_lens(self, batch: int):
+        return eet_cache_lens(self.handle, batch)
+
+    def close(self):
+        if self.handle:
+            eet_layer_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

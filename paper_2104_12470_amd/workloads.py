@@ -6,12 +6,13 @@ can be fed the same buffers.  The paper evaluates on fake inputs (Section 4, fir
 paragraph), so random tensors of the stated shapes are the paper's own workload.
 
 Generator: a counter-based hash (splitmix64 finaliser) keyed by (seed, tensor id) gives
-64 random bits per counter value; two of them make a Box-Muller normal.  Any slice of any
-tensor can be regenerated without state, and the result does not depend on chunking.
+64 random bits per counter value; each counter makes one Box-Muller pair of normals.  Any
+slice of any tensor can be regenerated without state, and the result does not depend on chunking.
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+import os
+from dataclasses import dataclass
 from typing import Dict, List, Tuple
 
 import numpy as np
@@ -50,17 +51,36 @@ def uniform01(seed: int, tensor_id: int, start: int, count: int) -> np.ndarray:
     return ((bits >> _U64(11)).astype(np.float64) + 0.5) * (1.0 / 9007199254740992.0)
 
 
+def _normal_chunk(seed: int, tensor_id: int, lo: int, m: int, sigma: float, mean: float, out: np.ndarray) -> None:
+    """Fill out[lo:lo+m] (m even or the tail).  Counter c yields elements 2c and 2c+1."""
+    c0, c1 = lo // 2, (lo + m + 1) // 2
+    bits = random_bits(seed, tensor_id, c0, c1 - c0)
+    u1 = ((bits >> _U64(40)).astype(np.float32) + np.float32(0.5)) * np.float32(1.0 / 16777216.0)
+    u2 = ((bits & _U64(0xFFFFFF)).astype(np.float32) + np.float32(0.5)) * np.float32(1.0 / 16777216.0)
+    r = np.sqrt(np.float32(-2.0) * np.log(u1)) * np.float32(sigma)
+    ang = np.float32(2.0 * np.pi) * u2
+    z = np.empty(2 * (c1 - c0), dtype=np.float32)
+    z[0::2] = r * np.cos(ang) + np.float32(mean)
+    z[1::2] = r * np.sin(ang) + np.float32(mean)
+    out[lo:lo + m] = z[lo - 2 * c0: lo - 2 * c0 + m].astype(out.dtype)
+
+
 def normal(seed: int, tensor_id: int, shape, sigma: float = 1.0, mean: float = 0.0,
-           dtype=np.float16, chunk: int = 1 << 24) -> np.ndarray:
-    """Tensor of N(mean, sigma^2) samples (Box-Muller), rounded to `dtype`."""
+           dtype=np.float16, chunk: int = 1 << 22) -> np.ndarray:
+    """Tensor of N(mean, sigma^2) samples (Box-Muller on 24-bit uniforms, float32 arithmetic),
+    rounded to `dtype`.  Large tensors are filled by a thread pool; the values do not depend
+    on the chunking."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=dtype)
-    for lo in range(0, n, chunk):
-        m = min(chunk, n - lo)
-        u = uniform01(seed, tensor_id, 2 * lo, 2 * m)
-        r = np.sqrt(-2.0 * np.log(u[0::2]))
-        z = r * np.cos(2.0 * np.pi * u[1::2])
-        out[lo:lo + m] = (mean + sigma * z).astype(dtype)
+    jobs = [(lo, min(chunk, n - lo)) for lo in range(0, n, chunk)]   # chunk is even
+    if len(jobs) <= 1:
+        for lo, m in jobs:
+            _normal_chunk(seed, tensor_id, lo, m, sigma, mean, out)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        workers = min(len(jobs), max(1, len(os.sched_getaffinity(0))), 16)
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(lambda j: _normal_chunk(seed, tensor_id, j[0], j[1], sigma, mean, out), jobs))
     return out.reshape(shape)
 
 

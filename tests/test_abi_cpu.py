@@ -1,0 +1,119 @@
+"""The C-ABI library loads, exports every symbol include/eet.h declares, and rejects bad
+arguments before any device work (no GPU needed: these paths return before the first HIP call)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import eet_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "eet.h")
+
+
+@pytest.fixture(scope="module")
+def eet():
+    from paper_2104_12470_amd import eet as binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2104_12470_amd.build import build_library
+        build_library(verbose=False)
+    binding.lib()
+    return binding
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(eet_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(eet):
+    names = declared_functions()
+    assert "eet_layer_create" in names and "eet_prefill" in names and "eet_decode_step" in names \
+        and "eet_layer_destroy" in names
+    for n in names:
+        assert hasattr(eet.lib(), n), f"{n} declared in eet.h but not exported"
+    assert sorted(eet.EXPORTS) == names            # the binding covers the whole header
+
+
+def test_size_queries(eet):
+    cfg = eet.make_config(1024, 16, 4096, 8, 512, 1024)
+    # Section 3.1: 2*b*h*s elements per layer, fp16
+    assert eet.eet_kv_cache_bytes(cfg) == 2 * orc.kv_cache_elements(8, 1024, 1024, 1)
+    ws = eet.eet_workspace_bytes(cfg)
+    T = 8 * 512
+    need = 2 * T * (3 * 1024 + 4096)               # three [T,H] buffers and one [T,F] buffer, fp16
+    assert need <= ws <= need + (1 << 20)
+    # same order as the paper's activation-cache + buffer bound (Sections 3.1, 3.2), in bytes
+    bound = 2 * (orc.activation_cache_elements(8, 1024, 512) + orc.buffer_elements(8, 512, 1024, 16))
+    assert ws <= bound
+    assert eet.eet_workspace_bytes(eet.make_config(96, 1, 256, 1, 8, 8)) == 0          # head size 96
+    assert eet.eet_kv_cache_bytes(eet.make_config(0, 1, 256, 1, 8, 8)) == 0
+
+
+def _fake_layer(eet, cfg):
+    w = eet.LayerWeights(*[0x10000 + 0x100 * i for i in range(12)])
+    h = C.c_void_p()
+    rc = eet.lib().eet_layer_create(C.byref(cfg), C.byref(w), 0x100000, C.byref(h))
+    return rc, h
+
+
+def test_create_rejects_bad_configs(eet):
+    L = eet.lib()
+    rc, h = _fake_layer(eet, eet.make_config(768, 12, 3072, 4, 64, 64))
+    assert rc == eet.EET_OK and h.value
+    assert L.eet_layer_destroy(h) == eet.EET_OK
+    for cfg, code in [(eet.make_config(768, 5, 3072, 4, 64, 64), eet.EET_ERR_INVALID_ARG),       # heads !| hidden
+                      (eet.make_config(960, 10, 3072, 4, 64, 64), eet.EET_ERR_UNSUPPORTED_SHAPE),  # d = 96
+                      (eet.make_config(768, 12, 3000, 4, 64, 64), eet.EET_ERR_UNSUPPORTED_SHAPE),  # ffn % 64
+                      (eet.make_config(768, 12, 3072, 129, 64, 64), eet.EET_ERR_UNSUPPORTED_SHAPE),
+                      (eet.make_config(768, 12, 3072, 4, 64, 32), eet.EET_ERR_UNSUPPORTED_SHAPE),  # s < p
+                      (eet.make_config(768, 12, 3072, 0, 64, 64), eet.EET_ERR_INVALID_ARG)]:
+        rc, h = _fake_layer(eet, cfg)
+        assert rc == code and not h.value
+        assert L.eet_last_error()
+    w = eet.LayerWeights(*[0x10000] * 11, 0)
+    h = C.c_void_p()
+    cfg = eet.make_config(768, 12, 3072, 4, 64, 64)
+    assert L.eet_layer_create(C.byref(cfg), C.byref(w), 0x100000, C.byref(h)) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_layer_create(C.byref(cfg), C.byref(eet.LayerWeights(*[0x10000] * 12)), 0x100010, C.byref(h)) \
+        == eet.EET_ERR_INVALID_ARG                                                              # workspace alignment
+
+
+def test_prefill_and_decode_validate_before_any_launch(eet):
+    L = eet.lib()
+    cfg = eet.make_config(768, 12, 3072, 4, 64, 80)
+    rc, h = _fake_layer(eet, cfg)
+    assert rc == 0
+    lens = (C.c_int32 * 4)(5, 2, 4, 10)
+    P = 0x200000
+    assert L.eet_decode_step(h, P, P, P, None) == eet.EET_ERR_STATE                  # decode before prefill
+    assert b"prefill" in L.eet_last_error()
+    assert L.eet_cache_lens(h, lens, None) == eet.EET_ERR_STATE
+    assert L.eet_prefill(h, lens, 5, 10, P, P, P, None) == eet.EET_ERR_CAPACITY      # batch > max_batch
+    assert L.eet_prefill(h, lens, 4, 65, P, P, P, None) == eet.EET_ERR_CAPACITY      # padded_len > max_prompt
+    assert L.eet_prefill(h, lens, 4, 9, P, P, P, None) == eet.EET_ERR_INVALID_ARG    # q_lens[3] = 10 > 9
+    assert L.eet_prefill(h, (C.c_int32 * 4)(5, 0, 4, 10), 4, 10, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_prefill(h, lens, 0, 10, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_prefill(h, lens, 4, 10, None, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_prefill(h, lens, 4, 10, P + 2, P, P, None) == eet.EET_ERR_INVALID_ARG   # alignment
+    assert L.eet_decode_step(h, P, P, P, None) == eet.EET_ERR_STATE                  # failures changed no state
+    assert L.eet_layer_destroy(h) == 0
+
+
+def test_op_entry_points_validate(eet):
+    L = eet.lib()
+    P = 0x200000
+    lens = (C.c_int32 * 2)(3, 9)
+    assert L.eet_op_layernorm(None, P, P, P, 4, 64, 1e-5, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_layernorm(P, P, P, P, 4, 0, 1e-5, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_softmax_maskfree(P, lens, 2, 2, 8, 1.0, None) == eet.EET_ERR_INVALID_ARG   # len 9 > S 8
+    assert L.eet_op_softmax_maskfree(P, lens, 200, 2, 16, 1.0, None) == eet.EET_ERR_CAPACITY
+    assert L.eet_op_bias_gelu(P, None, P, 4, 64, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_bias_residual(P, P, None, P, 4, 64, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_linear(P, P, P, None, P, 4, 100, 64, 0, None) == eet.EET_ERR_UNSUPPORTED_SHAPE
+    assert L.eet_op_linear(P, P, P, P, P, 4, 64, 64, 1, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_attention_prefill(P, P, P, P, lens, 2, 16, 2, 96, 16, None) == eet.EET_ERR_UNSUPPORTED_SHAPE
+    assert L.eet_op_attention_prefill(P, P, P, P, lens, 2, 16, 2, 64, 8, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_attention_decode(P, P, P, P, P, 2, 2, 64, 16, None, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_attention_decode_scratch_bytes(2, 2, 64, 4096) > 0

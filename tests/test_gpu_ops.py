@@ -1,0 +1,156 @@
+"""Operator-level parity: each HIP kernel, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Shapes span several tiles and ragged tails; widths follow the row-kernel
+extents the paper targets (Section 2.2: hidden up to 12288/16384, sequence up to 4096)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import eet_oracle as orc
+from paper_2104_12470_amd import workloads as wl
+from tests.gpu_util import dev, gate, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eet():
+    from paper_2104_12470_amd import eet as binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+# fp16 rounding of an O(1) output: half an ulp at |x| in [2,4) is 1e-3; budget a few of them
+OP_MAX, OP_MEAN = 6e-3, 6e-4
+
+
+@pytest.mark.parametrize("rows,width", [(7, 64), (5, 768), (3, 1024), (3, 1280), (2, 2048), (3, 4096), (2, 12288),
+                                        (2, 16384), (2, 49152), (4, 100), (3, 1283), (300, 1024)])
+def test_layernorm(eet, rows, width):
+    x = (wl.normal(101, width, (rows, width)).astype(np.float32) * 1.7 + 0.3).astype(np.float16)
+    g = wl.normal(102, width, (width,), 0.1, 1.0)
+    b = wl.normal(103, width, (width,), 0.1, 0.0)
+    y = torch.full((rows, width), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_layernorm(dev(x), dev(g), dev(b), y, 1e-5)
+    torch.cuda.synchronize()
+    gate(host(y), orc.layernorm(x, g, b, 1e-5), f"layernorm {rows}x{width}", OP_MAX, OP_MEAN)
+
+
+@pytest.mark.parametrize("rows,width", [(5, 3072), (3, 49152), (4, 100), (2, 16392), (70000, 64)])
+def test_bias_gelu_and_bias_residual(eet, rows, width):
+    x = (wl.normal(111, width, (rows, width)).astype(np.float32) * 2.0).astype(np.float16)
+    b = wl.normal(112, width, (width,), 0.5)
+    r = wl.normal(113, width, (rows, width))
+    y = torch.full((rows, width), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_bias_gelu(dev(x), dev(b), y)
+    torch.cuda.synchronize()
+    gate(host(y), orc.bias_gelu(x, b), f"bias_gelu {rows}x{width}", OP_MAX, OP_MEAN)
+    y.fill_(float("nan"))
+    eet.eet_op_bias_residual(dev(x), dev(b), dev(r), y)
+    torch.cuda.synchronize()
+    gate(host(y), orc.bias_residual(x, b, r), f"bias_residual {rows}x{width}", OP_MAX, OP_MEAN)
+
+
+@pytest.mark.parametrize("B,nh,S,lens", [
+    (3, 2, 9, [9, 1, 5]),              # scalar path (S % 8 != 0)
+    (4, 1, 10, [5, 2, 4, 10]),         # the uneven batch of the paper's Section 4.1 example
+    (2, 3, 64, [64, 17]),
+    (2, 2, 520, [333, 520]),           # two vectors per lane, ragged
+    (1, 2, 1024, [1000]),
+    (2, 1, 4096, [4096, 2049]),        # the longest row the paper targets
+    (1, 1, 4224, [4200]),
+])
+def test_softmax_maskfree(eet, B, nh, S, lens):
+    s = wl.scores(200 + S, B, nh, S)
+    # entries the method must never use: masked part of valid rows and whole pad rows get NaN
+    poisoned = s.copy()
+    iu = np.triu_indices(S, 1)
+    poisoned[:, :, iu[0], iu[1]] = np.nan
+    for b, L in enumerate(lens):
+        poisoned[b, :, L:, :] = np.nan
+    t = dev(poisoned)
+    eet.eet_op_softmax_maskfree(t, lens, 0.37)
+    torch.cuda.synchronize()
+    got = host(t)
+    want = orc.softmax_maskfree(s, lens, 0.37)
+    for b, L in enumerate(lens):
+        gate(got[b, :, :L], want[b, :, :L], f"softmax b={b}", 1e-3, 1e-4)
+        assert np.all(got[b, :, :L][:, np.triu_indices(L, 1)[0], np.triu_indices(L, 1)[1]] == 0)
+        assert np.all(got[b, :, :L, L:] == 0)                     # masked entries are exact zeros
+        assert np.all(np.isnan(got[b, :, L:, :]))                 # pad rows untouched
+        np.testing.assert_allclose(got[b, :, :L].astype(np.float64).sum(-1), 1.0, atol=4e-3)
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 130, 300])
+@pytest.mark.parametrize("K,N", [(64, 64), (256, 192), (1024, 3072), (4096, 1024)])
+def test_linear(eet, M, K, N):
+    x = wl.normal(300 + M, K, (M, K))
+    w = wl.normal(301, K * 7 + N, (N, K), 1.0 / np.sqrt(K))
+    b = wl.normal(302, N, (N,), 0.5)
+    r = wl.normal(303 + M, N, (M, N))
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+    xd, wd, bd, rd = dev(x), dev(w), dev(b), dev(r)
+    lin = orc.linear(x, w, b)
+    eet.eet_op_linear(xd, wd, bd, y)
+    torch.cuda.synchronize()
+    gate(host(y), lin, f"linear {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    y.fill_(float("nan"))
+    eet.eet_op_linear(xd, wd, bd, y, act=1)
+    torch.cuda.synchronize()
+    gate(host(y), orc.gelu_tanh(lin), f"linear+gelu {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    y.fill_(float("nan"))
+    eet.eet_op_linear(xd, wd, bd, y, residual=rd)
+    torch.cuda.synchronize()
+    gate(host(y), lin + r.astype(np.float64), f"linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
+
+
+@pytest.mark.parametrize("d,heads,S,cap,lens", [
+    (64, 2, 24, 32, [24, 1, 7]),
+    (64, 3, 200, 224, [200, 3, 129, 64, 65]),
+    (128, 2, 333, 352, [333, 40, 129]),
+    (128, 1, 1030, 1030, [1030, 512]),
+])
+def test_attention_prefill(eet, d, heads, S, cap, lens):
+    B, H = len(lens), heads * d
+    q = wl.normal(400 + d, 1, (B, S, heads, d))
+    k = wl.normal(400 + d, 2, (B, S, heads, d))
+    v = wl.normal(400 + d, 3, (B, S, heads, d))
+    want = orc.attention_prefill(q, k, v, lens)
+    kc = np.full((B, heads, cap, d), np.nan, np.float16)          # slots >= L must never be read
+    vc = np.full((B, heads, cap, d), np.nan, np.float16)
+    qp = q.copy()
+    for b, L in enumerate(lens):
+        kc[b, :, :L] = k[b, :L].transpose(1, 0, 2)
+        vc[b, :, :L] = v[b, :L].transpose(1, 0, 2)
+        qp[b, L:] = np.nan                                        # pad queries must never be read
+    ctx = torch.full((B, S, H), 7.0, dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_prefill(dev(qp.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads)
+    torch.cuda.synchronize()
+    got = host(ctx).reshape(B, S, heads, d)
+    for b, L in enumerate(lens):
+        gate(got[b, :L], want[b, :L], f"attention prefill b={b} L={L}", OP_MAX, OP_MEAN)
+        assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
+
+
+@pytest.mark.parametrize("d,heads,cap,n_keys", [
+    (64, 4, 600, [1, 17, 600]),
+    (128, 4, 600, [600, 16, 33]),
+    (64, 2, 2048, [2048, 100]),        # several key ranges per (sequence, head), one of them empty for the short one
+    (128, 2, 4224, [4224, 1]),
+])
+def test_attention_decode(eet, d, heads, cap, n_keys):
+    B = len(n_keys)
+    q = wl.normal(500 + d, 1, (B, heads, d))
+    kc = wl.normal(500 + d, 2, (B, heads, cap, d))
+    vc = wl.normal(500 + d, 3, (B, heads, cap, d))
+    want = orc.attention_decode(q, kc, vc, n_keys)
+    kp, vp = kc.copy(), vc.copy()
+    for b, n in enumerate(n_keys):
+        kp[b, :, n:] = np.nan
+        vp[b, :, n:] = np.nan
+    scratch = torch.empty(eet.eet_op_attention_decode_scratch_bytes(B, heads, d, cap), dtype=torch.uint8, device="cuda:0")
+    ctx = torch.full((B, heads * d), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_decode(dev(q.reshape(B, heads * d)), dev(kp), dev(vp), ctx,
+                                dev(np.asarray(n_keys, np.int32)), scratch)
+    torch.cuda.synchronize()
+    gate(host(ctx).reshape(B, heads, d), want, f"attention decode d={d}", OP_MAX, OP_MEAN)
