@@ -1,0 +1,300 @@
+#!/usr/bin/env python3
+"""Benchmark of the decoder-layer hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch of the named workload:
+whole-prompt prefill through every layer, then every incremental decode step through every
+layer (K/V caches filled by the prefill and extended by each step).  Inputs, weights and caches
+are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=3)
+    p.add_argument("--warmup", type=int, default=1)
+    p.add_argument("--workload", default="cfg2")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--kernel-reps", type=int, default=200, help="launches per kernel in the roofline measurement")
+    p.add_argument("--roofline-only", action="store_true",
+                   help="skip the timed pass and the CPU baseline: only the per-kernel measurement plus one plain "
+                        "256 MiB device copy (the reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
+    return p.parse_args()
+
+
+class Stack:
+    """The layers of a workload with their caches, plus ping-pong activation buffers."""
+
+    def __init__(self, w, eet, torch, wl):
+        self.w, self.eet, self.torch = w, eet, torch
+        cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+        self.layers = []
+        for li in range(w.layers):
+            W = wl.layer_weights(w, li)
+            self.layers.append(eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in W.items()}))
+        self.lens = [int(v) for v in wl.lengths(w)]
+        dev = "cuda:0"
+        self.x0 = torch.from_numpy(wl.prompt_embeddings(w)).to(dev)
+        self.dec_in = torch.stack([torch.from_numpy(wl.decode_embeddings(w, k)) for k in range(w.decode_steps)]).to(dev) \
+            if w.decode_steps else None
+        self.pbuf = [torch.empty_like(self.x0) for _ in range(2)]
+        self.dbuf = [torch.empty((w.batch, w.hidden), dtype=torch.float16, device=dev) for _ in range(2)]
+
+    def prefill(self):
+        h = self.x0
+        for li, layer in enumerate(self.layers):
+            layer.prefill(h, self.lens, self.pbuf[li & 1])
+            h = self.pbuf[li & 1]
+        return h
+
+    def decode(self):
+        h = None
+        for k in range(self.w.decode_steps):
+            h = self.dec_in[k]
+            for li, layer in enumerate(self.layers):
+                layer.decode_step(h, self.dbuf[li & 1])
+                h = self.dbuf[li & 1]
+        return h
+
+    def one_pass(self):
+        self.prefill()
+        self.decode()
+
+
+def time_region(torch, fn, reps):
+    """Average duration of fn() in ms, HIP events on the stream the kernels are launched on."""
+    s = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    for _ in range(reps):
+        fn()
+    e1.record(s)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def time_launches(torch, fn, calls, replays=5):
+    """Average duration of one fn() in ms with the launches truly back to back: `calls` invocations
+    are captured into a HIP graph on the launch stream (the library only enqueues kernels, so a
+    capture records exactly its launches) and the graph is replayed between two HIP events.  A
+    Python loop cannot issue launches as fast as these kernels run."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(calls):
+            fn()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(calls):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    s = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    for _ in range(replays):
+        g.replay()
+    e1.record(s)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / (replays * calls)
+
+
+def _kernel_candidates(stack, torch, eet, reps):
+    """Time the kernels that can dominate a pass, each through its operator-level entry point on
+    the stack's own weights and caches, cycling over the layers so that nothing is served from a
+    cache the real pass would not have.  Returns a list of records with the algorithmic bytes or
+    flops of one launch, the average launch duration and the launches per pass."""
+    w = stack.w
+    B, H, F, nl = w.batch, w.hidden, w.ffn, len(stack.layers)
+    d = H // w.heads
+    T = sum(stack.lens)
+    out = []
+    if w.decode_steps:
+        # (1) decode attention: K and V of every visible slot read once, q read, ctx written
+        ks = sorted({0, w.decode_steps // 4, w.decode_steps // 2, 3 * w.decode_steps // 4, w.decode_steps - 1})
+        nkeys = [torch.tensor([L + k + 1 for L in stack.lens], dtype=torch.int32, device="cuda:0") for k in ks]
+        bytes_k = [4.0 * H * sum(L + k + 1 for L in stack.lens) + 4.0 * B * H for k in ks]
+        scratch = torch.empty(eet.eet_op_attention_decode_scratch_bytes(B, w.heads, d, w.max_seq), dtype=torch.uint8,
+                              device="cuda:0")
+        q = torch.randn(B, H, device="cuda:0").half()
+        ctx = torch.empty_like(q)
+        st = {"i": 0}
+
+        def run_attn():
+            i = st["i"]
+            st["i"] += 1
+            kc, vc = stack.layers[i % nl].cache_views()
+            eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // nl) % len(ks)], scratch)
+        n = nl * len(ks)
+        ms = time_launches(torch, run_attn, n * max(1, reps // n))
+        out.append({"kernel": f"attn_decode_partial<{d}> (+combine): decode attention over the K/V cache",
+                    "bound": "hbm", "work": sum(bytes_k) / len(bytes_k), "ms": ms,
+                    "launches": w.decode_steps * nl})
+        # (2) decode projection (weight stream): FFN-1, the largest of the four
+        x = torch.randn(B, H, device="cuda:0").half()
+        y = torch.empty(B, F, device="cuda:0", dtype=torch.float16)
+        st2 = {"i": 0}
+
+        def run_ffn1():
+            layer = stack.layers[st2["i"] % nl]
+            st2["i"] += 1
+            eet.eet_op_linear(x, layer.weights["w_fc1"], layer.weights["b_fc1"], y, act=1)
+        ms = time_launches(torch, run_ffn1, nl * max(1, reps // nl))
+        out.append({"kernel": "gemm_skinny: FFN-1 projection + bias + GELU, decode (weight stream)", "bound": "hbm",
+                    "work": 2.0 * (F * H + B * H + F + B * F), "ms": ms,
+                    "launches": w.decode_steps * nl * (12 * H * H) / (H * F)})   # launches scaled to all 4 projections by bytes
+    # (3) prefill projection on the matrix cores: FFN-1 over all valid tokens
+    xp = torch.randn(T, H, device="cuda:0").half()
+    yp = torch.empty(T, F, device="cuda:0", dtype=torch.float16)
+    st3 = {"i": 0}
+
+    def run_pre():
+        layer = stack.layers[st3["i"] % nl]
+        st3["i"] += 1
+        eet.eet_op_linear(xp, layer.weights["w_fc1"], layer.weights["b_fc1"], yp, act=1)
+    ms = time_launches(torch, run_pre, max(4, min(reps, 24)), replays=2)
+    out.append({"kernel": "gemm_mfma: FFN-1 projection + bias + GELU, prefill (matrix cores)", "bound": "mfma",
+                "work": 2.0 * T * H * F, "ms": ms, "launches": nl * (12 * H * H) / (H * F)})
+    return out
+
+
+def roofline_for(stack, torch, eet, reps):
+    """Roofline record of the dominant kernel (largest share of the pass) and of the others."""
+    recs = []
+    for c in _kernel_candidates(stack, torch, eet, reps):
+        if c["bound"] == "hbm":
+            ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e12, MFMA_FP16_PEAK_TFLOPS, "TFLOP/s"
+        recs.append({"kernel": c["kernel"], "bound": c["bound"], "achieved": ach, "peak": peak, "unit": unit,
+                     "frac": ach / peak, "traffic": None, "avg_launch_us": c["ms"] * 1e3,
+                     "algorithmic_work_per_launch": c["work"], "share_ms_per_pass": c["ms"] * c["launches"]})
+    recs.sort(key=lambda r: -r["share_ms_per_pass"])
+    return recs[0], recs[1:]
+
+
+def cpu_baseline(w, wl, budget_s=25.0, min_s=10.0):
+    """The CPU oracle timed on a bounded sample of the same workload: whole layers (as many as it
+    takes to reach about ten seconds, at most the stack), as many whole sequences as fit a flop
+    budget, and decode steps until the time budget is used.  The result is scaled to whole-stack
+    tokens/s (time per layer multiplied by the number of layers)."""
+    import numpy as np
+
+    from oracle import eet_oracle as orc
+    lens_all = wl.lengths(w)
+    flops_seq = 24.0 * lens_all.astype(np.float64) * w.hidden * w.hidden
+    nseq = 1
+    while nseq < w.batch and flops_seq[: nseq + 1].sum() <= 1.5e12:
+        nseq += 1
+    lens = lens_all[:nseq]
+    weights = [{k: v.astype(np.float64) for k, v in wl.layer_weights(w, li).items()} for li in range(min(w.layers, 4))]
+    x = wl.prompt_embeddings(w)[:nseq]
+    dec = [wl.decode_embeddings(w, k)[:nseq] for k in range(w.decode_steps)]
+    total, layers_done, steps_done, tokens = 0.0, 0, [], 0
+    while layers_done < w.layers and total < min_s:
+        oracle = orc.DecoderLayerOracle(weights[layers_done % len(weights)], w.heads, nseq, w.max_seq, w.ln_eps)
+        t0 = time.perf_counter()
+        oracle.prefill(x, lens)
+        steps = 0
+        while steps < w.decode_steps and time.perf_counter() - t0 < budget_s:
+            oracle.decode_step(dec[steps])
+            steps += 1
+        total += time.perf_counter() - t0
+        layers_done += 1
+        steps_done.append(steps)
+        tokens += int(lens.sum()) + nseq * steps
+    cores = len(os.sched_getaffinity(0))
+    try:
+        from threadpoolctl import threadpool_info
+        nthreads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        nthreads = cores
+    per_layer_tokens = tokens / layers_done
+    return {"value": per_layer_tokens / (total / layers_done * w.layers), "unit": "tokens/s",
+            "cores": min(cores, nthreads), "kind": "oracle",
+            "sample": f"float64 oracle, {layers_done} of {w.layers} layer(s) (time per layer scaled by {w.layers}), "
+                      f"{nseq} of {w.batch} sequences (lengths {lens.tolist()}), prefill + {steps_done[0]} of "
+                      f"{w.decode_steps} decode steps each; {total:.1f} s of CPU work, {tokens} layer-tokens"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (asked for --gpus {a.gpus}); sharding by sequence is a "
+              "design note, not code", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2104_12470_amd import eet, workloads as wl
+    eet.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = wl.WORKLOADS[a.workload]
+    stack = Stack(w, eet, torch, wl)
+    tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
+
+    if a.roofline_only:
+        stack.one_pass() if w.decode_steps <= 64 else stack.prefill()   # caches hold real keys/values
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                                   # plain copy kernel of known size
+        torch.cuda.synchronize()
+        main_rec, others = roofline_for(stack, torch, eet, a.kernel_reps)
+        print(json.dumps({"roofline": main_rec, "roofline_other_kernels": others, "copy_bytes": 256 << 20}))
+        return
+
+    for _ in range(a.warmup):
+        stack.one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        stack.one_pass()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+
+    # phase split (informative): prefill alone and decode alone, HIP events
+    ms_prefill = time_region(torch, stack.prefill, 2)
+    ms_decode = time_region(torch, stack.decode, 1) if w.decode_steps else 0.0
+
+    rec = {
+        "metric": "decoder-layer tokens/s (prefill+decode) fp16; % of HBM/MFMA roofline",
+        "value": tokens / (dt / a.steps), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.layers} layer(s), hidden {w.hidden}, heads {w.heads}, ffn {w.ffn}, "
+                               f"batch {w.batch}, prompts {w.len_lo}-{w.len_hi} padded to {w.padded_len}, "
+                               f"{w.decode_steps} decode steps, cache {w.max_seq}",
+                   "valid_tokens_per_step": tokens, "prefill_tokens": sum(stack.lens),
+                   "decode_tokens": w.batch * w.decode_steps,
+                   "prefill_ms": ms_prefill, "decode_ms": ms_decode,
+                   "prefill_tokens_per_s": sum(stack.lens) / (ms_prefill * 1e-3),
+                   "decode_tokens_per_s": (w.batch * w.decode_steps) / (ms_decode * 1e-3) if ms_decode else None},
+    }
+    rec["roofline"], rec["roofline_other_kernels"] = roofline_for(stack, torch, eet, a.kernel_reps)
+    if not a.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w, wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
