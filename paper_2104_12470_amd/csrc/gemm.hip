@@ -14,6 +14,8 @@
 //                workgroup and reduced through LDS.
 // Both compute the transposed tile (weights as the MFMA "A" operand) so that each lane ends up
 // with 4 consecutive output columns of one row: 8-byte stores, and 8-byte bias/residual loads.
+#include <cstdlib>
+
 #include "kernels.hpp"
 
 namespace eet {
@@ -276,7 +278,14 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
-        launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
+        static const int tile = getenv("EET_GEMM_TILE") ? atoi(getenv("EET_GEMM_TILE")) : 0;
+        switch (tile) {
+            case 1: launch_mfma_cfg<256, 256, 2, 2>(a, epi, s); break;
+            case 2: launch_mfma_cfg<256, 256, 2, 4>(a, epi, s); break;
+            case 3: launch_mfma_cfg<256, 128, 2, 2>(a, epi, s); break;
+            case 4: launch_mfma_cfg<256, 128, 4, 2>(a, epi, s); break;
+            default: launch_mfma_cfg<128, 128, 2, 2>(a, epi, s); break;
+        }
     }
     return hipGetLastError();
 }
