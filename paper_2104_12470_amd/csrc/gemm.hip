@@ -65,6 +65,23 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
 // --------------------------------------------------------------------------------------------
 // MFMA tile kernel
 // --------------------------------------------------------------------------------------------
+// Tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x is
+// given a contiguous range of a tile sequence in which any 32 consecutive tiles (one per CU of the
+// XCD) form a block of 8 row-tiles x 4 column-tiles: 12 operand panels are shared by 32 tiles.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    constexpr int GM = 8;
+    const int nb = tiles_m * tiles_n;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int q = nb >> 3, rem = nb & 7;
+    const int t = xcd * q + (xcd < rem ? xcd : rem) + local;   // position in the sequence
+    const int per_group = GM * tiles_n;
+    const int grp = t / per_group, in_grp = t - grp * per_group;
+    const int gm0 = grp * GM;
+    const int gsz = tiles_m - gm0 < GM ? tiles_m - gm0 : GM;    // last group may be shorter
+    tile_n = in_grp / gsz;
+    tile_m = gm0 + in_grp - tile_n * gsz;
+}
+
 constexpr int kBK = 64;          // K depth of one LDS stage
 constexpr int kLdk = kBK + 8;    // padded LDS row (144 B): 16-byte fragment reads hit distinct banks
 
@@ -79,14 +96,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
     __shared__ __attribute__((aligned(16))) half_t As[2][BM * kLdk];
     __shared__ __attribute__((aligned(16))) half_t Ws[2][BN * kLdk];
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles
-    // so that neighbours in the range (which share a weight panel) also share an L2.
-    const int nb = tiles_m * tiles_n;
-    const int pid = blockIdx.x;
-    const int xcd = pid & 7, local = pid >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    const int tile = xcd * q + (xcd < rem ? xcd : rem) + local;
-    const int tile_n = tile / tiles_m, tile_m = tile - tile_n * tiles_m;
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -159,6 +170,338 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
     }
 
     // acc[i][j][r]: row m = lane%32 of fragment i, column n = (r/4)*8 + (lane/32)*4 + r%4 of fragment j
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = m0 + wm0 + i * 32 + (lane & 31);
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int n = n0 + wn0 + j * 32 + rg * 8 + (lane >> 5) * 4;
+                if (n < N)
+                    epilogue4<EPI>(a, m, n, acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2],
+                                   acc[i][j][rg * 4 + 3]);
+            }
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// MFMA tile kernel with direct global->LDS loads
+// --------------------------------------------------------------------------------------------
+// 256x256 tile, WGM x WGN waves, K steps of 32 through a ring of four LDS stages filled by
+// global_load_lds_dwordx4 (no staging registers, no ds_write): the loads of K step kt+3 are in
+// flight while step kt is multiplied.  An LDS row is the 64 bytes of one operand row; a wave-level
+// load deposits 16 rows contiguously, so instead of padding, the four 16-byte chunks of a row are
+// XOR-permuted by (row/4)%4 -- applied on the global address of each lane when loading and on the
+// LDS address when reading fragments -- which spreads any 16 consecutive rows over all 64 banks.
+// MFMA fragments are double-buffered in registers: the reads of the next half-step are issued
+// before the MFMAs of the current one.
+//
+// Fragment reads and every wait in the main loop are inline assembly / raw builtins.  The compiler
+// cannot tell that an LDS read does not alias an in-flight global->LDS load and would otherwise
+// drain all of them (vmcnt(0)) before each read and before each barrier, which undoes the pipeline.
+#ifndef EET_DBG_DMA
+#define EET_DBG_DMA 1      // 0: timing experiment without the steady-state loads (wrong results)
+#endif
+constexpr int kDK = 32;
+constexpr int kDStages = 4;
+
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds + 16*l (the LDS
+// base must be wave-uniform).  Kept out of the templates: the builtin only exists for the device.
+__device__ __forceinline__ void load_lds_16B(const half_t* gptr, half_t* lds) {
+    __builtin_amdgcn_global_load_lds(gptr, lds, 16, 0, 0);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_lgkm() {
+    static_assert(N == 0 || N == 6 || N == 8, "add the count");
+    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)");
+    if (N == 6) asm volatile("s_waitcnt lgkmcnt(6)");
+    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(N == 0 || N == 8 || N == 16, "add the count");
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)");
+    if (N == 8) asm volatile("s_waitcnt vmcnt(8)");
+    if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
+}
+
+template <int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma(GemmArgs a, int tiles_m, int tiles_n) {
+    constexpr int BM = 256, BN = 256, NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+    constexpr int LR = 256 / NW;          // rows of each operand tile a wave loads per K step
+    constexpr int LI = LR / 16;           // wave-level load instructions per operand per K step
+    constexpr int kInFlight2 = 2 * 2 * LI;   // instructions of two later K steps
+    __shared__ __attribute__((aligned(1024))) half_t As[kDStages][BM * kDK];
+    __shared__ __attribute__((aligned(1024))) half_t Ws[kDStages][BN * kDK];
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    const int M = a.M, N = a.N, K = a.K;
+    const int nk = K / kDK;
+
+    // this lane's rows of each operand tile, and the chunk it fetches for LDS position lane%4
+    const half_t* pa[LI];
+    const half_t* pw[LI];
+#pragma unroll
+    for (int v = 0; v < LI; ++v) {
+        const int row = wave * LR + v * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        int gr = m0 + row;
+        gr = gr < M ? gr : M - 1;
+        pa[v] = a.x + (int64_t)gr * K + c * 8;
+        gr = n0 + row;
+        gr = gr < N ? gr : N - 1;
+        pw[v] = a.w + (int64_t)gr * K + c * 8;
+    }
+    // fragment addressing: row = lane%32 (+ offsets that are multiples of 32), logical chunk ks*2 + lane/32
+    const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 2) & 3;
+    const unsigned a_lds = (unsigned)(uintptr_t)&As[0][(wm0 + frow) * kDK];
+    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[0][(wn0 + frow) * kDK];
+    unsigned foff[2];
+    foff[0] = (unsigned)(((0 + fG) ^ fsw) * 16);
+    foff[1] = (unsigned)(((2 + fG) ^ fsw) * 16);
+
+    half8v fa[2][FM], fw[2][FN];
+    float16v acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#define EET_DLOAD(T, ST)                                                                                 \
+    do {                                                                                                 \
+        _Pragma("unroll") for (int v = 0; v < LI; ++v) {                                                 \
+            load_lds_16B(pa[v] + (int64_t)(T) * kDK, &As[ST][(wave * LR + v * 16) * kDK]);               \
+            load_lds_16B(pw[v] + (int64_t)(T) * kDK, &Ws[ST][(wave * LR + v * 16) * kDK]);               \
+        }                                                                                                \
+    } while (0)
+#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
+#define EET_DFRAG(FS, ST, KS)                                                                            \
+    do {                                                                                                 \
+        const unsigned va_ = a_lds + (ST) * (BM * kDK * 2) + foff[KS];                                   \
+        const unsigned vw_ = w_lds + (ST) * (BN * kDK * 2) + foff[KS];                                   \
+        EET_DREAD(fa[FS][0], va_, 0);                                                                    \
+        if (FM > 1) EET_DREAD(fa[FS][1 % FM], va_, 2048);                                                \
+        if (FM > 2) EET_DREAD(fa[FS][2 % FM], va_, 4096);                                                \
+        if (FM > 3) EET_DREAD(fa[FS][3 % FM], va_, 6144);                                                \
+        EET_DREAD(fw[FS][0], vw_, 0);                                                                    \
+        if (FN > 1) EET_DREAD(fw[FS][1 % FN], vw_, 2048);                                                \
+        if (FN > 2) EET_DREAD(fw[FS][2 % FN], vw_, 4096);                                                \
+        if (FN > 3) EET_DREAD(fw[FS][3 % FN], vw_, 6144);                                                \
+    } while (0)
+    // wait until at most CNT LDS operations are outstanding, and tie fragment set FS to the wait
+#define EET_DWAIT(FS, CNT)                                                                               \
+    do {                                                                                                 \
+        wait_lgkm<CNT>();                                                                                \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[FS][i]));              \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[FS][j]));              \
+    } while (0)
+#define EET_DMMA(FS)                                                                                     \
+    do {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < (EET_DBG_DMA == 3 ? 1 : FM); ++i)                          \
+            _Pragma("unroll") for (int j = 0; j < (EET_DBG_DMA == 3 ? 1 : FN); ++j)                      \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[FS][j], fa[FS][i], acc[i][j], 0, 0, 0); \
+    } while (0)
+
+    // prologue: tiles 0..2 in flight, tile 0 landed and published
+    EET_DLOAD(0, 0);
+    if (nk > 1) EET_DLOAD(1, 1);
+    if (nk > 2) EET_DLOAD(2, 2);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    EET_DFRAG(0, 0, 0);
+    int kt = 0;
+    for (; kt + 3 < nk; ++kt) {           // steady state: tiles kt+1, kt+2 in flight, kt+3 issued now
+        const int st = kt & 3, st1 = (kt + 1) & 3, st3 = (kt + 3) & 3;
+#if EET_DBG_DMA == 1 || EET_DBG_DMA == 3
+        EET_DLOAD(kt + 3, st3);
+#endif
+        EET_DFRAG(1, st, 1);
+        EET_DWAIT(0, FM + FN);                // set 0 (requested one half-step ago) is in; set 1 may be pending
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DMMA(0);
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DWAIT(1, 0);                      // all of this wave's reads of tile kt are done
+#if EET_DBG_DMA != 0
+        wait_vm<kInFlight2>();                // this wave's part of tile kt+1 has landed
+#endif
+        __builtin_amdgcn_s_barrier();         // ... and everybody else's; tile kt-1's stage is free
+        EET_DFRAG(0, st1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DMMA(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (; kt < nk; ++kt) {               // drain: nothing new to issue
+        const int st = kt & 3, st1 = (kt + 1) & 3;
+        EET_DFRAG(1, st, 1);
+        EET_DWAIT(0, FM + FN);
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DMMA(0);
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DWAIT(1, 0);
+        asm volatile("s_waitcnt vmcnt(0)");
+        __builtin_amdgcn_s_barrier();
+        EET_DFRAG(0, st1, 0);                 // past the last tile this reads a stale stage; never used
+        __builtin_amdgcn_sched_barrier(0);
+        EET_DMMA(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    EET_DWAIT(0, 0);
+#undef EET_DLOAD
+#undef EET_DREAD
+#undef EET_DFRAG
+#undef EET_DWAIT
+#undef EET_DMMA
+
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = m0 + wm0 + i * 32 + (lane & 31);
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int n = n0 + wn0 + j * 32 + rg * 8 + (lane >> 5) * 4;
+                if (n < N)
+                    epilogue4<EPI>(a, m, n, acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2],
+                                   acc[i][j][rg * 4 + 3]);
+            }
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Same scheme with 128-byte rows: K steps of 64, two LDS stages
+// --------------------------------------------------------------------------------------------
+// A wave-level load covers 8 rows x 128 bytes, i.e. whole cache lines: the L2 serves one request
+// per channel per clock whatever its size, so 128-byte requests double the fetch bandwidth that
+// 64-byte rows get.  The price is LDS capacity: 64 KB per stage leaves room for two stages, so the
+// loads of step t+1 are issued at the start of step t.  Chunk permutation: (row/2)%8.
+template <int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
+    constexpr int BM = 256, BN = 256, NW = WGM * WGN, BK = 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+    constexpr int LR = 256 / NW;          // rows of each operand tile a wave loads per K step
+    constexpr int LI = LR / 8;            // wave-level load instructions per operand per K step
+    __shared__ __attribute__((aligned(1024))) half_t As[2][BM * BK];
+    __shared__ __attribute__((aligned(1024))) half_t Ws[2][BN * BK];
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    const int M = a.M, N = a.N, K = a.K;
+    const int nk = K / BK;
+
+    const half_t* pa[LI];
+    const half_t* pw[LI];
+#pragma unroll
+    for (int v = 0; v < LI; ++v) {
+        const int row = wave * LR + v * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        int gr = m0 + row;
+        gr = gr < M ? gr : M - 1;
+        pa[v] = a.x + (int64_t)gr * K + c * 8;
+        gr = n0 + row;
+        gr = gr < N ? gr : N - 1;
+        pw[v] = a.w + (int64_t)gr * K + c * 8;
+    }
+    const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 1) & 7;
+    const unsigned a_lds = (unsigned)(uintptr_t)&As[0][(wm0 + frow) * BK];
+    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[0][(wn0 + frow) * BK];
+    unsigned foff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) foff[ks] = (unsigned)(((ks * 2 + fG) ^ fsw) * 16);
+
+    half8v fa[2][FM], fw[2][FN];
+    float16v acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#define EET_DLOAD(T, ST)                                                                                 \
+    do {                                                                                                 \
+        _Pragma("unroll") for (int v = 0; v < LI; ++v) {                                                 \
+            load_lds_16B(pa[v] + (int64_t)(T) * BK, &As[ST][(wave * LR + v * 8) * BK]);                  \
+            load_lds_16B(pw[v] + (int64_t)(T) * BK, &Ws[ST][(wave * LR + v * 8) * BK]);                  \
+        }                                                                                                \
+    } while (0)
+#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
+#define EET_DFRAG(FS, ST, KS)                                                                            \
+    do {                                                                                                 \
+        const unsigned va_ = a_lds + (ST) * (BM * BK * 2) + foff[KS];                                    \
+        const unsigned vw_ = w_lds + (ST) * (BN * BK * 2) + foff[KS];                                    \
+        EET_DREAD(fa[FS][0], va_, 0);                                                                    \
+        if (FM > 1) EET_DREAD(fa[FS][1 % FM], va_, 4096);                                                \
+        if (FM > 2) EET_DREAD(fa[FS][2 % FM], va_, 8192);                                                \
+        if (FM > 3) EET_DREAD(fa[FS][3 % FM], va_, 12288);                                               \
+        EET_DREAD(fw[FS][0], vw_, 0);                                                                    \
+        if (FN > 1) EET_DREAD(fw[FS][1 % FN], vw_, 4096);                                                \
+        if (FN > 2) EET_DREAD(fw[FS][2 % FN], vw_, 8192);                                                \
+        if (FN > 3) EET_DREAD(fw[FS][3 % FN], vw_, 12288);                                               \
+    } while (0)
+#define EET_DWAIT(FS, CNT)                                                                               \
+    do {                                                                                                 \
+        wait_lgkm<CNT>();                                                                                \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[FS][i]));              \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[FS][j]));              \
+    } while (0)
+#define EET_DMMA(FS)                                                                                     \
+    do {                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
+        _Pragma("unroll") for (int i = 0; i < (EET_DBG_DMA == 3 ? 1 : FM); ++i)                          \
+            _Pragma("unroll") for (int j = 0; j < (EET_DBG_DMA == 3 ? 1 : FN); ++j)                      \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[FS][j], fa[FS][i], acc[i][j], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
+    } while (0)
+
+    EET_DLOAD(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)");
+    __syncthreads();
+    EET_DFRAG(0, 0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int st = kt & 1;
+        if (kt + 1 < nk) {
+#if EET_DBG_DMA != 0
+            EET_DLOAD(kt + 1, st ^ 1);        // stage st^1 was released by the barrier of the previous step
+#endif
+        }
+        EET_DFRAG(1, st, 1);
+        EET_DWAIT(0, FM + FN);
+        EET_DMMA(0);
+        EET_DFRAG(0, st, 2);
+        EET_DWAIT(1, FM + FN);
+        EET_DMMA(1);
+        EET_DFRAG(1, st, 3);
+        EET_DWAIT(0, FM + FN);
+        EET_DMMA(0);
+        EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
+        asm volatile("s_waitcnt vmcnt(0)");   // this wave's part of tile kt+1 has landed
+        __builtin_amdgcn_s_barrier();         // ... and everybody else's
+        EET_DFRAG(0, st ^ 1, 0);              // (past the last tile: stale data, never used)
+        EET_DMMA(1);
+    }
+    EET_DWAIT(0, 0);
+#undef EET_DLOAD
+#undef EET_DREAD
+#undef EET_DFRAG
+#undef EET_DWAIT
+#undef EET_DMMA
+
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int m = m0 + wm0 + i * 32 + (lane & 31);
@@ -259,6 +602,30 @@ static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
 }
 
+template <int WGM, int WGN>
+static void launch_dma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
+    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+    switch (epi) {
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
+    }
+}
+
+template <int WGM, int WGN>
+static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
+    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+    switch (epi) {
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
+    }
+}
+
 template <int NF>
 static void launch_skinny_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const dim3 grid((a.N + NF * 16 - 1) / (NF * 16), (a.M + 15) / 16), block(256);
@@ -278,12 +645,14 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
-        static const int tile = getenv("EET_GEMM_TILE") ? atoi(getenv("EET_GEMM_TILE")) : 0;
+        // 256x256 direct-to-LDS tiles once they can fill the chip, 128x128 register-staged tiles below that
+        static const int forced = getenv("EET_GEMM_TILE") ? atoi(getenv("EET_GEMM_TILE")) : -1;
+        const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+        const int tile = forced >= 0 ? forced : (big_tiles >= 192 ? 11 : 0);
         switch (tile) {
-            case 1: launch_mfma_cfg<256, 256, 2, 2>(a, epi, s); break;
             case 2: launch_mfma_cfg<256, 256, 2, 4>(a, epi, s); break;
-            case 3: launch_mfma_cfg<256, 128, 2, 2>(a, epi, s); break;
-            case 4: launch_mfma_cfg<256, 128, 4, 2>(a, epi, s); break;
+            case 8: launch_dma_cfg<2, 4>(a, epi, s); break;
+            case 11: launch_dma64_cfg<2, 4>(a, epi, s); break;
             default: launch_mfma_cfg<128, 128, 2, 2>(a, epi, s); break;
         }
     }

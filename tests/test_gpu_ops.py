@@ -104,6 +104,24 @@ def test_linear(eet, M, K, N):
     gate(host(y), lin + r.astype(np.float64), f"linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
 
 
+@pytest.mark.parametrize("M,K,N", [(3000, 1024, 4160), (4099, 192, 3136), (2049, 4096, 6144)])
+def test_linear_large_tiles(eet, M, K, N):
+    """Shapes that take the 256x256 direct-to-LDS tile kernel, with ragged row and column tails."""
+    x = wl.normal(350, M, (M, K))
+    w = wl.normal(351, N, (N, K), 1.0 / np.sqrt(K))
+    b = wl.normal(352, N, (N,), 0.5)
+    r = wl.normal(353, M, (M, N))
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+    lin = orc.linear(x, w, b)
+    eet.eet_op_linear(dev(x), dev(w), dev(b), y, act=1)
+    torch.cuda.synchronize()
+    gate(host(y), orc.gelu_tanh(lin), f"large linear+gelu {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    y.fill_(float("nan"))
+    eet.eet_op_linear(dev(x), dev(w), dev(b), y, residual=dev(r))
+    torch.cuda.synchronize()
+    gate(host(y), lin + r.astype(np.float64), f"large linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
+
+
 @pytest.mark.parametrize("d,heads,S,cap,lens", [
     (64, 2, 24, 32, [24, 1, 7]),
     (64, 3, 200, 224, [200, 3, 129, 64, 65]),
