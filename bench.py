@@ -145,7 +145,7 @@ def _kernel_candidates(stack, torch, eet, reps):
             eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // nl) % len(ks)], scratch)
         n = nl * len(ks)
         ms = time_launches(torch, run_attn, n * max(1, reps // n))
-        out.append({"kernel": f"attn_decode_partial<{d}> (+combine): decode attention over the K/V cache",
+        out.append({"kernel": f"attn_decode<{d}> (+ range merge when split): decode attention over the K/V cache",
                     "bound": "hbm", "work": sum(bytes_k) / len(bytes_k), "ms": ms,
                     "launches": w.decode_steps * nl})
         # (2) decode projection (weight stream): FFN-1, the largest of the four

@@ -153,7 +153,8 @@ int eet_op_attention_prefill(const void *q, const void *k_cache, const void *v_c
 
 /* Incremental attention: q, ctx [batch, heads*d]; sequence b attends to slots 0..n_keys[b]-1.
  * n_keys is DEVICE int32[batch], each 1..capacity.  scratch: DEVICE, at least
- * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes. */
+ * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes (partial results of the
+ * key ranges; contents on entry do not matter). */
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity);
 int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_cache, void *ctx,
                             const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,

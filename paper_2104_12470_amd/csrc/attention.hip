@@ -206,16 +206,23 @@ hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& len
 // ============================================================================================
 // Decode: one query per (sequence, head), K and V streamed once from HBM
 // ============================================================================================
-// grid = (splits, heads, batch); a workgroup of 4 waves owns one contiguous range of keys and
-// its waves take groups of 16 keys round-robin.  Per group: K fragments go straight from global
-// memory into v_mfma_f32_16x16x32_f16 (the query replicated over the 16 columns), so the q.k
-// reduction costs no cross-lane traffic; every lane of group G = lane/16 then holds the scores
-// of keys 4G..4G+3 and multiplies them into its own 16-byte slice of those keys' V rows.
+// grid = (splits, heads, batch); a workgroup of 4 waves owns one contiguous range of keys, each
+// wave a quarter of it, walked in chunks of 64 keys whose loads are all issued before any of them
+// is used (the work per (sequence, head) is small: memory-level parallelism, not arithmetic, sets
+// the speed).  Per group of 16 keys the K fragments go straight from global memory into
+// v_mfma_f32_16x16x32_f16 (the query replicated over the 16 columns), so the q.k reduction costs
+// no cross-lane traffic; every lane of group G = lane/16 then holds the scores of keys 4G..4G+3
+// and multiplies them into its own 16-byte slice of those keys' V rows.
 // The padding offset is the loop bound: slots >= n_b are never read.
+//
+// With more than one range per (sequence, head) each workgroup writes a partial (max, sum,
+// values) and attn_decode_combine merges them.
 template <int D>
-__global__ __launch_bounds__(256) void attn_decode_partial(AttnDecodeArgs a) {
+__global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
     constexpr int CH = D / 8;            // 16-byte chunks per row (16 or 8)
-    constexpr int VR = CH == 16 ? 4 : 2; // V rows per lane per group
+    constexpr int VR = CH == 16 ? 4 : 2; // V rows per lane per group of 16 keys
+    constexpr int KF = D / 32;           // K fragments per group
+    constexpr int U = 4;                 // groups in flight per wave
     __shared__ float sm_m[4], sm_l[4];
     __shared__ float sm_acc[4][D];
 
@@ -227,71 +234,87 @@ __global__ __launch_bounds__(256) void attn_decode_partial(AttnDecodeArgs a) {
     int per = (n + splits - 1) / splits;
     per = (per + 15) & ~15;
     const int c0 = sp * per;
-    const int c1 = (c0 + per < n) ? c0 + per : n;
+    const int c1 = (c0 + per < n) ? c0 + per : n;        // may be <= c0: empty range of a short sequence
     const int64_t bh = (int64_t)b * a.heads + g;
-    if (c0 >= n) {                                        // empty range (short sequence): neutral partial
-        if (tid < D) a.part_acc[(bh * splits + sp) * D + tid] = 0.f;
-        if (tid == 0) {
-            a.part_ml[(bh * splits + sp) * 2 + 0] = -INFINITY;
-            a.part_ml[(bh * splits + sp) * 2 + 1] = 0.f;
-        }
-        return;
-    }
     const half_t* kbase = a.k_cache + bh * a.capacity * D;
     const half_t* vbase = a.v_cache + bh * a.capacity * D;
 
-    half8v qf[D / 32];
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk)
-        qf[kk] = *reinterpret_cast<const half8v*>(a.q + bh * D + kk * 32 + G * 8);
+    // this wave's quarter of the range
+    int pw = (c1 - c0 + 3) / 4;
+    pw = pw > 0 ? (pw + 15) & ~15 : 0;
+    const int w0 = c0 + wave * pw;
+    const int w1 = (w0 + pw < c1) ? w0 + pw : c1;
 
-    // V slice of this lane: chunk vc of rows 4G + vr0 + r
-    const int vc = fr % CH, vr0 = (CH == 16) ? 0 : (fr / CH) * 2;
+    half8v qf[KF];
+#pragma unroll
+    for (int kk = 0; kk < KF; ++kk) qf[kk] = *reinterpret_cast<const half8v*>(a.q + bh * D + kk * 32 + G * 8);
+
+    const bool hi = (CH == 8) && fr >= 8;                            // d = 64: lanes 8..15 of a group take rows 4G+2, 4G+3
+    const int vc = fr % CH, vr0 = hi ? 2 : 0;                        // V slice of this lane: chunk vc, rows 4G+vr0+r
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     float m = -INFINITY, l = 0.f;
     const float c = rsqrtf((float)D) * kLog2e;
 
-    for (int j0 = c0 + wave * 16; j0 < c1; j0 += 64) {
-        int jk = j0 + fr;
-        jk = jk < c1 ? jk : c1 - 1;
-        half8v kf[D / 32], vf[VR];
+    for (int j0 = w0; j0 < w1; j0 += 16 * U) {
+        half8v kf[U][KF], vf[U][VR];
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk)
-            kf[kk] = *reinterpret_cast<const half8v*>(kbase + (int64_t)jk * D + kk * 32 + G * 8);
+        for (int u = 0; u < U; ++u) {
+            int jk = j0 + 16 * u + fr;
+            jk = jk < w1 ? jk : w1 - 1;                   // rows past the range: clamp, masked below
 #pragma unroll
-        for (int r = 0; r < VR; ++r) {
-            int jv = j0 + 4 * G + vr0 + r;
-            jv = jv < c1 ? jv : c1 - 1;
-            vf[r] = *reinterpret_cast<const half8v*>(vbase + (int64_t)jv * D + vc * 8);
+            for (int kk = 0; kk < KF; ++kk)
+                kf[u][kk] = *reinterpret_cast<const half8v*>(kbase + (int64_t)jk * D + kk * 32 + G * 8);
+#pragma unroll
+            for (int r = 0; r < VR; ++r) {
+                int jv = j0 + 16 * u + 4 * G + vr0 + r;
+                jv = jv < w1 ? jv : w1 - 1;
+                vf[u][r] = *reinterpret_cast<const half8v*>(vbase + (int64_t)jv * D + vc * 8);
+            }
         }
-        float4v s = {0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_sched_barrier(0);                // keep every load of the chunk ahead of its first use
+        float t[U][4], gmax = -INFINITY;
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[kk], qf[kk], s, 0, 0, 0);
-        float t[4], gmax = -INFINITY;
+        for (int u = 0; u < U; ++u) {
+            float4v s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            t[r] = (j0 + 4 * G + r < c1) ? s[r] * c : -INFINITY;
-            gmax = fmaxf(gmax, t[r]);
+            for (int kk = 0; kk < KF; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[u][kk], qf[kk], s, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                t[u][r] = (j0 + 16 * u + 4 * G + r < w1) ? s[r] * c : -INFINITY;
+                gmax = fmaxf(gmax, t[u][r]);
+            }
         }
         gmax = fmaxf(gmax, __shfl_xor(gmax, 16, kWave));
         gmax = fmaxf(gmax, __shfl_xor(gmax, 32, kWave));
         const float m_new = fmaxf(m, gmax);               // finite: key j0 is inside the range
         const float alpha = exp2f(m - m_new);
-        float p[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) p[r] = exp2f(t[r] - m_new);
-        l = l * alpha + (p[0] + p[1] + p[2] + p[3]);
-        m = m_new;
+        l *= alpha;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] *= alpha;
 #pragma unroll
-        for (int r = 0; r < VR; ++r) {
-            const float pr = (CH == 16) ? p[r] : (vr0 == 0 ? p[r] : p[2 + r]);
+        for (int u = 0; u < U; ++u) {
+            float p[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += pr * (float)vf[r][e];
+            for (int r = 0; r < 4; ++r) p[r] = exp2f(t[u][r] - m_new);
+            l += (p[0] + p[1]) + (p[2] + p[3]);
+            // weights of this lane's V rows: rows 4G..4G+3 (d = 128) or the row pair picked by hi (d = 64)
+            float pv[VR];
+            if (CH == 16) {
+#pragma unroll
+                for (int r = 0; r < VR; ++r) pv[r] = p[r];
+            } else {
+                pv[0] = hi ? p[2] : p[0];
+                pv[1 % VR] = hi ? p[3] : p[1];
+            }
+#pragma unroll
+            for (int r = 0; r < VR; ++r) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += pv[r] * (float)vf[u][r][e];
+            }
         }
+        m = m_new;
     }
     // fold the lane groups: keys were spread over G (and over the two row pairs when d = 64)
     l += __shfl_xor(l, 16, kWave);
@@ -311,52 +334,74 @@ __global__ __launch_bounds__(256) void attn_decode_partial(AttnDecodeArgs a) {
         sm_l[wave] = l;
     }
     __syncthreads();
-    if (tid < D) {
-        float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));   // wave 0 always has keys
-        float Lsum = 0.f, A = 0.f;
+    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));   // -inf only for an empty range
+    float Lsum = 0.f, A = 0.f;
+    if (tid < D && M > -INFINITY) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const float sc = exp2f(sm_m[w] - M);                               // idle wave: exp2(-inf) = 0
             Lsum += sm_l[w] * sc;
             A += sm_acc[w][tid] * sc;
         }
-        if (splits == 1) {
-            a.ctx[bh * D + tid] = (half_t)(A / Lsum);
-        } else {
-            a.part_acc[(bh * splits + sp) * D + tid] = A;
-            if (tid == 0) {
-                a.part_ml[(bh * splits + sp) * 2 + 0] = M;
-                a.part_ml[(bh * splits + sp) * 2 + 1] = Lsum;
-            }
-        }
+    }
+    if (splits == 1) {
+        if (tid < D) a.ctx[bh * D + tid] = (half_t)(A / Lsum);
+        return;
+    }
+    if (tid < D) a.part_acc[(bh * splits + sp) * D + tid] = A;
+    if (tid == 0) {
+        a.part_ml[(bh * splits + sp) * 2 + 0] = M;
+        a.part_ml[(bh * splits + sp) * 2 + 1] = Lsum;
     }
 }
 
-// Merge the per-range partials (max, sum, weighted values) of one (sequence, head).
-__global__ __launch_bounds__(128) void attn_decode_combine(AttnDecodeArgs a) {
-    const int64_t bh = blockIdx.x;
-    const int D = a.d, splits = a.splits, tid = threadIdx.x;
-    if (tid >= D) return;
+// Merge the per-range partials (max, sum, weighted values) of the (sequence, head) pairs, in
+// range order.  A separate launch: a device-scope release/acquire inside the attention kernel
+// (last workgroup merges) costs an L2 write-back and invalidate on this multi-die part, far more
+// than the launch it would save.  Workgroup = 256 threads = 256/d pairs; all loads of a pair's
+// ranges are issued before they are combined.
+template <int D>
+__global__ __launch_bounds__(256) void attn_decode_combine(AttnDecodeArgs a) {
+    constexpr int PPB = 256 / D;                         // pairs per workgroup
+    constexpr int MAXS = 16;                             // ranges held in registers at a time
+    const int tid = threadIdx.x, dd = tid % D;
+    const int64_t bh = (int64_t)blockIdx.x * PPB + tid / D;
+    if (bh >= (int64_t)a.batch * a.heads) return;
+    const int splits = a.splits;
     const float* ml = a.part_ml + bh * splits * 2;
+    const float* pa = a.part_acc + bh * splits * D + dd;
     float M = -INFINITY;
     for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[s * 2]);     // range 0 is never empty
     float Lsum = 0.f, A = 0.f;
-    for (int s = 0; s < splits; ++s) {
-        const float sc = exp2f(ml[s * 2] - M);
-        Lsum += ml[s * 2 + 1] * sc;
-        A += a.part_acc[(bh * splits + s) * D + tid] * sc;
+    for (int s0 = 0; s0 < splits; s0 += MAXS) {
+        float mv[MAXS], lv[MAXS], av[MAXS];
+#pragma unroll
+        for (int u = 0; u < MAXS; ++u) {
+            const int s = s0 + u < splits ? s0 + u : splits - 1;
+            mv[u] = ml[s * 2];
+            lv[u] = ml[s * 2 + 1];
+            av[u] = pa[s * D];
+        }
+#pragma unroll
+        for (int u = 0; u < MAXS; ++u) {
+            const float sc = s0 + u < splits ? exp2f(mv[u] - M) : 0.f;
+            Lsum += lv[u] * sc;
+            A += av[u] * sc;
+        }
     }
-    a.ctx[bh * D + tid] = (half_t)(A / Lsum);
+    a.ctx[bh * D + dd] = (half_t)(A / Lsum);
 }
 
 int attention_decode_splits(int batch, int heads, int capacity) {
-    // aim for ~1024 workgroups on 256 CUs, but keep at least 256 keys per range at full capacity
-    int by_fill = 1024 / (batch * heads);
-    int by_len = capacity / 256;
-    int s = by_fill < by_len ? by_fill : by_len;
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    return s;
+    // One key range per (sequence, head) once there are 128 pairs (measured: as fast as splitting,
+    // and no merge launch).  Below that, about 256 workgroups, a power of two, and no range shorter
+    // than 128 keys at full capacity.
+    const int pairs = batch * heads;
+    if (pairs >= 128) return 1;
+    int s = 1;
+    while (s * pairs < 256) s *= 2;
+    while (s > 1 && capacity / s < 128) s /= 2;
+    return s > 64 ? 64 : s;
 }
 
 size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits) {
@@ -366,10 +411,13 @@ size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits) {
 
 hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s) {
     const dim3 grid(a.splits, a.heads, a.batch), block(256);
-    if (a.d == 128) hipLaunchKernelGGL(attn_decode_partial<128>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(attn_decode_partial<64>, grid, block, 0, s, a);
-    if (a.splits > 1)
-        hipLaunchKernelGGL(attn_decode_combine, dim3(a.batch * a.heads), dim3(128), 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL(attn_decode<128>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(attn_decode<64>, grid, block, 0, s, a);
+    if (a.splits > 1) {
+        const int pairs = a.batch * a.heads;
+        if (a.d == 128) hipLaunchKernelGGL(attn_decode_combine<128>, dim3((pairs + 1) / 2), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(attn_decode_combine<64>, dim3((pairs + 3) / 4), dim3(256), 0, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -244,13 +244,22 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     half_t* kc = static_cast<half_t*>(kv_cache);
     half_t* vc = kc + (size_t)c.max_batch * H * c.max_seq;
 
-    EET_LAUNCH(launch_layernorm(x, nullptr, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, B, H, c.ln_eps,
-                                nullptr, 0, s), "layernorm 1");
+    // Small layers are launch-bound in decode: there the two LayerNorms run inside the projections
+    // that consume them (each workgroup recomputes the row statistics of the <= 16 token rows).
+    // Large layers are weight-streaming-bound and keep the separate row kernel.
+    const bool fuse_ln = B <= 16 && (size_t)F * H * sizeof(half_t) <= ((size_t)40 << 20);
+    const half_t* qkv_in = x;
+    if (!fuse_ln) {
+        EET_LAUNCH(launch_layernorm(x, nullptr, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, B, H,
+                                    c.ln_eps, nullptr, 0, s), "layernorm 1");
+        qkv_in = bufA;
+    }
     GemmArgs g{};
-    g.x = bufA; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
+    g.x = qkv_in; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
     g.M = B; g.N = 3 * H; g.K = H;
     g.k_cache = kc; g.v_cache = vc; g.tok_row_map = nullptr; g.lens = d_lens;   // new token -> slot n_b
     g.S = 1; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
+    if (fuse_ln) { g.ln_gamma = (const half_t*)L->w.ln1_g; g.ln_beta = (const half_t*)L->w.ln1_b; g.ln_eps = c.ln_eps; }
     EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
     AttnDecodeArgs at{};
     at.q = bufB; at.ctx = bufA; at.k_cache = kc; at.v_cache = vc; at.lens = d_lens; at.len_bias = 1;
@@ -259,16 +268,24 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     at.part_acc = reinterpret_cast<float*>(L->ws + L->lay.part);
     at.part_ml = at.part_acc + (size_t)B * c.heads * at.splits * L->d;
     EET_LAUNCH(launch_attention_decode(at, s), "decode attention");
+    // output projection + bias + residual; its first workgroup also advances n_b: every reader of
+    // n_b in this step (cache append, attention) is already ordered before it on the stream
     GemmArgs o{};
     o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
     o.M = B; o.N = H; o.K = H; o.res = x;
+    const bool bump_in_gemm = B <= 16;
+    if (bump_in_gemm) { o.bump_lens = d_lens; o.bump_count = B; }
     EET_LAUNCH(launch_gemm(o, EPI_BIAS_RES, s), "output projection");
-    // LN2; its row blocks also advance n_b: every reader of n_b in this step is already enqueued
-    EET_LAUNCH(launch_layernorm(bufY, nullptr, (const half_t*)L->w.ln2_g, (const half_t*)L->w.ln2_b, bufB, B, H,
-                                c.ln_eps, d_lens, B, s), "layernorm 2");
+    const half_t* fc1_in = bufY;
+    if (!fuse_ln || !bump_in_gemm) {
+        EET_LAUNCH(launch_layernorm(bufY, nullptr, (const half_t*)L->w.ln2_g, (const half_t*)L->w.ln2_b, bufB, B, H,
+                                    c.ln_eps, bump_in_gemm ? nullptr : d_lens, B, s), "layernorm 2");
+        fc1_in = bufB;
+    }
     GemmArgs f1{};
-    f1.x = bufB; f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
+    f1.x = fc1_in; f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
     f1.M = B; f1.N = F; f1.K = H;
+    if (fc1_in == bufY) { f1.ln_gamma = (const half_t*)L->w.ln2_g; f1.ln_beta = (const half_t*)L->w.ln2_b; f1.ln_eps = c.ln_eps; }
     EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
     GemmArgs f2{};
     f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);

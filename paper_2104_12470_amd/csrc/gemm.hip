@@ -524,15 +524,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 // --------------------------------------------------------------------------------------------
 // Workgroup = 4 waves; it owns 16*NF output columns.  K steps of 32 are dealt round-robin to
 // the waves (adjacent waves read adjacent 64-byte pieces of the same weight rows).
-template <int NF, int EPI>
+// LN = true fuses the LayerNorm that precedes the projection (decode: LN1 -> QKV, LN2 -> FFN-1):
+// every workgroup first computes mean and 1/std of its <= 16 activation rows (two passes over
+// rows that stay in L1/L2), then normalises the activation fragments on their way into the MFMA,
+// so the normalised activations never exist in memory and one launch per projection is saved.
+// BUMP: the workgroup with blockIdx 0 also advances the per-sequence cache lengths (n_b += 1).
+template <int NF, int EPI, bool LN>
 __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     constexpr int UN = 4;                       // K steps in flight per wave
     __shared__ float red[4][NF * 16][17];
+    __shared__ float ln_mean[16], ln_rstd[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, G = lane >> 4;
     const int n0 = blockIdx.x * (NF * 16), mc = blockIdx.y * 16;
     const int M = a.M, N = a.N, K = a.K;
     const int nsteps = K / 32;
+
+    if (a.bump_lens != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
 
     int xr = mc + fr;
     xr = xr < M ? xr : M - 1;
@@ -544,30 +552,75 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         wr = wr < N ? wr : N - 1;
         wp[f] = a.w + (int64_t)wr * K + G * 8;
     }
+    float mean = 0.f, rstd = 1.f;
+    if (LN) {
+        // 16 threads per row: thread (row = tid/16, sub = tid%16) walks the row in 16-byte vectors
+        const int row = tid >> 4, sub = tid & 15;
+        int rr = mc + row;
+        rr = rr < M ? rr : M - 1;
+        const half_t* rp = a.x + (int64_t)rr * K;
+        float sum = 0.f;
+        for (int cidx = sub * 8; cidx < K; cidx += 128) {
+            const half8v v = *reinterpret_cast<const half8v*>(rp + cidx);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += (float)v[e];
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+        const float mu = sum / (float)K;
+        float sq = 0.f;
+        for (int cidx = sub * 8; cidx < K; cidx += 128) {
+            const half8v v = *reinterpret_cast<const half8v*>(rp + cidx);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dlt = (float)v[e] - mu;
+                sq += dlt * dlt;
+            }
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
+        if (sub == 0) {
+            ln_mean[row] = mu;
+            ln_rstd[row] = rsqrtf(sq / (float)K + a.ln_eps);
+        }
+        __syncthreads();
+        mean = ln_mean[fr];
+        rstd = ln_rstd[fr];
+    }
     float4v acc[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) acc[f] = float4v{0.f, 0.f, 0.f, 0.f};
 
     for (int s0 = wave; s0 < nsteps; s0 += 4 * UN) {
-        half8v xf[UN], wf[UN][NF];
+        half8v xf[UN], wf[UN][NF], gf[UN], bf[UN];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int step = s0 + 4 * u;
             const bool ok = step < nsteps;
             const int k = (ok ? step : s0) * 32;
             xf[u] = *reinterpret_cast<const half8v*>(xp + k);
-            if (!ok) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xf[u][e] = (half_t)0.f;
+            if (LN) {
+                gf[u] = *reinterpret_cast<const half8v*>(a.ln_gamma + k + G * 8);
+                bf[u] = *reinterpret_cast<const half8v*>(a.ln_beta + k + G * 8);
             }
 #pragma unroll
             for (int f = 0; f < NF; ++f) wf[u][f] = *reinterpret_cast<const half8v*>(wp[f] + k);
         }
 #pragma unroll
-        for (int u = 0; u < UN; ++u)
+        for (int u = 0; u < UN; ++u) {
+            if (LN) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    xf[u][e] = (half_t)(((float)xf[u][e] - mean) * rstd * (float)gf[u][e] + (float)bf[u][e]);
+            }
+            if (s0 + 4 * u >= nsteps) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xf[u][e] = (half_t)0.f;
+            }
 #pragma unroll
             for (int f = 0; f < NF; ++f)
                 acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u][f], xf[u], acc[f], 0, 0, 0);
+        }
     }
     // acc[f][r]: output column n0 + f*16 + 4G + r, row mc + lane%16
 #pragma unroll
@@ -626,15 +679,20 @@ static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
 }
 
-template <int NF>
-static void launch_skinny_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+template <int NF, bool LN>
+static void launch_skinny_ln(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const dim3 grid((a.N + NF * 16 - 1) / (NF * 16), (a.M + 15) / 16), block(256);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS>), grid, block, 0, s, a); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_GELU>), grid, block, 0, s, a); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_RES>), grid, block, 0, s, a); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_skinny<NF, EPI_QKV>), grid, block, 0, s, a); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_GELU, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_RES, LN>), grid, block, 0, s, a); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_skinny<NF, EPI_QKV, LN>), grid, block, 0, s, a); break;
     }
+}
+template <int NF>
+static void launch_skinny_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    if (a.ln_gamma != nullptr) launch_skinny_ln<NF, true>(a, epi, s);
+    else launch_skinny_ln<NF, false>(a, epi, s);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {

@@ -45,6 +45,13 @@ struct GemmArgs {
     const int32_t* tok_row_map;   // prefill: packed row -> b*S + pos ; nullptr in decode
     const int32_t* lens;          // decode: device cache lengths
     int S, hidden, heads, d, max_seq;
+    // weight-streaming kernel only (M <= 16): LayerNorm of x fused in front (nullptr = x is used as it is),
+    // and n_b += 1 for the first bump_count sequences (nullptr = no)
+    const half_t* ln_gamma;
+    const half_t* ln_beta;
+    float ln_eps;
+    int32_t* bump_lens;
+    int bump_count;
 };
 
 // M > 16: MFMA tile kernel.  M <= 16 (decode): weight-streaming kernel.
