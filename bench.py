@@ -31,6 +31,7 @@ def parse():
     p.add_argument("--warmup", type=int, default=1)
     p.add_argument("--workload", default="cfg2")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-graph", action="store_true", help="launch decode kernels directly instead of replaying a graph")
     p.add_argument("--kernel-reps", type=int, default=200, help="launches per kernel in the roofline measurement")
     p.add_argument("--roofline-only", action="store_true",
                    help="skip the timed pass and the CPU baseline: only the per-kernel measurement plus one plain "
@@ -39,47 +40,52 @@ def parse():
 
 
 class Stack:
-    """The layers of a workload with their caches, plus ping-pong activation buffers."""
+    """The workload's layers behind the stack entry points (one call per prefill, one per decode
+    step; decode steps are replayed from a HIP graph recorded by the library), on its own stream."""
 
-    def __init__(self, w, eet, torch, wl):
+    def __init__(self, w, eet, torch, wl, use_graph=True):
         self.w, self.eet, self.torch = w, eet, torch
         cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
-        self.layers = []
+        weights = []
         for li in range(w.layers):
             W = wl.layer_weights(w, li)
-            self.layers.append(eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in W.items()}))
+            weights.append({k: torch.from_numpy(v) for k, v in W.items()})
+        self.stack = eet.DecoderStack(cfg, weights, use_graph=use_graph)
+        self.n_layers = w.layers
         self.lens = [int(v) for v in wl.lengths(w)]
         dev = "cuda:0"
         self.x0 = torch.from_numpy(wl.prompt_embeddings(w)).to(dev)
         self.dec_in = torch.stack([torch.from_numpy(wl.decode_embeddings(w, k)) for k in range(w.decode_steps)]).to(dev) \
             if w.decode_steps else None
-        self.pbuf = [torch.empty_like(self.x0) for _ in range(2)]
-        self.dbuf = [torch.empty((w.batch, w.hidden), dtype=torch.float16, device=dev) for _ in range(2)]
+        self.pout = torch.empty_like(self.x0)
+        self.tok = torch.empty((w.batch, w.hidden), dtype=torch.float16, device=dev)   # fixed decode input buffer
+        self.dout = torch.empty_like(self.tok)
+        self.stream = torch.cuda.Stream()      # the null stream cannot be captured into a graph
+
+    def weights(self, layer):
+        return self.stack.weights[layer]
+
+    def cache_views(self, layer):
+        return self.stack.cache_views(layer)
 
     def prefill(self):
-        h = self.x0
-        for li, layer in enumerate(self.layers):
-            layer.prefill(h, self.lens, self.pbuf[li & 1])
-            h = self.pbuf[li & 1]
-        return h
+        with self.torch.cuda.stream(self.stream):
+            self.stack.prefill(self.x0, self.lens, self.pout)
 
     def decode(self):
-        h = None
-        for k in range(self.w.decode_steps):
-            h = self.dec_in[k]
-            for li, layer in enumerate(self.layers):
-                layer.decode_step(h, self.dbuf[li & 1])
-                h = self.dbuf[li & 1]
-        return h
+        with self.torch.cuda.stream(self.stream):
+            for k in range(self.w.decode_steps):
+                self.tok.copy_(self.dec_in[k])          # this step's input embeddings
+                self.stack.decode_step(self.tok, self.dout)
 
     def one_pass(self):
         self.prefill()
         self.decode()
 
 
-def time_region(torch, fn, reps):
+def time_region(torch, fn, reps, stream=None):
     """Average duration of fn() in ms, HIP events on the stream the kernels are launched on."""
-    s = torch.cuda.current_stream()
+    s = stream if stream is not None else torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(s)
     for _ in range(reps):
@@ -123,7 +129,7 @@ def _kernel_candidates(stack, torch, eet, reps):
     cache the real pass would not have.  Returns a list of records with the algorithmic bytes or
     flops of one launch, the average launch duration and the launches per pass."""
     w = stack.w
-    B, H, F, nl = w.batch, w.hidden, w.ffn, len(stack.layers)
+    B, H, F, nl = w.batch, w.hidden, w.ffn, stack.n_layers
     d = H // w.heads
     T = sum(stack.lens)
     out = []
@@ -141,7 +147,7 @@ def _kernel_candidates(stack, torch, eet, reps):
         def run_attn():
             i = st["i"]
             st["i"] += 1
-            kc, vc = stack.layers[i % nl].cache_views()
+            kc, vc = stack.cache_views(i % nl)
             eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // nl) % len(ks)], scratch)
         n = nl * len(ks)
         ms = time_launches(torch, run_attn, n * max(1, reps // n))
@@ -154,9 +160,9 @@ def _kernel_candidates(stack, torch, eet, reps):
         st2 = {"i": 0}
 
         def run_ffn1():
-            layer = stack.layers[st2["i"] % nl]
+            wts = stack.weights(st2["i"] % nl)
             st2["i"] += 1
-            eet.eet_op_linear(x, layer.weights["w_fc1"], layer.weights["b_fc1"], y, act=1)
+            eet.eet_op_linear(x, wts["w_fc1"], wts["b_fc1"], y, act=1)
         ms = time_launches(torch, run_ffn1, nl * max(1, reps // nl))
         out.append({"kernel": "gemm_skinny: FFN-1 projection + bias + GELU, decode (weight stream)", "bound": "hbm",
                     "work": 2.0 * (F * H + B * H + F + B * F), "ms": ms,
@@ -167,9 +173,9 @@ def _kernel_candidates(stack, torch, eet, reps):
     st3 = {"i": 0}
 
     def run_pre():
-        layer = stack.layers[st3["i"] % nl]
+        wts = stack.weights(st3["i"] % nl)
         st3["i"] += 1
-        eet.eet_op_linear(xp, layer.weights["w_fc1"], layer.weights["b_fc1"], yp, act=1)
+        eet.eet_op_linear(xp, wts["w_fc1"], wts["b_fc1"], yp, act=1)
     ms = time_launches(torch, run_pre, max(4, min(reps, 24)), replays=2)
     out.append({"kernel": "gemm_mfma: FFN-1 projection + bias + GELU, prefill (matrix cores)", "bound": "mfma",
                 "work": 2.0 * T * H * F, "ms": ms, "launches": nl * (12 * H * H) / (H * F)})
@@ -249,7 +255,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = wl.WORKLOADS[a.workload]
-    stack = Stack(w, eet, torch, wl)
+    stack = Stack(w, eet, torch, wl, use_graph=not a.no_graph)
     tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
 
     if a.roofline_only:
@@ -273,8 +279,8 @@ def main():
     ms_per_step = dt / a.steps * 1e3
 
     # phase split (informative): prefill alone and decode alone, HIP events
-    ms_prefill = time_region(torch, stack.prefill, 2)
-    ms_decode = time_region(torch, stack.decode, 1) if w.decode_steps else 0.0
+    ms_prefill = time_region(torch, stack.prefill, 2, stack.stream)
+    ms_decode = time_region(torch, stack.decode, 1, stack.stream) if w.decode_steps else 0.0
 
     rec = {
         "metric": "decoder-layer tokens/s (prefill+decode) fp16; % of HBM/MFMA roofline",

@@ -114,6 +114,35 @@ int eet_layer_destroy(eet_layer_t *layer);
 const char *eet_last_error(void);
 
 /* ---------------------------------------------------------------------------------------------
+ * A stack of identical-shape layers driven by one call per phase (the paper's model-level API,
+ * Section 5).  The layers share one scratch workspace and two ping-pong activation buffers of
+ * max_batch*max_prompt*hidden elements each -- the activation caches of Section 3.1, reused
+ * across layers -- and one set of device-side cache lengths.  The K/V cache is
+ * 2*b*h*s*l elements (Section 3.1): layer l uses bytes [l, l+1) * eet_kv_cache_bytes(cfg).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct eet_stack eet_stack_t;
+
+size_t eet_stack_kv_cache_bytes(const eet_layer_config *cfg, int32_t n_layers);
+size_t eet_stack_workspace_bytes(const eet_layer_config *cfg, int32_t n_layers);
+
+/* weights: HOST array of n_layers structs of DEVICE pointers (borrowed).  workspace: DEVICE,
+ * eet_stack_workspace_bytes, 256-byte aligned.  use_graph != 0: eet_stack_decode_step records its
+ * launches into a HIP graph the first time it sees a (tokens, out, kv_cache) triple and replays
+ * it afterwards (the graph is instantiated inside that call; it is skipped on the null stream
+ * and while the caller is capturing the stream itself).  Errors as eet_layer_create. */
+int eet_stack_create(const eet_layer_config *cfg, int32_t n_layers, const eet_layer_weights *weights,
+                     void *workspace, int32_t use_graph, eet_stack_t **out_stack);
+
+/* As eet_prefill / eet_decode_step / eet_cache_lens, through all layers: the output of layer l is
+ * the input of layer l+1; `out` receives the last layer's output. */
+int eet_stack_prefill(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                      const void *tokens, void *out, void *kv_cache, void *hip_stream);
+int eet_stack_decode_step(eet_stack_t *stack, const void *tokens, void *out, void *kv_cache,
+                          void *hip_stream);
+int eet_stack_cache_lens(eet_stack_t *stack, int32_t *out_host, void *hip_stream);
+int eet_stack_destroy(eet_stack_t *stack);
+
+/* ---------------------------------------------------------------------------------------------
  * Operator-level entry points: the individual kernels of the layer, for parity tests and
  * profiling (the paper exposes an operator-level API as well, Section 5).
  * ------------------------------------------------------------------------------------------- */

@@ -147,27 +147,9 @@ int eet_layer_destroy(eet_layer_t* layer) {
         if (e_ != hipSuccess) return hip_fail(e_, what); \
     } while (0)
 
-int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
-                void* out, void* kv_cache, void* hip_stream) {
-    if (!L || !q_lens || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_prefill: null argument");
-    if (batch < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "eet_prefill: batch and padded_len must be >= 1");
-    if (batch > L->cfg.max_batch) return fail(EET_ERR_CAPACITY, "eet_prefill: batch %d > max_batch %d", batch, L->cfg.max_batch);
-    if (padded_len > L->cfg.max_prompt)
-        return fail(EET_ERR_CAPACITY, "eet_prefill: padded_len %d > max_prompt %d", padded_len, L->cfg.max_prompt);
-    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
-        return fail(EET_ERR_INVALID_ARG, "eet_prefill: tokens/out/kv_cache must be 16-byte aligned");
-    SeqLens lens;
-    std::memset(&lens, 0, sizeof(lens));
-    int64_t T = 0;
-    int max_len = 0;
-    for (int b = 0; b < batch; ++b) {
-        if (q_lens[b] < 1 || q_lens[b] > padded_len)
-            return fail(EET_ERR_INVALID_ARG, "eet_prefill: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
-        lens.len[b] = q_lens[b];
-        T += q_lens[b];
-        max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
-    }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+// Enqueue the kernels of one layer's prefill (arguments already validated).
+static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int padded_len, int64_t T, int max_len,
+                           const void* tokens, void* out, void* kv_cache, hipStream_t s) {
     const eet_layer_config& c = L->cfg;
     const int H = c.hidden, F = c.ffn;
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
@@ -219,22 +201,54 @@ int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t pa
     f2.M = (int)T; f2.N = H; f2.K = F; f2.res = bufY; f2.res_row_map = nullptr; f2.out_row_map = d_map;
     EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
 
+    return EET_OK;
+}
+
+// Shared argument checks of a prefill; fills the by-value length table.
+static int check_prefill(const char* who, const eet_layer_config& cfg, const int32_t* q_lens, int32_t batch,
+                         int32_t padded_len, const void* tokens, const void* out, const void* kv_cache, SeqLens& lens,
+                         int64_t& T, int& max_len) {
+    if (!q_lens || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "%s: batch and padded_len must be >= 1", who);
+    if (batch > cfg.max_batch) return fail(EET_ERR_CAPACITY, "%s: batch %d > max_batch %d", who, batch, cfg.max_batch);
+    if (padded_len > cfg.max_prompt)
+        return fail(EET_ERR_CAPACITY, "%s: padded_len %d > max_prompt %d", who, padded_len, cfg.max_prompt);
+    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(EET_ERR_INVALID_ARG, "%s: tokens/out/kv_cache must be 16-byte aligned", who);
+    std::memset(&lens, 0, sizeof(lens));
+    T = 0;
+    max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "%s: q_lens[%d] = %d outside [1, %d]", who, b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+        T += q_lens[b];
+        max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
+    }
+    return EET_OK;
+}
+
+int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                void* out, void* kv_cache, void* hip_stream) {
+    if (!L) return fail(EET_ERR_INVALID_ARG, "eet_prefill: null argument");
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_prefill", L->cfg, q_lens, batch, padded_len, tokens, out, kv_cache, lens, T, max_len))
+        return rc;
+    const int rc = enqueue_prefill(L, lens, batch, padded_len, T, max_len, tokens, out, kv_cache,
+                                   static_cast<hipStream_t>(hip_stream));
+    if (rc != EET_OK) return rc;
     L->batch = batch;
     for (int b = 0; b < batch; ++b) L->host_lens[b] = q_lens[b];
     return EET_OK;
 }
 
-int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
-    if (!L || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_decode_step: null argument");
-    if (L->batch == 0) return fail(EET_ERR_STATE, "eet_decode_step: no prefill has been run on this layer");
-    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
-        return fail(EET_ERR_INVALID_ARG, "eet_decode_step: tokens/out/kv_cache must be 16-byte aligned");
+// Enqueue the kernels of one layer's decode step (arguments already validated).  `bump`: this
+// layer advances the device-side cache lengths (in a stack only the last layer does).
+static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_cache, hipStream_t s, bool bump) {
     const eet_layer_config& c = L->cfg;
     const int B = L->batch, H = c.hidden, F = c.ffn;
-    for (int b = 0; b < B; ++b)
-        if (L->host_lens[b] + 1 > c.max_seq)
-            return fail(EET_ERR_CAPACITY, "eet_decode_step: sequence %d is at the cache capacity %d", b, c.max_seq);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
     half_t* bufA = reinterpret_cast<half_t*>(L->ws + L->lay.buf_a);
     half_t* bufB = reinterpret_cast<half_t*>(L->ws + L->lay.buf_b);
@@ -246,8 +260,8 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
 
     // Small layers are launch-bound in decode: there the two LayerNorms run inside the projections
     // that consume them (each workgroup recomputes the row statistics of the <= 16 token rows).
-    // Large layers are weight-streaming-bound and keep the separate row kernel.
-    const bool fuse_ln = B <= 16 && (size_t)F * H * sizeof(half_t) <= ((size_t)40 << 20);
+    // Measured break-even is near 16 MB of FFN-1 weights; larger layers keep the separate row kernel.
+    const bool fuse_ln = B <= 16 && (size_t)F * H * sizeof(half_t) <= ((size_t)16 << 20);
     const half_t* qkv_in = x;
     if (!fuse_ln) {
         EET_LAUNCH(launch_layernorm(x, nullptr, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, B, H,
@@ -274,12 +288,12 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
     o.M = B; o.N = H; o.K = H; o.res = x;
     const bool bump_in_gemm = B <= 16;
-    if (bump_in_gemm) { o.bump_lens = d_lens; o.bump_count = B; }
+    if (bump && bump_in_gemm) { o.bump_lens = d_lens; o.bump_count = B; }
     EET_LAUNCH(launch_gemm(o, EPI_BIAS_RES, s), "output projection");
     const half_t* fc1_in = bufY;
     if (!fuse_ln || !bump_in_gemm) {
         EET_LAUNCH(launch_layernorm(bufY, nullptr, (const half_t*)L->w.ln2_g, (const half_t*)L->w.ln2_b, bufB, B, H,
-                                    c.ln_eps, bump_in_gemm ? nullptr : d_lens, B, s), "layernorm 2");
+                                    c.ln_eps, (bump && !bump_in_gemm) ? d_lens : nullptr, B, s), "layernorm 2");
         fc1_in = bufB;
     }
     GemmArgs f1{};
@@ -291,6 +305,21 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
     f2.M = B; f2.N = H; f2.K = F; f2.res = bufY;
     EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
+    return EET_OK;
+}
+
+int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
+    if (!L || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_decode_step: null argument");
+    if (L->batch == 0) return fail(EET_ERR_STATE, "eet_decode_step: no prefill has been run on this layer");
+    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(EET_ERR_INVALID_ARG, "eet_decode_step: tokens/out/kv_cache must be 16-byte aligned");
+    const eet_layer_config& c = L->cfg;
+    const int B = L->batch;
+    for (int b = 0; b < B; ++b)
+        if (L->host_lens[b] + 1 > c.max_seq)
+            return fail(EET_ERR_CAPACITY, "eet_decode_step: sequence %d is at the cache capacity %d", b, c.max_seq);
+    const int rc = enqueue_decode(L, tokens, out, kv_cache, static_cast<hipStream_t>(hip_stream), true);
+    if (rc != EET_OK) return rc;
     for (int b = 0; b < B; ++b) L->host_lens[b] += 1;
     return EET_OK;
 }
@@ -303,6 +332,176 @@ int eet_cache_lens(eet_layer_t* L, int32_t* out_host, void* hip_stream) {
                "copy of cache lengths");
     EET_LAUNCH(hipStreamSynchronize(s), "stream synchronise");
     return EET_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// a stack of layers
+// ------------------------------------------------------------------------------------------------
+struct eet_stack {
+    eet_layer_config cfg;
+    int n_layers;
+    eet_layer** layers;                // every layer borrows the same scratch: they run one after another
+    char* ws;
+    size_t act[2];                     // byte offsets of the two inter-layer activation buffers
+    size_t layer_cache_bytes;
+    int batch;
+    int32_t host_lens[EET_MAX_BATCH];
+    int use_graph;
+    hipGraphExec_t exec;               // captured decode step, valid for (g_tokens, g_out, g_kv, g_batch)
+    const void* g_tokens;
+    void* g_out;
+    void* g_kv;
+    int g_batch;
+};
+
+static size_t stack_act_bytes(const eet_layer_config* c) {
+    return align_up((size_t)2 * c->max_batch * c->max_prompt * c->hidden, 256);
+}
+
+size_t eet_stack_kv_cache_bytes(const eet_layer_config* cfg, int32_t n_layers) {
+    if (n_layers < 1) return 0;
+    return eet_kv_cache_bytes(cfg) * (size_t)n_layers;
+}
+
+size_t eet_stack_workspace_bytes(const eet_layer_config* cfg, int32_t n_layers) {
+    if (n_layers < 1 || config_problem(cfg) || shape_problem(cfg)) return 0;
+    return layout_of(cfg).total + 2 * stack_act_bytes(cfg);
+}
+
+int eet_stack_destroy(eet_stack_t* st) {
+    if (!st) return EET_OK;
+    if (st->exec) (void)hipGraphExecDestroy(st->exec);
+    if (st->layers) {
+        for (int l = 0; l < st->n_layers; ++l) delete st->layers[l];
+        delete[] st->layers;
+    }
+    delete st;
+    return EET_OK;
+}
+
+int eet_stack_create(const eet_layer_config* cfg, int32_t n_layers, const eet_layer_weights* weights, void* workspace,
+                     int32_t use_graph, eet_stack_t** out_stack) {
+    if (!out_stack) return fail(EET_ERR_INVALID_ARG, "eet_stack_create: out_stack is null");
+    *out_stack = nullptr;
+    if (n_layers < 1) return fail(EET_ERR_INVALID_ARG, "eet_stack_create: n_layers must be >= 1");
+    if (!weights) return fail(EET_ERR_INVALID_ARG, "eet_stack_create: weights is null");
+    eet_stack* st = new (std::nothrow) eet_stack();
+    if (!st) return fail(EET_ERR_INVALID_ARG, "eet_stack_create: out of host memory");
+    st->layers = new (std::nothrow) eet_layer*[n_layers]();
+    st->n_layers = n_layers;
+    if (!st->layers) {
+        eet_stack_destroy(st);
+        return fail(EET_ERR_INVALID_ARG, "eet_stack_create: out of host memory");
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const int rc = eet_layer_create(cfg, &weights[l], workspace, &st->layers[l]);
+        if (rc != EET_OK) {
+            eet_stack_destroy(st);
+            return rc;
+        }
+    }
+    st->cfg = *cfg;
+    st->ws = static_cast<char*>(workspace);
+    st->act[0] = layout_of(cfg).total;
+    st->act[1] = st->act[0] + stack_act_bytes(cfg);
+    st->layer_cache_bytes = eet_kv_cache_bytes(cfg);
+    st->batch = 0;
+    st->use_graph = use_graph != 0;
+    st->exec = nullptr;
+    *out_stack = st;
+    return EET_OK;
+}
+
+int eet_stack_prefill(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                      void* out, void* kv_cache, void* hip_stream) {
+    if (!st) return fail(EET_ERR_INVALID_ARG, "eet_stack_prefill: null argument");
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_stack_prefill", st->cfg, q_lens, batch, padded_len, tokens, out, kv_cache,
+                                     lens, T, max_len))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const void* in = tokens;
+    for (int l = 0; l < st->n_layers; ++l) {
+        void* o = (l == st->n_layers - 1) ? out : static_cast<void*>(st->ws + st->act[l & 1]);
+        char* kv = static_cast<char*>(kv_cache) + (size_t)l * st->layer_cache_bytes;
+        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv, s);
+        if (rc != EET_OK) return rc;
+        st->layers[l]->batch = batch;
+        in = o;
+    }
+    st->batch = batch;
+    for (int b = 0; b < batch; ++b) st->host_lens[b] = q_lens[b];
+    return EET_OK;
+}
+
+static int stack_enqueue_decode(eet_stack* st, const void* tokens, void* out, void* kv_cache, hipStream_t s) {
+    const void* in = tokens;
+    for (int l = 0; l < st->n_layers; ++l) {
+        const bool last = l == st->n_layers - 1;
+        void* o = last ? out : static_cast<void*>(st->ws + st->act[l & 1]);
+        char* kv = static_cast<char*>(kv_cache) + (size_t)l * st->layer_cache_bytes;
+        const int rc = enqueue_decode(st->layers[l], in, o, kv, s, last);   // lengths shared: advanced once, at the end
+        if (rc != EET_OK) return rc;
+        in = o;
+    }
+    return EET_OK;
+}
+
+int eet_stack_decode_step(eet_stack_t* st, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
+    if (!st || !tokens || !out || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_stack_decode_step: null argument");
+    if (st->batch == 0) return fail(EET_ERR_STATE, "eet_stack_decode_step: no prefill has been run on this stack");
+    if (!aligned16(tokens) || !aligned16(out) || !aligned16(kv_cache))
+        return fail(EET_ERR_INVALID_ARG, "eet_stack_decode_step: tokens/out/kv_cache must be 16-byte aligned");
+    const int B = st->batch;
+    for (int b = 0; b < B; ++b)
+        if (st->host_lens[b] + 1 > st->cfg.max_seq)
+            return fail(EET_ERR_CAPACITY, "eet_stack_decode_step: sequence %d is at the cache capacity %d", b, st->cfg.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // A step has no host-varying argument (the cache lengths live on the device), so its launches
+    // can be recorded once and replayed.  Not on the null stream (it cannot be captured) and not
+    // while the caller is capturing this stream itself (then the launches join the caller's graph).
+    bool graph = st->use_graph && s != nullptr;
+    if (graph) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) graph = false;
+    }
+    if (!graph) {
+        if (const int rc = stack_enqueue_decode(st, tokens, out, kv_cache, s)) return rc;
+    } else {
+        if (st->exec && (st->g_tokens != tokens || st->g_out != out || st->g_kv != kv_cache || st->g_batch != B)) {
+            (void)hipGraphExecDestroy(st->exec);
+            st->exec = nullptr;
+        }
+        if (!st->exec) {
+            hipGraph_t g = nullptr;
+            EET_LAUNCH(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal), "begin capture");
+            const int rc = stack_enqueue_decode(st, tokens, out, kv_cache, s);
+            const hipError_t e = hipStreamEndCapture(s, &g);
+            if (rc != EET_OK) {
+                if (g) (void)hipGraphDestroy(g);
+                return rc;
+            }
+            if (e != hipSuccess) return hip_fail(e, "end capture");
+            const hipError_t ei = hipGraphInstantiate(&st->exec, g, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(g);
+            if (ei != hipSuccess) {
+                st->exec = nullptr;
+                return hip_fail(ei, "graph instantiate");
+            }
+            st->g_tokens = tokens; st->g_out = out; st->g_kv = kv_cache; st->g_batch = B;
+        }
+        EET_LAUNCH(hipGraphLaunch(st->exec, s), "graph launch");
+    }
+    for (int b = 0; b < B; ++b) st->host_lens[b] += 1;
+    return EET_OK;
+}
+
+int eet_stack_cache_lens(eet_stack_t* st, int32_t* out_host, void* hip_stream) {
+    if (!st || !out_host) return fail(EET_ERR_INVALID_ARG, "eet_stack_cache_lens: null argument");
+    if (st->batch == 0) return fail(EET_ERR_STATE, "eet_stack_cache_lens: no prefill has been run on this stack");
+    return eet_cache_lens(st->layers[0], out_host, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -552,6 +552,29 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         wr = wr < N ? wr : N - 1;
         wp[f] = a.w + (int64_t)wr * K + G * 8;
     }
+    float4v acc[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) acc[f] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // The weight (and gamma/beta) fragments of a chunk of UN K steps are requested one chunk ahead
+    // of their use; the first chunk is requested before the LayerNorm statistics, whose latency
+    // (two passes over cached activation rows) then hides behind the first trip to HBM.
+    half8v xf[UN], wf[UN][NF], gf[UN], bf[UN];
+    auto request = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int step = s0 + 4 * u;
+            const int k = (step < nsteps ? step : wave) * 32;      // past the end: any valid step, zeroed below
+            xf[u] = *reinterpret_cast<const half8v*>(xp + k);
+            if (LN) {
+                gf[u] = *reinterpret_cast<const half8v*>(a.ln_gamma + k + G * 8);
+                bf[u] = *reinterpret_cast<const half8v*>(a.ln_beta + k + G * 8);
+            }
+#pragma unroll
+            for (int f = 0; f < NF; ++f) wf[u][f] = *reinterpret_cast<const half8v*>(wp[f] + k);
+        }
+    };
+    if (wave < nsteps) request(wave);
     float mean = 0.f, rstd = 1.f;
     if (LN) {
         // 16 threads per row: thread (row = tid/16, sub = tid%16) walks the row in 16-byte vectors
@@ -559,23 +582,43 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         int rr = mc + row;
         rr = rr < M ? rr : M - 1;
         const half_t* rp = a.x + (int64_t)rr * K;
+        // loads go out in batches of 8 independent 16-byte vectors (a scalar loop would pay one
+        // memory round trip per vector)
         float sum = 0.f;
-        for (int cidx = sub * 8; cidx < K; cidx += 128) {
-            const half8v v = *reinterpret_cast<const half8v*>(rp + cidx);
+        for (int c0 = sub * 8; c0 < K; c0 += 8 * 128) {
+            half8v v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sum += (float)v[e];
+            for (int i = 0; i < 8; ++i) {
+                const int cidx = c0 + i * 128;
+                v[i] = *reinterpret_cast<const half8v*>(rp + (cidx < K ? cidx : sub * 8));
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (c0 + i * 128 < K) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) sum += (float)v[i][e];
+                }
         }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
         const float mu = sum / (float)K;
         float sq = 0.f;
-        for (int cidx = sub * 8; cidx < K; cidx += 128) {
-            const half8v v = *reinterpret_cast<const half8v*>(rp + cidx);
+        for (int c0 = sub * 8; c0 < K; c0 += 8 * 128) {
+            half8v v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float dlt = (float)v[e] - mu;
-                sq += dlt * dlt;
+            for (int i = 0; i < 8; ++i) {
+                const int cidx = c0 + i * 128;
+                v[i] = *reinterpret_cast<const half8v*>(rp + (cidx < K ? cidx : sub * 8));
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (c0 + i * 128 < K) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float dlt = (float)v[i][e] - mu;
+                        sq += dlt * dlt;
+                    }
+                }
         }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
@@ -587,40 +630,29 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         mean = ln_mean[fr];
         rstd = ln_rstd[fr];
     }
-    float4v acc[NF];
-#pragma unroll
-    for (int f = 0; f < NF; ++f) acc[f] = float4v{0.f, 0.f, 0.f, 0.f};
-
     for (int s0 = wave; s0 < nsteps; s0 += 4 * UN) {
-        half8v xf[UN], wf[UN][NF], gf[UN], bf[UN];
+        half8v cx[UN], cw[UN][NF];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
-            const int step = s0 + 4 * u;
-            const bool ok = step < nsteps;
-            const int k = (ok ? step : s0) * 32;
-            xf[u] = *reinterpret_cast<const half8v*>(xp + k);
-            if (LN) {
-                gf[u] = *reinterpret_cast<const half8v*>(a.ln_gamma + k + G * 8);
-                bf[u] = *reinterpret_cast<const half8v*>(a.ln_beta + k + G * 8);
-            }
-#pragma unroll
-            for (int f = 0; f < NF; ++f) wf[u][f] = *reinterpret_cast<const half8v*>(wp[f] + k);
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
+            cx[u] = xf[u];
             if (LN) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    xf[u][e] = (half_t)(((float)xf[u][e] - mean) * rstd * (float)gf[u][e] + (float)bf[u][e]);
+                    cx[u][e] = (half_t)(((float)xf[u][e] - mean) * rstd * (float)gf[u][e] + (float)bf[u][e]);
             }
             if (s0 + 4 * u >= nsteps) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) xf[u][e] = (half_t)0.f;
+                for (int e = 0; e < 8; ++e) cx[u][e] = (half_t)0.f;
             }
 #pragma unroll
-            for (int f = 0; f < NF; ++f)
-                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u][f], xf[u], acc[f], 0, 0, 0);
+            for (int f = 0; f < NF; ++f) cw[u][f] = wf[u][f];
         }
+        if (s0 + 4 * UN < nsteps) request(s0 + 4 * UN);            // next chunk in flight during the MFMAs
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cw[u][f], cx[u], acc[f], 0, 0, 0);
     }
     // acc[f][r]: output column n0 + f*16 + 4G + r, row mc + lane%16
 #pragma unroll

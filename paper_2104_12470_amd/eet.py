@@ -65,6 +65,13 @@ def lib() -> C.CDLL:
             "eet_cache_lens": (i32, [vp, i32p, vp]),
             "eet_layer_destroy": (i32, [vp]),
             "eet_last_error": (C.c_char_p, []),
+            "eet_stack_kv_cache_bytes": (sz, [cfgp, i32]),
+            "eet_stack_workspace_bytes": (sz, [cfgp, i32]),
+            "eet_stack_create": (i32, [cfgp, i32, C.POINTER(LayerWeights), vp, i32, C.POINTER(vp)]),
+            "eet_stack_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_stack_decode_step": (i32, [vp, vp, vp, vp, vp]),
+            "eet_stack_cache_lens": (i32, [vp, i32p, vp]),
+            "eet_stack_destroy": (i32, [vp]),
             "eet_op_layernorm": (i32, [vp, vp, vp, vp, i64, i32, f32, vp]),
             "eet_op_softmax_maskfree": (i32, [vp, i32p, i32, i32, i32, f32, vp]),
             "eet_op_bias_gelu": (i32, [vp, vp, vp, i64, i32, vp]),
@@ -82,7 +89,9 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_decode_step",
-           "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_op_layernorm", "eet_op_softmax_maskfree",
+           "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_stack_kv_cache_bytes",
+           "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
+           "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
            "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill",
            "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode")
 
@@ -146,6 +155,42 @@ def eet_cache_lens(layer: int, batch: int, stream=None):
 
 def eet_layer_destroy(layer: int) -> None:
     _check(lib().eet_layer_destroy(layer))
+
+
+def eet_stack_kv_cache_bytes(cfg: LayerConfig, n_layers: int) -> int:
+    return lib().eet_stack_kv_cache_bytes(C.byref(cfg), n_layers)
+
+
+def eet_stack_workspace_bytes(cfg: LayerConfig, n_layers: int) -> int:
+    return lib().eet_stack_workspace_bytes(C.byref(cfg), n_layers)
+
+
+def eet_stack_create(cfg: LayerConfig, weights: Sequence[Dict[str, torch.Tensor]], workspace: torch.Tensor,
+                     use_graph: bool = True) -> int:
+    arr = (LayerWeights * len(weights))(*[LayerWeights(*[_ptr(w[n]) for n in WEIGHT_FIELDS]) for w in weights])
+    handle = C.c_void_p()
+    _check(lib().eet_stack_create(C.byref(cfg), len(weights), arr, _ptr(workspace), int(use_graph), C.byref(handle)))
+    return handle.value
+
+
+def eet_stack_prefill(stack: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens, out, kv_cache,
+                      stream=None) -> None:
+    _check(lib().eet_stack_prefill(stack, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
+                                   _ptr(kv_cache), _stream(stream)))
+
+
+def eet_stack_decode_step(stack: int, tokens, out, kv_cache, stream=None) -> None:
+    _check(lib().eet_stack_decode_step(stack, _ptr(tokens), _ptr(out), _ptr(kv_cache), _stream(stream)))
+
+
+def eet_stack_cache_lens(stack: int, batch: int, stream=None):
+    out = (C.c_int32 * batch)()
+    _check(lib().eet_stack_cache_lens(stack, out, _stream(stream)))
+    return list(out)
+
+
+def eet_stack_destroy(stack: int) -> None:
+    _check(lib().eet_stack_destroy(stack))
 
 
 def eet_op_layernorm(x, gamma, beta, y, eps=1e-5, stream=None) -> None:
@@ -227,6 +272,50 @@ class DecoderLayer:
     def close(self):
         if self.handle:
             eet_layer_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class DecoderStack:
+    """Owns the torch buffers a stack handle borrows (weights, workspace, K/V caches of all layers)."""
+
+    def __init__(self, cfg: LayerConfig, weights: Sequence[Dict[str, torch.Tensor]], device="cuda:0",
+                 cache_fill: float = 0.0, use_graph: bool = True):
+        self.cfg, self.n_layers = cfg, len(weights)
+        self.weights = [{n: w[n].to(device=device, dtype=torch.float16).contiguous() for n in WEIGHT_FIELDS}
+                        for w in weights]
+        self.workspace = torch.empty(eet_stack_workspace_bytes(cfg, self.n_layers), dtype=torch.uint8, device=device)
+        self.kv_cache = torch.full((eet_stack_kv_cache_bytes(cfg, self.n_layers) // 2,), cache_fill,
+                                   dtype=torch.float16, device=device)
+        self.handle = eet_stack_create(cfg, self.weights, self.workspace, use_graph)
+
+    def cache_views(self, layer: int):
+        c = self.cfg
+        kv = self.kv_cache.view(self.n_layers, 2, c.max_batch, c.heads, c.max_seq, c.hidden // c.heads)
+        return kv[layer, 0], kv[layer, 1]
+
+    def prefill(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_stack_prefill(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
+    def decode_step(self, tokens: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):
+        out = torch.empty_like(tokens) if out is None else out
+        eet_stack_decode_step(self.handle, tokens, out, self.kv_cache, stream)
+        return out
+
+    def cache_lens(self, batch: int):
+        return eet_stack_cache_lens(self.handle, batch)
+
+    def close(self):
+        if self.handle:
+            eet_stack_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

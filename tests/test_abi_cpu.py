@@ -117,3 +117,27 @@ def test_op_entry_points_validate(eet):
     assert L.eet_op_attention_prefill(P, P, P, P, lens, 2, 16, 2, 64, 8, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_attention_decode(P, P, P, P, P, 2, 2, 64, 16, None, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_attention_decode_scratch_bytes(2, 2, 64, 4096) > 0
+
+
+def test_stack_sizes_and_validation(eet):
+    L = eet.lib()
+    cfg = eet.make_config(1024, 16, 4096, 8, 512, 1024)
+    # Section 3.1: 2*b*h*s*l elements, fp16
+    assert eet.eet_stack_kv_cache_bytes(cfg, 24) == 2 * orc.kv_cache_elements(8, 1024, 1024, 24)
+    ws1, wsn = eet.eet_workspace_bytes(cfg), eet.eet_stack_workspace_bytes(cfg, 24)
+    # the layers share the scratch; the stack adds the two activation caches of 2*b*h*p elements (Section 3.1)
+    assert wsn - ws1 == 2 * orc.activation_cache_elements(8, 1024, 512)
+    assert eet.eet_stack_workspace_bytes(cfg, 0) == 0 and eet.eet_stack_kv_cache_bytes(cfg, 0) == 0
+    ws = (eet.LayerWeights * 2)(eet.LayerWeights(*[0x10000] * 12), eet.LayerWeights(*[0x10000] * 12))
+    h = C.c_void_p()
+    assert L.eet_stack_create(C.byref(cfg), 0, ws, 0x100000, 1, C.byref(h)) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_stack_create(C.byref(cfg), 2, ws, 0x100000, 1, C.byref(h)) == eet.EET_OK and h.value
+    P = 0x200000
+    lens = (C.c_int32 * 2)(5, 600)
+    assert L.eet_stack_decode_step(h, P, P, P, None) == eet.EET_ERR_STATE
+    assert L.eet_stack_prefill(h, lens, 2, 512, P, P, P, None) == eet.EET_ERR_INVALID_ARG     # 600 > 512
+    assert L.eet_stack_prefill(h, lens, 9, 512, P, P, P, None) == eet.EET_ERR_CAPACITY
+    assert L.eet_stack_cache_lens(h, lens, None) == eet.EET_ERR_STATE
+    assert L.eet_stack_destroy(h) == eet.EET_OK
+    bad = (eet.LayerWeights * 2)(eet.LayerWeights(*[0x10000] * 12), eet.LayerWeights(*[0x10000] * 11, 0))
+    assert L.eet_stack_create(C.byref(cfg), 2, bad, 0x100000, 1, C.byref(h)) == eet.EET_ERR_INVALID_ARG and not h.value

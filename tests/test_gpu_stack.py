@@ -1,0 +1,119 @@
+"""The stack entry points (all layers per call, decode steps replayed from a HIP graph) against the
+per-layer entry points and against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import eet_oracle as orc
+from paper_2104_12470_amd import workloads as wl
+from tests.gpu_util import dev, gate, host
+
+pytestmark = pytest.mark.gpu
+
+SENTINEL = 777.0
+
+
+@pytest.fixture(scope="module")
+def eet():
+    from paper_2104_12470_amd import eet as binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def build(eet, w, n_layers, use_graph):
+    cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+    Ws = [wl.layer_weights(w, li, random_affine=True) for li in range(n_layers)]
+    tw = [{k: torch.from_numpy(v) for k, v in W.items()} for W in Ws]
+    return cfg, Ws, eet.DecoderStack(cfg, tw, cache_fill=SENTINEL, use_graph=use_graph)
+
+
+@pytest.mark.parametrize("name,n_layers", [("small64", 2), ("small128", 3)])
+def test_stack_equals_layer_chain_and_oracle(eet, name, n_layers):
+    w = wl.WORKLOADS[name]
+    cfg, Ws, stack = build(eet, w, n_layers, use_graph=False)
+    lens, x = wl.lengths(w), wl.prompt_embeddings(w)
+    B = w.batch
+    layers = [eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in W.items()}) for W in Ws]
+    oracles = [orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps) for W in Ws]
+
+    got = stack.prefill(dev(x), lens)
+    h, ho = dev(x), x.astype(np.float64)
+    for layer, o in zip(layers, oracles):
+        h = layer.prefill(h, lens)
+        ho = o.prefill(ho, lens)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(got).view(np.uint16), host(h).view(np.uint16))          # same kernels, same bits
+    for b, L in enumerate(lens):
+        gate(host(got)[b, :L], ho[b, :L], f"{name} stack prefill b={b}")
+        assert np.all(host(got)[b, L:] == 0)
+    for k in range(4):
+        xs = wl.decode_embeddings(w, k)
+        got = stack.decode_step(dev(xs))
+        h, ho = dev(xs), xs.astype(np.float64)
+        for layer, o in zip(layers, oracles):
+            h = layer.decode_step(h)
+            ho = o.decode_step(ho)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(got).view(np.uint16), host(h).view(np.uint16))
+        gate(host(got), ho, f"{name} stack decode {k}")
+        assert stack.cache_lens(B) == [int(v) + k + 1 for v in lens] == oracles[0].lens[:B].tolist()
+    for li, o in enumerate(oracles):                                                     # per-layer caches, exact extents
+        kc, vc = stack.cache_views(li)
+        for b in range(B):
+            n = int(lens[b]) + 4
+            gate(host(kc[b, :, :n]), o.k_cache[b, :, :n], f"layer {li} K", 1.5e-2, 1.5e-3)
+            assert bool((kc[b, :, n:] == SENTINEL).all()) and bool((vc[b, :, n:] == SENTINEL).all())
+    stack.close()
+    for layer in layers:
+        layer.close()
+
+
+def test_graph_replay_matches_direct_launches(eet):
+    """Decode steps replayed from the recorded graph, with unrelated eager work and synchronisations
+    between the replays, give the same bits as direct launches, step after step; a new prefill with
+    another batch size re-records the graph."""
+    w = wl.WORKLOADS["small64"]
+    cfg, Ws, direct = build(eet, w, 2, use_graph=False)
+    _, _, graphed = build(eet, w, 2, use_graph=True)
+    side = torch.cuda.Stream()
+    x = dev(wl.prompt_embeddings(w))
+    tok = torch.empty((w.batch, w.hidden), dtype=torch.float16, device="cuda:0")      # fixed input buffer
+    out_g = torch.empty_like(tok)
+    for lens in ([int(v) for v in wl.lengths(w)], [7, 150, 64]):
+        B = len(lens)
+        with torch.cuda.stream(side):
+            direct.prefill(x[:B], lens)
+            graphed.prefill(x[:B], lens)
+            for k in range(6):
+                xs = dev(wl.decode_embeddings(w, k)[:B])
+                tok[:B].copy_(xs)
+                want = direct.decode_step(xs)
+                graphed.decode_step(tok[:B], out_g[:B])
+                side.synchronize()
+                assert np.array_equal(host(out_g[:B]).view(np.uint16), host(want).view(np.uint16)), (B, k)
+                assert graphed.cache_lens(B) == direct.cache_lens(B) == [v + k + 1 for v in lens]
+                junk = torch.randn(257, 129, device="cuda:0").softmax(-1).sum()                 # eager work in between
+                torch.cuda.synchronize()
+                assert float(junk) > 0
+    direct.close()
+    graphed.close()
+
+
+def test_stack_capacity(eet):
+    w = wl.WORKLOADS["tiny"]
+    cfg, Ws, stack = build(eet, w, 2, use_graph=True)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        stack.prefill(dev(wl.prompt_embeddings(w)), [24, 3, 1])
+        xs = dev(wl.decode_embeddings(w, 0))
+        o = torch.empty_like(xs)
+        for _ in range(8):
+            stack.decode_step(xs, o)
+        side.synchronize()
+        assert stack.cache_lens(3) == [32, 11, 9]
+        with pytest.raises(eet.EETError) as e:
+            stack.decode_step(xs, o)
+        assert e.value.code == eet.EET_ERR_CAPACITY
+        assert stack.cache_lens(3) == [32, 11, 9]
+    stack.close()
