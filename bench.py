@@ -179,6 +179,18 @@ def _kernel_candidates(stack, torch, eet, reps):
     ms = time_launches(torch, run_pre, max(4, min(reps, 24)), replays=2)
     out.append({"kernel": "gemm_mfma: FFN-1 projection + bias + GELU, prefill (matrix cores)", "bound": "mfma",
                 "work": 2.0 * T * H * F, "ms": ms, "launches": nl * (12 * H * H) / (H * F)})
+    # (4) prefill attention: QK^T and PV over the valid causal triangle of every sequence
+    qp = torch.randn(B, w.padded_len, H, device="cuda:0").half()
+    cp = torch.empty_like(qp)
+    st4 = {"i": 0}
+
+    def run_pattn():
+        kc, vc = stack.cache_views(st4["i"] % nl)
+        st4["i"] += 1
+        eet.eet_op_attention_prefill(qp, kc, vc, cp, stack.lens, w.heads)
+    ms = time_launches(torch, run_pattn, max(4, min(reps, 24)), replays=2)
+    out.append({"kernel": f"attn_prefill<{d}>: causal, padding-skipping prefill attention (matrix cores)",
+                "bound": "mfma", "work": sum(2.0 * H * L * (L + 1) for L in stack.lens), "ms": ms, "launches": nl})
     return out
 
 

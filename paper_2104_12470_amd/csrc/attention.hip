@@ -24,7 +24,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 // cross-lane exchange (lane ^ 32) and P^T is already in MFMA B-operand layout for
 // O^T = V^T P^T.
 template <int D>
-__global__ __launch_bounds__(256) void attn_prefill(AttnPrefillArgs a, SeqLens lens) {
+__global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLens lens) {
     constexpr int BQ = 128, BKV = 64;
     constexpr int LDKS = D + 8;         // K tile row stride (halfs): 16-byte reads conflict-free
     constexpr int LDVT = BKV + 8;       // V^T tile row stride
@@ -132,37 +132,46 @@ __global__ __launch_bounds__(256) void attn_prefill(AttnPrefillArgs a, SeqLens l
             }
         }
         // st[jb][r] belongs to key j0 + jb*32 + (r/4)*8 + G*4 + r%4 and query i.
-        const bool diag = j0 + BKV - 1 > iw0;    // some key of the tile is later than some row of the wave
+        // The attention mask is an index comparison, and only tiles that straddle the diagonal of
+        // this wave's rows pay for it (wave-uniform branch).
         float tmax = -INFINITY;
+        if (j0 + BKV - 1 > iw0) {
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+            for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + jb * 32 + (r >> 2) * 8 + G * 4 + (r & 3);
-                float t = st[jb][r] * c;
-                if (diag && j > i) t = -INFINITY;    // the attention mask, as an index comparison
-                st[jb][r] = t;
-                tmax = fmaxf(tmax, t);
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int j = j0 + jb * 32 + (r >> 2) * 8 + G * 4 + (r & 3);
+                    if (j > i) st[jb][r] = -INFINITY;
+                    tmax = fmaxf(tmax, st[jb][r]);
+                }
+        } else {
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, st[jb][r]);
+        }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-        const float m_new = fmaxf(m, tmax);          // finite: key 0 is visible to every row
-        const float alpha = exp2f(m - m_new);
+        // running maximum m lives in the exp2 domain (score * c): p = 2^(s*c - m), one FMA + one v_exp_f32
+        const float m_new = fmaxf(m, tmax * c);      // finite: key 0 is visible to every row
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         float psum = 0.f;
         half8v pf[2][2];
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = exp2f(st[jb][r] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][r], c, -m_new));
                 psum += p;
                 pf[jb][r >> 3][r & 7] = (half_t)p;
             }
         l = l * alpha + psum;
         m = m_new;
+        if (__any(alpha != 1.0f)) {                  // the maximum stops moving after the first tiles of a long row
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+            for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        }
         // O^T[dv][i] += V^T[dv][j] P^T[j][i]; operand slot s of lane group G <-> key
         // jb*32 + hf*16 + (s/4)*8 + G*4 + s%4 (the keys this lane already holds in pf[jb][hf]).
 #pragma unroll

@@ -23,17 +23,32 @@ namespace eet {
 // --------------------------------------------------------------------------------------------
 // epilogue on 4 consecutive output columns n..n+3 of row m
 // --------------------------------------------------------------------------------------------
+// Operands of the epilogue that come from memory; a latency-bound kernel fetches them before its
+// main loop so that no dependent round trip is left after the last MFMA.
+struct EpiOperands {
+    half4v bias, res;
+    int pos;            // QKV only: padded row of the token (prefill) or cache slot n_b (decode)
+};
+
 template <int EPI>
-__device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float v0, float v1, float v2, float v3) {
-    const half4v b = *reinterpret_cast<const half4v*>(a.bias + n);
-    v0 += (float)b[0]; v1 += (float)b[1]; v2 += (float)b[2]; v3 += (float)b[3];
+__device__ __forceinline__ void epilogue_fetch(const GemmArgs& a, int m, int n, EpiOperands& o) {
+    o.bias = *reinterpret_cast<const half4v*>(a.bias + n);
+    if (EPI == EPI_BIAS_RES) {
+        const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
+        o.res = *reinterpret_cast<const half4v*>(a.res + rr * a.N + n);
+    }
+    if (EPI == EPI_QKV) o.pos = a.tok_row_map ? a.tok_row_map[m] : a.lens[m];
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_apply(const GemmArgs& a, int m, int n, float v0, float v1, float v2, float v3,
+                                               const EpiOperands& e) {
+    v0 += (float)e.bias[0]; v1 += (float)e.bias[1]; v2 += (float)e.bias[2]; v3 += (float)e.bias[3];
     if (EPI == EPI_BIAS_GELU) {
         v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
     }
     if (EPI == EPI_BIAS_RES) {
-        const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
-        const half4v r = *reinterpret_cast<const half4v*>(a.res + rr * a.N + n);
-        v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
+        v0 += (float)e.res[0]; v1 += (float)e.res[1]; v2 += (float)e.res[2]; v3 += (float)e.res[3];
     }
     half4v o;
     o[0] = (half_t)v0; o[1] = (half_t)v1; o[2] = (half_t)v2; o[3] = (half_t)v3;
@@ -45,12 +60,11 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
         } else {
             int b_, pos;
             if (a.tok_row_map) {                 // prefill: token -> (sequence, position)
-                const int r = a.tok_row_map[m];
-                b_ = r / a.S;
-                pos = r - b_ * a.S;
+                b_ = e.pos / a.S;
+                pos = e.pos - b_ * a.S;
             } else {                             // decode: the new token goes to slot n_b
                 b_ = m;
-                pos = a.lens[m];
+                pos = e.pos;
             }
             const int g = c / a.d, dd = c - g * a.d;
             half_t* cache = which == 1 ? a.k_cache : a.v_cache;
@@ -60,6 +74,13 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
     }
     const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
     *reinterpret_cast<half4v*>(a.y + orow * a.N + n) = o;
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float v0, float v1, float v2, float v3) {
+    EpiOperands e;
+    epilogue_fetch<EPI>(a, m, n, e);
+    epilogue_apply<EPI>(a, m, n, v0, v1, v2, v3, e);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -522,17 +543,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 // --------------------------------------------------------------------------------------------
 // weight-streaming kernel for M <= 16 rows per grid.y slice
 // --------------------------------------------------------------------------------------------
-// Workgroup = 4 waves; it owns 16*NF output columns.  K steps of 32 are dealt round-robin to
+// Workgroup = NW waves; it owns 16*NF output columns.  K steps of 32 are dealt round-robin to
 // the waves (adjacent waves read adjacent 64-byte pieces of the same weight rows).
 // LN = true fuses the LayerNorm that precedes the projection (decode: LN1 -> QKV, LN2 -> FFN-1):
 // every workgroup first computes mean and 1/std of its <= 16 activation rows (two passes over
 // rows that stay in L1/L2), then normalises the activation fragments on their way into the MFMA,
 // so the normalised activations never exist in memory and one launch per projection is saved.
 // BUMP: the workgroup with blockIdx 0 also advances the per-sequence cache lengths (n_b += 1).
-template <int NF, int EPI, bool LN>
-__global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
+template <int NF, int EPI, bool LN, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_skinny(GemmArgs a) {
     constexpr int UN = 4;                       // K steps in flight per wave
-    __shared__ float red[4][NF * 16][17];
+    __shared__ float red[NW][NF * 16][17];
     __shared__ float ln_mean[16], ln_rstd[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, G = lane >> 4;
@@ -563,7 +584,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     auto request = [&](int s0) {
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
-            const int step = s0 + 4 * u;
+            const int step = s0 + NW * u;
             const int k = (step < nsteps ? step : wave) * 32;      // past the end: any valid step, zeroed below
             xf[u] = *reinterpret_cast<const half8v*>(xp + k);
             if (LN) {
@@ -578,7 +599,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     float mean = 0.f, rstd = 1.f;
     if (LN) {
         // 16 threads per row: thread (row = tid/16, sub = tid%16) walks the row in 16-byte vectors
-        const int row = tid >> 4, sub = tid & 15;
+        const int row = (tid >> 4) & 15, sub = tid & 15;       // (workgroups wider than 256 threads repeat the work)
         int rr = mc + row;
         rr = rr < M ? rr : M - 1;
         const half_t* rp = a.x + (int64_t)rr * K;
@@ -630,7 +651,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         mean = ln_mean[fr];
         rstd = ln_rstd[fr];
     }
-    for (int s0 = wave; s0 < nsteps; s0 += 4 * UN) {
+    for (int s0 = wave; s0 < nsteps; s0 += NW * UN) {
         half8v cx[UN], cw[UN][NF];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -640,14 +661,14 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
                 for (int e = 0; e < 8; ++e)
                     cx[u][e] = (half_t)(((float)xf[u][e] - mean) * rstd * (float)gf[u][e] + (float)bf[u][e]);
             }
-            if (s0 + 4 * u >= nsteps) {
+            if (s0 + NW * u >= nsteps) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) cx[u][e] = (half_t)0.f;
             }
 #pragma unroll
             for (int f = 0; f < NF; ++f) cw[u][f] = wf[u][f];
         }
-        if (s0 + 4 * UN < nsteps) request(s0 + 4 * UN);            // next chunk in flight during the MFMAs
+        if (s0 + NW * UN < nsteps) request(s0 + NW * UN);            // next chunk in flight during the MFMAs
 #pragma unroll
         for (int u = 0; u < UN; ++u)
 #pragma unroll
@@ -660,15 +681,151 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[wave][f * 16 + 4 * G + r][fr] = acc[f][r];
     __syncthreads();
-    for (int t = tid; t < 64 * NF; t += 256) {
+    for (int t = tid; t < 64 * NF; t += NW * 64) {
         const int ng = t % (4 * NF), ml = t / (4 * NF);
         const int m = mc + ml, n = n0 + ng * 4;
         if (m >= M || n >= N) continue;
         float v[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            v[c] = red[0][ng * 4 + c][ml] + red[1][ng * 4 + c][ml] + red[2][ng * 4 + c][ml] + red[3][ng * 4 + c][ml];
+        for (int c = 0; c < 4; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) part += red[w][ng * 4 + c][ml];
+            v[c] = part;
+        }
         epilogue4<EPI>(a, m, n, v[0], v[1], v[2], v[3]);
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// latency-bound variant of the weight-streaming kernel (small layers)
+// --------------------------------------------------------------------------------------------
+// When one projection moves only a few MB, its time is a chain of memory round trips, not bytes.
+// This variant has exactly one: a workgroup of NW waves owns TN output columns and K <= 256*NW, so
+// each wave's whole share of the weights (<= 8 K steps) is requested at once, together with the
+// activation rows and the epilogue's bias / residual / cache slot.  One CU sustains only a few
+// tens of GB/s, so narrow projections take TN = 8 or 4 (the MFMA's other weight rows are zeros)
+// to put a workgroup on every CU rather than 16 columns on a quarter of them.  With LN the 16 activation rows
+// are held in registers (4*NW threads per row), mean and variance are reduced with lane shuffles,
+// and the normalised rows go to LDS, where the MFMA fragments are read from.
+template <int NW, int TN, int EPI, bool LN>
+__global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
+    constexpr int UN = 8;                                   // K steps per wave, all in flight
+    constexpr int TPR = 4 * NW;                             // threads per activation row (LN)
+    constexpr int KMAX = NW * 256 < 1536 ? NW * 256 : 1536; // LN: longest row the LDS copy holds
+    constexpr int LDX = KMAX + 8;                           // padded LDS row: 16-byte reads of 16 rows spread over all banks
+    __shared__ __attribute__((aligned(16))) float red[NW][16][20];
+    __shared__ __attribute__((aligned(16))) half_t xs[LN ? 16 * LDX : 8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 15, G = lane >> 4;
+    const int n0 = blockIdx.x * TN, mc = blockIdx.y * 16;
+    const int M = a.M, N = a.N, K = a.K;
+    const int nsteps = K / 32;
+
+    if (a.bump_lens != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
+
+    // weights: row n0 + fr, 16 bytes at K offset 32*step + 8*G, steps wave, wave + NW, ...
+    int wr = n0 + fr;
+    wr = wr < N ? wr : N - 1;
+    const half_t* wp = a.w + (int64_t)wr * K + G * 8;
+    half8v wf[UN], xf[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+        const int step = wave + NW * u;
+        wf[u] = half8v{0, 0, 0, 0, 0, 0, 0, 0};
+        if (TN == 16 || fr < TN) wf[u] = *reinterpret_cast<const half8v*>(wp + (step < nsteps ? step : 0) * 32);
+    }
+    // epilogue operands of the 4*TN threads that write the 16 x TN outputs
+    const int eml = tid / (TN / 4), eng = tid % (TN / 4);
+    const int em = mc + eml, en = n0 + eng * 4;
+    const bool writer = tid < 4 * TN && em < M && en < N;
+    EpiOperands eo;
+    if (writer) epilogue_fetch<EPI>(a, em, en, eo);
+
+    if (LN) {
+        const int row = tid / TPR, sub = tid % TPR;
+        int rr = mc + row;
+        rr = rr < M ? rr : M - 1;
+        const half_t* rp = a.x + (int64_t)rr * K;
+        half8v xv[UN], gv[UN], bv[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int c = (sub + TPR * i) * 8;
+            const int cc = c < K ? c : 0;
+            xv[i] = *reinterpret_cast<const half8v*>(rp + cc);
+            gv[i] = *reinterpret_cast<const half8v*>(a.ln_gamma + cc);
+            bv[i] = *reinterpret_cast<const half8v*>(a.ln_beta + cc);
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if ((sub + TPR * i) * 8 < K) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum += (float)xv[i][e];
+            }
+#pragma unroll
+        for (int o = TPR / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+        const float mu = sum / (float)K;
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if ((sub + TPR * i) * 8 < K) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float dlt = (float)xv[i][e] - mu;
+                    sq += dlt * dlt;
+                }
+            }
+#pragma unroll
+        for (int o = TPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
+        const float rstd = rsqrtf(sq / (float)K + a.ln_eps);
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int c = (sub + TPR * i) * 8;
+            if (c < K) {
+                half8v o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = (half_t)(((float)xv[i][e] - mu) * rstd * (float)gv[i][e] + (float)bv[i][e]);
+                *reinterpret_cast<half8v*>(&xs[row * LDX + c]) = o;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int step = wave + NW * u;
+            xf[u] = *reinterpret_cast<const half8v*>(&xs[fr * LDX + (step < nsteps ? step : 0) * 32 + G * 8]);
+        }
+    } else {
+        int xr = mc + fr;
+        xr = xr < M ? xr : M - 1;
+        const half_t* xp = a.x + (int64_t)xr * K + G * 8;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int step = wave + NW * u;
+            xf[u] = *reinterpret_cast<const half8v*>(xp + (step < nsteps ? step : 0) * 32);
+        }
+    }
+    float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+        if (wave + NW * u >= nsteps) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xf[u][e] = (half_t)0.f;
+        }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[u], acc, 0, 0, 0);
+    }
+    // acc[r]: output column n0 + 4G + r, row mc + fr
+    if (4 * G < TN) *reinterpret_cast<float4v*>(&red[wave][fr][4 * G]) = acc;
+    __syncthreads();
+    if (writer) {
+        float4v v = *reinterpret_cast<const float4v*>(&red[0][eml][eng * 4]);
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            const float4v p = *reinterpret_cast<const float4v*>(&red[w][eml][eng * 4]);
+            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+        }
+        epilogue_apply<EPI>(a, em, en, v[0], v[1], v[2], v[3], eo);
     }
 }
 
@@ -711,26 +868,59 @@ static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
 }
 
-template <int NF, bool LN>
-static void launch_skinny_ln(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const dim3 grid((a.N + NF * 16 - 1) / (NF * 16), (a.M + 15) / 16), block(256);
+template <int NF, bool LN, int NW>
+static void launch_skinny_nw(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const dim3 grid((a.N + NF * 16 - 1) / (NF * 16), (a.M + 15) / 16), block(NW * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS, LN>), grid, block, 0, s, a); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_GELU, LN>), grid, block, 0, s, a); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_RES, LN>), grid, block, 0, s, a); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_skinny<NF, EPI_QKV, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS, LN, NW>), grid, block, 0, s, a); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_GELU, LN, NW>), grid, block, 0, s, a); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_skinny<NF, EPI_BIAS_RES, LN, NW>), grid, block, 0, s, a); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_skinny<NF, EPI_QKV, LN, NW>), grid, block, 0, s, a); break;
     }
 }
 template <int NF>
 static void launch_skinny_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    if (a.ln_gamma != nullptr) launch_skinny_ln<NF, true>(a, epi, s);
-    else launch_skinny_ln<NF, false>(a, epi, s);
+    if (a.ln_gamma != nullptr) launch_skinny_nw<NF, true, 4>(a, epi, s);
+    else launch_skinny_nw<NF, false, 4>(a, epi, s);
+}
+template <int NW, int TN, bool LN>
+static void launch_flat_tn(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const dim3 grid((a.N + TN - 1) / TN, (a.M + 15) / 16), block(NW * 64);
+    switch (epi) {
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS_GELU, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS_RES, LN>), grid, block, 0, s, a); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_QKV, LN>), grid, block, 0, s, a); break;
+    }
+}
+template <int NW, bool LN>
+static void launch_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    // narrowest column slice that still leaves a workgroup for (nearly) every CU
+    if (a.N >= 192 * 16) launch_flat_tn<NW, 16, LN>(a, epi, s);
+    else if (a.N >= 192 * 8) launch_flat_tn<NW, 8, LN>(a, epi, s);
+    else launch_flat_tn<NW, 4, LN>(a, epi, s);
+}
+// true when the flat kernel took the problem
+static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    static const bool off = getenv("EET_NO_FLAT") != nullptr;
+    if (off || (int64_t)a.N * a.K * 2 > (16 << 20) || a.K > 4096) return false;
+    const bool ln = a.ln_gamma != nullptr;
+    if (ln && a.K > 1536) return false;
+    if (a.K <= 1024) {
+        if (ln) launch_flat<4, true>(a, epi, s); else launch_flat<4, false>(a, epi, s);
+    } else if (a.K <= 2048) {
+        if (ln) launch_flat<8, true>(a, epi, s); else launch_flat<8, false>(a, epi, s);
+    } else {
+        launch_flat<16, false>(a, epi, s);
+    }
+    return true;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
     if (a.M <= 16) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
+        if (try_flat(a, epi, s)) return hipGetLastError();
         if (a.N >= 64 * 1024) launch_skinny_cfg<4>(a, epi, s);
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);

@@ -138,6 +138,7 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("tiny", 7, 64, 1, 256, 1, 3, 24, 1, 24, 4, 32),
     Workload("small64", 11, 256, 4, 1024, 2, 5, 200, 3, 200, 9, 224),
     Workload("small128", 13, 512, 4, 2048, 1, 3, 333, 40, 333, 7, 352),
+    Workload("wide1280", 17, 1280, 10, 5120, 1, 3, 80, 20, 80, 5, 96),
 ]}
 
 

@@ -89,7 +89,7 @@ def full_parity(eet, w, layer_idx=0, random_affine=True, steps=None, max_batch=N
     return errs
 
 
-@pytest.mark.parametrize("name", ["tiny", "small64", "small128"])
+@pytest.mark.parametrize("name", ["tiny", "small64", "small128", "wide1280"])
 def test_small_workloads_elementwise(eet, name):
     full_parity(eet, wl.WORKLOADS[name])
 
