@@ -8,6 +8,7 @@
 // unbounded (the goal of Section 2.2) and the S x S buffer of Section 3.2 is not needed.
 //
 // K/V cache layout: [batch][heads][capacity][d] fp16, slot t = token t of the sequence.
+#include <cstdlib>
 #include "kernels.hpp"
 
 namespace eet {
@@ -266,12 +267,15 @@ __global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
     float m = -INFINITY, l = 0.f;
     const float c = rsqrtf((float)D) * kLog2e;
 
-    for (int j0 = w0; j0 < w1; j0 += 16 * U) {
-        half8v kf[U][KF], vf[U][VR];
+    // One chunk = 16*U keys.  The loads of chunk i+1 are issued before chunk i is consumed (two
+    // register buffers, loop unrolled by two); rows past the range are clamped to its last row, so
+    // the look-ahead needs no branch and the in-order load counter never waits on the newer chunk.
+    auto request = [&](half8v (&kf)[U][KF], half8v (&vf)[U][VR], int j0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int jk = j0 + 16 * u + fr;
-            jk = jk < w1 ? jk : w1 - 1;                   // rows past the range: clamp, masked below
+            jk = jk < w1 ? jk : w1 - 1;                   // masked in consume()
+            jk = jk > 0 ? jk : 0;
 #pragma unroll
             for (int kk = 0; kk < KF; ++kk)
                 kf[u][kk] = *reinterpret_cast<const half8v*>(kbase + (int64_t)jk * D + kk * 32 + G * 8);
@@ -279,10 +283,12 @@ __global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
             for (int r = 0; r < VR; ++r) {
                 int jv = j0 + 16 * u + 4 * G + vr0 + r;
                 jv = jv < w1 ? jv : w1 - 1;
+                jv = jv > 0 ? jv : 0;
                 vf[u][r] = *reinterpret_cast<const half8v*>(vbase + (int64_t)jv * D + vc * 8);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);                // keep every load of the chunk ahead of its first use
+    };
+    auto consume = [&](const half8v (&kf)[U][KF], const half8v (&vf)[U][VR], int j0) {
         float t[U][4], gmax = -INFINITY;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -324,6 +330,19 @@ __global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
             }
         }
         m = m_new;
+    };
+    half8v kA[U][KF], vA[U][VR], kB[U][KF], vB[U][VR];
+    if (w0 < w1) {
+        request(kA, vA, w0);
+        for (int j0 = w0; j0 < w1; j0 += 32 * U) {
+            request(kB, vB, j0 + 16 * U);
+            __builtin_amdgcn_sched_barrier(0);            // keep the look-ahead loads ahead of the arithmetic
+            consume(kA, vA, j0);
+            if (j0 + 16 * U >= w1) break;
+            request(kA, vA, j0 + 32 * U);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(kB, vB, j0 + 16 * U);
+        }
     }
     // fold the lane groups: keys were spread over G (and over the two row pairs when d = 64)
     l += __shfl_xor(l, 16, kWave);

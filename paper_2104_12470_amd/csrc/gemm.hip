@@ -15,6 +15,10 @@
 // Both compute the transposed tile (weights as the MFMA "A" operand) so that each lane ends up
 // with 4 consecutive output columns of one row: 8-byte stores, and 8-byte bias/residual loads.
 #include <cstdlib>
+#include <mutex>
+#include <set>
+#include <type_traits>
+#include <utility>
 
 #include "kernels.hpp"
 
@@ -700,132 +704,208 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // latency-bound variant of the weight-streaming kernel (small layers)
 // --------------------------------------------------------------------------------------------
-// When one projection moves only a few MB, its time is a chain of memory round trips, not bytes.
-// This variant has exactly one: a workgroup of NW waves owns TN output columns and K <= 256*NW, so
-// each wave's whole share of the weights (<= 8 K steps) is requested at once, together with the
-// activation rows and the epilogue's bias / residual / cache slot.  One CU sustains only a few
-// tens of GB/s, so narrow projections take TN = 8 or 4 (the MFMA's other weight rows are zeros)
-// to put a workgroup on every CU rather than 16 columns on a quarter of them.  With LN the 16 activation rows
-// are held in registers (4*NW threads per row), mean and variance are reduced with lane shuffles,
-// and the normalised rows go to LDS, where the MFMA fragments are read from.
-template <int NW, int TN, int EPI, bool LN>
+// When one projection moves only a few MB, its time is a chain of memory round trips plus the
+// instructions each wave has to issue (a wave64 vector instruction takes 4 cycles: a thousand of
+// them are two microseconds), not bytes.  This variant is built for both:
+//   * K = 64 * NW * UPW is a compile-time constant (NW waves, UPW units of 64 K values per wave),
+//     so address arithmetic folds into immediate offsets and nothing is conditional;
+//   * a workgroup owns TN = 16 output columns (8 when 16 would leave most CUs without work: the
+//     staging rows 8..15 then hold nothing and their results are dropped); every wave requests its whole share of the weights at
+//     once, after the activation rows and before the epilogue's bias / residual / cache slot:
+//     one round trip to memory in all;
+//   * every load instruction reads whole 128-byte lines (8 lanes x 16 bytes per row; measured on
+//     this part: an instruction that takes 64 bytes from each of 16 lines, which is what the MFMA
+//     operand layout asks for, moves data several times slower out of L2).  The MFMA layout is
+//     produced in LDS instead: a wave writes each 16 x 128-byte unit it loaded into a private
+//     staging area and reads back 16 bytes per lane at (row lane%16, chunk lane/16 + 4u) for the
+//     two MFMAs u of the unit.  LDS operations of one wave execute in order, so the private
+//     areas need no barrier (and the wave's partial sums reuse the first one);
+//   * the activation rows (8, or 16 when M > 8; rows past M repeat row M-1 and their results
+//     are never written) are read as contiguous 16-byte vectors spread over all threads and
+//     shared through LDS: one barrier, after which every operand fragment is a 16-byte LDS read.
+//     With LN a row belongs to 8*NW lanes of one wave: its statistics are reduced by lane
+//     exchanges over values held in registers, and the row reaches LDS normalised.
+//
+// Dynamic LDS: [8 or 16][K + 8] activations, then per wave SA staging areas of 16 x 144 bytes.
+constexpr int kFlatStageRow = 72;                           // halves per staged row: 128 bytes + 16 padding
+__host__ __device__ constexpr int flat_stage_areas(int nw, int upw) { return (nw >= 16 && upw > 2) ? 2 : upw; }
+__host__ __device__ constexpr int flat_lds_bytes(int nw, int upw, int xrows) {
+    return xrows * (64 * nw * upw + 8) * 2 + nw * flat_stage_areas(nw, upw) * 16 * kFlatStageRow * 2;
+}
+
+// sum over aligned groups of W lanes (W = 32 or 64), result in every lane of the group
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+    auto dpp_add = [](float x, auto ctrl) {
+        constexpr int c = decltype(ctrl)::value;
+        const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), c, 0xf, 0xf, false);
+        return x + __builtin_bit_cast(float, y);
+    };
+    v = dpp_add(v, std::integral_constant<int, 0xb1>{});    // quad_perm [1,0,3,2]: lane ^ 1
+    v = dpp_add(v, std::integral_constant<int, 0x4e>{});    // quad_perm [2,3,0,1]: lane ^ 2
+    v = dpp_add(v, std::integral_constant<int, 0x141>{});   // row_half_mirror: the other quad of 8
+    v = dpp_add(v, std::integral_constant<int, 0x140>{});   // row_mirror: the other half of 16
+    v += __shfl_xor(v, 16, kWave);
+    if (W == 64) v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+template <int NW, int UPW, int TN, int EPI, bool LN>
 __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
-    constexpr int UN = 8;                                   // K steps per wave, all in flight
-    constexpr int TPR = 4 * NW;                             // threads per activation row (LN)
-    constexpr int KMAX = NW * 256 < 1536 ? NW * 256 : 1536; // LN: longest row the LDS copy holds
-    constexpr int LDX = KMAX + 8;                           // padded LDS row: 16-byte reads of 16 rows spread over all banks
-    __shared__ __attribute__((aligned(16))) float red[NW][16][20];
-    __shared__ __attribute__((aligned(16))) half_t xs[LN ? 16 * LDX : 8];
+    constexpr int NT = NW * 64;
+    constexpr int K = 64 * NW * UPW, KV = K / 8, LDX = K + 8;   // LDX: 16-byte reads of 16 rows spread over all banks
+    constexpr int SA = flat_stage_areas(NW, UPW);
+    constexpr int TPR = NT / 8;                             // LN: lanes per activation row (32 or 64)
+    static_assert(!LN || TPR <= 64, "a row's statistics are reduced inside one wave");
+    extern __shared__ __attribute__((aligned(16))) unsigned char flat_smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, G = lane >> 4;
-    const int n0 = blockIdx.x * TN, mc = blockIdx.y * 16;
-    const int M = a.M, N = a.N, K = a.K;
-    const int nsteps = K / 32;
+    constexpr int WA = TN / 8;                              // load instructions per unit (8 weight rows each)
+    const int n0 = blockIdx.x * TN;
+    const int M = a.M;
+    const int xrows = M <= 8 ? 8 : 16;
+    half_t* xs = reinterpret_cast<half_t*>(flat_smem);
+    half_t* wst = xs + xrows * LDX + wave * (SA * 16 * kFlatStageRow);
+    float* red = reinterpret_cast<float*>(xs + xrows * LDX);            // after the MFMAs: wave w's tile over its staging areas
+    constexpr int RW = SA * 16 * kFlatStageRow / 2;                     // floats between the waves' tiles
+    static_assert(RW >= 16 * 20, "partial-sum tile must fit the wave's own staging space");
 
-    if (a.bump_lens != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
+    if (a.bump_lens != nullptr && blockIdx.x == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
 
-    // weights: row n0 + fr, 16 bytes at K offset 32*step + 8*G, steps wave, wave + NW, ...
-    int wr = n0 + fr;
-    wr = wr < N ? wr : N - 1;
-    const half_t* wp = a.w + (int64_t)wr * K + G * 8;
-    half8v wf[UN], xf[UN];
+    // ---- requests, oldest first: activations, weights, epilogue operands --------------------
+    // half h of the activations = rows 8h .. 8h+7; thread -> (row, 16-byte vectors) per half:
+    //   LN:  row tid/TPR, vectors tid%TPR + TPR*i      (a row stays inside one wave)
+    //   else: vector tid + NT*i of the 8*KV vectors of the half
+    half8v xv[2][UPW], gv[LN ? UPW : 1], bv[LN ? UPW : 1];
+    uint32_t xdst[UPW];                                       // LDS offset (halves) of vector i inside a half
+    auto request_x = [&](int h) {
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-        const int step = wave + NW * u;
-        wf[u] = half8v{0, 0, 0, 0, 0, 0, 0, 0};
-        if (TN == 16 || fr < TN) wf[u] = *reinterpret_cast<const half8v*>(wp + (step < nsteps ? step : 0) * 32);
-    }
-    // epilogue operands of the 4*TN threads that write the 16 x TN outputs
-    const int eml = tid / (TN / 4), eng = tid % (TN / 4);
-    const int em = mc + eml, en = n0 + eng * 4;
-    const bool writer = tid < 4 * TN && em < M && en < N;
-    EpiOperands eo;
-    if (writer) epilogue_fetch<EPI>(a, em, en, eo);
-
-    if (LN) {
-        const int row = tid / TPR, sub = tid % TPR;
-        int rr = mc + row;
-        rr = rr < M ? rr : M - 1;
-        const half_t* rp = a.x + (int64_t)rr * K;
-        half8v xv[UN], gv[UN], bv[UN];
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int c = (sub + TPR * i) * 8;
-            const int cc = c < K ? c : 0;
-            xv[i] = *reinterpret_cast<const half8v*>(rp + cc);
-            gv[i] = *reinterpret_cast<const half8v*>(a.ln_gamma + cc);
-            bv[i] = *reinterpret_cast<const half8v*>(a.ln_beta + cc);
+        for (int i = 0; i < UPW; ++i) {
+            const int row = LN ? tid / TPR : (tid + NT * i) / KV;
+            const int col = LN ? tid % TPR + TPR * i : (tid + NT * i) % KV;
+            int src = 8 * h + row;
+            src = src < M ? src : M - 1;
+            xv[h][i] = *reinterpret_cast<const half8v*>(reinterpret_cast<const char*>(a.x) + (uint32_t)(src * K + col * 8) * 2u);
+            xdst[i] = row * LDX + col * 8;
+            if (LN && h == 0) {
+                gv[i] = *reinterpret_cast<const half8v*>(reinterpret_cast<const char*>(a.ln_gamma) + (uint32_t)col * 16u);
+                bv[i] = *reinterpret_cast<const half8v*>(reinterpret_cast<const char*>(a.ln_beta) + (uint32_t)col * 16u);
+            }
         }
-        float sum = 0.f;
+    };
+    request_x(0);
+    if (M > 8) request_x(1);
+    // weights: per unit, lane l takes 16 bytes (chunk l%8) of rows l/8 and 8 + l/8
+    const int wrow = lane >> 3, wchunk = lane & 7;
+    half8v wreg[UPW][WA];
+    {
+        const char* wbase = reinterpret_cast<const char*>(a.w) + (size_t)n0 * K * 2;
+        const uint32_t woff = (uint32_t)(wrow * K + wave * (UPW * 64) + wchunk * 8) * 2u;
 #pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if ((sub + TPR * i) * 8 < K) {
+        for (int q = 0; q < UPW; ++q)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sum += (float)xv[i][e];
-            }
+            for (int h = 0; h < WA; ++h)
+                wreg[q][h] = *reinterpret_cast<const half8v*>(wbase + woff + (uint32_t)(h * 8 * K + q * 64) * 2u);
+    }
+    // epilogue operands of the 4*TN threads that write the 16 x TN outputs (no row maps in decode)
+    const int eml = tid / (TN / 4), enl = (tid % (TN / 4)) * 4, en = n0 + enl;
+    const bool writer = tid < 4 * TN && eml < M;
+    EpiOperands eo;
+    if (writer) {
+        eo.bias = *reinterpret_cast<const half4v*>(a.bias + en);
+        if (EPI == EPI_BIAS_RES) eo.res = *reinterpret_cast<const half4v*>(a.res + (uint32_t)(eml * a.N + en));
+        if (EPI == EPI_QKV) eo.pos = a.lens[eml];
+    }
+
+    // ---- activations -> LDS (normalised when LN) ----------------------------------------------
+    auto publish_x = [&](int h) {
+        if (LN) {
+            // shifted sums: d = x - p with p the row's first element keeps the variance formula
+            // free of cancellation whatever the row's mean is
+            const half_t p = (half_t)__shfl((float)xv[h][0][0], lane & ~(TPR - 1), kWave);
+            const half2v p2 = {p, p}, one2 = {(half_t)1.f, (half_t)1.f};
+            float sd = 0.f, sq = 0.f;
 #pragma unroll
-        for (int o = TPR / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
-        const float mu = sum / (float)K;
-        float sq = 0.f;
+            for (int i = 0; i < UPW; ++i)
 #pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if ((sub + TPR * i) * 8 < K) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float dlt = (float)xv[i][e] - mu;
-                    sq += dlt * dlt;
+                for (int e = 0; e < 8; e += 2) {
+                    const half2v d2 = half2v{xv[h][i][e], xv[h][i][e + 1]} - p2;
+                    sd = __builtin_amdgcn_fdot2(d2, one2, sd, false);
+                    sq = __builtin_amdgcn_fdot2(d2, d2, sq, false);
                 }
-            }
+            sd = group_sum<TPR>(sd);
+            sq = group_sum<TPR>(sq);
+            const float md = sd * (1.0f / K);
+            const float mu = (float)p + md;
+            const float rstd = rsqrtf(fmaxf(sq * (1.0f / K) - md * md, 0.f) + a.ln_eps);
 #pragma unroll
-        for (int o = TPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
-        const float rstd = rsqrtf(sq / (float)K + a.ln_eps);
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int c = (sub + TPR * i) * 8;
-            if (c < K) {
+            for (int i = 0; i < UPW; ++i) {
                 half8v o;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = (half_t)(((float)xv[i][e] - mu) * rstd * (float)gv[i][e] + (float)bv[i][e]);
-                *reinterpret_cast<half8v*>(&xs[row * LDX + c]) = o;
+                for (int e = 0; e < 8; ++e) {
+                    // three fused multiply-adds that take their fp16 operand directly
+                    const float sc = __builtin_fmaf((float)gv[i][e], rstd, 0.f);
+                    const float sh = __builtin_fmaf(-mu, sc, (float)bv[i][e]);
+                    o[e] = (half_t)__builtin_fmaf((float)xv[h][i][e], sc, sh);
+                }
+                *reinterpret_cast<half8v*>(&xs[8 * h * LDX + xdst[i]]) = o;
             }
-        }
-        __syncthreads();
+        } else {
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int step = wave + NW * u;
-            xf[u] = *reinterpret_cast<const half8v*>(&xs[fr * LDX + (step < nsteps ? step : 0) * 32 + G * 8]);
+            for (int i = 0; i < UPW; ++i) *reinterpret_cast<half8v*>(&xs[8 * h * LDX + xdst[i]]) = xv[h][i];
         }
-    } else {
-        int xr = mc + fr;
-        xr = xr < M ? xr : M - 1;
-        const half_t* xp = a.x + (int64_t)xr * K + G * 8;
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int step = wave + NW * u;
-            xf[u] = *reinterpret_cast<const half8v*>(xp + (step < nsteps ? step : 0) * 32);
-        }
-    }
+    };
+    publish_x(0);
+    if (M > 8) publish_x(1);
+
+    // ---- weights -> MFMA layout, contraction ---------------------------------------------------
+    const uint32_t st_w = (uint32_t)(wrow * kFlatStageRow + wchunk * 8);                  // staging write (halves)
+    const uint32_t st_r = (uint32_t)(fr * kFlatStageRow + G * 8);                         // staging read
+    const uint32_t xs_r = (uint32_t)((fr & (xrows - 1)) * LDX + wave * (UPW * 64) + G * 8);
     float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+    auto stage = [&](int q0, int n) {
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-        if (wave + NW * u >= nsteps) {
+        for (int j = 0; j < n; ++j)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) xf[u][e] = (half_t)0.f;
-        }
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u], xf[u], acc, 0, 0, 0);
+            for (int h = 0; h < WA; ++h)
+                *reinterpret_cast<half8v*>(&wst[st_w + (j * 16 + 8 * h) * kFlatStageRow]) = wreg[q0 + j][h];
+    };
+    auto contract = [&](int q0, int n) {
+        half8v wf[SA][2], xf[SA][2];
+#pragma unroll
+        for (int j = 0; j < n; ++j)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                wf[j][u] = *reinterpret_cast<const half8v*>(&wst[st_r + j * 16 * kFlatStageRow + 32 * u]);
+                xf[j][u] = *reinterpret_cast<const half8v*>(&xs[xs_r + (q0 + j) * 64 + 32 * u]);
+            }
+#pragma unroll
+        for (int j = 0; j < n; ++j)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[j][u], xf[j][u], acc, 0, 0, 0);
+    };
+    stage(0, SA);
+    __syncthreads();
+    contract(0, SA);
+    if (SA < UPW) {
+        __builtin_amdgcn_wave_barrier();
+        stage(SA, UPW - SA);
+        __builtin_amdgcn_wave_barrier();
+        contract(SA, UPW - SA);
     }
-    // acc[r]: output column n0 + 4G + r, row mc + fr
-    if (4 * G < TN) *reinterpret_cast<float4v*>(&red[wave][fr][4 * G]) = acc;
+    __builtin_amdgcn_wave_barrier();
+    // acc[r]: output column n0 + 4G + r, row fr
+    *reinterpret_cast<float4v*>(&red[wave * RW + fr * 20 + 4 * G]) = acc;
     __syncthreads();
     if (writer) {
-        float4v v = *reinterpret_cast<const float4v*>(&red[0][eml][eng * 4]);
+        const float* rp = &red[eml * 20 + enl];
+        float4v v = *reinterpret_cast<const float4v*>(rp);
 #pragma unroll
         for (int w = 1; w < NW; ++w) {
-            const float4v p = *reinterpret_cast<const float4v*>(&red[w][eml][eng * 4]);
-            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+            const float4v pw = *reinterpret_cast<const float4v*>(rp + w * RW);
+            v[0] += pw[0]; v[1] += pw[1]; v[2] += pw[2]; v[3] += pw[3];
         }
-        epilogue_apply<EPI>(a, em, en, v[0], v[1], v[2], v[3], eo);
+        epilogue_apply<EPI>(a, eml, en, v[0], v[1], v[2], v[3], eo);
     }
 }
 
@@ -883,35 +963,70 @@ static void launch_skinny_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.ln_gamma != nullptr) launch_skinny_nw<NF, true, 4>(a, epi, s);
     else launch_skinny_nw<NF, false, 4>(a, epi, s);
 }
-template <int NW, int TN, bool LN>
-static void launch_flat_tn(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const dim3 grid((a.N + TN - 1) / TN, (a.M + 15) / 16), block(NW * 64);
+constexpr int kFlatLdsLimit = 160 * 1024;                  // LDS of one CU
+
+static void launch_flat_kernel(void (*kernel)(GemmArgs), const GemmArgs& a, dim3 grid, dim3 block, int lds, hipStream_t s) {
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel and device
+    if (lds > 64 * 1024) {
+        static std::mutex mu;
+        static std::set<std::pair<const void*, int>> allowed;
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        std::lock_guard<std::mutex> lock(mu);
+        if (allowed.insert({reinterpret_cast<const void*>(kernel), dev}).second)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kFlatLdsLimit);
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
+}
+
+template <int NW, int UPW, int TN, bool LN>
+static void launch_flat_epi(const GemmArgs& a, Epilogue epi, int lds, hipStream_t s) {
+    const dim3 grid(a.N / TN), block(NW * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS, LN>), grid, block, 0, s, a); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS_GELU, LN>), grid, block, 0, s, a); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_BIAS_RES, LN>), grid, block, 0, s, a); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_flat<NW, TN, EPI_QKV, LN>), grid, block, 0, s, a); break;
+        case EPI_BIAS: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS, LN>, a, grid, block, lds, s); break;
+        case EPI_BIAS_GELU: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_GELU, LN>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, LN>, a, grid, block, lds, s); break;
+        case EPI_QKV: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_QKV, LN>, a, grid, block, lds, s); break;
     }
 }
-template <int NW, bool LN>
-static void launch_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    // narrowest column slice that still leaves a workgroup for (nearly) every CU
-    if (a.N >= 192 * 16) launch_flat_tn<NW, 16, LN>(a, epi, s);
-    else if (a.N >= 192 * 8) launch_flat_tn<NW, 8, LN>(a, epi, s);
-    else launch_flat_tn<NW, 4, LN>(a, epi, s);
+template <int NW, int TN, bool LN>
+static void launch_flat(const GemmArgs& a, int upw, Epilogue epi, int lds, hipStream_t s) {
+    switch (upw) {
+        case 1: launch_flat_epi<NW, 1, TN, LN>(a, epi, lds, s); break;
+        case 2: launch_flat_epi<NW, 2, TN, LN>(a, epi, lds, s); break;
+        case 3: launch_flat_epi<NW, 3, TN, LN>(a, epi, lds, s); break;
+        default: launch_flat_epi<NW, 4, TN, LN>(a, epi, lds, s); break;
+    }
 }
-// true when the flat kernel took the problem
+// true when the flat kernel took the problem: a few MB of weights, K = 64 * NW * UPW with
+// NW in {4, 8, 16} and UPW in 1..4, N a multiple of 16, no row maps
 static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     static const bool off = getenv("EET_NO_FLAT") != nullptr;
-    if (off || (int64_t)a.N * a.K * 2 > (16 << 20) || a.K > 4096) return false;
+    static const int ln_nw = getenv("EET_FLAT_LN_NW") ? atoi(getenv("EET_FLAT_LN_NW")) : 8;
+    static const int tn8_wgs = getenv("EET_FLAT_TN8") ? atoi(getenv("EET_FLAT_TN8")) : 128;
+    if (off || (int64_t)a.N * a.K * 2 > (16 << 20) || a.N % 16 != 0 || a.K % 64 != 0) return false;
+    if (a.res_row_map != nullptr || a.out_row_map != nullptr || a.tok_row_map != nullptr) return false;
     const bool ln = a.ln_gamma != nullptr;
-    if (ln && a.K > 1536) return false;
-    if (a.K <= 1024) {
-        if (ln) launch_flat<4, true>(a, epi, s); else launch_flat<4, false>(a, epi, s);
-    } else if (a.K <= 2048) {
-        if (ln) launch_flat<8, true>(a, epi, s); else launch_flat<8, false>(a, epi, s);
+    const int units = a.K / 64;
+    auto fits = [&](int cand) { return units % cand == 0 && units / cand <= 4; };
+    // fewest waves that hold K; with LN 8 waves when possible: the normalisation is vector
+    // arithmetic spread over the threads
+    int nw = 0;
+    if (ln && ln_nw == 8 && fits(8)) nw = 8;
+    for (int cand : {4, 8, 16})
+        if (nw == 0 && fits(cand)) nw = cand;
+    if (nw == 0 || (ln && nw == 16)) return false;
+    const int upw = units / nw;
+    const int lds = flat_lds_bytes(nw, upw, a.M <= 8 ? 8 : 16);
+    if (lds > kFlatLdsLimit) return false;
+    if (nw == 4) {
+        if (ln) launch_flat<4, 16, true>(a, upw, epi, lds, s); else launch_flat<4, 16, false>(a, upw, epi, lds, s);
+    } else if (nw == 8) {
+        if (ln) launch_flat<8, 16, true>(a, upw, epi, lds, s); else launch_flat<8, 16, false>(a, upw, epi, lds, s);
+    } else if (a.N / 16 < tn8_wgs) {
+        launch_flat<16, 8, false>(a, upw, epi, lds, s);       // long rows, few columns: one CU cannot pull 16 rows fast enough
     } else {
-        launch_flat<16, false>(a, epi, s);
+        launch_flat<16, 16, false>(a, upw, epi, lds, s);
     }
     return true;
 }
