@@ -216,29 +216,40 @@ hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& len
 // ============================================================================================
 // Decode: one query per (sequence, head), K and V streamed once from HBM
 // ============================================================================================
-// grid = (splits, heads, batch); a workgroup of 4 waves owns one contiguous range of keys, each
-// wave a quarter of it, walked in chunks of 64 keys whose loads are all issued before any of them
-// is used (the work per (sequence, head) is small: memory-level parallelism, not arithmetic, sets
-// the speed).  Per group of 16 keys the K fragments go straight from global memory into
-// v_mfma_f32_16x16x32_f16 (the query replicated over the 16 columns), so the q.k reduction costs
-// no cross-lane traffic; every lane of group G = lane/16 then holds the scores of keys 4G..4G+3
-// and multiplies them into its own 16-byte slice of those keys' V rows.
-// The padding offset is the loop bound: slots >= n_b are never read.
+// grid = (splits, heads, batch); a workgroup of NW waves owns one contiguous range of keys and
+// walks it in blocks of BK keys dealt round-robin to the waves, so the waves stream one
+// region together.  The work per (sequence, head) is small and has no reuse: what sets the speed
+// is memory-level parallelism and the number of instructions a wave issues, not arithmetic, so
+// there is no MFMA here.  A key row (d halves) is spread over d/8 adjacent lanes, 16 bytes each:
+// every load instruction reads 1 KB of contiguous cache (whole 128-byte lines), K and V rows are
+// addressed by the same 32-bit offset, and the loads of block i+1 are issued before block i is
+// consumed.  q.k is four 2-way dot instructions per lane plus a lane-exchange reduction inside
+// the row's lanes; every lane then owns the softmax weight of its key and multiplies it into its
+// own 8 values of that key's V row.  Each group of d/8 lanes keeps its own running (max, sum,
+// values) over the keys it has seen (rescaled once per block); groups, then waves, are merged at
+// the end.  The padding offset is the loop bound: slots >= n_b are never used (the tail of the
+// last block re-reads the last valid row with weight zero).
 //
 // With more than one range per (sequence, head) each workgroup writes a partial (max, sum,
 // values) and attn_decode_combine merges them.
-template <int D>
-__global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
-    constexpr int CH = D / 8;            // 16-byte chunks per row (16 or 8)
-    constexpr int VR = CH == 16 ? 4 : 2; // V rows per lane per group of 16 keys
-    constexpr int KF = D / 32;           // K fragments per group
-    constexpr int U = 4;                 // groups in flight per wave
-    __shared__ float sm_m[4], sm_l[4];
-    __shared__ float sm_acc[4][D];
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_decode(AttnDecodeArgs a) {
+    constexpr int LPK = D / 8;           // lanes per key row (8 or 16)
+    constexpr int KPI = 64 / LPK;        // key rows per load instruction (8 or 4)
+    constexpr int U = 8;                 // load instructions (of K, and of V) per block
+    constexpr int BK = U * KPI;          // keys per block (64 or 32)
+    constexpr float kEmpty = -1e30f;     // running maximum before any key: finite, so exp2(m - m) is 1, not NaN
+    __shared__ float sm_m[NW], sm_l[NW];
+    __shared__ float sm_acc[NW][D];
 
     const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int fr = lane & 15, G = lane >> 4;
+    const int kslot = lane / LPK, chunk = lane % LPK;
     const int n = a.lens[b] + a.len_bias;                // visible keys
     const int splits = a.splits;
     int per = (n + splits - 1) / splits;
@@ -246,130 +257,117 @@ __global__ __launch_bounds__(256) void attn_decode(AttnDecodeArgs a) {
     const int c0 = sp * per;
     const int c1 = (c0 + per < n) ? c0 + per : n;        // may be <= c0: empty range of a short sequence
     const int64_t bh = (int64_t)b * a.heads + g;
-    const half_t* kbase = a.k_cache + bh * a.capacity * D;
-    const half_t* vbase = a.v_cache + bh * a.capacity * D;
+    // uniform bases + one 32-bit per-lane byte offset shared by the K and the V load of a row
+    const char* kbase = reinterpret_cast<const char*>(a.k_cache + bh * a.capacity * D);
+    const char* vbase = reinterpret_cast<const char*>(a.v_cache + bh * a.capacity * D);
+    const uint32_t lane_off = (uint32_t)chunk * 16u;
 
-    // this wave's quarter of the range
-    int pw = (c1 - c0 + 3) / 4;
-    pw = pw > 0 ? (pw + 15) & ~15 : 0;
-    const int w0 = c0 + wave * pw;
-    const int w1 = (w0 + pw < c1) ? w0 + pw : c1;
-
-    half8v qf[KF];
+    const half8v qv = *reinterpret_cast<const half8v*>(a.q + bh * D + chunk * 8);
+    half2v q2[4];
 #pragma unroll
-    for (int kk = 0; kk < KF; ++kk) qf[kk] = *reinterpret_cast<const half8v*>(a.q + bh * D + kk * 32 + G * 8);
+    for (int e = 0; e < 4; ++e) q2[e] = half2v{qv[2 * e], qv[2 * e + 1]};
 
-    const bool hi = (CH == 8) && fr >= 8;                            // d = 64: lanes 8..15 of a group take rows 4G+2, 4G+3
-    const int vc = fr % CH, vr0 = hi ? 2 : 0;                        // V slice of this lane: chunk vc, rows 4G+vr0+r
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    float m = kEmpty, l = 0.f;
     const float c = rsqrtf((float)D) * kLog2e;
 
-    // One chunk = 16*U keys.  The loads of chunk i+1 are issued before chunk i is consumed (two
-    // register buffers, loop unrolled by two); rows past the range are clamped to its last row, so
-    // the look-ahead needs no branch and the in-order load counter never waits on the newer chunk.
-    auto request = [&](half8v (&kf)[U][KF], half8v (&vf)[U][VR], int j0) {
+    auto request = [&](half8v (&kf)[U], half8v (&vf)[U], int j0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int jk = j0 + 16 * u + fr;
-            jk = jk < w1 ? jk : w1 - 1;                   // masked in consume()
-            jk = jk > 0 ? jk : 0;
-#pragma unroll
-            for (int kk = 0; kk < KF; ++kk)
-                kf[u][kk] = *reinterpret_cast<const half8v*>(kbase + (int64_t)jk * D + kk * 32 + G * 8);
-#pragma unroll
-            for (int r = 0; r < VR; ++r) {
-                int jv = j0 + 16 * u + 4 * G + vr0 + r;
-                jv = jv < w1 ? jv : w1 - 1;
-                jv = jv > 0 ? jv : 0;
-                vf[u][r] = *reinterpret_cast<const half8v*>(vbase + (int64_t)jv * D + vc * 8);
-            }
+            int row = j0 + u * KPI + kslot;
+            row = row < c1 ? row : c1 - 1;                // weight zero in consume()
+            const uint32_t off = (uint32_t)row * (uint32_t)(D * 2) + lane_off;
+            kf[u] = *reinterpret_cast<const half8v*>(kbase + off);
+            vf[u] = *reinterpret_cast<const half8v*>(vbase + off);
         }
     };
-    auto consume = [&](const half8v (&kf)[U][KF], const half8v (&vf)[U][VR], int j0) {
-        float t[U][4], gmax = -INFINITY;
+    auto consume = [&](const half8v (&kf)[U], const half8v (&vf)[U], int j0) {
+        float sc[U], mx = kEmpty;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float4v s = {0.f, 0.f, 0.f, 0.f};
+            float d = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KF; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[u][kk], qf[kk], s, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                t[u][r] = (j0 + 16 * u + 4 * G + r < w1) ? s[r] * c : -INFINITY;
-                gmax = fmaxf(gmax, t[u][r]);
-            }
+            for (int e = 0; e < 4; ++e) d = __builtin_amdgcn_fdot2(half2v{kf[u][2 * e], kf[u][2 * e + 1]}, q2[e], d, false);
+            d += dpp_f<0xb1>(d);                          // lane ^ 1
+            d += dpp_f<0x4e>(d);                          // lane ^ 2
+            d += dpp_f<0x141>(d);                         // the other quad of 8
+            if (LPK == 16) d += dpp_f<0x140>(d);          // the other half of 16
+            sc[u] = (j0 + u * KPI + kslot < c1) ? d * c : -INFINITY;
+            mx = fmaxf(mx, sc[u]);
         }
-        gmax = fmaxf(gmax, __shfl_xor(gmax, 16, kWave));
-        gmax = fmaxf(gmax, __shfl_xor(gmax, 32, kWave));
-        const float m_new = fmaxf(m, gmax);               // finite: key j0 is inside the range
-        const float alpha = exp2f(m - m_new);
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         l *= alpha;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] *= alpha;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float p[4];
+            const float p = __builtin_amdgcn_exp2f(sc[u] - m_new);
+            l += p;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) p[r] = exp2f(t[u][r] - m_new);
-            l += (p[0] + p[1]) + (p[2] + p[3]);
-            // weights of this lane's V rows: rows 4G..4G+3 (d = 128) or the row pair picked by hi (d = 64)
-            float pv[VR];
-            if (CH == 16) {
-#pragma unroll
-                for (int r = 0; r < VR; ++r) pv[r] = p[r];
-            } else {
-                pv[0] = hi ? p[2] : p[0];
-                pv[1 % VR] = hi ? p[3] : p[1];
-            }
-#pragma unroll
-            for (int r = 0; r < VR; ++r) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] += pv[r] * (float)vf[u][r][e];
-            }
+            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(p, (float)vf[u][e], acc[e]);
         }
         m = m_new;
     };
-    half8v kA[U][KF], vA[U][VR], kB[U][KF], vB[U][VR];
-    if (w0 < w1) {
-        request(kA, vA, w0);
-        for (int j0 = w0; j0 < w1; j0 += 32 * U) {
-            request(kB, vB, j0 + 16 * U);
+    // blocks wave, wave + 4, ... of the range; two register buffers, loop unrolled by two
+    half8v kA[U], vA[U], kB[U], vB[U];
+    int j0 = c0 + wave * BK;
+    if (j0 < c1) {
+        request(kA, vA, j0);
+        while (true) {
+            request(kB, vB, j0 + NW * BK);                 // past the range: the last row again, never consumed
             __builtin_amdgcn_sched_barrier(0);            // keep the look-ahead loads ahead of the arithmetic
             consume(kA, vA, j0);
-            if (j0 + 16 * U >= w1) break;
-            request(kA, vA, j0 + 32 * U);
+            j0 += NW * BK;
+            if (j0 >= c1) break;
+            request(kA, vA, j0 + NW * BK);
             __builtin_amdgcn_sched_barrier(0);
-            consume(kB, vB, j0 + 16 * U);
+            consume(kB, vB, j0);
+            j0 += NW * BK;
+            if (j0 >= c1) break;
         }
     }
-    // fold the lane groups: keys were spread over G (and over the two row pairs when d = 64)
+    // merge the KPI lane groups of the wave: common maximum, rescale, sum
+    float mw = m;
+    if (LPK == 8) mw = fmaxf(mw, dpp_f<0x128>(mw));      // lane ^ 8 (rotate the row of 16 by 8)
+    mw = fmaxf(mw, __shfl_xor(mw, 16, kWave));
+    mw = fmaxf(mw, __shfl_xor(mw, 32, kWave));
+    {
+        const float r = __builtin_amdgcn_exp2f(m - mw);
+        l *= r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= r;
+    }
+    if (LPK == 8) l += dpp_f<0x128>(l);
     l += __shfl_xor(l, 16, kWave);
     l += __shfl_xor(l, 32, kWave);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
+        if (LPK == 8) acc[e] += dpp_f<0x128>(acc[e]);
         acc[e] += __shfl_xor(acc[e], 16, kWave);
         acc[e] += __shfl_xor(acc[e], 32, kWave);
-        if (CH == 8) acc[e] += __shfl_xor(acc[e], 8, kWave);
     }
-    if (lane < CH) {
+    if (lane < LPK) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) sm_acc[wave][lane * 8 + e] = acc[e];
     }
     if (lane == 0) {
-        sm_m[wave] = m;
+        sm_m[wave] = mw;
         sm_l[wave] = l;
     }
     __syncthreads();
-    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));   // -inf only for an empty range
-    float Lsum = 0.f, A = 0.f;
-    if (tid < D && M > -INFINITY) {
+    float M = sm_m[0];                                   // kEmpty only for an empty range
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float sc = exp2f(sm_m[w] - M);                               // idle wave: exp2(-inf) = 0
-            Lsum += sm_l[w] * sc;
-            A += sm_acc[w][tid] * sc;
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w]);
+    float Lsum = 0.f, A = 0.f;
+    if (tid < D) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float r = __builtin_amdgcn_exp2f(sm_m[w] - M);              // idle wave: sum and values are zero
+            Lsum += sm_l[w] * r;
+            A += sm_acc[w][tid] * r;
         }
     }
     if (splits == 1) {
@@ -439,8 +437,8 @@ size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits) {
 
 hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s) {
     const dim3 grid(a.splits, a.heads, a.batch), block(256);
-    if (a.d == 128) hipLaunchKernelGGL(attn_decode<128>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(attn_decode<64>, grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((attn_decode<128, 4>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((attn_decode<64, 4>), grid, block, 0, s, a);
     if (a.splits > 1) {
         const int pairs = a.batch * a.heads;
         if (a.d == 128) hipLaunchKernelGGL(attn_decode_combine<128>, dim3((pairs + 1) / 2), dim3(256), 0, s, a);
