@@ -910,6 +910,143 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 }
 
 // --------------------------------------------------------------------------------------------
+// weight streaming for large layers (M <= 16 rows, tens of MB to GBs of weights per projection)
+// --------------------------------------------------------------------------------------------
+// Same data path as gemm_flat (whole-line loads, MFMA layout made in wave-private LDS staging
+// areas, no barrier inside the K loop), but K is a loop and the activations do not fit in LDS:
+//   * a workgroup of 4 waves owns 16*NF output columns; groups of UQ = 4 units (256 K values,
+//     512 contiguous bytes of every weight row) are dealt round-robin to the waves;
+//   * a wave loads, per group, NF*UQ*2 instructions of weights and UQ*XH of activations (the
+//     16 x 64 activation unit has the shape of a weight unit and takes the same road through the
+//     staging areas; XH = 1 when M <= 8), for group i+1 before group i is consumed (two register
+//     buffers); the scalar base pointers advance by one stride per group, so a load costs no
+//     vector arithmetic at all;
+//   * the four partial tiles are summed through LDS once, at the end.
+template <int NF, int EPI, int XH>
+__global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
+    constexpr int UQ = 4;                                   // units per group
+    constexpr int AREAS = UQ * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
+    extern __shared__ __attribute__((aligned(16))) unsigned char stream_smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 15, G = lane >> 4;
+    const int wrow = lane >> 3, wchunk = lane & 7;
+    const int n0 = blockIdx.x * (16 * NF);
+    const int M = a.M, N = a.N, K = a.K;
+    const int ngroups = K / (64 * UQ);
+    half_t* wst = reinterpret_cast<half_t*>(stream_smem) + wave * (AREAS * 16 * kFlatStageRow);
+    float* red = reinterpret_cast<float*>(stream_smem);
+
+    if (a.bump_lens != nullptr && blockIdx.x == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
+
+    // epilogue operands of the 64*NF threads that write the 16 x 16*NF outputs
+    const int eml = tid / (4 * NF), enl = (tid % (4 * NF)) * 4, en = n0 + enl;
+    const bool writer = tid < 64 * NF && eml < M && en < N;
+    EpiOperands eo;
+    if (writer) epilogue_fetch<EPI>(a, eml, en, eo);
+
+    // per-lane byte offsets inside a group (loop invariant); the group itself moves the scalar base
+    uint32_t woff[NF][2], xoff[XH];
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int wr = n0 + 16 * f + 8 * h + wrow;
+            wr = wr < N ? wr : N - 1;
+            woff[f][h] = ((uint32_t)(wr - n0) * (uint32_t)K + wchunk * 8) * 2u;
+        }
+#pragma unroll
+    for (int h = 0; h < XH; ++h) {
+        int xr = 8 * h + wrow;
+        xr = xr < M ? xr : M - 1;
+        xoff[h] = ((uint32_t)xr * (uint32_t)K + wchunk * 8) * 2u;
+    }
+    const char* wbase = reinterpret_cast<const char*>(a.w) + (size_t)n0 * K * 2;
+    const char* xbase = reinterpret_cast<const char*>(a.x);
+
+    half8v wA[UQ][NF][2], xA[UQ][XH], wB[UQ][NF][2], xB[UQ][XH];
+    auto request = [&](half8v (&wr)[UQ][NF][2], half8v (&xr)[UQ][XH], int g) {
+        g = g < ngroups ? g : ngroups - 1;                    // look-ahead past the end: a valid group, never consumed
+        const char* wg = wbase + (size_t)g * (UQ * 128);
+        const char* xg = xbase + (size_t)g * (UQ * 128);
+#pragma unroll
+        for (int q = 0; q < UQ; ++q) {
+#pragma unroll
+            for (int h = 0; h < XH; ++h) xr[q][h] = *reinterpret_cast<const half8v*>(xg + xoff[h] + q * 128);
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) wr[q][f][h] = *reinterpret_cast<const half8v*>(wg + woff[f][h] + q * 128);
+        }
+    };
+    float4v acc[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) acc[f] = float4v{0.f, 0.f, 0.f, 0.f};
+    const uint32_t st_w = (uint32_t)(wrow * kFlatStageRow + wchunk * 8);     // staging write (halves)
+    const uint32_t st_r = (uint32_t)(fr * kFlatStageRow + G * 8);            // staging read
+    auto consume = [&](const half8v (&wr)[UQ][NF][2], const half8v (&xr)[UQ][XH]) {
+        // area (q*(NF+1) + 0) holds the activation unit q, areas +1.. the weight units
+#pragma unroll
+        for (int q = 0; q < UQ; ++q) {
+#pragma unroll
+            for (int h = 0; h < XH; ++h)
+                *reinterpret_cast<half8v*>(&wst[st_w + ((q * (NF + 1)) * 16 + 8 * h) * kFlatStageRow]) = xr[q][h];
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    *reinterpret_cast<half8v*>(&wst[st_w + ((q * (NF + 1) + 1 + f) * 16 + 8 * h) * kFlatStageRow]) = wr[q][f][h];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < UQ; ++q)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                // rows 8..15 of the activation area are stale when XH = 1: those outputs are never written
+                const half8v xf = *reinterpret_cast<const half8v*>(&wst[st_r + (q * (NF + 1)) * 16 * kFlatStageRow + 32 * u]);
+#pragma unroll
+                for (int f = 0; f < NF; ++f) {
+                    const half8v wf = *reinterpret_cast<const half8v*>(&wst[st_r + (q * (NF + 1) + 1 + f) * 16 * kFlatStageRow + 32 * u]);
+                    acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf, acc[f], 0, 0, 0);
+                }
+            }
+        __builtin_amdgcn_wave_barrier();
+    };
+    int g = wave;
+    if (g < ngroups) {
+        request(wA, xA, g);
+        while (true) {
+            request(wB, xB, g + 4);
+            __builtin_amdgcn_sched_barrier(0);                // keep the look-ahead loads ahead of the arithmetic
+            consume(wA, xA);
+            g += 4;
+            if (g >= ngroups) break;
+            request(wA, xA, g + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(wB, xB);
+            g += 4;
+            if (g >= ngroups) break;
+        }
+    }
+    // acc[f][r]: output column n0 + 16f + 4G + r, row fr.  The partial tiles go over the staging
+    // space, which other waves may still be reading as theirs: barrier first.
+    __syncthreads();
+    constexpr int RT = 16 * (16 * NF + 4);                    // floats per wave tile: [16 rows][16*NF + 4]
+#pragma unroll
+    for (int f = 0; f < NF; ++f) *reinterpret_cast<float4v*>(&red[wave * RT + fr * (16 * NF + 4) + 16 * f + 4 * G]) = acc[f];
+    __syncthreads();
+    if (writer) {
+        const float* rp = &red[eml * (16 * NF + 4) + enl];
+        float4v v = *reinterpret_cast<const float4v*>(rp);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float4v pw = *reinterpret_cast<const float4v*>(rp + w * RT);
+            v[0] += pw[0]; v[1] += pw[1]; v[2] += pw[2]; v[3] += pw[3];
+        }
+        epilogue_apply<EPI>(a, eml, en, v[0], v[1], v[2], v[3], eo);
+    }
+}
+
+// --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN>
@@ -1031,11 +1168,37 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     return true;
 }
 
+template <int NF, int XH>
+static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const dim3 grid(a.N / (16 * NF)), block(256);
+    const int lds = 4 * 4 * (NF + 1) * 16 * kFlatStageRow * 2;
+    switch (epi) {
+        case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH>, a, grid, block, lds, s); break;
+        case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH>, a, grid, block, lds, s); break;
+        case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH>, a, grid, block, lds, s); break;
+    }
+}
+// true when the streaming kernel took the problem: K a multiple of 256, whole column tiles, no LayerNorm
+static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    static const bool off = getenv("EET_NO_STREAM") != nullptr;
+    if (off || a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
+    if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
+    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU
+    if (a.M <= 8) {
+        if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
+    } else {
+        if (wide) launch_stream<2, 2>(a, epi, s); else launch_stream<1, 2>(a, epi, s);
+    }
+    return true;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
     if (a.M <= 16) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
         if (try_flat(a, epi, s)) return hipGetLastError();
+        if (try_stream(a, epi, s)) return hipGetLastError();
         if (a.N >= 64 * 1024) launch_skinny_cfg<4>(a, epi, s);
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);
