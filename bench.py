@@ -151,22 +151,28 @@ def _kernel_candidates(stack, torch, eet, reps):
             eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // nl) % len(ks)], scratch)
         n = nl * len(ks)
         ms = time_launches(torch, run_attn, n * max(1, reps // n))
-        out.append({"kernel": f"attn_decode<{d}> (+ range merge when split): decode attention over the K/V cache",
+        out.append({"kernel": f"attn_decode<{d}, 4> (+ attn_decode_combine when the key range is split): decode attention over the K/V cache",
                     "bound": "hbm", "work": sum(bytes_k) / len(bytes_k), "ms": ms,
                     "launches": w.decode_steps * nl})
-        # (2) decode projection (weight stream): FFN-1, the largest of the four
-        x = torch.randn(B, H, device="cuda:0").half()
-        y = torch.empty(B, F, device="cuda:0", dtype=torch.float16)
-        st2 = {"i": 0}
+        # (2) decode projections (weight stream) that have an operator-level twin: FFN-2 + bias +
+        # residual and the attention output projection + bias + residual.  (The QKV and FFN-1
+        # launches of small layers carry a fused LayerNorm and exist only inside the layer call.)
+        def projection(name, wkey, bkey, n_out, n_in):
+            x = torch.randn(B, n_in, device="cuda:0").half()
+            r = torch.randn(B, n_out, device="cuda:0").half()
+            y = torch.empty(B, n_out, device="cuda:0", dtype=torch.float16)
+            st2 = {"i": 0}
 
-        def run_ffn1():
-            wts = stack.weights(st2["i"] % nl)
-            st2["i"] += 1
-            eet.eet_op_linear(x, wts["w_fc1"], wts["b_fc1"], y, act=1)
-        ms = time_launches(torch, run_ffn1, nl * max(1, reps // nl))
-        out.append({"kernel": "gemm_skinny: FFN-1 projection + bias + GELU, decode (weight stream)", "bound": "hbm",
-                    "work": 2.0 * (F * H + B * H + F + B * F), "ms": ms,
-                    "launches": w.decode_steps * nl * (12 * H * H) / (H * F)})   # launches scaled to all 4 projections by bytes
+            def run():
+                wts = stack.weights(st2["i"] % nl)
+                st2["i"] += 1
+                eet.eet_op_linear(x, wts[wkey], wts[bkey], y, residual=r)
+            ms = time_launches(torch, run, nl * max(1, reps // nl))
+            out.append({"kernel": f"decode {name} + bias + residual (weight stream, M = {B} rows)", "bound": "hbm",
+                        "work": 2.0 * (n_out * n_in + B * n_in + n_out + 2 * B * n_out), "ms": ms,
+                        "launches": w.decode_steps * nl})
+        projection("FFN-2 projection", "w_fc2", "b_fc2", H, F)
+        projection("attention output projection", "w_o", "b_o", H, H)
     # (3) prefill projection on the matrix cores: FFN-1 over all valid tokens
     xp = torch.randn(T, H, device="cuda:0").half()
     yp = torch.empty(T, F, device="cuda:0", dtype=torch.float16)
@@ -177,8 +183,8 @@ def _kernel_candidates(stack, torch, eet, reps):
         st3["i"] += 1
         eet.eet_op_linear(xp, wts["w_fc1"], wts["b_fc1"], yp, act=1)
     ms = time_launches(torch, run_pre, max(4, min(reps, 24)), replays=2)
-    out.append({"kernel": "gemm_mfma: FFN-1 projection + bias + GELU, prefill (matrix cores)", "bound": "mfma",
-                "work": 2.0 * T * H * F, "ms": ms, "launches": nl * (12 * H * H) / (H * F)})
+    out.append({"kernel": "prefill FFN-1 projection + bias + GELU (MFMA tile kernel)", "bound": "mfma",
+                "work": 2.0 * T * H * F, "ms": ms, "launches": nl})
     # (4) prefill attention: QK^T and PV over the valid causal triangle of every sequence
     qp = torch.randn(B, w.padded_len, H, device="cuda:0").half()
     cp = torch.empty_like(qp)

@@ -920,12 +920,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 //     16 x 64 activation unit has the shape of a weight unit and takes the same road through the
 //     staging areas; XH = 1 when M <= 8), for group i+1 before group i is consumed (two register
 //     buffers); the scalar base pointers advance by one stride per group, so a load costs no
-//     vector arithmetic at all;
+//     vector arithmetic at all; a group is staged two units at a time, which keeps the staging
+//     space small enough for two workgroups per CU;
 //   * the four partial tiles are summed through LDS once, at the end.
+constexpr int kStreamStagedUnits = 2;
+
 template <int NF, int EPI, int XH>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     constexpr int UQ = 4;                                   // units per group
-    constexpr int AREAS = UQ * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
+    constexpr int SU = kStreamStagedUnits;                  // units staged at a time
+    constexpr int AREAS = SU * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
     extern __shared__ __attribute__((aligned(16))) unsigned char stream_smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, G = lane >> 4;
@@ -984,32 +988,35 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     const uint32_t st_w = (uint32_t)(wrow * kFlatStageRow + wchunk * 8);     // staging write (halves)
     const uint32_t st_r = (uint32_t)(fr * kFlatStageRow + G * 8);            // staging read
     auto consume = [&](const half8v (&wr)[UQ][NF][2], const half8v (&xr)[UQ][XH]) {
-        // area (q*(NF+1) + 0) holds the activation unit q, areas +1.. the weight units
+        // area (j*(NF+1) + 0) holds the activation unit j of the round, areas +1.. its weight units
 #pragma unroll
-        for (int q = 0; q < UQ; ++q) {
+        for (int q0 = 0; q0 < UQ; q0 += SU) {
 #pragma unroll
-            for (int h = 0; h < XH; ++h)
-                *reinterpret_cast<half8v*>(&wst[st_w + ((q * (NF + 1)) * 16 + 8 * h) * kFlatStageRow]) = xr[q][h];
+            for (int j = 0; j < SU; ++j) {
 #pragma unroll
-            for (int f = 0; f < NF; ++f)
+                for (int h = 0; h < XH; ++h)
+                    *reinterpret_cast<half8v*>(&wst[st_w + ((j * (NF + 1)) * 16 + 8 * h) * kFlatStageRow]) = xr[q0 + j][h];
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    *reinterpret_cast<half8v*>(&wst[st_w + ((q * (NF + 1) + 1 + f) * 16 + 8 * h) * kFlatStageRow]) = wr[q][f][h];
-        }
-        __builtin_amdgcn_wave_barrier();
+                for (int f = 0; f < NF; ++f)
 #pragma unroll
-        for (int q = 0; q < UQ; ++q)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                // rows 8..15 of the activation area are stale when XH = 1: those outputs are never written
-                const half8v xf = *reinterpret_cast<const half8v*>(&wst[st_r + (q * (NF + 1)) * 16 * kFlatStageRow + 32 * u]);
-#pragma unroll
-                for (int f = 0; f < NF; ++f) {
-                    const half8v wf = *reinterpret_cast<const half8v*>(&wst[st_r + (q * (NF + 1) + 1 + f) * 16 * kFlatStageRow + 32 * u]);
-                    acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf, acc[f], 0, 0, 0);
-                }
+                    for (int h = 0; h < 2; ++h)
+                        *reinterpret_cast<half8v*>(&wst[st_w + ((j * (NF + 1) + 1 + f) * 16 + 8 * h) * kFlatStageRow]) = wr[q0 + j][f][h];
             }
-        __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < SU; ++j)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    // rows 8..15 of the activation area are stale when XH = 1: those outputs are never written
+                    const half8v xf = *reinterpret_cast<const half8v*>(&wst[st_r + (j * (NF + 1)) * 16 * kFlatStageRow + 32 * u]);
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) {
+                        const half8v wf = *reinterpret_cast<const half8v*>(&wst[st_r + (j * (NF + 1) + 1 + f) * 16 * kFlatStageRow + 32 * u]);
+                        acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf, acc[f], 0, 0, 0);
+                    }
+                }
+            __builtin_amdgcn_wave_barrier();
+        }
     };
     int g = wave;
     if (g < ngroups) {
@@ -1171,7 +1178,7 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 template <int NF, int XH>
 static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const dim3 grid(a.N / (16 * NF)), block(256);
-    const int lds = 4 * 4 * (NF + 1) * 16 * kFlatStageRow * 2;
+    const int lds = 4 * kStreamStagedUnits * (NF + 1) * 16 * kFlatStageRow * 2;
     switch (epi) {
         case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH>, a, grid, block, lds, s); break;
         case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH>, a, grid, block, lds, s); break;
@@ -1184,7 +1191,8 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     static const bool off = getenv("EET_NO_STREAM") != nullptr;
     if (off || a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
     if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
-    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU
+    static const int wide_at = getenv("EET_STREAM_WIDE") ? atoi(getenv("EET_STREAM_WIDE")) : 1024;
+    const bool wide = a.N / 32 >= wide_at;                       // 32 columns per workgroup once that still leaves four workgroups per CU
     if (a.M <= 8) {
         if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
     } else {
