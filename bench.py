@@ -197,6 +197,25 @@ def _kernel_candidates(stack, torch, eet, reps):
     ms = time_launches(torch, run_pattn, max(4, min(reps, 24)), replays=2)
     out.append({"kernel": f"attn_prefill<{d}>: causal, padding-skipping prefill attention (matrix cores)",
                 "bound": "mfma", "work": sum(2.0 * H * L * (L + 1) for L in stack.lens), "ms": ms, "launches": nl})
+    # (5) LayerNorm over the valid rows of the prompt (row kernel, HBM bound): read + write of every row
+    xl = torch.randn(T, H, device="cuda:0").half()
+    yl = torch.empty_like(xl)
+    gam, bet = torch.ones(H, device="cuda:0").half(), torch.zeros(H, device="cuda:0").half()
+    ms = time_launches(torch, lambda: eet.eet_op_layernorm(xl, gam, bet, yl, w.ln_eps), max(8, min(reps, 48)), replays=2)
+    out.append({"kernel": "layernorm_cached: LayerNorm over the valid prompt rows (row kernel)", "bound": "hbm",
+                "work": 4.0 * T * H + 4.0 * H, "ms": ms, "launches": 2 * nl})
+    # (6) stand-alone mask-free softmax (Algorithm 1) over [B, heads', S, S] scores, in place: the valid
+    # causal triangle is read and written, the strip i < j < S of valid rows is zero-filled.  Not on the
+    # layer's path (the fused attention never materialises scores): measured for its own roofline row,
+    # on as many heads as fit 2 GB.
+    S = w.padded_len
+    nh = max(1, min(w.heads, int((2 << 30) // (2 * B * S * S))))
+    sc = torch.randn(B, nh, S, S, device="cuda:0").half()
+    ms = time_launches(torch, lambda: eet.eet_op_softmax_maskfree(sc, stack.lens, 0.125), 4, replays=2)
+    tri = sum(L * (L + 1) / 2 for L in stack.lens)
+    out.append({"kernel": f"softmax_maskfree_vec: stand-alone mask-free softmax (Algorithm 1), {nh} head(s), not on the layer path",
+                "bound": "hbm", "work": nh * (2.0 * 2 * tri + 2.0 * sum(L * S - L * (L + 1) / 2 for L in stack.lens)),
+                "ms": ms, "launches": 0})
     return out
 
 
@@ -278,9 +297,11 @@ def main():
 
     if a.roofline_only:
         stack.one_pass() if w.decode_steps <= 64 else stack.prefill()   # caches hold real keys/values
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        # plain copy kernel of known size under a name nothing else in the run uses: x + 0 over
+        # 256 MiB of int32 reads 256 MiB and writes 256 MiB
+        src = torch.ones(64 << 20, dtype=torch.int32, device="cuda:0")
         dst = torch.empty_like(src)
-        dst.copy_(src)                                                   # plain copy kernel of known size
+        torch.add(src, 0, out=dst)
         torch.cuda.synchronize()
         main_rec, others = roofline_for(stack, torch, eet, a.kernel_reps)
         print(json.dumps({"roofline": main_rec, "roofline_other_kernels": others, "copy_bytes": 256 << 20}))
