@@ -23,6 +23,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
 
+# HBM bytes per launch from the last `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of
+# `bench.py --roofline-only` (counters scaled by the plain copy kernel of the same run: x 2.000 and
+# x 1.000; summary in profiles/cfg2_hbm_traffic_counters.txt), keyed by workload and by the start of
+# the record's kernel name.  Workloads that were not profiled report null.
+MEASURED_TRAFFIC = {
+    "cfg2": {
+        "attn_decode<64, 4>": 21.45e6,
+        "decode FFN-2 projection": 9.14e6,
+        "decode attention output projection": 2.36e6,
+        "prefill FFN-1 projection": 80.61e6,
+        "attn_prefill<64>": 46.32e6,
+        "layernorm_cached": 12.99e6,
+        "softmax_maskfree_vec": 75.64e6,
+    },
+}
+
 
 def parse():
     p = argparse.ArgumentParser()
@@ -222,13 +238,16 @@ def _kernel_candidates(stack, torch, eet, reps):
 def roofline_for(stack, torch, eet, reps):
     """Roofline record of the dominant kernel (largest share of the pass) and of the others."""
     recs = []
+    measured = MEASURED_TRAFFIC.get(stack.w.name, {})
     for c in _kernel_candidates(stack, torch, eet, reps):
         if c["bound"] == "hbm":
             ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
             ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e12, MFMA_FP16_PEAK_TFLOPS, "TFLOP/s"
         recs.append({"kernel": c["kernel"], "bound": c["bound"], "achieved": ach, "peak": peak, "unit": unit,
-                     "frac": ach / peak, "traffic": None, "avg_launch_us": c["ms"] * 1e3,
+                     "frac": ach / peak,
+                     "traffic": next((v for k, v in measured.items() if c["kernel"].startswith(k)), None),
+                     "avg_launch_us": c["ms"] * 1e3,
                      "algorithmic_work_per_launch": c["work"], "share_ms_per_pass": c["ms"] * c["launches"]})
     recs.sort(key=lambda r: -r["share_ms_per_pass"])
     return recs[0], recs[1:]
