@@ -5,14 +5,15 @@
 // (Section 3.2: "kernels are not always fused, especially ... GEMM calls").  Here the epilogue
 // runs on the accumulators, so the intermediate never visits HBM.
 //
-// Two kernels:
-//   gemm_mfma    prefill (M = valid tokens of the batch, packed): LDS-tiled, v_mfma_f32_32x32x16_f16,
-//                double-buffered LDS with register prefetch; bound by the matrix cores.
-//   gemm_skinny  decode (M <= 16 rows): every weight is read from HBM exactly once per step, so the
-//                kernel is a weight stream; v_mfma_f32_16x16x32_f16 does the 16-row contraction on
-//                fragments loaded straight from global memory, K is split over the 4 waves of a
-//                workgroup and reduced through LDS.
-// Both compute the transposed tile (weights as the MFMA "A" operand) so that each lane ends up
+// Kernels:
+//   gemm_mfma_dma64  prefill (M = valid tokens of the batch, packed), large problems: 256x256 tiles,
+//                    direct global->LDS loads, v_mfma_f32_32x32x16_f16; bound by the matrix cores.
+//   gemm_mfma        prefill, small problems: 128x128 register-staged tiles.
+//   gemm_flat        decode (M <= 16 rows), small layers: one memory round trip, few instructions.
+//   gemm_stream      decode, large layers: every weight is read from HBM exactly once per step, so
+//                    the kernel is a weight stream; v_mfma_f32_16x16x32_f16 does the 16-row contraction.
+//   gemm_skinny      decode, shapes the two above do not take.
+// All compute the transposed tile (weights as the MFMA "A" operand) so that each lane ends up
 // with 4 consecutive output columns of one row: 8-byte stores, and 8-byte bias/residual loads.
 #include <cstdlib>
 #include <mutex>
@@ -215,23 +216,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
 // --------------------------------------------------------------------------------------------
 // MFMA tile kernel with direct global->LDS loads
 // --------------------------------------------------------------------------------------------
-// 256x256 tile, WGM x WGN waves, K steps of 32 through a ring of four LDS stages filled by
-// global_load_lds_dwordx4 (no staging registers, no ds_write): the loads of K step kt+3 are in
-// flight while step kt is multiplied.  An LDS row is the 64 bytes of one operand row; a wave-level
-// load deposits 16 rows contiguously, so instead of padding, the four 16-byte chunks of a row are
-// XOR-permuted by (row/4)%4 -- applied on the global address of each lane when loading and on the
-// LDS address when reading fragments -- which spreads any 16 consecutive rows over all 64 banks.
-// MFMA fragments are double-buffered in registers: the reads of the next half-step are issued
+// 256x256 tile, WGM x WGN waves, K steps of 64 through two LDS stages filled by
+// global_load_lds_dwordx4 (no staging registers, no ds_write): the loads of K step kt+1 are issued
+// at the start of step kt.  An LDS row is the 128 bytes of one operand row, and a wave-level load
+// covers 8 rows x 128 bytes, i.e. whole cache lines.  Instead of padding, the eight 16-byte chunks
+// of a row are XOR-permuted by (row/2)%8 -- applied on the global address of each lane when loading
+// and on the LDS address when reading fragments -- which spreads consecutive rows over all banks.
+// MFMA fragments are double-buffered in registers: the reads of the next quarter-step are issued
 // before the MFMAs of the current one.
 //
 // Fragment reads and every wait in the main loop are inline assembly / raw builtins.  The compiler
 // cannot tell that an LDS read does not alias an in-flight global->LDS load and would otherwise
 // drain all of them (vmcnt(0)) before each read and before each barrier, which undoes the pipeline.
-#ifndef EET_DBG_DMA
-#define EET_DBG_DMA 1      // 0: timing experiment without the steady-state loads (wrong results)
-#endif
-constexpr int kDK = 32;
-constexpr int kDStages = 4;
 
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds + 16*l (the LDS
 // base must be wave-uniform).  Kept out of the templates: the builtin only exists for the device.
@@ -254,164 +250,6 @@ __device__ __forceinline__ void wait_vm() {
     if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
 }
 
-template <int WGM, int WGN, int EPI>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma(GemmArgs a, int tiles_m, int tiles_n) {
-    constexpr int BM = 256, BN = 256, NW = WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
-    constexpr int LR = 256 / NW;          // rows of each operand tile a wave loads per K step
-    constexpr int LI = LR / 16;           // wave-level load instructions per operand per K step
-    constexpr int kInFlight2 = 2 * 2 * LI;   // instructions of two later K steps
-    __shared__ __attribute__((aligned(1024))) half_t As[kDStages][BM * kDK];
-    __shared__ __attribute__((aligned(1024))) half_t Ws[kDStages][BN * kDK];
-
-    int tile_m, tile_n;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-    const int M = a.M, N = a.N, K = a.K;
-    const int nk = K / kDK;
-
-    // this lane's rows of each operand tile, and the chunk it fetches for LDS position lane%4
-    const half_t* pa[LI];
-    const half_t* pw[LI];
-#pragma unroll
-    for (int v = 0; v < LI; ++v) {
-        const int row = wave * LR + v * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((row >> 2) & 3);
-        int gr = m0 + row;
-        gr = gr < M ? gr : M - 1;
-        pa[v] = a.x + (int64_t)gr * K + c * 8;
-        gr = n0 + row;
-        gr = gr < N ? gr : N - 1;
-        pw[v] = a.w + (int64_t)gr * K + c * 8;
-    }
-    // fragment addressing: row = lane%32 (+ offsets that are multiples of 32), logical chunk ks*2 + lane/32
-    const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 2) & 3;
-    const unsigned a_lds = (unsigned)(uintptr_t)&As[0][(wm0 + frow) * kDK];
-    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[0][(wn0 + frow) * kDK];
-    unsigned foff[2];
-    foff[0] = (unsigned)(((0 + fG) ^ fsw) * 16);
-    foff[1] = (unsigned)(((2 + fG) ^ fsw) * 16);
-
-    half8v fa[2][FM], fw[2][FN];
-    float16v acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-#define EET_DLOAD(T, ST)                                                                                 \
-    do {                                                                                                 \
-        _Pragma("unroll") for (int v = 0; v < LI; ++v) {                                                 \
-            load_lds_16B(pa[v] + (int64_t)(T) * kDK, &As[ST][(wave * LR + v * 16) * kDK]);               \
-            load_lds_16B(pw[v] + (int64_t)(T) * kDK, &Ws[ST][(wave * LR + v * 16) * kDK]);               \
-        }                                                                                                \
-    } while (0)
-#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
-#define EET_DFRAG(FS, ST, KS)                                                                            \
-    do {                                                                                                 \
-        const unsigned va_ = a_lds + (ST) * (BM * kDK * 2) + foff[KS];                                   \
-        const unsigned vw_ = w_lds + (ST) * (BN * kDK * 2) + foff[KS];                                   \
-        EET_DREAD(fa[FS][0], va_, 0);                                                                    \
-        if (FM > 1) EET_DREAD(fa[FS][1 % FM], va_, 2048);                                                \
-        if (FM > 2) EET_DREAD(fa[FS][2 % FM], va_, 4096);                                                \
-        if (FM > 3) EET_DREAD(fa[FS][3 % FM], va_, 6144);                                                \
-        EET_DREAD(fw[FS][0], vw_, 0);                                                                    \
-        if (FN > 1) EET_DREAD(fw[FS][1 % FN], vw_, 2048);                                                \
-        if (FN > 2) EET_DREAD(fw[FS][2 % FN], vw_, 4096);                                                \
-        if (FN > 3) EET_DREAD(fw[FS][3 % FN], vw_, 6144);                                                \
-    } while (0)
-    // wait until at most CNT LDS operations are outstanding, and tie fragment set FS to the wait
-#define EET_DWAIT(FS, CNT)                                                                               \
-    do {                                                                                                 \
-        wait_lgkm<CNT>();                                                                                \
-        _Pragma("unroll") for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[FS][i]));              \
-        _Pragma("unroll") for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[FS][j]));              \
-    } while (0)
-#define EET_DMMA(FS)                                                                                     \
-    do {                                                                                                 \
-        _Pragma("unroll") for (int i = 0; i < (EET_DBG_DMA == 3 ? 1 : FM); ++i)                          \
-            _Pragma("unroll") for (int j = 0; j < (EET_DBG_DMA == 3 ? 1 : FN); ++j)                      \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[FS][j], fa[FS][i], acc[i][j], 0, 0, 0); \
-    } while (0)
-
-    // prologue: tiles 0..2 in flight, tile 0 landed and published
-    EET_DLOAD(0, 0);
-    if (nk > 1) EET_DLOAD(1, 1);
-    if (nk > 2) EET_DLOAD(2, 2);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    EET_DFRAG(0, 0, 0);
-    int kt = 0;
-    for (; kt + 3 < nk; ++kt) {           // steady state: tiles kt+1, kt+2 in flight, kt+3 issued now
-        const int st = kt & 3, st1 = (kt + 1) & 3, st3 = (kt + 3) & 3;
-#if EET_DBG_DMA == 1 || EET_DBG_DMA == 3
-        EET_DLOAD(kt + 3, st3);
-#endif
-        EET_DFRAG(1, st, 1);
-        EET_DWAIT(0, FM + FN);                // set 0 (requested one half-step ago) is in; set 1 may be pending
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DMMA(0);
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DWAIT(1, 0);                      // all of this wave's reads of tile kt are done
-#if EET_DBG_DMA != 0
-        wait_vm<kInFlight2>();                // this wave's part of tile kt+1 has landed
-#endif
-        __builtin_amdgcn_s_barrier();         // ... and everybody else's; tile kt-1's stage is free
-        EET_DFRAG(0, st1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DMMA(1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    for (; kt < nk; ++kt) {               // drain: nothing new to issue
-        const int st = kt & 3, st1 = (kt + 1) & 3;
-        EET_DFRAG(1, st, 1);
-        EET_DWAIT(0, FM + FN);
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DMMA(0);
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DWAIT(1, 0);
-        asm volatile("s_waitcnt vmcnt(0)");
-        __builtin_amdgcn_s_barrier();
-        EET_DFRAG(0, st1, 0);                 // past the last tile this reads a stale stage; never used
-        __builtin_amdgcn_sched_barrier(0);
-        EET_DMMA(1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    EET_DWAIT(0, 0);
-#undef EET_DLOAD
-#undef EET_DREAD
-#undef EET_DFRAG
-#undef EET_DWAIT
-#undef EET_DMMA
-
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm0 + i * 32 + (lane & 31);
-        if (m >= M) continue;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int n = n0 + wn0 + j * 32 + rg * 8 + (lane >> 5) * 4;
-                if (n < N)
-                    epilogue4<EPI>(a, m, n, acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2],
-                                   acc[i][j][rg * 4 + 3]);
-            }
-        }
-    }
-}
-
-// --------------------------------------------------------------------------------------------
-// Same scheme with 128-byte rows: K steps of 64, two LDS stages
-// --------------------------------------------------------------------------------------------
-// A wave-level load covers 8 rows x 128 bytes, i.e. whole cache lines: the L2 serves one request
-// per channel per clock whatever its size, so 128-byte requests double the fetch bandwidth that
-// 64-byte rows get.  The price is LDS capacity: 64 KB per stage leaves room for two stages, so the
-// loads of step t+1 are issued at the start of step t.  Chunk permutation: (row/2)%8.
 template <int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
     constexpr int BM = 256, BN = 256, NW = WGM * WGN, BK = 64;
@@ -488,8 +326,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 #define EET_DMMA(FS)                                                                                     \
     do {                                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                               \
-        _Pragma("unroll") for (int i = 0; i < (EET_DBG_DMA == 3 ? 1 : FM); ++i)                          \
-            _Pragma("unroll") for (int j = 0; j < (EET_DBG_DMA == 3 ? 1 : FN); ++j)                      \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i)                          \
+            _Pragma("unroll") for (int j = 0; j < FN; ++j)                      \
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[FS][j], fa[FS][i], acc[i][j], 0, 0, 0); \
         __builtin_amdgcn_sched_barrier(0);                                                               \
     } while (0)
@@ -500,11 +338,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
     EET_DFRAG(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
         const int st = kt & 1;
-        if (kt + 1 < nk) {
-#if EET_DBG_DMA != 0
-            EET_DLOAD(kt + 1, st ^ 1);        // stage st^1 was released by the barrier of the previous step
-#endif
-        }
+        if (kt + 1 < nk) EET_DLOAD(kt + 1, st ^ 1);   // stage st^1 was released by the barrier of the previous step
         EET_DFRAG(1, st, 1);
         EET_DWAIT(0, FM + FN);
         EET_DMMA(0);
@@ -1069,18 +903,6 @@ static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 }
 
 template <int WGM, int WGN>
-static void launch_dma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
-    const dim3 grid(tm * tn), block(WGM * WGN * 64);
-    switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma<WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
-    }
-}
-
-template <int WGM, int WGN>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
     const dim3 grid(tm * tn), block(WGM * WGN * 64);
@@ -1145,10 +967,8 @@ static void launch_flat(const GemmArgs& a, int upw, Epilogue epi, int lds, hipSt
 // true when the flat kernel took the problem: a few MB of weights, K = 64 * NW * UPW with
 // NW in {4, 8, 16} and UPW in 1..4, N a multiple of 16, no row maps
 static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    static const bool off = getenv("EET_NO_FLAT") != nullptr;
-    static const int ln_nw = getenv("EET_FLAT_LN_NW") ? atoi(getenv("EET_FLAT_LN_NW")) : 8;
-    static const int tn8_wgs = getenv("EET_FLAT_TN8") ? atoi(getenv("EET_FLAT_TN8")) : 128;
-    if (off || (int64_t)a.N * a.K * 2 > (16 << 20) || a.N % 16 != 0 || a.K % 64 != 0) return false;
+    constexpr int tn8_wgs = 128;                              // fewer 16-column workgroups than this: 8-column ones
+    if ((int64_t)a.N * a.K * 2 > (16 << 20) || a.N % 16 != 0 || a.K % 64 != 0) return false;
     if (a.res_row_map != nullptr || a.out_row_map != nullptr || a.tok_row_map != nullptr) return false;
     const bool ln = a.ln_gamma != nullptr;
     const int units = a.K / 64;
@@ -1156,7 +976,7 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // fewest waves that hold K; with LN 8 waves when possible: the normalisation is vector
     // arithmetic spread over the threads
     int nw = 0;
-    if (ln && ln_nw == 8 && fits(8)) nw = 8;
+    if (ln && fits(8)) nw = 8;
     for (int cand : {4, 8, 16})
         if (nw == 0 && fits(cand)) nw = cand;
     if (nw == 0 || (ln && nw == 16)) return false;
@@ -1188,11 +1008,9 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 }
 // true when the streaming kernel took the problem: K a multiple of 256, whole column tiles, no LayerNorm
 static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    static const bool off = getenv("EET_NO_STREAM") != nullptr;
-    if (off || a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
+    if (a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
     if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
-    static const int wide_at = getenv("EET_STREAM_WIDE") ? atoi(getenv("EET_STREAM_WIDE")) : 1024;
-    const bool wide = a.N / 32 >= wide_at;                       // 32 columns per workgroup once that still leaves four workgroups per CU
+    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU                       // 32 columns per workgroup once that still leaves four workgroups per CU
     if (a.M <= 8) {
         if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
     } else {
@@ -1212,15 +1030,9 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
         // 256x256 direct-to-LDS tiles once they can fill the chip, 128x128 register-staged tiles below that
-        static const int forced = getenv("EET_GEMM_TILE") ? atoi(getenv("EET_GEMM_TILE")) : -1;
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-        const int tile = forced >= 0 ? forced : (big_tiles >= 192 ? 11 : 0);
-        switch (tile) {
-            case 2: launch_mfma_cfg<256, 256, 2, 4>(a, epi, s); break;
-            case 8: launch_dma_cfg<2, 4>(a, epi, s); break;
-            case 11: launch_dma64_cfg<2, 4>(a, epi, s); break;
-            default: launch_mfma_cfg<128, 128, 2, 2>(a, epi, s); break;
-        }
+        if (big_tiles >= 192) launch_dma64_cfg<2, 4>(a, epi, s);
+        else launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
     }
     return hipGetLastError();
 }
