@@ -134,9 +134,12 @@ def attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_keys: int) -> np.ndarr
     return o
 
 
-def attention_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_lens: Sequence[int]) -> np.ndarray:
-    """Op-level causal, padding-skipping attention.  q, k, v: [B, S, heads, d] (padded);
-    returns the context [B, S, heads, d] with pad rows zero."""
+def attention_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_lens: Sequence[int],
+                      causal: bool = True) -> np.ndarray:
+    """Op-level padding-skipping attention.  q, k, v: [B, S, heads, d] (padded); returns the
+    context [B, S, heads, d] with pad rows zero.  causal: query i sees keys 0..i (decoder);
+    otherwise every valid query sees all L_b valid keys (the encoder layer of Section 4's
+    Bert experiment: padding skip only, no sequence mask)."""
     q = np.asarray(q, F64); k = np.asarray(k, F64); v = np.asarray(v, F64)
     B, S, nh, d = q.shape
     out = np.zeros_like(q)
@@ -144,7 +147,7 @@ def attention_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_lens: Seque
         Kb = np.ascontiguousarray(k[b].transpose(1, 0, 2))
         Vb = np.ascontiguousarray(v[b].transpose(1, 0, 2))
         for i in range(int(q_lens[b])):
-            out[b, i] = attend(q[b, i], Kb, Vb, i + 1)
+            out[b, i] = attend(q[b, i], Kb, Vb, i + 1 if causal else int(q_lens[b]))
     return out
 
 
@@ -202,13 +205,15 @@ class DecoderLayerOracle:
 
     # ---- prefill ------------------------------------------------------------------------
     def prefill(self, x: np.ndarray, q_lens: Sequence[int],
-                rows: Optional[Dict[int, Iterable[int]]] = None) -> np.ndarray:
+                rows: Optional[Dict[int, Iterable[int]]] = None, causal: bool = True) -> np.ndarray:
         """Process whole prompts.  x [B, S, H]; q_lens[b] valid rows per sequence.
 
         Returns [B, S, H] float64: valid rows hold the layer output, pad rows are zero.
         With `rows` = {b: positions}, only those query rows are evaluated (the cache is
         still filled for every valid token of the listed sequences); other valid rows of
         the result are NaN, and sequences not listed are left out of the cache.
+        causal=False is the encoder use of the same layer: every valid row attends to all
+        L_b valid tokens of its sequence (see encode()).
         """
         B, S, H = x.shape
         assert H == self.H and B <= self.max_batch and S <= self.max_seq and len(q_lens) == B
@@ -234,9 +239,18 @@ class DecoderLayerOracle:
             ctx = np.empty((len(want), H), F64)
             for r, i in enumerate(want):
                 assert 0 <= i < L
-                ctx[r] = attend(q[i], self.k_cache[b], self.v_cache[b], i + 1).reshape(H)
+                ctx[r] = attend(q[i], self.k_cache[b], self.v_cache[b], i + 1 if causal else L).reshape(H)
             idx = np.fromiter(want, dtype=np.int64, count=len(want))
             out[b, idx] = self._after_attention(xb[idx], ctx)
+        return out
+
+    def encode(self, x: np.ndarray, q_lens: Sequence[int],
+               rows: Optional[Dict[int, Iterable[int]]] = None) -> np.ndarray:
+        """The layer as a bidirectional encoder (Section 4, Bert layer experiment): the same
+        block with the window predicate j <= i replaced by j < L_b.  Pad tokens are skipped,
+        there is no sequence mask, and no decode step follows."""
+        out = self.prefill(x, q_lens, rows, causal=False)
+        self.batch = 0
         return out
 
     # ---- incremental decode -------------------------------------------------------------

@@ -26,8 +26,9 @@ def _gelu(t):
     return 0.5 * t * (1.0 + math.tanh(0.7978845608028654 * (t + 0.044715 * t ** 3)))
 
 
-def masked_layer(x, q_lens, W, heads, eps=1e-5):
-    """x [B,S,H] -> [B,S,H]; rows of pad positions are returned as zeros."""
+def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True):
+    """x [B,S,H] -> [B,S,H]; rows of pad positions are returned as zeros.  causal_mask=False
+    drops the -inf triangle and keeps only the padding mask (the bidirectional encoder)."""
     x = np.asarray(x, np.float64)
     B, S, H = x.shape
     d = H // heads
@@ -40,7 +41,7 @@ def masked_layer(x, q_lens, W, heads, eps=1e-5):
         # implementation needs finite pad content; its value must not matter.
         rows = [x[b, i].tolist() if i < L else [0.25] * H for i in range(S)]
         qkv = [_matvec(Wl["w_qkv"], Wl["b_qkv"], _ln(r, Wl["ln1_g"], Wl["ln1_b"], eps)) for r in rows]
-        causal = [[0.0 if j <= i else NEG for j in range(S)] for i in range(S)]
+        causal = [[0.0 if (j <= i or not causal_mask) else NEG for j in range(S)] for i in range(S)]
         padmask = [0.0 if j < L else NEG for j in range(S)]
         ctx = [[0.0] * H for _ in range(S)]
         for g in range(heads):

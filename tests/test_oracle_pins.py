@@ -242,6 +242,60 @@ def test_size_formulas():
     assert orc.buffer_elements(b, p, h, n) == eval(g["buffer_formula"], {}, env)
 
 
+# ------------------------------------------------------------------ encoder use (no sequence mask)
+@pytest.mark.parametrize("lens,S,H,heads,F", [([7, 4, 1], 7, 16, 2, 32), ([3, 6], 6, 12, 3, 24)])
+def test_encoder_matches_padding_mask_bruteforce(lens, S, H, heads, F):
+    W = tiny_weights(3, H, F)
+    x = wl.normal(5, 1, (len(lens), S, H)).astype(np.float64)
+    got = make_layer(W, heads, len(lens), S).encode(x, lens)
+    want = bf.masked_layer(x, lens, W, heads, causal_mask=False)
+    for b, L in enumerate(lens):
+        np.testing.assert_allclose(got[b, :L], want[b, :L], rtol=0, atol=1e-9)
+        assert np.all(got[b, L:] == 0.0)
+    # and it is not the causal layer (except for one-token sequences and every last row)
+    causal = make_layer(W, heads, len(lens), S).prefill(x, lens)
+    for b, L in enumerate(lens):
+        np.testing.assert_allclose(got[b, L - 1], causal[b, L - 1], rtol=0, atol=1e-12)
+        if L > 1:
+            assert np.abs(got[b, 0] - causal[b, 0]).max() > 1e-6
+
+
+def test_encoder_is_permutation_equivariant_and_pad_independent():
+    """Without a sequence mask and without positions, permuting the valid tokens of a sequence
+    permutes its outputs; pad content (NaN here) never matters."""
+    W = tiny_weights(70, 32, 64)
+    lens = [9, 5]
+    x = wl.normal(71, 1, (2, 12, 32)).astype(np.float64)
+    base = make_layer(W, 4, 2, 12).encode(x, lens)
+    perm = np.array([4, 0, 8, 2, 6, 1, 7, 3, 5])
+    xp = x.copy()
+    xp[0, :9] = x[0, perm]
+    xp[0, 9:] = np.nan
+    xp[1, 5:] = np.nan
+    got = make_layer(W, 4, 2, 12).encode(xp, lens)
+    np.testing.assert_allclose(got[0, :9], base[0, perm], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(got[1, :5], base[1, :5])
+    assert np.all(got[0, 9:] == 0) and np.all(got[1, 5:] == 0)
+
+
+def test_encoder_unpadded_case_matches_torch_float64():
+    torch = pytest.importorskip("torch")
+    Fn = torch.nn.functional
+    B, S, heads, d = 2, 21, 3, 8
+    q = wl.normal(80, 1, (B, S, heads, d)).astype(np.float64)
+    k = wl.normal(80, 2, (B, S, heads, d)).astype(np.float64)
+    v = wl.normal(80, 3, (B, S, heads, d)).astype(np.float64)
+    t = [torch.from_numpy(a).permute(0, 2, 1, 3) for a in (q, k, v)]
+    want = Fn.scaled_dot_product_attention(t[0], t[1], t[2], is_causal=False).permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(orc.attention_prefill(q, k, v, [S] * B, causal=False), want, atol=1e-12)
+    # shorter valid lengths = the library routine on the truncated sequence
+    L = 13
+    want_L = Fn.scaled_dot_product_attention(t[0][:, :, :L], t[1][:, :, :L], t[2][:, :, :L]).permute(0, 2, 1, 3).numpy()
+    got_L = orc.attention_prefill(q, k, v, [L] * B, causal=False)
+    np.testing.assert_allclose(got_L[:, :L], want_L, atol=1e-12)
+    assert np.all(got_L[:, L:] == 0)
+
+
 # ------------------------------------------------------------------ planted mistakes must be caught
 class _Mutant:
     """Temporarily replace an attribute of the oracle module."""
@@ -290,3 +344,14 @@ def test_planted_mistakes_fail_the_bruteforce_pin(name, fn):
     with _Mutant(name, fn):
         with pytest.raises(AssertionError):
             test_layer_matches_additive_mask_bruteforce([7, 4, 1], 7, 16, 2, 32)
+
+
+def _attend_causal_in_encoder(q, K, V, n):   # an encoder that still applies a sequence mask
+    return _REAL["attend"](q, K, V, max(1, n - 1))
+
+
+@pytest.mark.parametrize("name,fn", [("attend", _attend_causal_in_encoder), ("attend", _attend_no_scale)])
+def test_planted_mistakes_fail_the_encoder_pin(name, fn):
+    with _Mutant(name, fn):
+        with pytest.raises(AssertionError):
+            test_encoder_matches_padding_mask_bruteforce([7, 4, 1], 7, 16, 2, 32)
