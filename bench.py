@@ -99,6 +99,40 @@ class Stack:
         self.decode()
 
 
+class EncoderStack:
+    """The workload's layers used as a bidirectional encoder (no sequence mask, no decode): one
+    eet_layer_encode call per layer, activations ping-ponged between two buffers."""
+
+    def __init__(self, w, eet, torch, wl):
+        self.w, self.eet, self.torch = w, eet, torch
+        cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+        self.layers = [eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in wl.layer_weights(w, li).items()})
+                       for li in range(w.layers)]
+        self.n_layers = w.layers
+        self.lens = [int(v) for v in wl.lengths(w)]
+        self.x0 = torch.from_numpy(wl.prompt_embeddings(w)).to("cuda:0")
+        self.buf = [torch.empty_like(self.x0), torch.empty_like(self.x0)]
+        self.stream = torch.cuda.Stream()
+
+    def weights(self, layer):
+        return self.layers[layer].weights
+
+    def cache_views(self, layer):
+        return self.layers[layer].cache_views()
+
+    def prefill(self):
+        with self.torch.cuda.stream(self.stream):
+            x = self.x0
+            for li, layer in enumerate(self.layers):
+                x = layer.encode(x, self.lens, self.buf[li & 1])
+
+    def decode(self):
+        pass
+
+    def one_pass(self):
+        self.prefill()
+
+
 def time_region(torch, fn, reps, stream=None):
     """Average duration of fn() in ms, HIP events on the stream the kernels are launched on."""
     s = stream if stream is not None else torch.cuda.current_stream()
@@ -206,13 +240,19 @@ def _kernel_candidates(stack, torch, eet, reps):
     cp = torch.empty_like(qp)
     st4 = {"i": 0}
 
+    attn_op = eet.eet_op_attention_encoder if w.encoder else eet.eet_op_attention_prefill
+
     def run_pattn():
         kc, vc = stack.cache_views(st4["i"] % nl)
         st4["i"] += 1
-        eet.eet_op_attention_prefill(qp, kc, vc, cp, stack.lens, w.heads)
+        attn_op(qp, kc, vc, cp, stack.lens, w.heads)
     ms = time_launches(torch, run_pattn, max(4, min(reps, 24)), replays=2)
-    out.append({"kernel": f"attn_prefill<{d}>: causal, padding-skipping prefill attention (matrix cores)",
-                "bound": "mfma", "work": sum(2.0 * H * L * (L + 1) for L in stack.lens), "ms": ms, "launches": nl})
+    if w.encoder:       # every valid row sees all L valid keys: 2 * (2 * L * L * H) flop per sequence
+        out.append({"kernel": f"attn_prefill<{d}, false>: padding-skipping attention without sequence mask (matrix cores)",
+                    "bound": "mfma", "work": sum(4.0 * H * L * L for L in stack.lens), "ms": ms, "launches": nl})
+    else:
+        out.append({"kernel": f"attn_prefill<{d}>: causal, padding-skipping prefill attention (matrix cores)",
+                    "bound": "mfma", "work": sum(2.0 * H * L * (L + 1) for L in stack.lens), "ms": ms, "launches": nl})
     # (5) LayerNorm over the valid rows of the prompt (row kernel, HBM bound): read + write of every row
     xl = torch.randn(T, H, device="cuda:0").half()
     yl = torch.empty_like(xl)
@@ -274,7 +314,7 @@ def cpu_baseline(w, wl, budget_s=25.0, min_s=10.0):
     while layers_done < w.layers and total < min_s:
         oracle = orc.DecoderLayerOracle(weights[layers_done % len(weights)], w.heads, nseq, w.max_seq, w.ln_eps)
         t0 = time.perf_counter()
-        oracle.prefill(x, lens)
+        oracle.encode(x, lens) if w.encoder else oracle.prefill(x, lens)
         steps = 0
         while steps < w.decode_steps and time.perf_counter() - t0 < budget_s:
             oracle.decode_step(dec[steps])
@@ -311,7 +351,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = wl.WORKLOADS[a.workload]
-    stack = Stack(w, eet, torch, wl, use_graph=not a.no_graph)
+    stack = EncoderStack(w, eet, torch, wl) if w.encoder else Stack(w, eet, torch, wl, use_graph=not a.no_graph)
     tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
 
     if a.roofline_only:
@@ -341,7 +381,8 @@ def main():
     ms_decode = time_region(torch, stack.decode, 1, stack.stream) if w.decode_steps else 0.0
 
     rec = {
-        "metric": "decoder-layer tokens/s (prefill+decode) fp16; % of HBM/MFMA roofline",
+        "metric": ("encoder-layer tokens/s (one pass, no sequence mask) fp16; % of HBM/MFMA roofline" if w.encoder else
+                   "decoder-layer tokens/s (prefill+decode) fp16; % of HBM/MFMA roofline"),
         "value": tokens / (dt / a.steps), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",

@@ -93,6 +93,16 @@ int eet_layer_create(const eet_layer_config *cfg, const eet_layer_weights *weigh
 int eet_prefill(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                 const void *tokens, void *out, void *kv_cache, void *hip_stream);
 
+/* The layer as a bidirectional encoder (Section 4, "Speedup for Bert Layer": padding tokens are
+ * skipped, there is no sequence mask): the same pass as eet_prefill with the window of a valid
+ * row i of sequence b widened from slots 0..i to all q_lens[b] valid slots.
+ * Arguments as eet_prefill; kv_scratch is DEVICE memory of eet_kv_cache_bytes(cfg) that holds the
+ * keys and values of this pass only (slots [0, q_lens[b]) are written).  The layer's workspace is
+ * reused, so any prefill / decode state of the layer is dropped: a following eet_decode_step
+ * returns STATE until the next eet_prefill.  Errors as eet_prefill. */
+int eet_layer_encode(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                     const void *tokens, void *out, void *kv_scratch, void *hip_stream);
+
 /* One incremental decoding step for every sequence of the last prefill (Section 3.1: keys and
  * values of each step are kept for the next).
  *   tokens     DEVICE fp16 [batch, hidden]; out DEVICE fp16 [batch, hidden]
@@ -177,6 +187,12 @@ int eet_op_linear(const void *x, const void *w, const void *bias, const void *re
  *   k_cache, v_cache   [batch, heads, capacity, d]
  * Row i of sequence b attends to slots 0..i.  q_lens is HOST int32[batch]. */
 int eet_op_attention_prefill(const void *q, const void *k_cache, const void *v_cache, void *ctx,
+                             const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                             int32_t heads, int32_t d, int32_t capacity, void *hip_stream);
+
+/* Same layouts and errors; padding skip only, no sequence mask (Section 4, Bert layer): every
+ * valid row of sequence b attends to slots 0..q_lens[b]-1. */
+int eet_op_attention_encoder(const void *q, const void *k_cache, const void *v_cache, void *ctx,
                              const int32_t *q_lens, int32_t batch, int32_t padded_len,
                              int32_t heads, int32_t d, int32_t capacity, void *hip_stream);
 

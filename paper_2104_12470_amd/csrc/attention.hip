@@ -24,7 +24,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 // every lane holding scores of ONE query (column lane%32): row statistics need a single
 // cross-lane exchange (lane ^ 32) and P^T is already in MFMA B-operand layout for
 // O^T = V^T P^T.
-template <int D>
+// CAUSAL = false is the encoder's window (Section 4, Bert layer): padding skip only, no sequence
+// mask; every query tile then walks all key tiles of its sequence and only the last tile compares
+// key indices (against L_b).
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLens lens) {
     constexpr int BQ = 128, BKV = 64;
     constexpr int LDKS = D + 8;         // K tile row stride (halfs): 16-byte reads conflict-free
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
     float m = -INFINITY, l = 0.f;
     const float c = rsqrtf((float)D) * kLog2e;
 
-    const int jlast = (i0 + BQ - 1 < L - 1) ? i0 + BQ - 1 : L - 1;   // last key any row of the tile sees
+    const int jlast = (CAUSAL && i0 + BQ - 1 < L - 1) ? i0 + BQ - 1 : L - 1;   // last key any row of the tile sees
     const int ntiles = jlast / BKV + 1;
 
     half8v rk[KVEC], rv[RPT];
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
         __syncthreads();
         if (jt + 1 < ntiles) gload(jt + 1);  // in flight during the MFMAs below
         const int j0 = jt * BKV;
-        if (j0 > iw0 + 31) continue;         // whole key tile is in the future of this wave's rows
+        if (CAUSAL && j0 > iw0 + 31) continue;   // whole key tile is in the future of this wave's rows
 
         // S^T[j][i] for 64 keys x 32 queries
         float16v st[2];
@@ -136,13 +139,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
         // The attention mask is an index comparison, and only tiles that straddle the diagonal of
         // this wave's rows pay for it (wave-uniform branch).
         float tmax = -INFINITY;
-        if (j0 + BKV - 1 > iw0) {
+        const int jmax = CAUSAL ? i : L - 1;             // last key this lane's query sees
+        if (CAUSAL ? j0 + BKV - 1 > iw0 : j0 + BKV > L) {
 #pragma unroll
             for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int j = j0 + jb * 32 + (r >> 2) * 8 + G * 4 + (r & 3);
-                    if (j > i) st[jb][r] = -INFINITY;
+                    if (j > jmax) st[jb][r] = -INFINITY;
                     tmax = fmaxf(tmax, st[jb][r]);
                 }
         } else {
@@ -208,8 +212,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
 
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s) {
     const dim3 grid((a.max_len + 127) / 128, a.heads, a.batch), block(256);
-    if (a.d == 128) hipLaunchKernelGGL(attn_prefill<128>, grid, block, 0, s, a, lens);
-    else hipLaunchKernelGGL(attn_prefill<64>, grid, block, 0, s, a, lens);
+    if (a.causal) {
+        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, true>), grid, block, 0, s, a, lens);
+        else hipLaunchKernelGGL((attn_prefill<64, true>), grid, block, 0, s, a, lens);
+    } else {
+        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, false>), grid, block, 0, s, a, lens);
+        else hipLaunchKernelGGL((attn_prefill<64, false>), grid, block, 0, s, a, lens);
+    }
     return hipGetLastError();
 }
 

@@ -149,7 +149,7 @@ int eet_layer_destroy(eet_layer_t* layer) {
 
 // Enqueue the kernels of one layer's prefill (arguments already validated).
 static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int padded_len, int64_t T, int max_len,
-                           const void* tokens, void* out, void* kv_cache, hipStream_t s) {
+                           const void* tokens, void* out, void* kv_cache, hipStream_t s, bool causal = true) {
     const eet_layer_config& c = L->cfg;
     const int H = c.hidden, F = c.ffn;
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
@@ -176,11 +176,11 @@ static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int pad
     g.k_cache = kc; g.v_cache = vc; g.tok_row_map = d_map; g.lens = nullptr;
     g.S = padded_len; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
     EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
-    // a4: mask-free causal attention over the cache
+    // a4: mask-free attention over the cache (causal window, or all valid keys for the encoder)
     AttnPrefillArgs at{};
     at.q = bufB; at.ctx = bufA; at.k_cache = kc; at.v_cache = vc;
     at.batch = batch; at.heads = c.heads; at.d = L->d; at.capacity = c.max_seq; at.hidden = H;
-    at.packed = 1; at.S = padded_len; at.max_len = max_len;
+    at.packed = 1; at.S = padded_len; at.max_len = max_len; at.causal = causal ? 1 : 0;
     EET_LAUNCH(launch_attention_prefill(at, lens, s), "prefill attention");
     // a6: output projection + bias + residual (residual gathered from the padded input)
     GemmArgs o{};
@@ -242,6 +242,20 @@ int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t pa
     L->batch = batch;
     for (int b = 0; b < batch; ++b) L->host_lens[b] = q_lens[b];
     return EET_OK;
+}
+
+int eet_layer_encode(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                     void* out, void* kv_scratch, void* hip_stream) {
+    if (!L) return fail(EET_ERR_INVALID_ARG, "eet_layer_encode: layer is null");
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_layer_encode", L->cfg, q_lens, batch, padded_len, tokens, out, kv_scratch, lens, T, max_len))
+        return rc;
+    // the pass overwrites the device-side lengths: whatever prefill / decode state the layer held is gone
+    L->batch = 0;
+    return enqueue_prefill(L, lens, batch, padded_len, T, max_len, tokens, out, kv_scratch,
+                           static_cast<hipStream_t>(hip_stream), false);
 }
 
 // Enqueue the kernels of one layer's decode step (arguments already validated).  `bump`: this
@@ -568,31 +582,44 @@ int eet_op_linear(const void* x, const void* w, const void* bias, const void* re
     return EET_OK;
 }
 
-int eet_op_attention_prefill(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* q_lens,
-                             int32_t batch, int32_t padded_len, int32_t heads, int32_t d, int32_t capacity,
-                             void* hip_stream) {
-    if (!q || !k_cache || !v_cache || !ctx || !q_lens) return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: null argument");
-    if (batch < 1 || padded_len < 1 || heads < 1 || capacity < padded_len)
-        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: bad size");
-    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_prefill: head size must be 64 or 128");
-    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "eet_op_attention_prefill: batch > EET_MAX_BATCH");
+static int op_attention_prompt(const char* who, bool causal, const void* q, const void* k_cache, const void* v_cache, void* ctx,
+                               const int32_t* q_lens, int32_t batch, int32_t padded_len, int32_t heads, int32_t d,
+                               int32_t capacity, void* hip_stream) {
+    if (!q || !k_cache || !v_cache || !ctx || !q_lens) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || padded_len < 1 || heads < 1 || capacity < padded_len) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: head size must be 64 or 128", who);
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "%s: batch > EET_MAX_BATCH", who);
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx))
-        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: pointers must be 16-byte aligned");
+        return fail(EET_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
     SeqLens lens;
     std::memset(&lens, 0, sizeof(lens));
     int max_len = 0;
     for (int b = 0; b < batch; ++b) {
         if (q_lens[b] < 1 || q_lens[b] > padded_len)
-            return fail(EET_ERR_INVALID_ARG, "eet_op_attention_prefill: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
+            return fail(EET_ERR_INVALID_ARG, "%s: q_lens[%d] = %d outside [1, %d]", who, b, q_lens[b], padded_len);
         lens.len[b] = q_lens[b];
         max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
     }
     AttnPrefillArgs a{};
     a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
     a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity; a.hidden = heads * d;
-    a.packed = 0; a.S = padded_len; a.max_len = max_len;
-    EET_LAUNCH(launch_attention_prefill(a, lens, (hipStream_t)hip_stream), "prefill attention");
+    a.packed = 0; a.S = padded_len; a.max_len = max_len; a.causal = causal ? 1 : 0;
+    EET_LAUNCH(launch_attention_prefill(a, lens, (hipStream_t)hip_stream), "prompt attention");
     return EET_OK;
+}
+
+int eet_op_attention_prefill(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* q_lens,
+                             int32_t batch, int32_t padded_len, int32_t heads, int32_t d, int32_t capacity,
+                             void* hip_stream) {
+    return op_attention_prompt("eet_op_attention_prefill", true, q, k_cache, v_cache, ctx, q_lens, batch, padded_len, heads, d,
+                               capacity, hip_stream);
+}
+
+int eet_op_attention_encoder(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* q_lens,
+                             int32_t batch, int32_t padded_len, int32_t heads, int32_t d, int32_t capacity,
+                             void* hip_stream) {
+    return op_attention_prompt("eet_op_attention_encoder", false, q, k_cache, v_cache, ctx, q_lens, batch, padded_len, heads, d,
+                               capacity, hip_stream);
 }
 
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity) {

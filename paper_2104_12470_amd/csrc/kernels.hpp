@@ -68,6 +68,7 @@ struct AttnPrefillArgs {
     int packed;             // 1: rows of sequence b start at sum(len[0..b)); 0: at b*S
     int S;                  // padded length (row stride between sequences when not packed)
     int max_len;            // max over lens (sizes the grid)
+    int causal;             // 1: query i sees keys 0..i; 0: every valid query sees all L_b keys (encoder)
 };
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s);
 

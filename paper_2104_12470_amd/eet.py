@@ -61,6 +61,7 @@ def lib() -> C.CDLL:
             "eet_workspace_bytes": (sz, [cfgp]),
             "eet_layer_create": (i32, [cfgp, C.POINTER(LayerWeights), vp, C.POINTER(vp)]),
             "eet_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_layer_encode": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_decode_step": (i32, [vp, vp, vp, vp, vp]),
             "eet_cache_lens": (i32, [vp, i32p, vp]),
             "eet_layer_destroy": (i32, [vp]),
@@ -78,6 +79,7 @@ def lib() -> C.CDLL:
             "eet_op_bias_residual": (i32, [vp, vp, vp, vp, i64, i32, vp]),
             "eet_op_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
             "eet_op_attention_prefill": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
+            "eet_op_attention_encoder": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
             "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
             "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
         }
@@ -88,11 +90,11 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_decode_step",
+EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_layer_encode", "eet_decode_step",
            "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_stack_kv_cache_bytes",
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
-           "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill",
+           "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
            "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode")
 
 
@@ -141,6 +143,12 @@ def eet_prefill(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, 
                 out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
     _check(lib().eet_prefill(layer, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
                              _ptr(kv_cache), _stream(stream)))
+
+
+def eet_layer_encode(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens: torch.Tensor,
+                     out: torch.Tensor, kv_scratch: torch.Tensor, stream=None) -> None:
+    _check(lib().eet_layer_encode(layer, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
+                                  _ptr(kv_scratch), _stream(stream)))
 
 
 def eet_decode_step(layer: int, tokens: torch.Tensor, out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
@@ -228,6 +236,14 @@ def eet_op_attention_prefill(q, k_cache, v_cache, ctx, q_lens, heads, stream=Non
                                           B, S, heads, d, cap, _stream(stream)))
 
 
+def eet_op_attention_encoder(q, k_cache, v_cache, ctx, q_lens, heads, stream=None) -> None:
+    B, S, H = q.shape
+    _, nh, cap, d = k_cache.shape
+    assert nh == heads and nh * d == H
+    _check(lib().eet_op_attention_encoder(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _lens_array(q_lens),
+                                          B, S, heads, d, cap, _stream(stream)))
+
+
 def eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) -> int:
     return lib().eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity)
 
@@ -259,6 +275,12 @@ class DecoderLayer:
         B, S, _ = tokens.shape
         out = torch.empty_like(tokens) if out is None else out
         eet_prefill(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
+    def encode(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_layer_encode(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
         return out
 
     def decode_step(self, tokens: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):

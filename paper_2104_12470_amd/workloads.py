@@ -119,6 +119,7 @@ class Workload:
     sigma_w: float = 0.02
     tid_offset: int = 0     # separates workloads that share a seed
     ln_eps: float = 1e-5
+    encoder: bool = False   # bidirectional use of the layer (no sequence mask, no decode)
 
     @property
     def d_head(self) -> int:
@@ -139,6 +140,8 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("small64", 11, 256, 4, 1024, 2, 5, 200, 3, 200, 9, 224),
     Workload("small128", 13, 512, 4, 2048, 1, 3, 333, 40, 333, 7, 352),
     Workload("wide1280", 17, 1280, 10, 5120, 1, 3, 80, 20, 80, 5, 96),
+    # encoder use (Section 4, Bert layer): hidden 1024, pad tokens about half of all tokens, no decode
+    Workload("bert1024", 1006, 1024, 16, 4096, 24, 16, 256, 64, 192, 0, 256, encoder=True),
 ]}
 
 

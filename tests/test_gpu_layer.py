@@ -94,6 +94,38 @@ def test_small_workloads_elementwise(eet, name):
     full_parity(eet, wl.WORKLOADS[name])
 
 
+@pytest.mark.parametrize("name", ["tiny", "small64", "small128", "bert1024"])
+def test_encoder_use_elementwise(eet, name):
+    """eet_layer_encode against the oracle's encoder use of the same layer (no sequence mask):
+    every valid row, pad rows zero, keys / values of the pass in their slots, pads never read."""
+    w = wl.WORKLOADS[name]
+    W = wl.layer_weights(w, 0, random_affine=True)
+    x, lens = wl.prompt_embeddings(w), wl.lengths(w)
+    B, S, H = x.shape
+    layer = make_gpu_layer(eet, w, W)
+    oracle = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps)
+    out = torch.full((B, S, H), float("nan"), dtype=torch.float16, device="cuda:0")
+    layer.encode(dev(poison_pads(x, lens)), lens, out)
+    torch.cuda.synchronize()
+    got, want = host(out), oracle.encode(x, lens)
+    for b, L in enumerate(lens):
+        gate(got[b, :L], want[b, :L], f"{w.name} encode b={b} L={L}")
+        assert np.all(got[b, L:] == 0), "pad rows of the output must be zero"
+    check_cache(layer, oracle, oracle.lens, B, f"{w.name} after encode")
+    # no decode session follows an encoder pass
+    with pytest.raises(eet.EETError) as e:
+        layer.decode_step(torch.zeros((B, H), dtype=torch.float16, device="cuda:0"))
+    assert e.value.code == eet.EET_ERR_STATE
+    # the layer still serves a causal prefill afterwards
+    out.fill_(float("nan"))
+    layer.prefill(dev(poison_pads(x, lens)), lens, out)
+    torch.cuda.synchronize()
+    want_c = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps).prefill(x, lens)
+    for b, L in enumerate(lens):
+        gate(host(out)[b, :L], want_c[b, :L], f"{w.name} prefill after encode b={b}")
+    layer.close()
+
+
 def test_batch_smaller_than_capacity_and_reuse(eet):
     """A layer sized for 8 sequences serves a batch of 5, then a second, different prefill."""
     w = wl.WORKLOADS["small64"]

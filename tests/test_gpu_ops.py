@@ -150,6 +150,35 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
         assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
 
 
+@pytest.mark.parametrize("d,heads,S,cap,lens", [
+    (64, 2, 24, 32, [24, 1, 7]),
+    (64, 3, 200, 224, [200, 3, 129, 64, 65]),
+    (128, 2, 333, 352, [333, 40, 129, 128]),
+    (128, 1, 1030, 1030, [1030, 512]),
+])
+def test_attention_encoder(eet, d, heads, S, cap, lens):
+    """Padding skip only, no sequence mask: every valid row sees all valid keys of its sequence."""
+    B, H = len(lens), heads * d
+    q = wl.normal(450 + d, 1, (B, S, heads, d))
+    k = wl.normal(450 + d, 2, (B, S, heads, d))
+    v = wl.normal(450 + d, 3, (B, S, heads, d))
+    want = orc.attention_prefill(q, k, v, lens, causal=False)
+    kc = np.full((B, heads, cap, d), np.nan, np.float16)          # slots >= L must never be read
+    vc = np.full((B, heads, cap, d), np.nan, np.float16)
+    qp = q.copy()
+    for b, L in enumerate(lens):
+        kc[b, :, :L] = k[b, :L].transpose(1, 0, 2)
+        vc[b, :, :L] = v[b, :L].transpose(1, 0, 2)
+        qp[b, L:] = np.nan                                        # pad queries must never be read
+    ctx = torch.full((B, S, H), 7.0, dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_encoder(dev(qp.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads)
+    torch.cuda.synchronize()
+    got = host(ctx).reshape(B, S, heads, d)
+    for b, L in enumerate(lens):
+        gate(got[b, :L], want[b, :L], f"attention encoder b={b} L={L}", OP_MAX, OP_MEAN)
+        assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
+
+
 @pytest.mark.parametrize("d,heads,cap,n_keys", [
     (64, 4, 600, [1, 17, 600]),
     (128, 4, 600, [600, 16, 33]),
