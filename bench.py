@@ -293,6 +293,16 @@ def roofline_for(stack, torch, eet, reps):
     return recs[0], recs[1:]
 
 
+def hbm_reference(torch):
+    """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written per
+    second): context for the HBM fractions, which divide by the published 8 TB/s."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(3)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ms = time_region(torch, lambda: dst.copy_(src), 5)
+    return {"kind": "device-to-device copy of 1 GiB (read + write bytes)", "GB/s": 2.0 * (1 << 30) / (ms * 1e-3) / 1e9}
+
+
 def cpu_baseline(w, wl, budget_s=25.0, min_s=10.0):
     """The CPU oracle timed on a bounded sample of the same workload: whole layers (as many as it
     takes to reach about ten seconds, at most the stack), as many whole sequences as fit a flop
@@ -396,6 +406,7 @@ def main():
                    "decode_tokens_per_s": (w.batch * w.decode_steps) / (ms_decode * 1e-3) if ms_decode else None},
     }
     rec["roofline"], rec["roofline_other_kernels"] = roofline_for(stack, torch, eet, a.kernel_reps)
+    rec["hbm_reference"] = hbm_reference(torch)
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w, wl)
     print(json.dumps(rec))

@@ -31,7 +31,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLens lens) {
     constexpr int BQ = 128, BKV = 64;
     constexpr int LDKS = D + 8;         // K tile row stride (halfs): 16-byte reads conflict-free
-    constexpr int LDVT = BKV + 8;       // V^T tile row stride
+    constexpr int LDVT = BKV + 4;       // V^T tile row stride: 34 dwords, so the 8-byte reads of 32 rows cover all 64 banks once
     constexpr int KVEC = BKV * D / 8 / 256;   // 16-byte vectors of K per thread per tile
     constexpr int RPT = D / 32;               // V rows per thread per tile (transposed on the way to LDS)
     constexpr int DCH = D / 8;                // 16-byte chunks per K/V row
@@ -126,15 +126,16 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
         // S^T[j][i] for 64 keys x 32 queries
         float16v st[2];
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
+        for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) st[jb][r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < D / 16; ++kk) {
+        for (int kk = 0; kk < D / 16; ++kk)           // the two accumulators alternate: no MFMA waits on the one before it
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
                 const half8v kf = *reinterpret_cast<const half8v*>(&Ks[(jb * 32 + li) * LDKS + kk * 16 + G * 8]);
                 st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], st[jb], 0, 0, 0);
             }
-        }
         // st[jb][r] belongs to key j0 + jb*32 + (r/4)*8 + G*4 + r%4 and query i.
         // The attention mask is an index comparison, and only tiles that straddle the diagonal of
         // this wave's rows pay for it (wave-uniform branch).
