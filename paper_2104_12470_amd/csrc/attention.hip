@@ -9,11 +9,20 @@
 //
 // K/V cache layout: [batch][heads][capacity][d] fp16, slot t = token t of the sequence.
 #include <cstdlib>
+#include <type_traits>
 #include "kernels.hpp"
 
 namespace eet {
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// Longest sequence of a call above which the 256-row prefill kernel is used (overridable for
+// measurements: EET_ATTN_WIDE_MIN).
+static int wide_min_len() {
+    const char* e = getenv("EET_ATTN_WIDE_MIN");
+    return e ? atoi(e) : 128;
+}
+static const int kWideMinLen = wide_min_len();
 
 // ============================================================================================
 // Prefill: flash-style, v_mfma_f32_32x32x16_f16
@@ -38,9 +47,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
     __shared__ __attribute__((aligned(16))) half_t Ks[BKV * LDKS];
     __shared__ __attribute__((aligned(16))) half_t Vt[D * LDVT];
 
-    const int b = blockIdx.z, g = blockIdx.y;
+    // grid = ((sequence, head) pairs, query tiles): the tiles are dispatched longest first over all pairs, and the
+    // tiles of a pair land on one XCD (workgroups are dealt round-robin to the 8 XCDs), whose L2 then holds its K/V
+    const int b = blockIdx.x / a.heads, g = blockIdx.x % a.heads;
     const int L = lens.len[b];
-    const int i0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * BQ;   // longest (latest) query tiles first
+    const int i0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * BQ;
     if (i0 >= L) return;                                          // pad queries are never visited
     int row0 = b * a.S;
     if (a.packed) {
@@ -211,9 +222,349 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
         }
 }
 
+// --------------------------------------------------------------------------------------------
+// Prefill, long sequences: 256 query rows per workgroup, 8 waves of 32 rows
+// --------------------------------------------------------------------------------------------
+// Same arithmetic as the kernel above (S^T = K Q^T, one query per lane, O^T = V^T P^T), different
+// data movement:
+//  * K and V tiles go from the cache straight into LDS (global_load_lds, 16 bytes per lane, no staging
+//    registers) through rings of three stages each, requested two key tiles ahead: the latency of
+//    the cache is covered by two tiles of arithmetic, and there is one barrier per key tile;
+//  * the tiles sit in LDS row-major, as they are in the cache: the A operand of O^T = V^T P^T is
+//    fetched with the LDS transpose read (ds_read_b64_tr_b16: within 16 lanes, lane r supplies the
+//    address of 4 consecutive halfs "row r"; lane l receives element l%4 of rows l/4, l/4+4, l/4+8,
+//    l/4+12), so no lane transposes anything;
+//  * the 16-byte chunks of a row are XOR-permuted by the row index (applied to the global address
+//    of each lane when loading, to the LDS address when reading), chosen so that both the 16-byte
+//    K fragment reads and the transpose reads of V touch every bank once;
+//  * every LDS fragment is requested one scheduling region before the MFMA that consumes it, and
+//    the scores of the next 32 keys are computed while the exponentials of the current 32 run.
+// Fragment reads and their waits are inline assembly: the compiler cannot tell that an LDS read
+// does not alias an in-flight global->LDS load and would drain all of them before each read.
+// A wave's 32 rows start at a multiple of 32, so exactly one half tile of 32 keys -- the wave's
+// last -- straddles the causal diagonal (or, without a sequence mask, the end of the sequence): it
+// is the only one that compares indices.  Waves whose rows end before the workgroup's last key
+// tile keep loading and synchronising but skip the arithmetic; the row blocks are dealt to the
+// waves so that the two waves of a SIMD (w and w+4) always sum to the same amount of work.
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds + 16*l (the LDS base
+// must be wave-uniform).  Kept out of the templates: the builtin only exists for the device.
+__device__ __forceinline__ void load_lds_16B(const char* gptr, char* lds) {
+    __builtin_amdgcn_global_load_lds(gptr, lds, 16, 0, 0);
+}
+template <int N>
+__device__ __forceinline__ void wait_lds() {
+    static_assert(N == 0 || N == 4 || N == 8 || N == 16, "add the count");
+    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)");
+    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)");
+    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)");
+    if (N == 16) asm volatile("s_waitcnt lgkmcnt(15)");   // the counter saturates at 15: one read more than needed is waited for
+}
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+    static_assert(N == 2 || N == 4, "add the count");
+    if (N == 2) asm volatile("s_waitcnt vmcnt(2)");
+    if (N == 4) asm volatile("s_waitcnt vmcnt(4)");
+}
+// lane ^ 32 maximum without the LDS: v_permlane32_swap exchanges the upper half of its first operand
+// with the lower half of its second
+__device__ __forceinline__ float max_xor32(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqLens lens) {
+    constexpr int BQ = 256, WQ = 32, BKV = 64, NWAVE = 8;
+    constexpr int ROWB = D * 2;                  // bytes of a K / V row
+    constexpr int TILEB = BKV * ROWB;            // bytes of a key tile
+    constexpr int CPR = ROWB / 16;               // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;                // rows one wave-level load instruction covers (1 KB of LDS)
+    constexpr int NV = TILEB / 1024 / NWAVE;     // load instructions per wave per tile
+    constexpr int KK = D / 16, DB = D / 32;
+    __shared__ __attribute__((aligned(1024))) char Ks[3][TILEB];
+    __shared__ __attribute__((aligned(1024))) char Vs[3][TILEB];
+
+    // grid = ((sequence, head) pairs, query tiles): the tiles are dispatched longest first over all pairs, and the
+    // tiles of a pair land on one XCD (workgroups are dealt round-robin to the 8 XCDs), whose L2 then holds its K/V
+    const int b = blockIdx.x / a.heads, g = blockIdx.x % a.heads;
+    const int L = lens.len[b];
+    const int i0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * BQ;
+    if (i0 >= L) return;                                          // pad queries are never visited
+    int row0 = b * a.S;
+    if (a.packed) {
+        row0 = 0;
+        for (int k = 0; k < b; ++k) row0 += lens.len[k];
+    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, G = lane >> 5;
+    const int iw0 = i0 + (wave < 4 ? wave : 11 - wave) * WQ;      // SIMD s hosts row blocks s and 7-s
+    const int i = iw0 + li;                                       // this lane's query
+
+    const int last_key = (CAUSAL && i0 + BQ - 1 < L - 1) ? i0 + BQ - 1 : L - 1;
+    const int nt_wg = last_key / BKV + 1;                         // key tiles the workgroup stages
+    // halves (32 keys) this wave uses; the last one is the only one with hidden keys
+    const int nh_w = iw0 >= L ? 0 : (CAUSAL ? iw0 / 32 + 1 : (L + 31) / 32);
+
+    // Q^T fragments (B operand): query i, depth kk*16 + G*8 .. +8
+    half8v qf[KK];
+    {
+        const half_t* qp = a.q + (int64_t)(row0 + (i < L ? i : L - 1)) * a.hidden + g * D + G * 8;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const half8v*>(qp + kk * 16);
+    }
+    const int64_t head_off = ((int64_t)b * a.heads + g) * a.capacity * D;
+    const char* kbase = reinterpret_cast<const char*>(a.k_cache + head_off);
+    const char* vbase = reinterpret_cast<const char*>(a.v_cache + head_off);
+
+    // Tile loads.  Load instruction v of this wave fills LDS bytes [(wave*NV + v)*1024, +1024) of a stage:
+    // lane -> row (wave*NV + v)*RPI + lane/CPR, position lane%CPR, which receives the source chunk
+    // position ^ swizzle(row).  Rows past the sequence are clamped: slots >= L of the cache are never read.
+    int ld_row[NV];
+    uint32_t ld_k[NV], ld_v[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int row = (wave * NV + v) * RPI + lane / CPR, pos = lane % CPR;
+        const int swk = D == 128 ? (row & 15) : ((row >> 1) & 7);
+        const int swv = D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+        ld_row[v] = row;
+        ld_k[v] = (uint32_t)((pos ^ swk) * 16);
+        ld_v[v] = (uint32_t)((pos ^ swv) * 16);
+    }
+    auto load_k = [&](int jt, int st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int key = jt * BKV + ld_row[v];
+            key = key < L ? key : L - 1;
+            load_lds_16B(kbase + ((uint32_t)key * ROWB + ld_k[v]), &Ks[st][(wave * NV + v) * 1024]);
+        }
+    };
+    auto load_v = [&](int jt, int st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int key = jt * BKV + ld_row[v];
+            key = key < L ? key : L - 1;
+            load_lds_16B(vbase + ((uint32_t)key * ROWB + ld_v[v]), &Vs[st][(wave * NV + v) * 1024]);
+        }
+    };
+
+    // fragment addresses (LDS byte addresses relative to stage 0 of the ring)
+    unsigned kaddr[KK];     // K row li (+ jb*32 rows), chunk kk*2 + G
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int sw = D == 128 ? (li & 15) : ((li >> 1) & 7);
+        kaddr[kk] = (unsigned)(uintptr_t)&Ks[0][0] + li * ROWB + (((kk * 2 + G) ^ sw) * 16);
+    }
+    unsigned vaddr[DB];     // transpose read: this lane supplies key G*4 + (li%16)/4 (+ offset), 4 halfs at dv db*32 + (li/16)*16 + (li%4)*4
+    {
+        const int lb = li & 15, blk = li >> 4;
+        const int sw = D == 128 ? (((lb >> 2) & 3) << 2) : (((lb >> 3) & 1) << 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int cc = db * 4 + blk * 2 + ((lb & 3) >> 1);
+            vaddr[db] = (unsigned)(uintptr_t)&Vs[0][0] + (G * 4 + (lb >> 2)) * ROWB + ((cc ^ sw) * 16) + (lb & 1) * 8;
+        }
+    }
+
+    float16v o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    float m = -INFINITY, l = 0.f, alpha = 1.f;
+    bool rescale = false;
+    constexpr float kSlack = 8.0f;
+    const float c = rsqrtf((float)D) * kLog2e;
+
+    // Pipeline over halves of 32 keys, h = 2*tile + jb.  Scores of half h: st[r] belongs to key
+    // jb*32 + (r/4)*8 + G*4 + r%4 of the tile and query i.  One step handles half h in two
+    // scheduling regions (fenced, so that the fragment reads issued in a region stay there: an LDS
+    // read takes longer than the MFMA it feeds):
+    //   region 1: LDS: V^T fragments of half h requested (transpose reads)
+    //             matrix cores: scores of half h+1 (K fragments requested one region earlier)
+    //             vector units: p = 2^(s*c - m) of half h, row sum, conversion to P^T (B-operand layout)
+    //   region 2: LDS: K fragments of half h+2 requested
+    //             matrix cores: O^T += V^T P^T of half h
+    //             vector units: window test (last half only) and running maximum of half h+1
+    // followed by the rescale of the accumulators in the rare case that some row's maximum moved.
+    half8v kf[KK];                // K fragments (A operand): key row jb*32 + li, depth kk*16 + G*8 .. +8
+    auto read_k = [](half8v (&dst)[KK], const unsigned (&ka)[KK], auto jb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[kk]) : "v"(ka[kk]), "n"(decltype(jb)::value * 32 * ROWB));
+    };
+    auto landed_k = [&]() __attribute__((always_inline)) {     // after a wait: the fragments are now defined
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+v"(kf[kk]));
+    };
+    auto scores = [&](float16v& st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) st = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[kk], st, 0, 0, 0);
+    };
+    // Window test + running maximum of one half.  The mask is an index comparison on the lane's own
+    // indices (Algorithm 1); nothing is read for it.  The maximum lives in the exp2 domain (score * c)
+    // and is finite from the first half on: key 0 is visible to every row.
+    auto row_max = [&](float16v& st, int j0, auto masked) __attribute__((always_inline)) {
+        if constexpr (decltype(masked)::value) {
+            const int jmax = CAUSAL ? i : L - 1;                  // last key this lane's query sees
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = j0 + (r >> 2) * 8 + G * 4 + (r & 3);
+                if (j > jmax) st[r] = -INFINITY;
+            }
+        }
+        float tmax = st[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, st[r]);
+        tmax = max_xor32(tmax) * c;
+        // m is the reference of the exponentials, not necessarily the maximum: it is moved (and the sum and the
+        // accumulators rescaled) only when some row's maximum has grown by more than kSlack since, so p stays
+        // below 2^kSlack -- exact in fp16 and fp32 all the same -- and the rescale is rare on any data.
+        rescale = __any(tmax > m + kSlack);
+        if (rescale) {
+            const float m_new = fmaxf(m, tmax);
+            alpha = __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+            m = m_new;
+        }
+    };
+    auto half_step = [&](float16v& cur, float16v& nxt, const unsigned (&va)[DB], auto jb, const unsigned (&ka2)[KK], int j0_next,
+                         auto has_next, auto mask_next, auto prefetch) __attribute__((always_inline)) {
+        // ---- region 1
+        half4v vlo[2][DB], vhi[2][DB];
+        constexpr int JB = decltype(jb)::value;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16) * ROWB));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16 + 8) * ROWB));
+            }
+        if constexpr (decltype(has_next)::value) {
+            wait_lds<4 * DB>();                                   // the K fragments requested one region ago
+            landed_k();
+            scores(nxt);
+        }
+        half8v pf[2];             // slot s of pf[hf] <-> key jb*32 + hf*16 + (s/4)*8 + G*4 + s%4
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r], c, -m));
+            psum += p;
+            pf[r >> 3][r & 7] = (half_t)p;
+        }
+        l += psum;
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- region 2
+        if constexpr (decltype(prefetch)::value) {
+            read_k(kf, ka2, jb);
+            wait_lds<KK>();                                       // the V fragments; the K reads stay in flight
+        } else {
+            wait_lds<0>();
+        }
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                asm volatile("" : "+v"(vlo[hf][db]), "+v"(vhi[hf][db]));
+                const half8v vf = __builtin_shufflevector(vlo[hf][db], vhi[hf][db], 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[hf], o[db], 0, 0, 0);
+            }
+        if constexpr (decltype(has_next)::value) row_max(nxt, j0_next, mask_next);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(has_next)::value) {
+            if (rescale) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+            }
+        }
+    };
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    // half h of the wave: cur holds its scores; the K fragments of half h+1 have been requested
+    auto wave_half = [&](int h, auto jb, float16v& cur, float16v& nxt, const unsigned (&va)[DB], const unsigned (&ka2)[KK]) __attribute__((always_inline)) {
+        const int j0_next = (h + 1) * 32;
+        if (h + 2 < nh_w) half_step(cur, nxt, va, jb, ka2, j0_next, yes, no, yes);
+        else if (h + 2 == nh_w) half_step(cur, nxt, va, jb, ka2, j0_next, yes, yes, no);   // the next half is the last: its keys are tested
+        else if (h + 1 == nh_w) half_step(cur, nxt, va, jb, ka2, j0_next, no, no, no);
+    };
+    constexpr std::integral_constant<int, 0> jb0{};
+    constexpr std::integral_constant<int, 1> jb1{};
+
+    // Rings: tile t lives in stage t%3.  During step jt the waves read V(jt) and K(jt+1) while K(jt+2), V(jt+1)
+    // (requested during step jt-1) and K(jt+3), V(jt+2) (requested now, into the stages step jt-1 was reading)
+    // are in flight.  Requests past the last tile re-read clamped rows into stages nobody reads: the number of
+    // loads per step stays fixed, which keeps the wait counts fixed.
+    float16v sa, sb;
+    load_k(0, 0);
+    load_k(1, 1);
+    load_v(0, 0);
+    load_k(2, 2);
+    load_v(1, 1);
+    wait_vmem<2 * NV>();                                  // K(0), K(1), V(0) of this wave have landed ...
+    __builtin_amdgcn_s_barrier();                         // ... and everybody else's
+    if (nh_w > 0) {
+        read_k(kf, kaddr, jb0);
+        wait_lds<0>();
+        landed_k();
+        scores(sa);
+        if (nh_w == 1) row_max(sa, 0, yes);
+        else row_max(sa, 0, no);                          // alpha = 0 and the accumulators are zero: nothing to rescale
+        if (nh_w > 1) read_k(kf, kaddr, jb1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_lds<0>();
+    __builtin_amdgcn_s_barrier();                         // step 0 refills the stage of K(0)
+    int s0 = 0;                                           // stage of tile jt
+    for (int jt = 0; jt < nt_wg; ++jt) {
+        const int s1 = s0 == 2 ? 0 : s0 + 1, s2 = s0 == 0 ? 2 : s0 - 1;
+        load_k(jt + 3, s0);                               // K(jt) was last read during step jt-1
+        load_v(jt + 2, s2);                               // V(jt-1) was last read during step jt-1
+        unsigned ka2[KK], va[DB];                         // fragment addresses in the stages of K(jt+1) and V(jt)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) ka2[kk] = kaddr[kk] + s1 * TILEB;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) va[db] = vaddr[db] + s0 * TILEB;
+        wave_half(2 * jt, jb0, sa, sb, va, ka2);          // requests the K fragments of half 2*jt+2: tile jt+1, jb 0
+        wave_half(2 * jt + 1, jb1, sb, sa, va, ka2);      // ... of half 2*jt+3: tile jt+1, jb 1
+        wait_lds<0>();                                    // this wave is done reading the stages of this step
+        wait_vmem<2 * NV>();                              // K(jt+2), V(jt+1) of this wave have landed ...
+        __builtin_amdgcn_s_barrier();                     // ... and everybody else's
+        s0 = s1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)");                   // no load may still be writing LDS when the workgroup ends
+
+    l += __shfl_xor(l, 32, kWave);
+    if (i >= L) return;
+    const float inv = 1.0f / l;
+    half_t* op = a.ctx + (int64_t)(row0 + i) * a.hidden + g * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            half4v t;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = (half_t)(o[db][rg * 4 + e] * inv);
+            *reinterpret_cast<half4v*>(op + db * 32 + rg * 8 + G * 4) = t;
+        }
+}
+
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s) {
-    const dim3 grid((a.max_len + 127) / 128, a.heads, a.batch), block(256);
-    if (a.causal) {
+    const bool wide = a.max_len > kWideMinLen;
+    const dim3 grid(a.heads * a.batch, (a.max_len + (wide ? 255 : 127)) / (wide ? 256 : 128)), block(wide ? 512 : 256);
+    if (wide) {
+        if (a.causal) {
+            if (a.d == 128) hipLaunchKernelGGL((attn_prefill_wide<128, true>), grid, block, 0, s, a, lens);
+            else hipLaunchKernelGGL((attn_prefill_wide<64, true>), grid, block, 0, s, a, lens);
+        } else {
+            if (a.d == 128) hipLaunchKernelGGL((attn_prefill_wide<128, false>), grid, block, 0, s, a, lens);
+            else hipLaunchKernelGGL((attn_prefill_wide<64, false>), grid, block, 0, s, a, lens);
+        }
+    } else if (a.causal) {
         if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, true>), grid, block, 0, s, a, lens);
         else hipLaunchKernelGGL((attn_prefill<64, true>), grid, block, 0, s, a, lens);
     } else {
