@@ -16,13 +16,6 @@ namespace eet {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Longest sequence of a call above which the 256-row prefill kernel is used (overridable for
-// measurements: EET_ATTN_WIDE_MIN).
-static int wide_min_len() {
-    const char* e = getenv("EET_ATTN_WIDE_MIN");
-    return e ? atoi(e) : 128;
-}
-static const int kWideMinLen = wide_min_len();
 
 // ============================================================================================
 // Prefill: flash-style, v_mfma_f32_32x32x16_f16
@@ -168,27 +161,33 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
                 for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, st[jb][r]);
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-        // running maximum m lives in the exp2 domain (score * c): p = 2^(s*c - m), one FMA + one v_exp_f32
-        const float m_new = fmaxf(m, tmax * c);      // finite: key 0 is visible to every row
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        // m is the reference of the exponentials in the exp2 domain (score * c): p = 2^(s*c - m), one FMA + one
+        // v_exp_f32.  It is moved (and the sum and the accumulators rescaled) only when some row's maximum has
+        // grown by more than kSlack since, so p stays below 2^kSlack -- as exact in fp16 and fp32 as below 1 --
+        // and the rescale is rare on any data.  m is finite from the first tile on: key 0 is visible to every row.
+        constexpr float kSlack = 8.0f;
+        const float tm = tmax * c;
+        if (__any(tm > m + kSlack)) {
+            const float m_new = fmaxf(m, tm);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+            m = m_new;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        }
         float psum = 0.f;
         half8v pf[2][2];
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][r], c, -m_new));
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][r], c, -m));
                 psum += p;
                 pf[jb][r >> 3][r & 7] = (half_t)p;
             }
-        l = l * alpha + psum;
-        m = m_new;
-        if (__any(alpha != 1.0f)) {                  // the maximum stops moving after the first tiles of a long row
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-        }
+        l += psum;
         // O^T[dv][i] += V^T[dv][j] P^T[j][i]; operand slot s of lane group G <-> key
         // jb*32 + hf*16 + (s/4)*8 + G*4 + s%4 (the keys this lane already holds in pf[jb][hf]).
 #pragma unroll
@@ -554,16 +553,14 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
 }
 
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s) {
-    const bool wide = a.max_len > kWideMinLen;
-    const dim3 grid(a.heads * a.batch, (a.max_len + (wide ? 255 : 127)) / (wide ? 256 : 128)), block(wide ? 512 : 256);
+    // 256-row kernel for heads of 128 once a sequence spans more than one 128-row tile; heads of 64 have half
+    // the matrix work per score, and the 128-row kernel (softmax over 64 keys at a time) is the faster one there.
+    const bool wide = a.d == 128 && a.max_len > 128;
+    const int bq = wide ? 256 : 128;
+    const dim3 grid(a.heads * a.batch, (a.max_len + bq - 1) / bq), block(wide ? 512 : 256);
     if (wide) {
-        if (a.causal) {
-            if (a.d == 128) hipLaunchKernelGGL((attn_prefill_wide<128, true>), grid, block, 0, s, a, lens);
-            else hipLaunchKernelGGL((attn_prefill_wide<64, true>), grid, block, 0, s, a, lens);
-        } else {
-            if (a.d == 128) hipLaunchKernelGGL((attn_prefill_wide<128, false>), grid, block, 0, s, a, lens);
-            else hipLaunchKernelGGL((attn_prefill_wide<64, false>), grid, block, 0, s, a, lens);
-        }
+        if (a.causal) hipLaunchKernelGGL((attn_prefill_wide<128, true>), grid, block, 0, s, a, lens);
+        else hipLaunchKernelGGL((attn_prefill_wide<128, false>), grid, block, 0, s, a, lens);
     } else if (a.causal) {
         if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, true>), grid, block, 0, s, a, lens);
         else hipLaunchKernelGGL((attn_prefill<64, true>), grid, block, 0, s, a, lens);

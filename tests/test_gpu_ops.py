@@ -127,6 +127,8 @@ def test_linear_large_tiles(eet, M, K, N):
     (64, 3, 200, 224, [200, 3, 129, 64, 65]),
     (128, 2, 333, 352, [333, 40, 129]),
     (128, 1, 1030, 1030, [1030, 512]),
+    (128, 2, 520, 544, [256, 257, 255, 512, 33, 1, 520, 289]),   # 256-row tiles: ends on, before and after tile and half-tile edges
+    (64, 2, 520, 544, [256, 257, 129, 520]),
 ])
 def test_attention_prefill(eet, d, heads, S, cap, lens):
     B, H = len(lens), heads * d
@@ -155,6 +157,8 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
     (64, 3, 200, 224, [200, 3, 129, 64, 65]),
     (128, 2, 333, 352, [333, 40, 129, 128]),
     (128, 1, 1030, 1030, [1030, 512]),
+    (128, 2, 520, 544, [256, 257, 255, 512, 33, 1, 520, 289]),
+    (64, 2, 520, 544, [256, 257, 129, 520]),
 ])
 def test_attention_encoder(eet, d, heads, S, cap, lens):
     """Padding skip only, no sequence mask: every valid row sees all valid keys of its sequence."""
