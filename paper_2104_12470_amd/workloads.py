@@ -188,3 +188,49 @@ def layer_weights(w: Workload, layer: int = 0, random_affine: bool = False) -> D
 def scores(seed: int, batch: int, heads: int, seq: int, sigma: float = 2.0) -> np.ndarray:
     """[batch, heads, seq, seq] fp16 raw attention scores for the stand-alone softmax op."""
     return normal(seed, 77, (batch, heads, seq, seq), sigma)
+
+
+# ---- request / release sequences for the buffer manager (Section 3.2): inputs, no policy ----------------
+ATTENTION_MODULE, FEED_FORWARD_MODULE = 0, 1
+
+
+def unfused_layer_buffer_trace(batch: int, prompt: int, hidden: int, heads: int, ffn: int, elem_bytes: int = 2):
+    """The buffers an unfused decoder layer asks for, in order, as ("req", name, bytes, module) and
+    ("rel", name) events: a library GEMM for the stacked QKV projection, a kernel that adds the bias and splits
+    heads into q, k, v, the materialised scores of Algorithm 1, the context and its head-merged copy, and the
+    feed-forward intermediate.  Results that go to the activation caches (Section 3.1) are not buffers."""
+    T = batch * prompt
+    row = T * hidden * elem_bytes
+    A, F = ATTENTION_MODULE, FEED_FORWARD_MODULE
+    return [
+        ("req", "qkv", 3 * row, A),
+        ("req", "q", row, A), ("req", "k", row, A), ("req", "v", row, A),
+        ("rel", "qkv"),
+        ("req", "scores", batch * heads * prompt * prompt * elem_bytes, A),
+        ("rel", "q"), ("rel", "k"),
+        ("req", "ctx", row, A),
+        ("rel", "v"), ("rel", "scores"),
+        ("req", "ctx_merged", row, A),
+        ("rel", "ctx"),
+        ("rel", "ctx_merged"),
+        ("req", "ffn1", T * ffn * elem_bytes, F),
+        ("rel", "ffn1"),
+    ]
+
+
+def random_buffer_trace(seed: int, events: int, modules: int = 3, max_units: int = 12, unit: int = 256):
+    """Seeded random requests (sizes of 1..max_units alignment units, minus a few bytes now and then) and
+    releases of live buffers, as ("req", name, bytes, module) / ("rel", name) events."""
+    r = uniform01(seed, 77, 0, 3 * events)
+    out, live, n = [], [], 0
+    for e in range(events):
+        a, b, c = r[3 * e], r[3 * e + 1], r[3 * e + 2]
+        if live and a < 0.45:
+            out.append(("rel", live.pop(int(b * len(live)) % len(live))))
+        else:
+            size = (1 + int(b * max_units) % max_units) * unit - (int(c * 7) if c < 0.3 else 0)
+            name = f"t{n}"
+            n += 1
+            out.append(("req", name, size, int(c * modules) % modules))
+            live.append(name)
+    return out
