@@ -205,6 +205,39 @@ int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_ca
                             const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,
                             int32_t capacity, void *scratch, void *hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Dynamic buffer manager (Section 3.2): the result buffers of operators that are not fused are
+ * requested by size and marked idle when no longer needed; the manager decides what to reuse.
+ *   - a request of a module is served by an idle buffer of the SAME module only if the sizes are
+ *     identical (no fragmentation), by an idle buffer of ANOTHER module if the buffer is at least
+ *     as large (no duplicated allocation); the list is scanned in creation order and the first
+ *     buffer that qualifies is taken; otherwise a new buffer is created;
+ *   - a buffer belongs to the module that used it last; sizes are rounded up to 256 bytes;
+ *   - buffers are carved, one after the other, out of `arena`: DEVICE memory of arena_bytes, 256-byte
+ *     aligned, owned by the caller for the life of the manager and never dereferenced by it
+ *     (Section 3.1: the maximum is allocated in advance).  The bytes carved so far are the section's
+ *     "total buffer size"; for an unfused layer that is b*p*(6h + n*p) elements.
+ * Host logic: no call touches the device or a stream.  A manager is not thread-safe.
+ * Errors: EET_ERR_INVALID_ARG (null, zero bytes, pointer that is not a buffer of the manager),
+ * EET_ERR_CAPACITY (the request does not fit in what is left of the arena), EET_ERR_STATE (release
+ * of a buffer that is already idle).  On error nothing changes.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct eet_bufmgr eet_bufmgr_t;   /* opaque, host memory owned by the library */
+typedef struct {
+    uint64_t arena_bytes;        /* size of the arena                                        */
+    uint64_t footprint_bytes;    /* bytes of all buffers created so far                      */
+    int64_t buffers, idle;       /* buffers in the list, and how many of them are idle       */
+    int64_t requests;            /* successful requests                                      */
+    int64_t reused_same_size;    /* ... served by an idle buffer of identical size           */
+    int64_t reused_larger;       /* ... served by a larger idle buffer of another module     */
+    int64_t created;             /* ... that created a buffer                                */
+} eet_bufmgr_stats;
+int eet_bufmgr_create(void *arena, size_t arena_bytes, eet_bufmgr_t **out);
+int eet_bufmgr_request(eet_bufmgr_t *mgr, size_t bytes, int32_t module, void **out /* DEVICE pointer into the arena */);
+int eet_bufmgr_release(eet_bufmgr_t *mgr, void *buffer);
+int eet_bufmgr_query(const eet_bufmgr_t *mgr, eet_bufmgr_stats *out);
+int eet_bufmgr_destroy(eet_bufmgr_t *mgr);
+
 #ifdef __cplusplus
 }
 #endif

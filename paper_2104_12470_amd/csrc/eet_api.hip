@@ -94,6 +94,15 @@ struct eet_layer {
     int32_t host_lens[EET_MAX_BATCH];  // host mirror of the device cache lengths (capacity checks only)
 };
 
+// error setter for the library's other translation units (same thread-local message as eet_last_error)
+int eet_set_error(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
 extern "C" {
 
 const char* eet_last_error(void) { return g_err; }

@@ -37,6 +37,12 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
 
 
+class BufMgrStats(C.Structure):
+    _fields_ = [("arena_bytes", C.c_uint64), ("footprint_bytes", C.c_uint64), ("buffers", C.c_int64), ("idle", C.c_int64),
+                ("requests", C.c_int64), ("reused_same_size", C.c_int64), ("reused_larger", C.c_int64),
+                ("created", C.c_int64)]
+
+
 class EETError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"eet error {code}: {message}")
@@ -82,6 +88,11 @@ def lib() -> C.CDLL:
             "eet_op_attention_encoder": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
             "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
             "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
+            "eet_bufmgr_create": (i32, [vp, sz, C.POINTER(vp)]),
+            "eet_bufmgr_request": (i32, [vp, sz, i32, C.POINTER(vp)]),
+            "eet_bufmgr_release": (i32, [vp, vp]),
+            "eet_bufmgr_query": (i32, [vp, C.POINTER(BufMgrStats)]),
+            "eet_bufmgr_destroy": (i32, [vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -95,7 +106,8 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
            "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
-           "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode")
+           "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
+           "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy")
 
 
 def _check(code: int) -> None:
@@ -256,6 +268,33 @@ def eet_op_attention_decode(q, k_cache, v_cache, ctx, n_keys, scratch, stream=No
 
 
 # ---- convenience holder: allocates workspace and cache with torch, keeps tensors alive -------------
+def eet_bufmgr_create(arena_ptr: int, arena_bytes: int) -> C.c_void_p:
+    """arena_ptr: address of caller-owned device memory (an int: the manager never dereferences it)."""
+    h = C.c_void_p()
+    _check(lib().eet_bufmgr_create(arena_ptr, arena_bytes, C.byref(h)))
+    return h
+
+
+def eet_bufmgr_request(handle, nbytes: int, module: int) -> int:
+    p = C.c_void_p()
+    _check(lib().eet_bufmgr_request(handle, nbytes, module, C.byref(p)))
+    return p.value
+
+
+def eet_bufmgr_release(handle, buffer_ptr: int) -> None:
+    _check(lib().eet_bufmgr_release(handle, buffer_ptr))
+
+
+def eet_bufmgr_query(handle) -> BufMgrStats:
+    st = BufMgrStats()
+    _check(lib().eet_bufmgr_query(handle, C.byref(st)))
+    return st
+
+
+def eet_bufmgr_destroy(handle) -> None:
+    _check(lib().eet_bufmgr_destroy(handle))
+
+
 class DecoderLayer:
     """Owns the torch buffers a layer handle borrows.  No arithmetic here."""
 

@@ -156,3 +156,107 @@ def test_oracle_errors():
         mgr.release(a)
     with pytest.raises(obm.BufferError):
         mgr.release(12345)
+
+
+# ---- the library's manager against the oracle, through the C ABI (host logic: runs without a GPU) ----------
+ARENA = 0x7F0000000000                      # an address, never dereferenced by the manager
+
+
+@pytest.fixture(scope="module")
+def eet():
+    from paper_2104_12470_amd import eet as binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2104_12470_amd.build import build_library
+        build_library(verbose=False)
+    binding.lib()
+    return binding
+
+
+class _LibManager:
+    """The library's manager behind the oracle's interface (offsets instead of pointers)."""
+
+    def __init__(self, eet, arena_bytes):
+        self.eet, self.h = eet, eet.eet_bufmgr_create(ARENA, arena_bytes)
+
+    def request(self, nbytes, module):
+        before = self.eet.eet_bufmgr_query(self.h)
+        p = self.eet.eet_bufmgr_request(self.h, nbytes, module)
+        after = self.eet.eet_bufmgr_query(self.h)
+        how = ("created" if after.created > before.created else
+               "larger" if after.reused_larger > before.reused_larger else "same_size")
+        return p - ARENA, how
+
+    def release(self, offset):
+        self.eet.eet_bufmgr_release(self.h, ARENA + offset)
+
+    @property
+    def footprint(self):
+        return self.eet.eet_bufmgr_query(self.h).footprint_bytes
+
+    def close(self):
+        self.eet.eet_bufmgr_destroy(self.h)
+
+
+def test_library_follows_the_hand_worked_scenario(eet):
+    m = _LibManager(eet, 1 << 20)
+    assert run_scenario(m) == []
+    m.close()
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_library_equals_oracle_on_random_traces(eet, seed):
+    arena = 48 * 256 if seed == 14 else 1 << 24          # seed 14: a small arena, so that some requests fail
+    lib_m, ora = _LibManager(eet, arena), obm.BufferManagerOracle(arena)
+    off, failures = {}, 0
+    for e in wl.random_buffer_trace(seed, 600):
+        if e[0] == "req":
+            try:
+                want = ora.request(e[2], e[3])
+            except obm.BufferError:
+                with pytest.raises(eet.EETError) as err:
+                    lib_m.request(e[2], e[3])
+                assert err.value.code == eet.EET_ERR_CAPACITY
+                failures += 1
+                continue
+            assert lib_m.request(e[2], e[3]) == want          # same buffer, same reason: exact integers
+            off[e[1]] = want[0]
+        elif e[1] in off:
+            ora.release(off[e[1]])
+            lib_m.release(off.pop(e[1]))
+        st = eet.eet_bufmgr_query(lib_m.h)
+        assert st.footprint_bytes == ora.footprint and st.buffers == len(ora.buffers)
+        assert st.idle == sum(b.idle for b in ora.buffers)
+        assert (st.requests, st.reused_same_size, st.reused_larger, st.created) == \
+            (ora.counts["requests"], ora.counts["same_size"], ora.counts["larger"], ora.counts["created"])
+    assert (failures > 0) == (seed == 14)
+    lib_m.close()
+
+
+def test_library_unfused_layer_total(eet):
+    b, p, h, n = 4, 1024, 1600, 25
+    m = _LibManager(eet, 1 << 40)
+    for _ in range(3):
+        replay(m, wl.unfused_layer_buffer_trace(b, p, h, n, 4 * h))
+    assert m.footprint == 2 * orc.buffer_elements(b, p, h, n)          # Section 3.2: b*p*(6h + n*p) elements, fp16
+    m.close()
+
+
+def test_library_errors(eet):
+    L = eet.lib()
+    h = C.c_void_p()
+    assert L.eet_bufmgr_create(None, 1024, C.byref(h)) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_bufmgr_create(ARENA + 8, 1024, C.byref(h)) == eet.EET_ERR_INVALID_ARG       # misaligned arena
+    assert L.eet_bufmgr_create(ARENA, 0, C.byref(h)) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_bufmgr_create(ARENA, 1024, C.byref(h)) == eet.EET_OK
+    p = C.c_void_p()
+    assert L.eet_bufmgr_request(h, 0, 0, C.byref(p)) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_bufmgr_request(h, 700, 0, C.byref(p)) == eet.EET_OK and p.value == ARENA
+    q = C.c_void_p()
+    assert L.eet_bufmgr_request(h, 512, 0, C.byref(q)) == eet.EET_ERR_CAPACITY and q.value is None
+    assert b"do not fit" in L.eet_last_error()
+    assert L.eet_bufmgr_release(h, ARENA + 256) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_bufmgr_release(h, p) == eet.EET_OK
+    assert L.eet_bufmgr_release(h, p) == eet.EET_ERR_STATE
+    st = eet.eet_bufmgr_query(h)
+    assert (st.footprint_bytes, st.buffers, st.idle, st.created) == (768, 1, 1, 1)
+    assert L.eet_bufmgr_destroy(h) == eet.EET_OK
