@@ -196,6 +196,17 @@ int eet_op_attention_encoder(const void *q, const void *k_cache, const void *v_c
                              const int32_t *q_lens, int32_t batch, int32_t padded_len,
                              int32_t heads, int32_t d, int32_t capacity, void *hip_stream);
 
+/* The same attention in the unfused form Section 2.1 starts from: scores = Q K^T materialised as
+ * [batch, heads, padded_len, padded_len] fp16, Algorithm 1 (eet_op_softmax_maskfree, scale 1/sqrt(d)) in place,
+ * ctx = P V.  The score buffer is requested from `buffers` for `module` (Section 3.2) and marked idle again
+ * before the call returns: its next user must run on the same stream.  Tiles of pad queries, of keys past a
+ * sequence and of keys no query of the tile sees are neither computed nor read.  Layouts as above; padded_len
+ * must be a multiple of 8.  Adds EET_ERR_CAPACITY when the manager's arena cannot hold the scores. */
+int eet_op_attention_unfused(const void *q, const void *k_cache, const void *v_cache, void *ctx,
+                             const int32_t *q_lens, int32_t batch, int32_t padded_len, int32_t heads,
+                             int32_t d, int32_t capacity, struct eet_bufmgr *buffers, int32_t module,
+                             void *hip_stream);
+
 /* Incremental attention: q, ctx [batch, heads*d]; sequence b attends to slots 0..n_keys[b]-1.
  * n_keys is DEVICE int32[batch], each 1..capacity.  scratch: DEVICE, at least
  * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes (partial results of the

@@ -245,6 +245,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
 // is the only one that compares indices.  Waves whose rows end before the workgroup's last key
 // tile keep loading and synchronising but skip the arithmetic; the row blocks are dealt to the
 // waves so that the two waves of a SIMD (w and w+4) always sum to the same amount of work.
+// LDS transpose read (gfx950): within 16 lanes, lane r supplies the address of 4 consecutive halfs "row r"; lane l
+// receives element l%4 of rows l/4, l/4+4, l/4+8, l/4+12.
+__device__ __forceinline__ half4v lds_read_tr16(const char* p) {
+    typedef short short4v __attribute__((ext_vector_type(4)));
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(half4v, v);
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds + 16*l (the LDS base
 // must be wave-uniform).  Kept out of the templates: the builtin only exists for the device.
 __device__ __forceinline__ void load_lds_16B(const char* gptr, char* lds) {
@@ -568,6 +576,166 @@ hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& len
         if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, false>), grid, block, 0, s, a, lens);
         else hipLaunchKernelGGL((attn_prefill<64, false>), grid, block, 0, s, a, lens);
     }
+    return hipGetLastError();
+}
+
+// ============================================================================================
+// Unfused, paper-form attention: scores = Q K^T, Algorithm 1 as a kernel of its own (rowops), O = P V
+// ============================================================================================
+// The form Section 2.1 describes: the scores of a prompt are materialised as [batch, heads, S, S], the
+// mask-free softmax runs in place on them, and a second contraction applies them to V.  Padding is skipped in
+// all three steps: tiles of pad queries, of keys past the sequence and of keys in the future of every query of
+// the tile are neither computed nor read; inside the tiles that are, the softmax kernel decides entry by entry.
+//
+// Scores: one 128 x 128 tile per workgroup, 2 x 2 waves of 64 x 64.  The contraction depth is the head size, so
+// every operand element is used by one wave exactly once: fragments come straight from global memory in MFMA
+// layout.  Computed transposed (keys as the A operand) so that a lane ends up with 4 consecutive keys of one query.
+template <int D>
+__global__ __launch_bounds__(256) void attn_scores(AttnPrefillArgs a, SeqLens lens, half_t* scores) {
+    constexpr int KK = D / 16;
+    const int b = blockIdx.x / a.heads, g = blockIdx.x % a.heads;
+    const int L = lens.len[b];
+    const int i0 = blockIdx.y * 128, j0 = blockIdx.z * 128;
+    if (i0 >= L || j0 >= L || j0 > i0 + 127) return;          // pad queries, pad keys, keys no query of the tile sees
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, G = lane >> 5;
+    const int iw = i0 + (wave >> 1) * 64, jw = j0 + (wave & 1) * 64;
+    const half_t* kbase = a.k_cache + ((int64_t)b * a.heads + g) * a.capacity * D;
+    const half_t* qbase = a.q + (int64_t)b * a.S * a.hidden + g * D;
+
+    half8v kf[2][KK], qf[2][KK];
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        int j = jw + f * 32 + li, i = iw + f * 32 + li;
+        j = j < L ? j : L - 1;                                  // slots >= L of the cache and pad rows of q are never read
+        i = i < L ? i : L - 1;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            kf[f][kk] = *reinterpret_cast<const half8v*>(kbase + (int64_t)j * D + kk * 16 + G * 8);
+            qf[f][kk] = *reinterpret_cast<const half8v*>(qbase + (int64_t)i * a.hidden + kk * 16 + G * 8);
+        }
+    }
+    half_t* out = scores + ((int64_t)b * a.heads + g) * a.S * a.S;
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi) {
+        const int i = iw + fi * 32 + li;
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj) {
+            float16v acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[fj][kk], qf[fi][kk], acc, 0, 0, 0);
+            if (i >= L) continue;
+            // acc[r]: key jw + fj*32 + (r/4)*8 + G*4 + r%4, query i.  Entries past the row's window hold raw scores;
+            // Algorithm 1 overwrites them.
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int j = jw + fj * 32 + rg * 8 + G * 4;
+                if (j >= a.S) continue;                          // S is a multiple of 8: a group of 4 is inside or outside
+                half4v t;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[e] = (half_t)acc[rg * 4 + e];
+                *reinterpret_cast<half4v*>(out + (int64_t)i * a.S + j) = t;
+            }
+        }
+    }
+}
+
+// O = P V from materialised probabilities.  Workgroup = 4 waves = 128 query rows, wave w rows 32w..32w+31; key tiles
+// of 64: V row-major in LDS (chunks XOR-permuted by the row, transpose reads give the A operand of O^T = V^T P^T), P^T
+// fragments straight from the probability rows (a lane owns one query and reads 8 consecutive keys).  Keys past
+// the diagonal tile are not visited; inside it the probabilities of hidden keys are the zeros Algorithm 1 wrote.
+template <int D>
+__global__ __launch_bounds__(256) void attn_apply(AttnPrefillArgs a, SeqLens lens, const half_t* probs) {
+    constexpr int BQ = 128, BKV = 64, ROWB = D * 2, CPR = ROWB / 16, DB = D / 32;
+    constexpr int NV = BKV * CPR / 256;                         // 16-byte chunks each thread stages per tile
+    __shared__ __attribute__((aligned(1024))) char Vs[BKV * ROWB];
+    const int b = blockIdx.x / a.heads, g = blockIdx.x % a.heads;
+    const int L = lens.len[b];
+    const int i0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * BQ; // longest query tiles first
+    if (i0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, G = lane >> 5;
+    const int iw0 = i0 + wave * 32, i = iw0 + li;
+    const char* vbase = reinterpret_cast<const char*>(a.v_cache + ((int64_t)b * a.heads + g) * a.capacity * D);
+    const half_t* prow = probs + (((int64_t)b * a.heads + g) * a.S + (i < L ? i : L - 1)) * a.S;
+
+    const int s_row = tid / CPR, s_pos = tid % CPR;
+    const int swv = D == 128 ? ((s_row & 3) << 2) : (((s_row >> 1) & 1) << 2);
+    const uint32_t v_src = (uint32_t)((s_pos ^ swv) * 16);
+    unsigned vaddr[DB];     // transpose read: this lane supplies key G*8 + (li%16)/4 (+ offset), 4 halfs at dv db*32 + (li/16)*16 + (li%4)*4
+    {
+        const int lb = li & 15, blk = li >> 4;
+        const int sw = D == 128 ? (((lb >> 2) & 3) << 2) : (((lb >> 3) & 1) << 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int cc = db * 4 + blk * 2 + ((lb & 3) >> 1);
+            vaddr[db] = (G * 8 + (lb >> 2)) * ROWB + ((cc ^ sw) * 16) + (lb & 1) * 8;
+        }
+    }
+    float16v o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+
+    const int last_key = i0 + BQ - 1 < L - 1 ? i0 + BQ - 1 : L - 1;
+    const int ntiles = last_key / BKV + 1;
+    for (int jt = 0; jt < ntiles; ++jt) {
+        const int j0 = jt * BKV;
+        half8v rv[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int key = j0 + v * (256 / CPR) + s_row;
+            key = key < L ? key : L - 1;                        // probabilities of keys >= L are zero; their values must be finite
+            rv[v] = *reinterpret_cast<const half8v*>(vbase + ((uint32_t)key * ROWB + v_src));
+        }
+        __syncthreads();                                        // everyone is done reading the previous tile
+#pragma unroll
+        for (int v = 0; v < NV; ++v) *reinterpret_cast<half8v*>(&Vs[(v * 256 + tid) * 16]) = rv[v];
+        __syncthreads();
+        if (j0 > iw0 + 31 || iw0 >= L) continue;                // whole key tile is in the future of this wave's rows
+#pragma unroll
+        for (int kk = 0; kk < BKV / 16; ++kk) {
+            // keys j0 + kk*16 + G*8 .. +8 of this lane's query (row stride S is a multiple of 8: 16-byte aligned)
+            const half8v pf = j0 + kk * 16 + G * 8 < a.S ? *reinterpret_cast<const half8v*>(prow + j0 + kk * 16 + G * 8)
+                                                         : half8v{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const char* vp = Vs + vaddr[db] + kk * 16 * ROWB;
+                const half4v lo = lds_read_tr16(vp);
+                const half4v hi = lds_read_tr16(vp + 4 * ROWB);
+                const half8v vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[db], 0, 0, 0);
+            }
+        }
+    }
+    if (i >= L) return;
+    half_t* op = a.ctx + ((int64_t)b * a.S + i) * a.hidden + g * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            half4v t;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = (half_t)o[db][rg * 4 + e];
+            *reinterpret_cast<half4v*>(op + db * 32 + rg * 8 + G * 4) = t;
+        }
+}
+
+hipError_t launch_attention_scores(const AttnPrefillArgs& a, const SeqLens& lens, half_t* scores, hipStream_t s) {
+    const int tiles = (a.max_len + 127) / 128;
+    const dim3 grid(a.heads * a.batch, tiles, tiles), block(256);
+    if (a.d == 128) hipLaunchKernelGGL(attn_scores<128>, grid, block, 0, s, a, lens, scores);
+    else hipLaunchKernelGGL(attn_scores<64>, grid, block, 0, s, a, lens, scores);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_apply(const AttnPrefillArgs& a, const SeqLens& lens, const half_t* probs, hipStream_t s) {
+    const dim3 grid(a.heads * a.batch, (a.max_len + 127) / 128), block(256);
+    if (a.d == 128) hipLaunchKernelGGL(attn_apply<128>, grid, block, 0, s, a, lens, probs);
+    else hipLaunchKernelGGL(attn_apply<64>, grid, block, 0, s, a, lens, probs);
     return hipGetLastError();
 }
 

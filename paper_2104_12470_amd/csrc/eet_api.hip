@@ -2,6 +2,7 @@
 // launch sequencing.  No device allocation, no synchronisation except eet_cache_lens.
 #include "../../include/eet.h"
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -629,6 +630,44 @@ int eet_op_attention_encoder(const void* q, const void* k_cache, const void* v_c
                              void* hip_stream) {
     return op_attention_prompt("eet_op_attention_encoder", false, q, k_cache, v_cache, ctx, q_lens, batch, padded_len, heads, d,
                                capacity, hip_stream);
+}
+
+int eet_op_attention_unfused(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* q_lens,
+                             int32_t batch, int32_t padded_len, int32_t heads, int32_t d, int32_t capacity,
+                             eet_bufmgr_t* buffers, int32_t module, void* hip_stream) {
+    const char* who = "eet_op_attention_unfused";
+    if (!q || !k_cache || !v_cache || !ctx || !q_lens || !buffers) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || padded_len < 1 || heads < 1 || capacity < padded_len) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: head size must be 64 or 128", who);
+    if (padded_len % 8 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: padded_len must be a multiple of 8", who);
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "%s: batch > EET_MAX_BATCH", who);
+    if ((int64_t)batch * heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: batch*heads > 65535", who);
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx))
+        return fail(EET_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "%s: q_lens[%d] = %d outside [1, %d]", who, b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+        max_len = q_lens[b] > max_len ? q_lens[b] : max_len;
+    }
+    void* scores = nullptr;
+    const size_t bytes = (size_t)batch * heads * padded_len * padded_len * sizeof(half_t);
+    const int rc = eet_bufmgr_request(buffers, bytes, module, &scores);     // the S x S buffer of Section 3.2
+    if (rc != EET_OK) return rc;
+    AttnPrefillArgs a{};
+    a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
+    a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity; a.hidden = heads * d;
+    a.packed = 0; a.S = padded_len; a.max_len = max_len; a.causal = 1;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_attention_scores(a, lens, (half_t*)scores, s);
+    if (e == hipSuccess) e = launch_softmax_maskfree((half_t*)scores, lens, batch, heads, padded_len, 1.0f / std::sqrt((float)d), s);
+    if (e == hipSuccess) e = launch_attention_apply(a, lens, (const half_t*)scores, s);
+    eet_bufmgr_release(buffers, scores);        // idle for the host; on the stream its next user runs after these kernels
+    if (e != hipSuccess) return hip_fail(e, who);
+    return EET_OK;
 }
 
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity) {

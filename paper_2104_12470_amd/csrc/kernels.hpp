@@ -71,6 +71,10 @@ struct AttnPrefillArgs {
     int causal;             // 1: query i sees keys 0..i; 0: every valid query sees all L_b keys (encoder)
 };
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s);
+// Unfused form (causal, not packed, S a multiple of 8): raw scores q.k into scores[batch, heads, S, S] for the tiles
+// Algorithm 1 will look at; and ctx = probs . V from the probabilities Algorithm 1 left there.
+hipError_t launch_attention_scores(const AttnPrefillArgs& a, const SeqLens& lens, half_t* scores, hipStream_t s);
+hipError_t launch_attention_apply(const AttnPrefillArgs& a, const SeqLens& lens, const half_t* probs, hipStream_t s);
 
 struct AttnDecodeArgs {
     const half_t* q;        // [batch, heads*d]

@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
             "eet_op_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
             "eet_op_attention_prefill": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
             "eet_op_attention_encoder": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
+            "eet_op_attention_unfused": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp, i32, vp]),
             "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
             "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
             "eet_bufmgr_create": (i32, [vp, sz, C.POINTER(vp)]),
@@ -106,7 +107,7 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
            "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
-           "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
+           "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy")
 
 
@@ -254,6 +255,14 @@ def eet_op_attention_encoder(q, k_cache, v_cache, ctx, q_lens, heads, stream=Non
     assert nh == heads and nh * d == H
     _check(lib().eet_op_attention_encoder(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _lens_array(q_lens),
                                           B, S, heads, d, cap, _stream(stream)))
+
+
+def eet_op_attention_unfused(q, k_cache, v_cache, ctx, q_lens, heads, buffers, module: int = 0, stream=None) -> None:
+    B, S, H = q.shape
+    _, nh, cap, d = k_cache.shape
+    assert nh == heads and nh * d == H
+    _check(lib().eet_op_attention_unfused(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _lens_array(q_lens),
+                                          B, S, heads, d, cap, buffers, module, _stream(stream)))
 
 
 def eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) -> int:

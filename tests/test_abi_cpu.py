@@ -117,6 +117,15 @@ def test_op_entry_points_validate(eet):
     assert L.eet_op_attention_prefill(P, P, P, P, lens, 2, 16, 2, 64, 8, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_attention_decode(P, P, P, P, P, 2, 2, 64, 16, None, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_attention_decode_scratch_bytes(2, 2, 64, 4096) > 0
+    # unfused form: needs a buffer manager, a padded length that is a multiple of 8, and an arena that holds the scores
+    mgr = C.c_void_p()
+    assert L.eet_bufmgr_create(0x7F0000000000, 1024, C.byref(mgr)) == eet.EET_OK
+    lens8 = (C.c_int32 * 2)(3, 8)
+    assert L.eet_op_attention_unfused(P, P, P, P, lens8, 2, 16, 2, 64, 16, None, 0, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_attention_unfused(P, P, P, P, lens8, 2, 12, 2, 64, 16, mgr, 0, None) == eet.EET_ERR_UNSUPPORTED_SHAPE
+    assert L.eet_op_attention_unfused(P, P, P, P, lens8, 2, 16, 2, 64, 16, mgr, 0, None) == eet.EET_ERR_CAPACITY   # 2 KB of scores
+    assert eet.eet_bufmgr_query(mgr).buffers == 0                       # nothing was created on the way out
+    assert L.eet_bufmgr_destroy(mgr) == eet.EET_OK
 
 
 def test_stack_sizes_and_validation(eet):

@@ -183,6 +183,57 @@ def test_attention_encoder(eet, d, heads, S, cap, lens):
         assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
 
 
+@pytest.mark.parametrize("d,heads,S,cap,lens", [
+    (64, 2, 24, 32, [24, 1, 7]),
+    (64, 3, 200, 224, [200, 3, 129, 64, 65]),
+    (128, 2, 336, 352, [333, 40, 129, 128]),
+    (128, 1, 520, 520, [520, 256, 257]),
+])
+def test_attention_unfused(eet, d, heads, S, cap, lens):
+    """Paper-form attention: materialised scores from the buffer manager, Algorithm 1 in place, then P.V.
+    Tolerance: the raw scores pass through fp16 before the exponent, so a probability carries a relative error of
+    up to max|s| * 2^-11 / sqrt(d) on top of its own rounding; the context inherits it (bound written below)."""
+    B, H = len(lens), heads * d
+    q = wl.normal(470 + d, 1, (B, S, heads, d))
+    k = wl.normal(470 + d, 2, (B, S, heads, d))
+    v = wl.normal(470 + d, 3, (B, S, heads, d))
+    want = orc.attention_prefill(q, k, v, lens)
+    raw = np.einsum("bihd,bjhd->bhij", q.astype(np.float64), k.astype(np.float64))
+    want_p = orc.softmax_maskfree(raw, lens, 1.0 / np.sqrt(d))
+    kc = np.full((B, heads, cap, d), np.nan, np.float16)          # slots >= L must never be read
+    vc = np.full((B, heads, cap, d), np.nan, np.float16)
+    qp = q.copy()
+    for b, L in enumerate(lens):
+        kc[b, :, :L] = k[b, :L].transpose(1, 0, 2)
+        vc[b, :, :L] = v[b, :L].transpose(1, 0, 2)
+        qp[b, L:] = np.nan                                        # pad queries must never be read
+    score_bytes = B * heads * S * S * 2
+    arena = torch.full((score_bytes + 4096,), 0x7E, dtype=torch.uint8, device="cuda:0")     # 0x7E7E is a NaN pattern in fp16
+    base = (arena.data_ptr() + 255) // 256 * 256
+    mgr = eet.eet_bufmgr_create(base, score_bytes + 256)
+    ctx = torch.full((B, S, H), 7.0, dtype=torch.float16, device="cuda:0")
+    rel = float(max(np.abs(raw[b, :, :L, :L]).max() for b, L in enumerate(lens))) * 2.0 ** -11 / np.sqrt(d)
+    for call in range(2):                                          # the second call reuses the idle score buffer
+        eet.eet_op_attention_unfused(dev(qp.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads, mgr, module=0)
+        torch.cuda.synchronize()
+        got = host(ctx).reshape(B, S, heads, d)
+        for b, L in enumerate(lens):
+            gate(got[b, :L], want[b, :L], f"unfused attention b={b} L={L} call {call}",
+                 OP_MAX + rel * float(np.abs(v[b, :L]).max()), OP_MEAN + rel)
+            assert np.all(got[b, L:] == 7.0)                      # pad rows are not written by the op
+    st = eet.eet_bufmgr_query(mgr)
+    assert (st.created, st.reused_same_size, st.idle, st.footprint_bytes) == (1, 1, 1, (score_bytes + 255) // 256 * 256)
+    # the probabilities Algorithm 1 left in the buffer: request it again (same module, same size: the same buffer)
+    ptr = eet.eet_bufmgr_request(mgr, score_bytes, 0)
+    assert ptr == base
+    off = base - arena.data_ptr()
+    probs = arena[off:off + score_bytes].view(torch.float16).reshape(B, heads, S, S).cpu().numpy().astype(np.float64)
+    for b, L in enumerate(lens):
+        assert np.abs(probs[b, :, :L, :] - want_p[b, :, :L, :]).max() <= 1e-3 + rel        # zeros right of the diagonal included
+    eet.eet_bufmgr_release(mgr, ptr)
+    eet.eet_bufmgr_destroy(mgr)
+
+
 @pytest.mark.parametrize("d,heads,cap,n_keys", [
     (64, 4, 600, [1, 17, 600]),
     (128, 4, 600, [600, 16, 33]),
