@@ -50,13 +50,14 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return t;
 }
 
-// tanh-form GELU in fp32 (the GPT-2 activation).
+// tanh-form GELU in fp32 (the GPT-2 activation): 0.5 x (1 + tanh(u)), u = sqrt(2/pi) (x + 0.044715 x^3), written as
+// x * sigmoid(2u) = x / (1 + 2^(-x (A + B x^2))) with A = 2 sqrt(2/pi) log2(e), B = 0.044715 A: seven vector
+// instructions (one v_exp_f32, one v_rcp_f32), exact limits at +-inf (x * 0 and x * 1), no cancellation.
 __device__ __forceinline__ float gelu_tanh(float x) {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    // tanh(u) = 1 - 2/(exp(2u)+1); exact limits at +-inf, no cancellation problems for |u| small
-    const float e = __expf(2.0f * u);
-    const float t = 1.0f - 2.0f / (e + 1.0f);
-    return 0.5f * x * (1.0f + t);
+    constexpr float A = 2.3022081985f, B = 0.10294323952f;
+    const float t = __builtin_fmaf(x * x, B, A);
+    const float e = __builtin_amdgcn_exp2f(-x * t);
+    return x * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
 }  // namespace eet
