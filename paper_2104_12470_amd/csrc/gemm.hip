@@ -89,6 +89,96 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
 }
 
 // --------------------------------------------------------------------------------------------
+// epilogue of the MFMA tile kernels, through LDS
+// --------------------------------------------------------------------------------------------
+// The accumulator layout gives a lane one row and 4 consecutive columns: stored like that, a wave-level store
+// touches 32 rows with 16 bytes each, and the output (as large as an operand) leaves the chip at a fraction of
+// the memory rate.  Instead each wave turns its (FM*32) x 64 tile around in a private piece of the operand
+// stages, which are free after the main loop: the residual tile comes in with whole-line loads, the epilogue
+// arithmetic runs in fp32 on the accumulators, the rounded tile goes out with whole-line stores (8 rows x 128
+// bytes per instruction).  Rows are 128 bytes; their sixteen 8-byte units are XOR-permuted by (row/2)%16 so that
+// both access patterns spread over all banks.  `stage`: FM*32*128 bytes of LDS no other wave touches; mw, nw:
+// first row and column of the wave tile (its 64 columns are inside N or outside as a whole: N % 64 == 0).
+template <int FM, int FN, int EPI>
+__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float16v (&acc)[FM][FN], char* stage, int mw, int nw,
+                                                 int lane) {
+    static_assert(FN == 2, "64 columns per wave tile");
+    const int M = a.M, N = a.N;
+    if (nw >= N) return;
+    const int r8 = lane >> 3, c8 = lane & 7;              // whole-line pattern: row it*8 + r8, 16-byte chunk c8
+    if (EPI == EPI_BIAS_RES) {
+#pragma unroll 4
+        for (int it = 0; it < FM * 4; ++it) {
+            const int row = it * 8 + r8, m = mw + row;
+            if (m < M) {
+                const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
+                half8v v = *reinterpret_cast<const half8v*>(a.res + rr * N + nw + c8 * 8);
+                const int sw = (row >> 1) & 15;
+                if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
+                *reinterpret_cast<half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16)) = v;
+            }
+        }
+    }
+    // arithmetic on the accumulators: acc[i][j][rg*4 ..+4] = row i*32 + lane%32, columns j*32 + rg*8 + (lane/32)*4 ..+4
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int unit = j * 8 + rg * 2 + (lane >> 5);
+            const half4v bias = *reinterpret_cast<const half4v*>(a.bias + nw + unit * 4);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int row = i * 32 + (lane & 31);
+                half4v* slot = reinterpret_cast<half4v*>(stage + row * 128 + ((unit ^ ((row >> 1) & 15)) * 8));
+                float v0 = acc[i][j][rg * 4 + 0] + (float)bias[0], v1 = acc[i][j][rg * 4 + 1] + (float)bias[1];
+                float v2 = acc[i][j][rg * 4 + 2] + (float)bias[2], v3 = acc[i][j][rg * 4 + 3] + (float)bias[3];
+                if (EPI == EPI_BIAS_GELU) {
+                    v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
+                }
+                if (EPI == EPI_BIAS_RES) {
+                    const half4v r = *slot;
+                    v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
+                }
+                *slot = half4v{(half_t)v0, (half_t)v1, (half_t)v2, (half_t)v3};
+            }
+        }
+    // whole lines out
+#pragma unroll 4
+    for (int it = 0; it < FM * 4; ++it) {
+        const int row = it * 8 + r8, m = mw + row;
+        if (m >= M) continue;
+        const int sw = (row >> 1) & 15;
+        half8v v = *reinterpret_cast<const half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16));
+        if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
+        const int n = nw + c8 * 8;
+        half_t* dst;
+        if (EPI == EPI_QKV) {
+            const int which = n / a.hidden;              // 0 = Q, 1 = K, 2 = V
+            const int c = n - which * a.hidden;
+            if (which == 0) {
+                dst = a.y + (int64_t)m * a.hidden + c;
+            } else {
+                int b_, pos;
+                if (a.tok_row_map) {                     // prefill: token -> (sequence, position)
+                    const int tok = a.tok_row_map[m];
+                    b_ = tok / a.S;
+                    pos = tok - b_ * a.S;
+                } else {                                 // decode: the new token goes to slot n_b
+                    b_ = m;
+                    pos = a.lens[m];
+                }
+                const int g = c / a.d, dd = c - g * a.d;
+                dst = (which == 1 ? a.k_cache : a.v_cache) + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd;
+            }
+        } else {
+            const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
+            dst = a.y + orow * N + n;
+        }
+        *reinterpret_cast<half8v*>(dst) = v;
+    }
+}
+
+// --------------------------------------------------------------------------------------------
 // MFMA tile kernel
 // --------------------------------------------------------------------------------------------
 // Tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x is
@@ -195,22 +285,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
         __syncthreads();
     }
 
-    // acc[i][j][r]: row m = lane%32 of fragment i, column n = (r/4)*8 + (lane/32)*4 + r%4 of fragment j
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm0 + i * 32 + (lane & 31);
-        if (m >= M) continue;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int n = n0 + wn0 + j * 32 + rg * 8 + (lane >> 5) * 4;
-                if (n < N)
-                    epilogue4<EPI>(a, m, n, acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1], acc[i][j][rg * 4 + 2],
-                                   acc[i][j][rg * 4 + 3]);
-            }
-        }
-    }
+    // the loop ended on a barrier: every wave is done with the operand stages
+    static_assert(WN == 64 && FM * 32 * 128 * WGM * WGN <= (int)sizeof(As), "LDS epilogue: 64-column wave tiles staged in As");
+    epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * (FM * 32 * 128), m0 + wm0, n0 + wn0, lane);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -361,90 +438,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 #undef EET_DWAIT
 #undef EET_DMMA
 
-    // Epilogue through LDS.  The accumulator layout gives a lane one row and 4 consecutive columns: stored like
-    // that, a wave-level store touches 32 rows with 16 bytes each, and the output (as large as an operand) leaves
-    // the chip at a fraction of the memory rate.  Instead each wave turns its 128 x 64 tile (WM x WN) around in a
-    // private 16 KB piece of the operand stages, which are free now: the residual tile comes in with whole-line
-    // loads, the epilogue arithmetic runs in fp32 on the accumulators as before, the rounded tile goes out with
-    // whole-line stores (8 rows x 128 bytes per instruction).  Rows are 128 bytes; their sixteen 8-byte units are
-    // XOR-permuted by (row/2)%16 so that both access patterns spread over all banks.
-    static_assert(WM == 128 && WN == 64, "the LDS epilogue is laid out for 128 x 64 wave tiles");
+    static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
-    char* stage = reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * 16384;
-    const int nw = n0 + wn0;                              // first column of the wave tile: in or out as a whole (N % 64 == 0)
-    if (nw < N) {
-        const int r8 = lane >> 3, c8 = lane & 7;          // whole-line pattern: row it*8 + r8, 16-byte chunk c8
-        if (EPI == EPI_BIAS_RES) {
-#pragma unroll 4
-            for (int it = 0; it < 16; ++it) {
-                const int row = it * 8 + r8, m = m0 + wm0 + row;
-                if (m < M) {
-                    const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
-                    half8v v = *reinterpret_cast<const half8v*>(a.res + rr * N + nw + c8 * 8);
-                    const int sw = (row >> 1) & 15;
-                    if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
-                    *reinterpret_cast<half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16)) = v;
-                }
-            }
-        }
-        // arithmetic on the accumulators: acc[i][j][rg*4 ..+4] = row i*32 + lane%32, columns j*32 + rg*8 + (lane/32)*4 ..+4
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int unit = j * 8 + rg * 2 + (lane >> 5);
-                const half4v bias = *reinterpret_cast<const half4v*>(a.bias + nw + unit * 4);
-#pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    const int row = i * 32 + (lane & 31);
-                    half4v* slot = reinterpret_cast<half4v*>(stage + row * 128 + ((unit ^ ((row >> 1) & 15)) * 8));
-                    float v0 = acc[i][j][rg * 4 + 0] + (float)bias[0], v1 = acc[i][j][rg * 4 + 1] + (float)bias[1];
-                    float v2 = acc[i][j][rg * 4 + 2] + (float)bias[2], v3 = acc[i][j][rg * 4 + 3] + (float)bias[3];
-                    if (EPI == EPI_BIAS_GELU) {
-                        v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
-                    }
-                    if (EPI == EPI_BIAS_RES) {
-                        const half4v r = *slot;
-                        v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
-                    }
-                    *slot = half4v{(half_t)v0, (half_t)v1, (half_t)v2, (half_t)v3};
-                }
-            }
-        // whole lines out
-#pragma unroll 4
-        for (int it = 0; it < 16; ++it) {
-            const int row = it * 8 + r8, m = m0 + wm0 + row;
-            if (m >= M) continue;
-            const int sw = (row >> 1) & 15;
-            half8v v = *reinterpret_cast<const half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16));
-            if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
-            const int n = nw + c8 * 8;
-            half_t* dst;
-            if (EPI == EPI_QKV) {
-                const int which = n / a.hidden;          // 0 = Q, 1 = K, 2 = V
-                const int c = n - which * a.hidden;
-                if (which == 0) {
-                    dst = a.y + (int64_t)m * a.hidden + c;
-                } else {
-                    int b_, pos;
-                    if (a.tok_row_map) {                 // prefill: token -> (sequence, position)
-                        const int tok = a.tok_row_map[m];
-                        b_ = tok / a.S;
-                        pos = tok - b_ * a.S;
-                    } else {                             // decode: the new token goes to slot n_b
-                        b_ = m;
-                        pos = a.lens[m];
-                    }
-                    const int g = c / a.d, dd = c - g * a.d;
-                    dst = (which == 1 ? a.k_cache : a.v_cache) + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd;
-                }
-            } else {
-                const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
-                dst = a.y + orow * N + n;
-            }
-            *reinterpret_cast<half8v*>(dst) = v;
-        }
-    }
+    epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * 16384,
+                                  m0 + wm0, n0 + wn0, lane);
 }
 
 // --------------------------------------------------------------------------------------------
