@@ -29,13 +29,13 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
 # the record's kernel name.  Workloads that were not profiled report null.
 MEASURED_TRAFFIC = {
     "cfg2": {
-        "attn_decode<64, 4>": 21.45e6,
-        "decode FFN-2 projection": 9.14e6,
-        "decode attention output projection": 2.36e6,
-        "prefill FFN-1 projection": 80.61e6,
-        "attn_prefill<64>": 46.32e6,
+        "attn_decode<64, 4>": 21.44e6,
+        "decode FFN-2 projection": 9.13e6,
+        "decode attention output projection": 2.35e6,
+        "prefill FFN-1 projection": 74.73e6,
+        "attn_prefill<64, true>": 25.89e6,
         "layernorm_cached": 12.99e6,
-        "softmax_maskfree_vec": 75.64e6,
+        "softmax_maskfree_vec": 75.65e6,
     },
 }
 
@@ -247,11 +247,12 @@ def _kernel_candidates(stack, torch, eet, reps):
         st4["i"] += 1
         attn_op(qp, kc, vc, cp, stack.lens, w.heads)
     ms = time_launches(torch, run_pattn, max(4, min(reps, 24)), replays=2)
+    pname = "attn_prefill_wide" if d == 128 and max(stack.lens) > 128 else "attn_prefill"      # the library's own choice
     if w.encoder:       # every valid row sees all L valid keys: 2 * (2 * L * L * H) flop per sequence
-        out.append({"kernel": f"attn_prefill<{d}, false>: padding-skipping attention without sequence mask (matrix cores)",
+        out.append({"kernel": f"{pname}<{d}, false>: padding-skipping attention without sequence mask (matrix cores)",
                     "bound": "mfma", "work": sum(4.0 * H * L * L for L in stack.lens), "ms": ms, "launches": nl})
     else:
-        out.append({"kernel": f"attn_prefill<{d}>: causal, padding-skipping prefill attention (matrix cores)",
+        out.append({"kernel": f"{pname}<{d}, true>: causal, padding-skipping prefill attention (matrix cores)",
                     "bound": "mfma", "work": sum(2.0 * H * L * (L + 1) for L in stack.lens), "ms": ms, "launches": nl})
     # (5) LayerNorm over the valid rows of the prompt (row kernel, HBM bound): read + write of every row
     xl = torch.randn(T, H, device="cuda:0").half()
