@@ -89,21 +89,28 @@ def softmax_window(s: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Algorithm 1 as a stand-alone operator
 # --------------------------------------------------------------------------------------
-def softmax_maskfree(scores: np.ndarray, q_lens: Sequence[int], scale: float = 1.0) -> np.ndarray:
+def softmax_maskfree(scores: np.ndarray, q_lens: Sequence[int], scale: float = 1.0,
+                     left_padded: bool = False) -> np.ndarray:
     """Mask-free softmax over materialised scores [B, heads, S, S] (Algorithm 1).
 
-    For sequence b with L valid positions, row i < L becomes softmax over keys 0..i and
-    zero over keys i+1..S-1; rows i >= L (pad queries) are returned unchanged.
+    Right-padded (valid positions [0, L)): row i < L becomes softmax over keys 0..i and zero over
+    keys i+1..S-1; rows i >= L (pad queries) are returned unchanged.
+    left_padded: the layout Algorithm 1 is printed for.  With padLen = S - L, the row loop starts at the
+    first non-pad position padLen and ends at the last token S-1, and the window of row i is
+    padLen..i; entries of a valid row outside its window become zero, rows i < padLen are returned
+    unchanged.
     """
     out = np.array(scores, dtype=F64, copy=True)
     B, nh, S, S2 = out.shape
     assert S == S2 and len(q_lens) == B
     for b in range(B):
         L = int(q_lens[b])
+        first = S - L if left_padded else 0                 # first non-pad position
         for g in range(nh):
-            for i in range(L):
-                out[b, g, i, : i + 1] = softmax_window(out[b, g, i, : i + 1] * scale)
-                out[b, g, i, i + 1:] = 0.0
+            for i in range(first, first + L):
+                row = softmax_window(out[b, g, i, first: i + 1] * scale)
+                out[b, g, i, :] = 0.0
+                out[b, g, i, first: i + 1] = row
     return out
 
 
@@ -135,19 +142,22 @@ def attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_keys: int) -> np.ndarr
 
 
 def attention_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_lens: Sequence[int],
-                      causal: bool = True) -> np.ndarray:
+                      causal: bool = True, left_padded: bool = False) -> np.ndarray:
     """Op-level padding-skipping attention.  q, k, v: [B, S, heads, d] (padded); returns the
     context [B, S, heads, d] with pad rows zero.  causal: query i sees keys 0..i (decoder);
     otherwise every valid query sees all L_b valid keys (the encoder layer of Section 4's
-    Bert experiment: padding skip only, no sequence mask)."""
+    Bert experiment: padding skip only, no sequence mask).  left_padded: the valid tokens of
+    sequence b sit at positions S-L_b .. S-1 (the layout of Algorithm 1) instead of 0 .. L_b-1."""
     q = np.asarray(q, F64); k = np.asarray(k, F64); v = np.asarray(v, F64)
     B, S, nh, d = q.shape
     out = np.zeros_like(q)
     for b in range(B):
-        Kb = np.ascontiguousarray(k[b].transpose(1, 0, 2))
-        Vb = np.ascontiguousarray(v[b].transpose(1, 0, 2))
-        for i in range(int(q_lens[b])):
-            out[b, i] = attend(q[b, i], Kb, Vb, i + 1 if causal else int(q_lens[b]))
+        L = int(q_lens[b])
+        first = S - L if left_padded else 0
+        Kb = np.ascontiguousarray(k[b, first: first + L].transpose(1, 0, 2))     # token t of the sequence at index t
+        Vb = np.ascontiguousarray(v[b, first: first + L].transpose(1, 0, 2))
+        for t in range(L):
+            out[b, first + t] = attend(q[b, first + t], Kb, Vb, t + 1 if causal else L)
     return out
 
 
@@ -205,8 +215,14 @@ class DecoderLayerOracle:
 
     # ---- prefill ------------------------------------------------------------------------
     def prefill(self, x: np.ndarray, q_lens: Sequence[int],
-                rows: Optional[Dict[int, Iterable[int]]] = None, causal: bool = True) -> np.ndarray:
+                rows: Optional[Dict[int, Iterable[int]]] = None, causal: bool = True,
+                left_padded: bool = False) -> np.ndarray:
         """Process whole prompts.  x [B, S, H]; q_lens[b] valid rows per sequence.
+
+        left_padded: the valid rows of sequence b are x[b, S-L_b:] (the layout Algorithm 1 is printed
+        for) instead of x[b, :L_b]; the result has the same layout.  Cache slots, `rows` and the
+        lengths stay sequence-relative (slot t = token t of the sequence), so a decode step after
+        either layout is the same computation.
 
         Returns [B, S, H] float64: valid rows hold the layer output, pad rows are zero.
         With `rows` = {b: positions}, only those query rows are evaluated (the cache is
@@ -227,21 +243,22 @@ class DecoderLayerOracle:
             assert 1 <= L <= S
             self.lens[b] = L
             if rows is not None and b not in rows:
-                out[b, :L] = np.nan
+                out[b, (S - L if left_padded else 0):(S if left_padded else L)] = np.nan
                 continue
-            xb = np.asarray(x[b, :L], F64)                  # pad rows are never read
+            first = S - L if left_padded else 0
+            xb = np.asarray(x[b, first: first + L], F64)    # pad rows are never read
             q, k, v = self._qkv(xb)                         # [L, heads, d]
             self.k_cache[b, :, :L] = k.transpose(1, 0, 2)   # slot i <- token i
             self.v_cache[b, :, :L] = v.transpose(1, 0, 2)
             want = range(L) if rows is None else sorted(set(int(i) for i in rows[b]))
             if rows is not None:
-                out[b, :L] = np.nan
+                out[b, first: first + L] = np.nan
             ctx = np.empty((len(want), H), F64)
             for r, i in enumerate(want):
                 assert 0 <= i < L
                 ctx[r] = attend(q[i], self.k_cache[b], self.v_cache[b], i + 1 if causal else L).reshape(H)
             idx = np.fromiter(want, dtype=np.int64, count=len(want))
-            out[b, idx] = self._after_attention(xb[idx], ctx)
+            out[b, first + idx] = self._after_attention(xb[idx], ctx)
         return out
 
     def encode(self, x: np.ndarray, q_lens: Sequence[int],

@@ -26,9 +26,10 @@ def _gelu(t):
     return 0.5 * t * (1.0 + math.tanh(0.7978845608028654 * (t + 0.044715 * t ** 3)))
 
 
-def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True):
+def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True, left_padded=False):
     """x [B,S,H] -> [B,S,H]; rows of pad positions are returned as zeros.  causal_mask=False
-    drops the -inf triangle and keeps only the padding mask (the bidirectional encoder)."""
+    drops the -inf triangle and keeps only the padding mask (the bidirectional encoder).
+    left_padded: the pad positions are the first S-L of a sequence instead of the last."""
     x = np.asarray(x, np.float64)
     B, S, H = x.shape
     d = H // heads
@@ -39,10 +40,11 @@ def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True):
         L = int(q_lens[b])
         # finite stand-in for pad rows: an additive mask cannot cancel NaN/Inf, so a masked
         # implementation needs finite pad content; its value must not matter.
-        rows = [x[b, i].tolist() if i < L else [0.25] * H for i in range(S)]
+        valid = [(i >= S - L) if left_padded else (i < L) for i in range(S)]
+        rows = [x[b, i].tolist() if valid[i] else [0.25] * H for i in range(S)]
         qkv = [_matvec(Wl["w_qkv"], Wl["b_qkv"], _ln(r, Wl["ln1_g"], Wl["ln1_b"], eps)) for r in rows]
         causal = [[0.0 if (j <= i or not causal_mask) else NEG for j in range(S)] for i in range(S)]
-        padmask = [0.0 if j < L else NEG for j in range(S)]
+        padmask = [0.0 if valid[j] else NEG for j in range(S)]
         ctx = [[0.0] * H for _ in range(S)]
         for g in range(heads):
             lo = g * d
@@ -56,7 +58,9 @@ def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True):
                 z = sum(e)
                 for c in range(d):
                     ctx[i][lo + c] = sum(e[j] / z * qkv[j][2 * H + lo + c] for j in range(S))
-        for i in range(L):
+        for i in range(S):
+            if not valid[i]:
+                continue
             att = _matvec(Wl["w_o"], Wl["b_o"], ctx[i])
             y = [rows[i][c] + att[c] for c in range(H)]
             f = [_gelu(t) for t in _matvec(Wl["w_fc1"], Wl["b_fc1"], _ln(y, Wl["ln2_g"], Wl["ln2_b"], eps))]
@@ -65,7 +69,7 @@ def masked_layer(x, q_lens, W, heads, eps=1e-5, causal_mask=True):
     return out
 
 
-def masked_softmax(scores, q_lens, scale=1.0):
+def masked_softmax(scores, q_lens, scale=1.0, left_padded=False):
     """Dense additive-mask softmax of [B,nh,S,S]; returns probabilities for valid rows and the
     input unchanged for pad rows."""
     s = np.asarray(scores, np.float64)
@@ -75,11 +79,14 @@ def masked_softmax(scores, q_lens, scale=1.0):
         L = int(q_lens[b])
         mask = np.zeros((S, S))
         mask[np.triu_indices(S, 1)] = -np.inf
-        mask[:, L:] = -np.inf
+        lo, hi = (S - L, S) if left_padded else (0, L)
+        mask[:, :lo] = -np.inf
+        mask[:, hi:] = -np.inf
         for g in range(nh):
             t = s[b, g] * scale + mask
-            t = t - t.max(axis=1, keepdims=True)
-            e = np.exp(t)
-            p = e / e.sum(axis=1, keepdims=True)
-            out[b, g, :L] = p[:L]
+            with np.errstate(invalid="ignore"):              # rows of pad queries can be all -inf: they are not used
+                t = t - t.max(axis=1, keepdims=True)
+                e = np.exp(t)
+                p = e / e.sum(axis=1, keepdims=True)
+            out[b, g, lo:hi] = p[lo:hi]
     return out

@@ -355,3 +355,61 @@ def test_planted_mistakes_fail_the_encoder_pin(name, fn):
     with _Mutant(name, fn):
         with pytest.raises(AssertionError):
             test_encoder_matches_padding_mask_bruteforce([7, 4, 1], 7, 16, 2, 32)
+
+
+# ------------------------------------------------------------------ left-padded layout (the layout Algorithm 1 is printed for)
+def shift_left(x, lens):
+    """Right-padded [B, S, ...] -> left-padded: the valid rows of sequence b move to [S-L_b, S); pads are NaN."""
+    out = np.full_like(np.asarray(x, np.float64), np.nan)
+    S = x.shape[1]
+    for b, L in enumerate(lens):
+        out[b, S - L:] = x[b, :L]
+    return out
+
+
+@pytest.mark.parametrize("lens,S,H,heads,F", [([7, 4, 1], 7, 16, 2, 32), ([5, 2, 4, 10], 10, 8, 2, 16)])
+def test_left_padded_layer_matches_additive_mask_bruteforce(lens, S, H, heads, F):
+    """Algorithm 1 walks rows padLen .. seqLen-1 of a sequence and lets row i see keys padLen .. i: in that layout
+    the oracle must equal dense scores + additive causal mask + additive mask on the leading pad columns."""
+    W = tiny_weights(3, H, F)
+    xr = wl.normal(5, 1, (len(lens), S, H)).astype(np.float64)
+    xl = shift_left(xr, lens)
+    layer = make_layer(W, heads, len(lens), S)
+    got = layer.prefill(xl, lens, left_padded=True)                  # NaN pads: skipped, not masked
+    want = bf.masked_layer(np.nan_to_num(xl, nan=0.5), lens, W, heads, left_padded=True)
+    for b, L in enumerate(lens):
+        np.testing.assert_allclose(got[b, S - L:], want[b, S - L:], rtol=0, atol=1e-9)
+        assert np.all(got[b, :S - L] == 0.0)
+    # the padding side changes where rows live, nothing else: same numbers, same cache, same lengths
+    k_left, v_left, n_left = layer.k_cache.copy(), layer.v_cache.copy(), layer.lens.copy()
+    right = layer.prefill(xr, lens)
+    for b, L in enumerate(lens):
+        assert np.array_equal(got[b, S - L:], right[b, :L])
+    assert np.array_equal(k_left, layer.k_cache, equal_nan=True) and np.array_equal(v_left, layer.v_cache, equal_nan=True)
+    assert np.array_equal(n_left, layer.lens)
+
+
+def test_left_padded_softmax_op_matches_additive_mask_bruteforce():
+    lens, S = [9, 1, 5], 9
+    s = wl.scores(21, 3, 2, S).astype(np.float64)
+    got = orc.softmax_maskfree(s, lens, scale=0.7, left_padded=True)
+    want = bf.masked_softmax(s, lens, scale=0.7, left_padded=True)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    for b, L in enumerate(lens):
+        pad = S - L
+        assert np.array_equal(got[b, :, :pad], s[b, :, :pad])            # rows of pad queries untouched
+        assert np.all(got[b, :, pad:, :pad] == 0.0)                       # pad keys carry no weight
+        assert np.all(np.triu(got[b, 0], 1)[pad:] == 0.0)                 # nor do later keys
+        np.testing.assert_allclose(got[b, :, pad:].sum(-1), 1.0, atol=1e-12)
+    # a window that starts at key 0 instead of padLen (pad keys visible) is a different function
+    wrong = orc.softmax_maskfree(s, [S] * 3, scale=0.7)
+    assert np.abs(wrong[1, :, S - 1] - want[1, :, S - 1]).max() > 1e-3
+
+
+def test_left_padded_attention_op_equals_right_padded_shifted():
+    lens, S, heads, d = [6, 3, 1], 6, 2, 4
+    q, k, v = (wl.normal(31, t, (3, S, heads, d)).astype(np.float64) for t in (1, 2, 3))
+    right = orc.attention_prefill(q, k, v, lens)
+    left = orc.attention_prefill(shift_left(q, lens), shift_left(k, lens), shift_left(v, lens), lens, left_padded=True)
+    for b, L in enumerate(lens):
+        assert np.array_equal(left[b, S - L:], right[b, :L]) and np.all(left[b, :S - L] == 0.0)
