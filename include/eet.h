@@ -93,6 +93,14 @@ int eet_layer_create(const eet_layer_config *cfg, const eet_layer_weights *weigh
 int eet_prefill(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                 const void *tokens, void *out, void *kv_cache, void *hip_stream);
 
+/* eet_prefill for LEFT-padded prompts, the layout Algorithm 1 is printed for: the valid rows of sequence b are
+ * rows padded_len - q_lens[b] .. padded_len - 1 of `tokens` and of `out` (Algorithm 1's padLen = padded_len -
+ * q_lens[b] pad rows come first; they are never read and are written as 0).  Cache slots and lengths stay
+ * sequence-relative: slot t holds the t-th valid token, so the cache, the lengths and every following
+ * eet_decode_step are exactly those of eet_prefill on the same prompts right-padded.  Errors as eet_prefill. */
+int eet_prefill_left_padded(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                            const void *tokens, void *out, void *kv_cache, void *hip_stream);
+
 /* The layer as a bidirectional encoder (Section 4, "Speedup for Bert Layer": padding tokens are
  * skipped, there is no sequence mask): the same pass as eet_prefill with the window of a valid
  * row i of sequence b widened from slots 0..i to all q_lens[b] valid slots.
@@ -167,6 +175,12 @@ int eet_op_layernorm(const void *x, const void *gamma, const void *beta, void *y
  * window and entries j > i become 0; rows i >= q_lens[b] are not touched.  q_lens is HOST. */
 int eet_op_softmax_maskfree(void *scores, const int32_t *q_lens, int32_t batch, int32_t heads,
                             int32_t padded_len, float scale, void *hip_stream);
+
+/* Algorithm 1 in the layout it is printed for (pads first): with padLen = padded_len - q_lens[b], rows
+ * padLen .. padded_len-1 are the valid queries, row i becomes softmax(scale * score) over keys padLen .. i and 0
+ * elsewhere in the row; rows i < padLen are not touched.  Same errors. */
+int eet_op_softmax_maskfree_left_padded(void *scores, const int32_t *q_lens, int32_t batch, int32_t heads,
+                                        int32_t padded_len, float scale, void *hip_stream);
 
 /* y = gelu_tanh(x + bias); x, y [rows, width], bias [width]. */
 int eet_op_bias_gelu(const void *x, const void *bias, void *y, int64_t rows, int32_t width,

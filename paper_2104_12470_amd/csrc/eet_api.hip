@@ -159,7 +159,8 @@ int eet_layer_destroy(eet_layer_t* layer) {
 
 // Enqueue the kernels of one layer's prefill (arguments already validated).
 static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int padded_len, int64_t T, int max_len,
-                           const void* tokens, void* out, void* kv_cache, hipStream_t s, bool causal = true) {
+                           const void* tokens, void* out, void* kv_cache, hipStream_t s, bool causal = true,
+                           bool left_padded = false) {
     const eet_layer_config& c = L->cfg;
     const int H = c.hidden, F = c.ffn;
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
@@ -174,8 +175,10 @@ static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int pad
     half_t* vc = kc + (size_t)c.max_batch * H * c.max_seq;
 
     // a1: padding offsets -> integers on the device; pad rows of `out` zeroed
-    EET_LAUNCH(launch_prefill_setup(lens, batch, padded_len, H, d_lens, d_cu, d_map, static_cast<half_t*>(out), s),
-               "prefill_setup");
+    // (left_padded: the packed->padded row map starts each sequence at row S - L_b; every kernel below works on
+    // the packed rows and never sees the difference, except the cache scatter, which needs the position)
+    EET_LAUNCH(launch_prefill_setup(lens, batch, padded_len, H, d_lens, d_cu, d_map, static_cast<half_t*>(out), s,
+                                    left_padded), "prefill_setup");
     // a2: LN1 over valid rows only (gathered into the packed layout)
     EET_LAUNCH(launch_layernorm(x, d_map, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, T, H, c.ln_eps,
                                 nullptr, 0, s), "layernorm 1");
@@ -183,7 +186,8 @@ static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int pad
     GemmArgs g{};
     g.x = bufA; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
     g.M = (int)T; g.N = 3 * H; g.K = H;
-    g.k_cache = kc; g.v_cache = vc; g.tok_row_map = d_map; g.lens = nullptr;
+    g.k_cache = kc; g.v_cache = vc; g.tok_row_map = d_map; g.lens = left_padded ? d_lens : nullptr;
+    g.left_pad = left_padded ? 1 : 0;
     g.S = padded_len; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
     EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
     // a4: mask-free attention over the cache (causal window, or all valid keys for the encoder)
@@ -248,6 +252,23 @@ int eet_prefill(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t pa
         return rc;
     const int rc = enqueue_prefill(L, lens, batch, padded_len, T, max_len, tokens, out, kv_cache,
                                    static_cast<hipStream_t>(hip_stream));
+    if (rc != EET_OK) return rc;
+    L->batch = batch;
+    for (int b = 0; b < batch; ++b) L->host_lens[b] = q_lens[b];
+    return EET_OK;
+}
+
+int eet_prefill_left_padded(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                            void* out, void* kv_cache, void* hip_stream) {
+    if (!L) return fail(EET_ERR_INVALID_ARG, "eet_prefill_left_padded: null argument");
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_prefill_left_padded", L->cfg, q_lens, batch, padded_len, tokens, out, kv_cache, lens, T,
+                                     max_len))
+        return rc;
+    const int rc = enqueue_prefill(L, lens, batch, padded_len, T, max_len, tokens, out, kv_cache,
+                                   static_cast<hipStream_t>(hip_stream), true, true);
     if (rc != EET_OK) return rc;
     L->batch = batch;
     for (int b = 0; b < batch; ++b) L->host_lens[b] = q_lens[b];
@@ -541,22 +562,33 @@ int eet_op_layernorm(const void* x, const void* gamma, const void* beta, void* y
     return EET_OK;
 }
 
-int eet_op_softmax_maskfree(void* scores, const int32_t* q_lens, int32_t batch, int32_t heads, int32_t padded_len,
-                            float scale, void* hip_stream) {
-    if (!scores || !q_lens) return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: null argument");
-    if (batch < 1 || heads < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: bad size");
-    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "eet_op_softmax_maskfree: batch > EET_MAX_BATCH");
-    if ((int64_t)batch * heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_softmax_maskfree: batch*heads > 65535");
+static int op_softmax_maskfree(const char* who, bool left_padded, void* scores, const int32_t* q_lens, int32_t batch, int32_t heads,
+                               int32_t padded_len, float scale, void* hip_stream) {
+    if (!scores || !q_lens) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || heads < 1 || padded_len < 1) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "%s: batch > EET_MAX_BATCH", who);
+    if ((int64_t)batch * heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: batch*heads > 65535", who);
     SeqLens lens;
     std::memset(&lens, 0, sizeof(lens));
     for (int b = 0; b < batch; ++b) {
         if (q_lens[b] < 1 || q_lens[b] > padded_len)
-            return fail(EET_ERR_INVALID_ARG, "eet_op_softmax_maskfree: q_lens[%d] = %d outside [1, %d]", b, q_lens[b], padded_len);
+            return fail(EET_ERR_INVALID_ARG, "%s: q_lens[%d] = %d outside [1, %d]", who, b, q_lens[b], padded_len);
         lens.len[b] = q_lens[b];
     }
-    EET_LAUNCH(launch_softmax_maskfree((half_t*)scores, lens, batch, heads, padded_len, scale, (hipStream_t)hip_stream),
-               "softmax");
+    EET_LAUNCH(launch_softmax_maskfree((half_t*)scores, lens, batch, heads, padded_len, scale, (hipStream_t)hip_stream,
+                                       left_padded), "softmax");
     return EET_OK;
+}
+
+int eet_op_softmax_maskfree(void* scores, const int32_t* q_lens, int32_t batch, int32_t heads, int32_t padded_len,
+                            float scale, void* hip_stream) {
+    return op_softmax_maskfree("eet_op_softmax_maskfree", false, scores, q_lens, batch, heads, padded_len, scale, hip_stream);
+}
+
+int eet_op_softmax_maskfree_left_padded(void* scores, const int32_t* q_lens, int32_t batch, int32_t heads,
+                                        int32_t padded_len, float scale, void* hip_stream) {
+    return op_softmax_maskfree("eet_op_softmax_maskfree_left_padded", true, scores, q_lens, batch, heads, padded_len, scale,
+                               hip_stream);
 }
 
 int eet_op_bias_gelu(const void* x, const void* bias, void* y, int64_t rows, int32_t width, void* hip_stream) {

@@ -67,6 +67,7 @@ __device__ __forceinline__ void epilogue_apply(const GemmArgs& a, int m, int n, 
             if (a.tok_row_map) {                 // prefill: token -> (sequence, position)
                 b_ = e.pos / a.S;
                 pos = e.pos - b_ * a.S;
+                if (a.left_pad) pos -= a.S - a.lens[b_];
             } else {                             // decode: the new token goes to slot n_b
                 b_ = m;
                 pos = e.pos;
@@ -163,6 +164,7 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float1
                     const int tok = a.tok_row_map[m];
                     b_ = tok / a.S;
                     pos = tok - b_ * a.S;
+                    if (a.left_pad) pos -= a.S - a.lens[b_];   // pads lead: token 0 of the sequence is at row S - L_b
                 } else {                                 // decode: the new token goes to slot n_b
                     b_ = m;
                     pos = a.lens[m];

@@ -17,12 +17,14 @@ hipError_t launch_bias_gelu(const half_t* x, const half_t* bias, half_t* y, int6
                             hipStream_t s);
 hipError_t launch_bias_residual(const half_t* x, const half_t* bias, const half_t* res, half_t* y,
                                 int64_t rows, int width, hipStream_t s);
+// left_padded: the valid positions of sequence b are S-len[b] .. S-1 (the layout Algorithm 1 is printed for)
 hipError_t launch_softmax_maskfree(half_t* scores, const SeqLens& lens, int batch, int heads, int S,
-                                   float scale, hipStream_t s);
+                                   float scale, hipStream_t s, bool left_padded = false);
 // Index set-up of a prefill: device copies of the lengths, prefix sums, packed->padded row map,
 // and zero fill of the pad rows of `out` ([batch, S, width]).
 hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width, int32_t* cache_lens,
-                                int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s);
+                                int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s,
+                                bool left_padded = false);
 
 // ---- dense projections (gemm.hip) ------------------------------------------------------------
 enum Epilogue : int { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES = 2, EPI_QKV = 3 };
@@ -43,7 +45,8 @@ struct GemmArgs {
     half_t* k_cache;
     half_t* v_cache;
     const int32_t* tok_row_map;   // prefill: packed row -> b*S + pos ; nullptr in decode
-    const int32_t* lens;          // decode: device cache lengths
+    const int32_t* lens;          // decode: device cache lengths; prefill with left_pad: device prompt lengths
+    int left_pad;                 // prefill: tokens of sequence b sit at rows S-len[b] .. S-1 of its block (position = row - (S-len[b]))
     int S, hidden, heads, d, max_seq;
     // weight-streaming kernel only (M <= 16): LayerNorm of x fused in front (nullptr = x is used as it is),
     // and n_b += 1 for the first bump_count sequences (nullptr = no)

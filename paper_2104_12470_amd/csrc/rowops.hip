@@ -197,37 +197,39 @@ hipError_t launch_bias_residual(const half_t* x, const half_t* bias, const half_
 // NV = 8-wide vectors cached per lane (S <= NV*512, S % 8 == 0).
 template <int NV>
 __global__ __launch_bounds__(256) void softmax_maskfree_vec(half_t* __restrict__ scores, SeqLens lens, int heads,
-                                                            int S, float scale_log2e) {
+                                                            int S, float scale_log2e, int left) {
     const int lane = threadIdx.x % kWave;
     const int i = blockIdx.x * 4 + threadIdx.x / kWave;   // query row
     const int bh = blockIdx.y;
     const int b = bh / heads;
-    if (i >= lens.len[b]) return;                          // also covers i >= S
+    const int first = left ? S - lens.len[b] : 0;          // Algorithm 1's padLen when the pads lead: first non-pad position
+    if (i < first || i >= first + lens.len[b]) return;     // pad rows; also covers i >= S
     half8v* row = reinterpret_cast<half8v*>(scores + ((size_t)bh * S + i) * S);
     const int nvec = S >> 3;
-    const int nwin = (i >> 3) + 1;                         // vectors that intersect the window 0..i
+    const int nwin = (i >> 3) + 1;                         // vectors up to the end of the window first..i
+    const int vwin = first >> 3;                           // ... and from its start
 
     float t[NV][8];
     float m = -INFINITY;
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
         const int idx = lane + c * kWave;
-        if (idx < nwin) {
+        if (idx >= vwin && idx < nwin) {
             const half8v v = row[idx];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const bool ok = idx * 8 + e <= i;
+                const bool ok = idx * 8 + e <= i && idx * 8 + e >= first;
                 t[c][e] = ok ? (float)v[e] * scale_log2e : -INFINITY;
                 m = fmaxf(m, t[c][e]);
             }
         }
     }
-    m = wave_max(m);                                       // key 0 is always in the window: m is finite
+    m = wave_max(m);                                       // the first key is always in the window: m is finite
     float sum = 0.f;
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
         const int idx = lane + c * kWave;
-        if (idx < nwin) {
+        if (idx >= vwin && idx < nwin) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 t[c][e] = exp2f(t[c][e] - m);              // exp2(-inf) = 0 for masked entries
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(256) void softmax_maskfree_vec(half_t* __restrict__
         if (idx < nvec) {
             half8v o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (idx < nwin) ? (half_t)(t[c][e] * inv) : (half_t)0.f;
+            for (int e = 0; e < 8; ++e) o[e] = (idx >= vwin && idx < nwin) ? (half_t)(t[c][e] * inv) : (half_t)0.f;
             row[idx] = o;
         }
     }
@@ -251,36 +253,38 @@ __global__ __launch_bounds__(256) void softmax_maskfree_vec(half_t* __restrict__
 
 // Any S: scalar three-pass version, one wave per row.
 __global__ __launch_bounds__(256) void softmax_maskfree_generic(half_t* __restrict__ scores, SeqLens lens,
-                                                                int heads, int S, float scale_log2e) {
+                                                                int heads, int S, float scale_log2e, int left) {
     const int lane = threadIdx.x % kWave;
     const int i = blockIdx.x * 4 + threadIdx.x / kWave;
     const int bh = blockIdx.y;
     const int b = bh / heads;
-    if (i >= lens.len[b]) return;
+    const int first = left ? S - lens.len[b] : 0;
+    if (i < first || i >= first + lens.len[b]) return;
     half_t* row = scores + ((size_t)bh * S + i) * S;
     float m = -INFINITY;
-    for (int j = lane; j <= i; j += kWave) m = fmaxf(m, (float)row[j] * scale_log2e);
+    for (int j = first + lane; j <= i; j += kWave) m = fmaxf(m, (float)row[j] * scale_log2e);
     m = wave_max(m);
     float sum = 0.f;
-    for (int j = lane; j <= i; j += kWave) sum += exp2f((float)row[j] * scale_log2e - m);
+    for (int j = first + lane; j <= i; j += kWave) sum += exp2f((float)row[j] * scale_log2e - m);
     sum = wave_sum(sum);
     const float inv = 1.0f / sum;
     for (int j = lane; j < S; j += kWave)
-        row[j] = (j <= i) ? (half_t)(exp2f((float)row[j] * scale_log2e - m) * inv) : (half_t)0.f;
+        row[j] = (j >= first && j <= i) ? (half_t)(exp2f((float)row[j] * scale_log2e - m) * inv) : (half_t)0.f;
 }
 
 hipError_t launch_softmax_maskfree(half_t* scores, const SeqLens& lens, int batch, int heads, int S, float scale,
-                                   hipStream_t s) {
+                                   hipStream_t s, bool left_padded) {
+    const int left = left_padded ? 1 : 0;
     const dim3 grid((S + 3) / 4, batch * heads), block(256);
     const float sl2 = scale * 1.4426950408889634f;
     const bool vec = (S % 8 == 0) && aligned16(scores);
-#define EET_SM(NV) hipLaunchKernelGGL(softmax_maskfree_vec<NV>, grid, block, 0, s, scores, lens, heads, S, sl2)
+#define EET_SM(NV) hipLaunchKernelGGL(softmax_maskfree_vec<NV>, grid, block, 0, s, scores, lens, heads, S, sl2, left)
     if (vec && S <= 512) EET_SM(1);
     else if (vec && S <= 1024) EET_SM(2);
     else if (vec && S <= 2048) EET_SM(4);
     else if (vec && S <= 4096) EET_SM(8);
     else if (vec && S <= 8192) EET_SM(16);
-    else hipLaunchKernelGGL(softmax_maskfree_generic, grid, block, 0, s, scores, lens, heads, S, sl2);
+    else hipLaunchKernelGGL(softmax_maskfree_generic, grid, block, 0, s, scores, lens, heads, S, sl2, left);
 #undef EET_SM
     return hipGetLastError();
 }
@@ -292,13 +296,14 @@ hipError_t launch_softmax_maskfree(half_t* scores, const SeqLens& lens, int batc
 // the output row.  Block 0 also publishes the lengths and their prefix sums.
 __global__ __launch_bounds__(64) void prefill_setup(SeqLens lens, int batch, int S, int width,
                                                     int32_t* __restrict__ cache_lens, int32_t* __restrict__ cu_seqlens,
-                                                    int32_t* __restrict__ row_map, half_t* __restrict__ out) {
+                                                    int32_t* __restrict__ row_map, half_t* __restrict__ out, int left) {
     const int r = blockIdx.x;
     const int b = r / S, i = r % S;
     int cu = 0;
     for (int k = 0; k < b; ++k) cu += lens.len[k];
-    if (i < lens.len[b]) {
-        if (threadIdx.x == 0) row_map[cu + i] = r;
+    const int first = left ? S - lens.len[b] : 0;          // position of the sequence's token 0 in its padded row block
+    if (i >= first && i < first + lens.len[b]) {
+        if (threadIdx.x == 0) row_map[cu + i - first] = r;
     } else {
         half_t* o = out + (size_t)r * width;
         if ((width & 7) == 0) {
@@ -324,9 +329,9 @@ __global__ __launch_bounds__(64) void prefill_setup(SeqLens lens, int batch, int
 }
 
 hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width, int32_t* cache_lens,
-                                int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s) {
+                                int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s, bool left_padded) {
     hipLaunchKernelGGL(prefill_setup, dim3(batch * S), dim3(64), 0, s, lens, batch, S, width, cache_lens,
-                       cu_seqlens, row_map, out);
+                       cu_seqlens, row_map, out, left_padded ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
             "eet_workspace_bytes": (sz, [cfgp]),
             "eet_layer_create": (i32, [cfgp, C.POINTER(LayerWeights), vp, C.POINTER(vp)]),
             "eet_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_prefill_left_padded": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_layer_encode": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_decode_step": (i32, [vp, vp, vp, vp, vp]),
             "eet_cache_lens": (i32, [vp, i32p, vp]),
@@ -81,6 +82,7 @@ def lib() -> C.CDLL:
             "eet_stack_destroy": (i32, [vp]),
             "eet_op_layernorm": (i32, [vp, vp, vp, vp, i64, i32, f32, vp]),
             "eet_op_softmax_maskfree": (i32, [vp, i32p, i32, i32, i32, f32, vp]),
+            "eet_op_softmax_maskfree_left_padded": (i32, [vp, i32p, i32, i32, i32, f32, vp]),
             "eet_op_bias_gelu": (i32, [vp, vp, vp, i64, i32, vp]),
             "eet_op_bias_residual": (i32, [vp, vp, vp, vp, i64, i32, vp]),
             "eet_op_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
@@ -102,7 +104,8 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_layer_encode", "eet_decode_step",
+EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet_prefill", "eet_prefill_left_padded",
+           "eet_op_softmax_maskfree_left_padded", "eet_layer_encode", "eet_decode_step",
            "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_stack_kv_cache_bytes",
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
@@ -156,6 +159,12 @@ def eet_prefill(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, 
                 out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
     _check(lib().eet_prefill(layer, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
                              _ptr(kv_cache), _stream(stream)))
+
+
+def eet_prefill_left_padded(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens: torch.Tensor,
+                            out: torch.Tensor, kv_cache: torch.Tensor, stream=None) -> None:
+    _check(lib().eet_prefill_left_padded(layer, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
+                                         _ptr(kv_cache), _stream(stream)))
 
 
 def eet_layer_encode(layer: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens: torch.Tensor,
@@ -223,6 +232,12 @@ def eet_op_softmax_maskfree(scores, q_lens, scale=1.0, stream=None) -> None:
     B, nh, S, S2 = scores.shape
     assert S == S2
     _check(lib().eet_op_softmax_maskfree(_ptr(scores), _lens_array(q_lens), B, nh, S, scale, _stream(stream)))
+
+
+def eet_op_softmax_maskfree_left_padded(scores, q_lens, scale=1.0, stream=None) -> None:
+    B, nh, S, S2 = scores.shape
+    assert S == S2
+    _check(lib().eet_op_softmax_maskfree_left_padded(_ptr(scores), _lens_array(q_lens), B, nh, S, scale, _stream(stream)))
 
 
 def eet_op_bias_gelu(x, bias, y, stream=None) -> None:
@@ -323,6 +338,12 @@ class DecoderLayer:
         B, S, _ = tokens.shape
         out = torch.empty_like(tokens) if out is None else out
         eet_prefill(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
+    def prefill_left_padded(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_prefill_left_padded(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
         return out
 
     def encode(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):

@@ -109,6 +109,8 @@ def test_op_entry_points_validate(eet):
     assert L.eet_op_layernorm(P, P, P, P, 4, 0, 1e-5, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_softmax_maskfree(P, lens, 2, 2, 8, 1.0, None) == eet.EET_ERR_INVALID_ARG   # len 9 > S 8
     assert L.eet_op_softmax_maskfree(P, lens, 200, 2, 16, 1.0, None) == eet.EET_ERR_CAPACITY
+    assert L.eet_op_softmax_maskfree_left_padded(P, lens, 2, 2, 8, 1.0, None) == eet.EET_ERR_INVALID_ARG   # len 9 > S 8
+    assert L.eet_op_softmax_maskfree_left_padded(None, lens, 2, 2, 16, 1.0, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_bias_gelu(P, None, P, 4, 64, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_bias_residual(P, P, None, P, 4, 64, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_linear(P, P, P, None, P, 4, 100, 64, 0, None) == eet.EET_ERR_UNSUPPORTED_SHAPE

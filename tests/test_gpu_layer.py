@@ -126,6 +126,47 @@ def test_encoder_use_elementwise(eet, name):
     layer.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "small64", "small128", "cfg3"])
+def test_left_padded_prefill(eet, name):
+    """eet_prefill_left_padded (the layout Algorithm 1 is printed for: pads first) against the oracle in that layout,
+    and against eet_prefill on the same prompts right-padded: same numbers bit for bit, same cache, same lengths,
+    same decode steps afterwards.  cfg3 (full size, 256-row attention tiles) compares GPU with GPU only."""
+    w = wl.WORKLOADS[name]
+    W = wl.layer_weights(w, 0, random_affine=True)
+    x, lens = wl.prompt_embeddings(w), wl.lengths(w)
+    B, S, H = x.shape
+    xl = np.full_like(x, np.nan)                                   # pads (leading) are poison: never read
+    for b, L in enumerate(lens):
+        xl[b, S - L:] = x[b, :L]
+    left, right = make_gpu_layer(eet, w, W), make_gpu_layer(eet, w, W)
+    out_l = torch.full((B, S, H), float("nan"), dtype=torch.float16, device="cuda:0")
+    out_r = torch.full((B, S, H), float("nan"), dtype=torch.float16, device="cuda:0")
+    left.prefill_left_padded(dev(xl), lens, out_l)
+    right.prefill(dev(poison_pads(x, lens)), lens, out_r)
+    torch.cuda.synchronize()
+    got_l, got_r = host(out_l), host(out_r)
+    for b, L in enumerate(lens):
+        assert np.array_equal(got_l[b, S - L:].view(np.uint16), got_r[b, :L].view(np.uint16)), f"{name} b={b}"
+        assert np.all(got_l[b, :S - L] == 0), "pad rows of the output must be zero"
+    assert left.cache_lens(B) == right.cache_lens(B) == [int(v) for v in lens]
+    for a, c in zip(left.cache_views(), right.cache_views()):     # slot t = token t of the sequence in both layouts
+        assert np.array_equal(host(a).view(np.uint16), host(c).view(np.uint16))
+    if name != "cfg3":
+        oracle = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps)
+        want = oracle.prefill(xl, lens, left_padded=True)
+        for b, L in enumerate(lens):
+            gate(got_l[b, S - L:], want[b, S - L:], f"{name} left-padded prefill b={b} L={L}")
+        check_cache(left, oracle, oracle.lens, B, f"{name} after left-padded prefill")
+    for k in range(2):                                             # decode does not know which side the pads were on
+        xs = dev(wl.decode_embeddings(w, k))
+        a, c = left.decode_step(xs), right.decode_step(xs)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(a).view(np.uint16), host(c).view(np.uint16))
+    assert left.cache_lens(B) == [int(v) + 2 for v in lens]
+    left.close()
+    right.close()
+
+
 def test_batch_smaller_than_capacity_and_reuse(eet):
     """A layer sized for 8 sequences serves a batch of 5, then a second, different prefill."""
     w = wl.WORKLOADS["small64"]

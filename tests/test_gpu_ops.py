@@ -81,6 +81,36 @@ def test_softmax_maskfree(eet, B, nh, S, lens):
         np.testing.assert_allclose(got[b, :, :L].astype(np.float64).sum(-1), 1.0, atol=4e-3)
 
 
+@pytest.mark.parametrize("B,nh,S,lens", [
+    (3, 2, 9, [9, 1, 5]),              # scalar path (S % 8 != 0)
+    (4, 1, 10, [5, 2, 4, 10]),
+    (2, 3, 64, [64, 17]),
+    (2, 2, 520, [333, 520]),
+    (2, 1, 4096, [4093, 2049]),        # windows that start and end inside 8-wide vectors
+])
+def test_softmax_maskfree_left_padded(eet, B, nh, S, lens):
+    """Algorithm 1 in the layout it is printed for: pads first, rows padLen..S-1, window padLen..i."""
+    s = wl.scores(230 + S, B, nh, S)
+    poisoned = s.copy()
+    iu = np.triu_indices(S, 1)
+    poisoned[:, :, iu[0], iu[1]] = np.nan                         # keys after the query
+    for b, L in enumerate(lens):
+        poisoned[b, :, :S - L, :] = np.nan                        # rows of pad queries
+        poisoned[b, :, :, :S - L] = np.nan                        # pad keys
+    t = dev(poisoned)
+    eet.eet_op_softmax_maskfree_left_padded(t, lens, 0.37)
+    torch.cuda.synchronize()
+    got = host(t)
+    want = orc.softmax_maskfree(s, lens, 0.37, left_padded=True)
+    for b, L in enumerate(lens):
+        pad = S - L
+        gate(got[b, :, pad:], want[b, :, pad:], f"left-padded softmax b={b}", 1e-3, 1e-4)
+        assert np.all(got[b, :, pad:, :pad] == 0)                 # masked entries are exact zeros
+        assert np.all(got[b, :, pad:][:, np.triu_indices(L, 1)[0], pad + np.triu_indices(L, 1)[1]] == 0)
+        assert np.all(np.isnan(got[b, :, :pad, :]))               # pad rows untouched
+        np.testing.assert_allclose(got[b, :, pad:].astype(np.float64).sum(-1), 1.0, atol=4e-3)
+
+
 @pytest.mark.parametrize("M", [1, 5, 16, 17, 130, 300])
 @pytest.mark.parametrize("K,N", [(64, 64), (256, 192), (1024, 3072), (4096, 1024), (1088, 1216), (1024, 2048), (4608, 3072), (512, 32832), (1280, 1280)])
 def test_linear(eet, M, K, N):
