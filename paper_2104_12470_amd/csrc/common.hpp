@@ -60,4 +60,48 @@ __device__ __forceinline__ float gelu_tanh(float x) {
     return x * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
+// The work of one prefetch workgroup (see PrefetchArgs in kernels.hpp): part `part` of `parts`, `nthreads` threads.
+// One 4-byte load per 128-byte line.  The loads are ordinary loads whose values are xor-ed into a register that an
+// empty asm statement "uses" at the end: nothing is stored, the compiler cannot drop the loads, and it keeps track
+// of the registers they land in (a load whose destination the compiler believes dead would write that register
+// later, after it has been given to something else).
+// lines [lo, hi) of `base`, thread tid of nthreads: eight independent loads in flight per thread
+__device__ __forceinline__ int touch_lines(const char* base, uint32_t lo, uint32_t hi, int tid, int nthreads) {
+    int acc = 0;
+    for (uint32_t i = lo + tid; i < hi; i += 8u * nthreads) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t j = i + (uint32_t)u * nthreads;
+            v[u] = j < hi ? *reinterpret_cast<const int*>(base + (size_t)j * 128) : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    return acc;
+}
+template <class PF>
+__device__ __forceinline__ void run_prefetch(const PF& p, int part, int parts, int tid, int nthreads) {
+    int acc = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const uint32_t lines = p.lin_lines[r];
+        const uint32_t per = (lines + parts - 1) / parts, lo = part * per;
+        const uint32_t hi = lo + per < lines ? lo + per : lines;
+        if (lo < hi) acc ^= touch_lines(static_cast<const char*>(p.lin[r]), lo, hi, tid, nthreads);
+    }
+    if (p.k_cache != nullptr) {
+        const int pairs = p.kv_batch * p.kv_heads;
+        for (int bh = part; bh < pairs; bh += parts) {
+            int rows = p.lens[bh / p.kv_heads];
+            rows = rows < 0 ? 0 : (rows > p.kv_capacity ? p.kv_capacity : rows);                  // never past the pair's slots
+            const uint32_t lines = (uint32_t)rows * (uint32_t)(p.kv_d * 2 / 128);                  // a row is 128 or 256 bytes
+            const size_t off = (size_t)bh * p.kv_capacity * p.kv_d * 2;
+            acc ^= touch_lines(reinterpret_cast<const char*>(p.k_cache) + off, 0, lines, tid, nthreads);
+            acc ^= touch_lines(reinterpret_cast<const char*>(p.v_cache) + off, 0, lines, tid, nthreads);
+        }
+    }
+    asm volatile("" ::"v"(acc));
+}
+
 }  // namespace eet

@@ -291,7 +291,8 @@ int eet_layer_encode(eet_layer_t* L, const int32_t* q_lens, int32_t batch, int32
 
 // Enqueue the kernels of one layer's decode step (arguments already validated).  `bump`: this
 // layer advances the device-side cache lengths (in a stack only the last layer does).
-static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_cache, hipStream_t s, bool bump) {
+static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_cache, hipStream_t s, bool bump,
+                          const eet_layer* next = nullptr, const void* next_kv = nullptr) {
     const eet_layer_config& c = L->cfg;
     const int B = L->batch, H = c.hidden, F = c.ffn;
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
@@ -307,6 +308,16 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     // that consume them (each workgroup recomputes the row statistics of the <= 16 token rows).
     // Measured break-even is near 16 MB of FFN-1 weights; larger layers keep the separate row kernel.
     const bool fuse_ln = B <= 16 && (size_t)F * H * sizeof(half_t) <= ((size_t)16 << 20);
+    // The same small layers leave CUs idle in every launch: extra workgroups of the two launches with the fewest
+    // workgroups pull operands of later launches towards the memory-side cache (PrefetchArgs).  `next`: the layer
+    // whose step follows this one (the next layer of a stack, or this layer's own next step).  Measured on the
+    // 24-layer hidden-1024 stack, one call: 346 -> 324 ms for 512 decode steps.  Prefetching during the attention or
+    // the QKV projection, other workgroup counts (64, 96, 112, 192, 256) and the first feed-forward matrix instead
+    // of the second were all slower: the attention streams from HBM itself, and 128 keeps main plus extra
+    // workgroups at one per CU.
+    constexpr int kPrefetchBlocks = 128;
+    const bool prefetch = fuse_ln;
+    auto lines = [](size_t bytes) { return (uint32_t)(bytes / 128); };
     const half_t* qkv_in = x;
     if (!fuse_ln) {
         EET_LAUNCH(launch_layernorm(x, nullptr, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, B, H,
@@ -334,6 +345,10 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     o.M = B; o.N = H; o.K = H; o.res = x;
     const bool bump_in_gemm = B <= 16;
     if (bump && bump_in_gemm) { o.bump_lens = d_lens; o.bump_count = B; }
+    if (prefetch) {                                       // during the output projection (64 workgroups): the second feed-forward matrix
+        o.pf.lin[0] = L->w.w_fc2; o.pf.lin_lines[0] = lines((size_t)H * F * 2);
+        o.pf.blocks = kPrefetchBlocks;
+    }
     EET_LAUNCH(launch_gemm(o, EPI_BIAS_RES, s), "output projection");
     const half_t* fc1_in = bufY;
     if (!fuse_ln || !bump_in_gemm) {
@@ -349,6 +364,14 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     GemmArgs f2{};
     f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
     f2.M = B; f2.N = H; f2.K = F; f2.res = bufY;
+    if (prefetch && next != nullptr) {                    // during FFN-2 (128 workgroups): the QKV matrix and the K/V rows of the step that follows
+        f2.pf.lin[0] = next->w.w_qkv; f2.pf.lin_lines[0] = lines((size_t)3 * H * H * 2);
+        f2.pf.k_cache = static_cast<const half_t*>(next_kv);
+        f2.pf.v_cache = f2.pf.k_cache + (size_t)c.max_batch * H * c.max_seq;
+        f2.pf.lens = d_lens;
+        f2.pf.kv_batch = B; f2.pf.kv_heads = c.heads; f2.pf.kv_d = L->d; f2.pf.kv_capacity = c.max_seq;
+        f2.pf.blocks = kPrefetchBlocks;
+    }
     EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
     return EET_OK;
 }
@@ -363,7 +386,7 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     for (int b = 0; b < B; ++b)
         if (L->host_lens[b] + 1 > c.max_seq)
             return fail(EET_ERR_CAPACITY, "eet_decode_step: sequence %d is at the cache capacity %d", b, c.max_seq);
-    const int rc = enqueue_decode(L, tokens, out, kv_cache, static_cast<hipStream_t>(hip_stream), true);
+    const int rc = enqueue_decode(L, tokens, out, kv_cache, static_cast<hipStream_t>(hip_stream), true, L, kv_cache);
     if (rc != EET_OK) return rc;
     for (int b = 0; b < B; ++b) L->host_lens[b] += 1;
     return EET_OK;
@@ -487,7 +510,9 @@ static int stack_enqueue_decode(eet_stack* st, const void* tokens, void* out, vo
         const bool last = l == st->n_layers - 1;
         void* o = last ? out : static_cast<void*>(st->ws + st->act[l & 1]);
         char* kv = static_cast<char*>(kv_cache) + (size_t)l * st->layer_cache_bytes;
-        const int rc = enqueue_decode(st->layers[l], in, o, kv, s, last);   // lengths shared: advanced once, at the end
+        const int ln = last ? 0 : l + 1;                                    // the step that follows this layer's
+        const int rc = enqueue_decode(st->layers[l], in, o, kv, s, last,    // lengths shared: advanced once, at the end
+                                      st->layers[ln], static_cast<char*>(kv_cache) + (size_t)ln * st->layer_cache_bytes);
         if (rc != EET_OK) return rc;
         in = o;
     }

@@ -672,6 +672,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
     constexpr int RW = SA * 16 * kFlatStageRow / 2;                     // floats between the waves' tiles
     static_assert(RW >= 16 * 20, "partial-sum tile must fit the wave's own staging space");
 
+    if (a.pf.blocks > 0 && (int)blockIdx.x >= a.N / TN) {   // extra workgroups: operands of the launches that follow
+        run_prefetch(a.pf, (int)blockIdx.x - a.N / TN, a.pf.blocks, tid, NT);
+        return;
+    }
     if (a.bump_lens != nullptr && blockIdx.x == 0 && tid < a.bump_count) a.bump_lens[tid] += 1;
 
     // ---- requests, oldest first: activations, weights, epilogue operands --------------------
@@ -1015,7 +1019,7 @@ static void launch_flat_kernel(void (*kernel)(GemmArgs), const GemmArgs& a, dim3
 
 template <int NW, int UPW, int TN, bool LN>
 static void launch_flat_epi(const GemmArgs& a, Epilogue epi, int lds, hipStream_t s) {
-    const dim3 grid(a.N / TN), block(NW * 64);
+    const dim3 grid(a.N / TN + (a.pf.blocks > 0 ? a.pf.blocks : 0)), block(NW * 64);
     switch (epi) {
         case EPI_BIAS: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS, LN>, a, grid, block, lds, s); break;
         case EPI_BIAS_GELU: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_GELU, LN>, a, grid, block, lds, s); break;

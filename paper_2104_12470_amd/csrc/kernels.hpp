@@ -26,6 +26,21 @@ hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width
                                 int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s,
                                 bool left_padded = false);
 
+// ---- operands of the launches that follow, pulled towards the memory-side cache -------------
+// A latency-bound decode projection leaves CUs idle (64-128 workgroups on 256 CUs).  Extra workgroups of the same
+// launch use them to touch one word of every 128-byte line of what the NEXT launches will read (weights; the K/V
+// rows of the next attention): those launches then find their operands in the memory-side cache, at about half
+// the latency of HBM.  Nothing depends on it: the data is read and dropped.
+struct PrefetchArgs {
+    const void* lin[2];         // linear ranges ...
+    uint32_t lin_lines[2];      // ... in 128-byte lines
+    const half_t* k_cache;      // K/V rows [0, lens[b]) of every (sequence, head); nullptr = none
+    const half_t* v_cache;
+    const int32_t* lens;        // DEVICE
+    int kv_batch, kv_heads, kv_d, kv_capacity;
+    int blocks;                 // extra workgroups that do nothing else; 0 = no prefetch
+};
+
 // ---- dense projections (gemm.hip) ------------------------------------------------------------
 enum Epilogue : int { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES = 2, EPI_QKV = 3 };
 
@@ -55,6 +70,7 @@ struct GemmArgs {
     float ln_eps;
     int32_t* bump_lens;
     int bump_count;
+    PrefetchArgs pf;              // gemm_flat only
 };
 
 // M > 16: MFMA tile kernel.  M <= 16 (decode): weight-streaming kernel.
