@@ -33,7 +33,9 @@ The attention is plain loops over (sequence, head, query row).
 
 Pinned by tests/test_oracle_pins.py (brute force with explicit additive masks, causality and
 padding-independence invariants, decode == prefill of the extended prompt, closed forms, a
-float64 torch cross-check of the unpadded case, and the values the paper prints).
+float64 torch cross-check of the unpadded case, and the values the paper prints) and, for the
+model around the stack, by tests/test_model_pins.py (hand-built tables, a float64 torch model of the
+unpadded case, decode == prefill of the extended prompt, pad ids never read).
 """
 from __future__ import annotations
 
@@ -291,6 +293,87 @@ class DecoderLayerOracle:
         self.lens[:B] += 1
         self.slot_log.append(slots)
         return out
+
+
+# --------------------------------------------------------------------------------------
+# the model around the stack of layers (the model-level interface named in the Conclusion)
+# --------------------------------------------------------------------------------------
+# The paper names an embedding operator and a final output (Section 3.1, first bullet on activation
+# caches) and GPT-2 as the model (Section 4) but prints none of their arithmetic.  Readings taken,
+# all GPT-2's: the input of layer 0 is the token embedding plus a learned absolute position
+# embedding; token t of a sequence has position t whatever the padding; after the last layer comes
+# one more LayerNorm; the logits are that row times the transposed token-embedding matrix (any
+# [vocab, hidden] matrix here), no bias; greedy decoding takes the first maximum.
+def embedding(ids: Sequence[int], positions: Sequence[int], wte: np.ndarray, wpe: np.ndarray) -> np.ndarray:
+    """Rows wte[id] + wpe[position], one per token.  Raises IndexError on an id or a position outside its table."""
+    wte = np.asarray(wte, F64); wpe = np.asarray(wpe, F64)
+    out = np.empty((len(ids), wte.shape[1]), F64)
+    for r, (t, p) in enumerate(zip(ids, positions)):
+        t = int(t); p = int(p)
+        if not (0 <= t < wte.shape[0]) or not (0 <= p < wpe.shape[0]):
+            raise IndexError(f"token {t} / position {p} outside the tables")
+        out[r] = wte[t] + wpe[p]
+    return out
+
+
+def lm_head(x: np.ndarray, lnf_g: np.ndarray, lnf_b: np.ndarray, w_out: np.ndarray, eps: float = 1e-5) -> np.ndarray:
+    """Logits of hidden rows x [rows, H]: LayerNorm, then the product with w_out^T (w_out [vocab, H])."""
+    return layernorm(x, lnf_g, lnf_b, eps) @ np.asarray(w_out, F64).T
+
+
+def greedy_token(logits: np.ndarray, vocab: Optional[int] = None) -> np.ndarray:
+    """Index of the first maximum of each row over columns [0, vocab); a NaN never wins."""
+    logits = np.asarray(logits, F64)
+    vocab = logits.shape[-1] if vocab is None else vocab
+    out = np.zeros(logits.shape[0], np.int32)
+    for r in range(logits.shape[0]):
+        best = -np.inf
+        for j in range(vocab):
+            if logits[r, j] > best:           # strict: the first of equal values stays; NaN compares false
+                best = logits[r, j]
+                out[r] = j
+    return out
+
+
+class DecoderModelOracle:
+    """Embedding, a stack of decoder layers with their K/V caches, final LayerNorm and output projection.
+
+    `layer_weights`: one dict per layer (see DecoderLayerOracle); `head`: wte [vocab, H], wpe [max_pos, H],
+    lnf_g, lnf_b.  The output projection is wte itself (tied weights)."""
+
+    def __init__(self, layer_weights: Sequence[Dict[str, np.ndarray]], head: Dict[str, np.ndarray], heads: int,
+                 max_batch: int, max_seq: int, eps: float = 1e-5):
+        self.layers = [DecoderLayerOracle(w, heads, max_batch, max_seq, eps) for w in layer_weights]
+        self.head = {k: np.asarray(v, F64) for k, v in head.items()}
+        self.eps = eps
+        self.hidden_in = None        # input of layer 0 and output of the last layer of the latest call (for per-part checks)
+        self.hidden_out = None
+
+    def prefill(self, ids: np.ndarray, q_lens: Sequence[int]) -> np.ndarray:
+        """ids [B, S] (right-padded; pad entries are never read), q_lens[b] valid tokens.  Returns the logits
+        [B, vocab] of the LAST valid token of every sequence (the ones the first generated token is drawn from)."""
+        B, S = ids.shape
+        H = self.head["wte"].shape[1]
+        x = np.zeros((B, S, H), F64)
+        for b in range(B):
+            L = int(q_lens[b])
+            x[b, :L] = embedding(ids[b, :L], range(L), self.head["wte"], self.head["wpe"])
+        self.hidden_in = x
+        for layer in self.layers:
+            x = layer.prefill(x, q_lens)
+        self.hidden_out = x
+        last = np.stack([x[b, int(q_lens[b]) - 1] for b in range(B)])
+        return lm_head(last, self.head["lnf_g"], self.head["lnf_b"], self.head["wte"], self.eps)
+
+    def decode_step(self, ids: Sequence[int]) -> np.ndarray:
+        """One new token per sequence, at position n_b.  Returns its logits [B, vocab]."""
+        pos = [int(n) for n in self.layers[0].lens[:len(ids)]]
+        x = embedding(ids, pos, self.head["wte"], self.head["wpe"])
+        self.hidden_in = x
+        for layer in self.layers:
+            x = layer.decode_step(x)
+        self.hidden_out = x
+        return lm_head(x, self.head["lnf_g"], self.head["lnf_b"], self.head["wte"], self.eps)
 
 
 # --------------------------------------------------------------------------------------

@@ -97,6 +97,9 @@ TID_LENS = 1
 TID_PROMPT = 2
 TID_DECODE = 3            # + step * 4096 + layer  (decode inputs are per step)
 TID_LAYER_BASE = 1 << 20  # + layer * 64 + weight slot
+TID_MODEL_HEAD = 1 << 19  # + slot (wte, wpe, lnf_g, lnf_b)
+TID_PROMPT_IDS = 5
+TID_DECODE_IDS = 6        # + step * 4096
 _WEIGHT_SLOTS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -183,6 +186,31 @@ def layer_weights(w: Workload, layer: int = 0, random_affine: bool = False) -> D
         else:
             out[name] = normal(w.seed, tid, shapes[name], w.sigma_w)
     return out
+
+
+def model_head(w: Workload, vocab: int, max_pos: int, random_affine: bool = False) -> Dict[str, np.ndarray]:
+    """fp16 parameters around the stack: token embeddings wte [vocab, hidden] ~ N(0, 0.02) (also the output
+    projection), position embeddings wpe [max_pos, hidden] ~ N(0, 0.01), final LayerNorm lnf_g / lnf_b."""
+    H = w.hidden
+    tid = w.tid_offset + TID_MODEL_HEAD
+    return {"wte": normal(w.seed, tid, (vocab, H), 0.02), "wpe": normal(w.seed, tid + 1, (max_pos, H), 0.01),
+            "lnf_g": normal(w.seed, tid + 2, (H,), 0.1, 1.0) if random_affine else np.ones(H, dtype=np.float16),
+            "lnf_b": normal(w.seed, tid + 3, (H,), 0.1, 0.0) if random_affine else np.zeros(H, dtype=np.float16)}
+
+
+def prompt_ids(w: Workload, vocab: int, pad_value: int = -1) -> np.ndarray:
+    """[batch, padded_len] int32 token ids uniform on [0, vocab); entries past each sequence's length hold
+    `pad_value` (out of range on purpose: nothing may read them)."""
+    ids = uniform_int(w.seed, w.tid_offset + TID_PROMPT_IDS, w.batch * w.padded_len, 0, vocab - 1)
+    ids = ids.reshape(w.batch, w.padded_len)
+    for b, L in enumerate(lengths(w)):
+        ids[b, int(L):] = pad_value
+    return ids
+
+
+def decode_ids(w: Workload, step: int, vocab: int) -> np.ndarray:
+    """[batch] int32 token ids fed at decode step `step` when the generated tokens are not fed back."""
+    return uniform_int(w.seed, w.tid_offset + TID_DECODE_IDS + step * 4096, w.batch, 0, vocab - 1)
 
 
 def scores(seed: int, batch: int, heads: int, seq: int, sigma: float = 2.0) -> np.ndarray:
