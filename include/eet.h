@@ -161,6 +161,71 @@ int eet_stack_cache_lens(eet_stack_t *stack, int32_t *out_host, void *hip_stream
 int eet_stack_destroy(eet_stack_t *stack);
 
 /* ---------------------------------------------------------------------------------------------
+ * The model around a stack: token ids in, logits and the greedy next token out (the model-level
+ * interface of Section 5 for the paper's GPT-2 workload; the paper prints none of this arithmetic,
+ * the readings are GPT-2's).  Input of layer 0 = wte[id] + wpe[position], token t of a sequence at
+ * position t whatever the padding; after the last layer one more LayerNorm (lnf_g, lnf_b, the
+ * stack's ln_eps); logits = that row times wte^T, no bias; next token = first maximum over
+ * columns [0, vocab).
+ * Section 3.1's first rule for activation caches is followed literally: the embedding is written
+ * into one of the stack's two activation buffers, the feed-forward outputs of the layers alternate
+ * between the two, and the final output lands in the same pair -- the model adds no prompt-sized
+ * buffer of its own.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct eet_model eet_model_t;    /* opaque, host memory owned by the library */
+
+typedef struct {
+    int32_t vocab;         /* valid token ids are [0, vocab)                                                  */
+    int32_t vocab_padded;  /* rows of wte that exist in memory and columns of a logits row: >= vocab, multiple */
+                           /* of 64 (rows [vocab, vocab_padded) may hold anything finite; their logits are     */
+                           /* written and never chosen)                                                        */
+    int32_t max_pos;       /* rows of wpe; every position the model is asked for must be below it             */
+} eet_model_config;
+
+typedef struct {           /* DEVICE fp16, BORROWED for the life of the model, 16-byte aligned */
+    const void *wte;       /* [vocab_padded, hidden] token embeddings = output projection (tied) */
+    const void *wpe;       /* [max_pos, hidden] position embeddings                               */
+    const void *lnf_g, *lnf_b; /* [hidden] final LayerNorm                                        */
+} eet_model_weights;
+
+/* Workspace of the model itself (a few [max_batch, hidden] rows and a zero bias of vocab_padded
+ * elements); 0 for an invalid configuration. */
+size_t eet_model_workspace_bytes(const eet_layer_config *cfg, const eet_model_config *mcfg);
+
+/* `stack` is BORROWED and must outlive the model; `cfg` must be the configuration it was created
+ * with.  workspace: DEVICE, eet_model_workspace_bytes, 256-byte aligned; its zero bias is cleared
+ * here with a synchronous memset (the only blocking call besides eet_stack_cache_lens).
+ * Errors: EET_ERR_INVALID_ARG (null, vocab < 1, vocab_padded < vocab, max_pos < max_seq of the
+ * stack, misaligned pointers), EET_ERR_UNSUPPORTED_SHAPE (vocab_padded not a multiple of 64). */
+int eet_model_create(eet_stack_t *stack, const eet_layer_config *cfg, const eet_model_config *mcfg,
+                     const eet_model_weights *weights, void *workspace, eet_model_t **out_model);
+
+/* Whole prompts.  ids: DEVICE int32 [batch, padded_len], right-padded, entries at i >= q_lens[b]
+ * are never read; q_lens: HOST.  logits: DEVICE fp16 [batch, vocab_padded], row b = logits of the
+ * LAST valid token of sequence b.  next_ids: DEVICE int32 [batch] or NULL, the greedy choice.
+ * An id outside [0, vocab) poisons its sequence: its logits come out NaN (and its choice 0).
+ * Arguments, errors and cache behaviour otherwise as eet_stack_prefill. */
+int eet_model_prefill(eet_model_t *model, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                      const int32_t *ids, void *logits, int32_t *next_ids, void *kv_cache, void *hip_stream);
+
+/* One new token per sequence, at position n_b (read on the device).  ids: DEVICE int32 [batch];
+ * it may be the next_ids buffer of the previous call, so generation needs no host round trip.
+ * logits [batch, vocab_padded], next_ids as above.  EET_ERR_CAPACITY when a sequence is at the
+ * cache capacity, EET_ERR_STATE before the first prefill; otherwise as eet_stack_decode_step
+ * (the stack's recorded graph is replayed: the model feeds it from fixed buffers of its own). */
+int eet_model_decode_step(eet_model_t *model, const int32_t *ids, void *logits, int32_t *next_ids,
+                          void *kv_cache, void *hip_stream);
+
+/* DEVICE pointers to what the latest call left in the activation caches, for per-part checks:
+ * *hidden_in = input of layer 0, *hidden_out = output of the last layer; [batch, padded_len,
+ * hidden] after a prefill, [batch, hidden] after a decode step.  Either argument may be NULL.
+ * After a prefill through an EVEN number of layers *hidden_in is NULL: the two activation caches
+ * alternate, so the final output has replaced the embedding. */
+int eet_model_hidden_states(eet_model_t *model, const void **hidden_in, const void **hidden_out);
+
+int eet_model_destroy(eet_model_t *model);   /* frees host memory only; the stack stays */
+
+/* ---------------------------------------------------------------------------------------------
  * Operator-level entry points: the individual kernels of the layer, for parity tests and
  * profiling (the paper exposes an operator-level API as well, Section 5).
  * ------------------------------------------------------------------------------------------- */
@@ -225,6 +290,24 @@ int eet_op_attention_unfused(const void *q, const void *k_cache, const void *v_c
  * n_keys is DEVICE int32[batch], each 1..capacity.  scratch: DEVICE, at least
  * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes (partial results of the
  * key ranges; contents on entry do not matter). */
+/* Embedding of whole prompts: out [batch, padded_len, hidden] fp16; row (b, i) = wte[ids[b, i]] +
+ * wpe[i] (sum in fp32, rounded once) for i < q_lens[b], zeros for pad rows, whose ids are never
+ * read.  ids: DEVICE int32; q_lens: HOST.  hidden must be a multiple of 8.  A row whose id is
+ * outside [0, vocab) or whose position is >= max_pos becomes NaN (nothing is indexed). */
+int eet_op_embedding(const int32_t *ids, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                     int32_t hidden, int32_t vocab, int32_t max_pos, const void *wte, const void *wpe,
+                     void *out, void *hip_stream);
+/* Embedding of one token per sequence: out[b] = wte[ids[b]] + wpe[positions[b]]; ids and positions
+ * DEVICE int32 [batch]. */
+int eet_op_embedding_decode(const int32_t *ids, const int32_t *positions, int32_t batch, int32_t hidden,
+                            int32_t vocab, int32_t max_pos, const void *wte, const void *wpe, void *out,
+                            void *hip_stream);
+/* Greedy choice: out[r] (DEVICE int32 [rows]) = index of the first maximum of the fp16 row
+ * logits[r*row_stride + 0 .. vocab); NaN never wins; a row with nothing above -inf gives 0.
+ * row_stride >= vocab, a multiple of 8 elements; logits 16-byte aligned. */
+int eet_op_argmax(const void *logits, int32_t rows, int32_t vocab, int32_t row_stride, int32_t *out,
+                  void *hip_stream);
+
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity);
 int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_cache, void *ctx,
                             const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,

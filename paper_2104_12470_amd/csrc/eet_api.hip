@@ -575,6 +575,153 @@ int eet_stack_cache_lens(eet_stack_t* st, int32_t* out_host, void* hip_stream) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// the model around a stack
+// ------------------------------------------------------------------------------------------------
+struct eet_model {
+    eet_stack* st;
+    eet_model_config mc;
+    eet_model_weights w;
+    char* ws;
+    size_t zero_bias, last_row, x_dec, y_dec, ln_out;   // byte offsets into ws
+    const void* hidden_in;                               // what the latest call left behind (see eet_model_hidden_states)
+    const void* hidden_out;
+};
+
+struct ModelLayout {
+    size_t zero_bias, last_row, x_dec, y_dec, ln_out, total;
+};
+
+static ModelLayout model_layout(const eet_layer_config* c, const eet_model_config* m) {
+    ModelLayout l{};
+    const size_t row = align_up((size_t)2 * c->max_batch * c->hidden, 256);
+    size_t off = 0;
+    l.zero_bias = off; off = align_up(off + (size_t)2 * m->vocab_padded, 256);
+    l.last_row = off;  off = align_up(off + sizeof(int32_t) * EET_MAX_BATCH, 256);
+    l.x_dec = off;     off += row;
+    l.y_dec = off;     off += row;
+    l.ln_out = off;    off += row;
+    l.total = off;
+    return l;
+}
+
+static const char* model_config_problem(const eet_model_config* m) {
+    if (!m) return "model config is null";
+    if (m->vocab < 1 || m->vocab_padded < m->vocab || m->max_pos < 1) return "vocab, vocab_padded >= vocab and max_pos must be positive";
+    return nullptr;
+}
+
+size_t eet_model_workspace_bytes(const eet_layer_config* cfg, const eet_model_config* mcfg) {
+    if (config_problem(cfg) || shape_problem(cfg) || model_config_problem(mcfg) || mcfg->vocab_padded % 64 != 0) return 0;
+    return model_layout(cfg, mcfg).total;
+}
+
+int eet_model_destroy(eet_model_t* m) {
+    delete m;
+    return EET_OK;
+}
+
+int eet_model_create(eet_stack_t* stack, const eet_layer_config* cfg, const eet_model_config* mcfg,
+                     const eet_model_weights* weights, void* workspace, eet_model_t** out_model) {
+    if (!out_model) return fail(EET_ERR_INVALID_ARG, "eet_model_create: out_model is null");
+    *out_model = nullptr;
+    if (!stack || !cfg || !weights || !workspace) return fail(EET_ERR_INVALID_ARG, "eet_model_create: null argument");
+    if (const char* p = model_config_problem(mcfg)) return fail(EET_ERR_INVALID_ARG, "eet_model_create: %s", p);
+    if (std::memcmp(cfg, &stack->cfg, sizeof(*cfg)) != 0)
+        return fail(EET_ERR_INVALID_ARG, "eet_model_create: cfg is not the configuration the stack was created with");
+    if (mcfg->vocab_padded % 64 != 0)
+        return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_model_create: vocab_padded must be a multiple of 64");
+    if (mcfg->max_pos < cfg->max_seq)
+        return fail(EET_ERR_INVALID_ARG, "eet_model_create: max_pos %d < max_seq %d of the stack", mcfg->max_pos, cfg->max_seq);
+    if (!weights->wte || !weights->wpe || !weights->lnf_g || !weights->lnf_b)
+        return fail(EET_ERR_INVALID_ARG, "eet_model_create: a weight pointer is null");
+    if (!aligned16(weights->wte) || !aligned16(weights->wpe) || !aligned16(weights->lnf_g) || !aligned16(weights->lnf_b) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return fail(EET_ERR_INVALID_ARG, "eet_model_create: weights must be 16-byte and the workspace 256-byte aligned");
+    eet_model* m = new (std::nothrow) eet_model();
+    if (!m) return fail(EET_ERR_INVALID_ARG, "eet_model_create: out of host memory");
+    const ModelLayout l = model_layout(cfg, mcfg);
+    m->st = stack; m->mc = *mcfg; m->w = *weights; m->ws = static_cast<char*>(workspace);
+    m->zero_bias = l.zero_bias; m->last_row = l.last_row; m->x_dec = l.x_dec; m->y_dec = l.y_dec; m->ln_out = l.ln_out;
+    m->hidden_in = m->hidden_out = nullptr;
+    const hipError_t e = hipMemset(m->ws + m->zero_bias, 0, (size_t)2 * mcfg->vocab_padded);
+    if (e != hipSuccess) {
+        delete m;
+        return hip_fail(e, "eet_model_create: clearing the zero bias");
+    }
+    *out_model = m;
+    return EET_OK;
+}
+
+// final LayerNorm of `batch` rows of `hidden` (gathered through row_map when given), output projection, greedy choice
+static int model_head(eet_model* m, const void* hidden, const int32_t* row_map, int batch, void* logits, int32_t* next_ids,
+                      hipStream_t s) {
+    const eet_layer_config& c = m->st->cfg;
+    half_t* ln = reinterpret_cast<half_t*>(m->ws + m->ln_out);
+    EET_LAUNCH(launch_layernorm((const half_t*)hidden, row_map, (const half_t*)m->w.lnf_g, (const half_t*)m->w.lnf_b, ln,
+                                batch, c.hidden, c.ln_eps, nullptr, 0, s), "final layernorm");
+    GemmArgs g{};
+    g.x = ln; g.w = (const half_t*)m->w.wte; g.bias = reinterpret_cast<const half_t*>(m->ws + m->zero_bias);
+    g.y = (half_t*)logits; g.M = batch; g.N = m->mc.vocab_padded; g.K = c.hidden;
+    EET_LAUNCH(launch_gemm(g, EPI_BIAS, s), "output projection");
+    if (next_ids) EET_LAUNCH(launch_argmax((const half_t*)logits, batch, m->mc.vocab, m->mc.vocab_padded, next_ids, s), "greedy choice");
+    return EET_OK;
+}
+
+int eet_model_prefill(eet_model_t* m, const int32_t* q_lens, int32_t batch, int32_t padded_len, const int32_t* ids,
+                      void* logits, int32_t* next_ids, void* kv_cache, void* hip_stream) {
+    if (!m || !ids || !logits) return fail(EET_ERR_INVALID_ARG, "eet_model_prefill: null argument");
+    if (!aligned16(logits)) return fail(EET_ERR_INVALID_ARG, "eet_model_prefill: logits must be 16-byte aligned");
+    eet_stack* st = m->st;
+    void* x0 = st->ws + st->act[1];                              // embedding -> one activation cache ...
+    void* xn = st->ws + st->act[(st->n_layers - 1) & 1];         // ... final output -> where the last layer's turn falls
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_model_prefill", st->cfg, q_lens, batch, padded_len, x0, xn, kv_cache, lens, T, max_len))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int32_t* last_row = reinterpret_cast<int32_t*>(m->ws + m->last_row);
+    EET_LAUNCH(launch_embedding(ids, lens, nullptr, batch, padded_len, st->cfg.hidden, m->mc.vocab, m->mc.max_pos,
+                                (const half_t*)m->w.wte, (const half_t*)m->w.wpe, (half_t*)x0, last_row, s), "embedding");
+    if (const int rc = eet_stack_prefill(st, q_lens, batch, padded_len, x0, xn, kv_cache, hip_stream)) return rc;
+    m->hidden_in = x0 == xn ? nullptr : x0;      // an even number of layers ends in the buffer the embedding was in
+    m->hidden_out = xn;
+    return model_head(m, xn, last_row, batch, logits, next_ids, s);
+}
+
+int eet_model_decode_step(eet_model_t* m, const int32_t* ids, void* logits, int32_t* next_ids, void* kv_cache,
+                          void* hip_stream) {
+    if (!m || !ids || !logits || !kv_cache) return fail(EET_ERR_INVALID_ARG, "eet_model_decode_step: null argument");
+    if (!aligned16(logits)) return fail(EET_ERR_INVALID_ARG, "eet_model_decode_step: logits must be 16-byte aligned");
+    eet_stack* st = m->st;
+    if (st->batch == 0) return fail(EET_ERR_STATE, "eet_model_decode_step: no prefill has been run on this model");
+    const int B = st->batch;
+    for (int b = 0; b < B; ++b)      // before anything is enqueued (the stack call repeats the check, but after the embedding)
+        if (st->host_lens[b] + 1 > st->cfg.max_seq)
+            return fail(EET_ERR_CAPACITY, "eet_model_decode_step: sequence %d is at the cache capacity %d", b, st->cfg.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    void* x = m->ws + m->x_dec;
+    void* y = m->ws + m->y_dec;
+    const int32_t* d_lens = reinterpret_cast<const int32_t*>(st->layers[0]->ws + st->layers[0]->lay.lens);
+    SeqLens none;
+    std::memset(&none, 0, sizeof(none));
+    EET_LAUNCH(launch_embedding(ids, none, d_lens, B, 1, st->cfg.hidden, m->mc.vocab, m->mc.max_pos, (const half_t*)m->w.wte,
+                                (const half_t*)m->w.wpe, (half_t*)x, nullptr, s), "embedding");
+    if (const int rc = eet_stack_decode_step(st, x, y, kv_cache, hip_stream)) return rc;
+    m->hidden_in = x;
+    m->hidden_out = y;
+    return model_head(m, y, nullptr, B, logits, next_ids, s);
+}
+
+int eet_model_hidden_states(eet_model_t* m, const void** hidden_in, const void** hidden_out) {
+    if (!m) return fail(EET_ERR_INVALID_ARG, "eet_model_hidden_states: null argument");
+    if (!m->hidden_out) return fail(EET_ERR_STATE, "eet_model_hidden_states: no call has been run on this model");
+    if (hidden_in) *hidden_in = m->hidden_in;
+    if (hidden_out) *hidden_out = m->hidden_out;
+    return EET_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // operator-level entry points
 // ------------------------------------------------------------------------------------------------
 int eet_op_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int32_t width,
@@ -724,6 +871,50 @@ int eet_op_attention_unfused(const void* q, const void* k_cache, const void* v_c
     if (e == hipSuccess) e = launch_attention_apply(a, lens, (const half_t*)scores, s);
     eet_bufmgr_release(buffers, scores);        // idle for the host; on the stream its next user runs after these kernels
     if (e != hipSuccess) return hip_fail(e, who);
+    return EET_OK;
+}
+
+int eet_op_embedding(const int32_t* ids, const int32_t* q_lens, int32_t batch, int32_t padded_len, int32_t hidden,
+                     int32_t vocab, int32_t max_pos, const void* wte, const void* wpe, void* out, void* hip_stream) {
+    const char* who = "eet_op_embedding";
+    if (!ids || !q_lens || !wte || !wpe || !out) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || padded_len < 1 || hidden < 1 || vocab < 1 || max_pos < 1) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (hidden % 8 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: hidden must be a multiple of 8", who);
+    if (batch > EET_MAX_BATCH) return fail(EET_ERR_CAPACITY, "%s: batch > EET_MAX_BATCH", who);
+    if ((int64_t)batch * padded_len > 0x7fffffff) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: more than 2^31-1 rows", who);
+    if (!aligned16(wte) || !aligned16(wpe) || !aligned16(out)) return fail(EET_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    for (int b = 0; b < batch; ++b) {
+        if (q_lens[b] < 1 || q_lens[b] > padded_len)
+            return fail(EET_ERR_INVALID_ARG, "%s: q_lens[%d] = %d outside [1, %d]", who, b, q_lens[b], padded_len);
+        lens.len[b] = q_lens[b];
+    }
+    EET_LAUNCH(launch_embedding(ids, lens, nullptr, batch, padded_len, hidden, vocab, max_pos, (const half_t*)wte,
+                                (const half_t*)wpe, (half_t*)out, nullptr, (hipStream_t)hip_stream), "embedding");
+    return EET_OK;
+}
+
+int eet_op_embedding_decode(const int32_t* ids, const int32_t* positions, int32_t batch, int32_t hidden, int32_t vocab,
+                            int32_t max_pos, const void* wte, const void* wpe, void* out, void* hip_stream) {
+    const char* who = "eet_op_embedding_decode";
+    if (!ids || !positions || !wte || !wpe || !out) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || hidden < 1 || vocab < 1 || max_pos < 1) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (hidden % 8 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: hidden must be a multiple of 8", who);
+    if (!aligned16(wte) || !aligned16(wpe) || !aligned16(out)) return fail(EET_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+    SeqLens none;
+    std::memset(&none, 0, sizeof(none));
+    EET_LAUNCH(launch_embedding(ids, none, positions, batch, 1, hidden, vocab, max_pos, (const half_t*)wte, (const half_t*)wpe,
+                                (half_t*)out, nullptr, (hipStream_t)hip_stream), "embedding");
+    return EET_OK;
+}
+
+int eet_op_argmax(const void* logits, int32_t rows, int32_t vocab, int32_t row_stride, int32_t* out, void* hip_stream) {
+    if (!logits || !out) return fail(EET_ERR_INVALID_ARG, "eet_op_argmax: null argument");
+    if (rows < 0 || vocab < 1 || row_stride < vocab) return fail(EET_ERR_INVALID_ARG, "eet_op_argmax: bad size");
+    if (row_stride % 8 != 0 || !aligned16(logits))
+        return fail(EET_ERR_INVALID_ARG, "eet_op_argmax: row_stride must be a multiple of 8 and logits 16-byte aligned");
+    EET_LAUNCH(launch_argmax((const half_t*)logits, rows, vocab, row_stride, out, (hipStream_t)hip_stream), "greedy choice");
     return EET_OK;
 }
 

@@ -43,6 +43,17 @@ class BufMgrStats(C.Structure):
                 ("created", C.c_int64)]
 
 
+class ModelConfig(C.Structure):
+    _fields_ = [("vocab", C.c_int32), ("vocab_padded", C.c_int32), ("max_pos", C.c_int32)]
+
+
+MODEL_WEIGHT_FIELDS = ("wte", "wpe", "lnf_g", "lnf_b")
+
+
+class ModelWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in MODEL_WEIGHT_FIELDS]
+
+
 class EETError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"eet error {code}: {message}")
@@ -91,6 +102,15 @@ def lib() -> C.CDLL:
             "eet_op_attention_unfused": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp, i32, vp]),
             "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
             "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
+            "eet_model_workspace_bytes": (sz, [cfgp, C.POINTER(ModelConfig)]),
+            "eet_model_create": (i32, [vp, cfgp, C.POINTER(ModelConfig), C.POINTER(ModelWeights), vp, C.POINTER(vp)]),
+            "eet_model_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp, vp]),
+            "eet_model_decode_step": (i32, [vp, vp, vp, vp, vp, vp]),
+            "eet_model_hidden_states": (i32, [vp, C.POINTER(vp), C.POINTER(vp)]),
+            "eet_model_destroy": (i32, [vp]),
+            "eet_op_embedding": (i32, [vp, i32p, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
+            "eet_op_embedding_decode": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
+            "eet_op_argmax": (i32, [vp, i32, i32, i32, vp, vp]),
             "eet_bufmgr_create": (i32, [vp, sz, C.POINTER(vp)]),
             "eet_bufmgr_request": (i32, [vp, sz, i32, C.POINTER(vp)]),
             "eet_bufmgr_release": (i32, [vp, vp]),
@@ -111,7 +131,9 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
            "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
            "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
-           "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy")
+           "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
+           "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
+           "eet_op_embedding_decode", "eet_op_argmax")
 
 
 def _check(code: int) -> None:
@@ -291,6 +313,58 @@ def eet_op_attention_decode(q, k_cache, v_cache, ctx, n_keys, scratch, stream=No
                                          cap, _ptr(scratch), _stream(stream)))
 
 
+def eet_op_embedding(ids, q_lens, wte, wpe, out, vocab: Optional[int] = None, stream=None) -> None:
+    B, S = ids.shape
+    assert ids.dtype == torch.int32 and ids.is_cuda
+    _check(lib().eet_op_embedding(_ptr(ids), _lens_array(q_lens), B, S, wte.shape[1], wte.shape[0] if vocab is None else vocab,
+                                  wpe.shape[0], _ptr(wte), _ptr(wpe), _ptr(out), _stream(stream)))
+
+
+def eet_op_embedding_decode(ids, positions, wte, wpe, out, vocab: Optional[int] = None, stream=None) -> None:
+    assert ids.dtype == torch.int32 and positions.dtype == torch.int32 and ids.is_cuda and positions.is_cuda
+    _check(lib().eet_op_embedding_decode(_ptr(ids), _ptr(positions), ids.shape[0], wte.shape[1],
+                                         wte.shape[0] if vocab is None else vocab, wpe.shape[0], _ptr(wte), _ptr(wpe), _ptr(out),
+                                         _stream(stream)))
+
+
+def eet_op_argmax(logits, out, vocab: Optional[int] = None, stream=None) -> None:
+    rows, stride = logits.shape
+    assert out.dtype == torch.int32 and out.is_cuda
+    _check(lib().eet_op_argmax(_ptr(logits), rows, stride if vocab is None else vocab, stride, _ptr(out), _stream(stream)))
+
+
+def eet_model_workspace_bytes(cfg: LayerConfig, mcfg: ModelConfig) -> int:
+    return lib().eet_model_workspace_bytes(C.byref(cfg), C.byref(mcfg))
+
+
+def eet_model_create(stack: int, cfg: LayerConfig, mcfg: ModelConfig, weights: Dict[str, torch.Tensor], workspace) -> int:
+    w = ModelWeights(*[_ptr(weights[n]) for n in MODEL_WEIGHT_FIELDS])
+    handle = C.c_void_p()
+    _check(lib().eet_model_create(stack, C.byref(cfg), C.byref(mcfg), C.byref(w), _ptr(workspace), C.byref(handle)))
+    return handle.value
+
+
+def eet_model_prefill(model: int, q_lens: Sequence[int], batch: int, padded_len: int, ids, logits, next_ids, kv_cache,
+                      stream=None) -> None:
+    _check(lib().eet_model_prefill(model, _lens_array(q_lens), batch, padded_len, _ptr(ids), _ptr(logits), _ptr(next_ids),
+                                   _ptr(kv_cache), _stream(stream)))
+
+
+def eet_model_decode_step(model: int, ids, logits, next_ids, kv_cache, stream=None) -> None:
+    _check(lib().eet_model_decode_step(model, _ptr(ids), _ptr(logits), _ptr(next_ids), _ptr(kv_cache), _stream(stream)))
+
+
+def eet_model_hidden_states(model: int):
+    """Device addresses (ints) of the input of layer 0 and the output of the last layer of the latest call."""
+    a, b = C.c_void_p(), C.c_void_p()
+    _check(lib().eet_model_hidden_states(model, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def eet_model_destroy(model: int) -> None:
+    _check(lib().eet_model_destroy(model))
+
+
 # ---- convenience holder: allocates workspace and cache with torch, keeps tensors alive -------------
 def eet_bufmgr_create(arena_ptr: int, arena_bytes: int) -> C.c_void_p:
     """arena_ptr: address of caller-owned device memory (an int: the manager never dereferences it)."""
@@ -408,6 +482,66 @@ class DecoderStack:
         if self.handle:
             eet_stack_destroy(self.handle)
             self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class DecoderModel:
+    """A DecoderStack plus the embedding tables and the final LayerNorm: token ids in, logits and greedy tokens out.
+    Owns the torch buffers the model handle borrows.  No arithmetic here."""
+
+    def __init__(self, cfg: LayerConfig, layer_weights: Sequence[Dict[str, torch.Tensor]], head: Dict[str, torch.Tensor],
+                 vocab: int, device="cuda:0", cache_fill: float = 0.0, use_graph: bool = True):
+        self.stack = DecoderStack(cfg, layer_weights, device=device, cache_fill=cache_fill, use_graph=use_graph)
+        self.cfg, self.vocab = cfg, vocab
+        self.head = {n: head[n].to(device=device, dtype=torch.float16).contiguous() for n in MODEL_WEIGHT_FIELDS}
+        vp = (vocab + 63) // 64 * 64
+        if self.head["wte"].shape[0] < vp:          # rows up to the padded vocabulary exist in memory (zeros)
+            pad = torch.zeros((vp - self.head["wte"].shape[0], cfg.hidden), dtype=torch.float16, device=device)
+            self.head["wte"] = torch.cat([self.head["wte"], pad]).contiguous()
+        self.mcfg = ModelConfig(vocab, vp, self.head["wpe"].shape[0])
+        self.workspace = torch.empty(eet_model_workspace_bytes(cfg, self.mcfg), dtype=torch.uint8, device=device)
+        self.handle = eet_model_create(self.stack.handle, cfg, self.mcfg, self.head, self.workspace)
+        self.batch = 0
+
+    def prefill(self, ids: torch.Tensor, q_lens: Sequence[int], stream=None):
+        B, S = ids.shape
+        logits = torch.empty((B, self.mcfg.vocab_padded), dtype=torch.float16, device=ids.device)
+        nxt = torch.empty((B,), dtype=torch.int32, device=ids.device)
+        eet_model_prefill(self.handle, q_lens, B, S, ids, logits, nxt, self.stack.kv_cache, stream)
+        self.batch, self.padded_len = B, S
+        return logits, nxt
+
+    def decode_step(self, ids: torch.Tensor, stream=None):
+        logits = torch.empty((ids.shape[0], self.mcfg.vocab_padded), dtype=torch.float16, device=ids.device)
+        nxt = torch.empty((ids.shape[0],), dtype=torch.int32, device=ids.device)
+        eet_model_decode_step(self.handle, ids, logits, nxt, self.stack.kv_cache, stream)
+        return logits, nxt
+
+    def hidden_states(self, decode: bool):
+        """Views of the activation caches after the latest call: (input of layer 0, output of the last layer)."""
+        shape = (self.batch, self.cfg.hidden) if decode else (self.batch, self.padded_len, self.cfg.hidden)
+        n = 2 * self.batch * self.cfg.hidden * (1 if decode else self.padded_len)
+        out = []
+        for addr in eet_model_hidden_states(self.handle):
+            view = None
+            for buf in (self.stack.workspace, self.workspace):
+                off = -1 if addr is None else addr - buf.data_ptr()
+                if 0 <= off and off + n <= buf.numel():
+                    view = buf[off: off + n].view(torch.float16).view(shape)
+            out.append(view)                        # None: the buffer has been reused (see eet_model_hidden_states)
+        assert out[1] is not None
+        return out[0], out[1]
+
+    def close(self):
+        if self.handle:
+            eet_model_destroy(self.handle)
+            self.handle = None
+        self.stack.close()
 
     def __del__(self):
         try:

@@ -152,3 +152,45 @@ def test_stack_sizes_and_validation(eet):
     assert L.eet_stack_destroy(h) == eet.EET_OK
     bad = (eet.LayerWeights * 2)(eet.LayerWeights(*[0x10000] * 12), eet.LayerWeights(*[0x10000] * 11, 0))
     assert L.eet_stack_create(C.byref(cfg), 2, bad, 0x100000, 1, C.byref(h)) == eet.EET_ERR_INVALID_ARG and not h.value
+
+
+def test_model_and_its_operators_validate(eet):
+    L = eet.lib()
+    cfg = eet.make_config(1024, 16, 4096, 8, 512, 1024)
+    P = 0x200000
+    # sizes: a zero bias of vocab_padded halfs, the per-sequence row indices and three [max_batch, hidden] rows -- no
+    # prompt-sized buffer (Section 3.1: the embedding and the final output live in the stack's activation caches)
+    mc = eet.ModelConfig(50257, 50304, 1024)
+    ws = eet.eet_model_workspace_bytes(cfg, mc)
+    assert 2 * 50304 + 3 * 2 * 8 * 1024 <= ws <= 2 * 50304 + 3 * 2 * 8 * 1024 + 4096
+    assert eet.eet_model_workspace_bytes(cfg, eet.ModelConfig(50257, 50257, 1024)) == 0      # not a multiple of 64
+    assert eet.eet_model_workspace_bytes(cfg, eet.ModelConfig(50257, 50240, 1024)) == 0      # padded < vocab
+    lw = (eet.LayerWeights * 1)(eet.LayerWeights(*[0x10000] * 12))
+    st = C.c_void_p()
+    assert L.eet_stack_create(C.byref(cfg), 1, lw, 0x100000, 1, C.byref(st)) == eet.EET_OK
+    mw = eet.ModelWeights(P, P, P, P)
+    h = C.c_void_p()
+    create = lambda s, c, m, w, wsp: L.eet_model_create(s, C.byref(c), C.byref(m), C.byref(w), wsp, C.byref(h))
+    assert create(None, cfg, mc, mw, P) == eet.EET_ERR_INVALID_ARG
+    assert create(st, eet.make_config(1024, 16, 4096, 8, 512, 2048), mc, mw, P) == eet.EET_ERR_INVALID_ARG   # another configuration
+    assert create(st, cfg, eet.ModelConfig(50257, 50257, 1024), mw, P) == eet.EET_ERR_UNSUPPORTED_SHAPE
+    assert create(st, cfg, eet.ModelConfig(0, 64, 1024), mw, P) == eet.EET_ERR_INVALID_ARG
+    assert create(st, cfg, eet.ModelConfig(50257, 50304, 1000), mw, P) == eet.EET_ERR_INVALID_ARG          # max_pos < max_seq
+    assert create(st, cfg, mc, eet.ModelWeights(P, P, 0, P), P) == eet.EET_ERR_INVALID_ARG
+    assert create(st, cfg, mc, eet.ModelWeights(P + 2, P, P, P), P) == eet.EET_ERR_INVALID_ARG
+    assert create(st, cfg, mc, mw, P + 16) == eet.EET_ERR_INVALID_ARG and not h.value                      # workspace alignment
+    assert L.eet_model_prefill(None, None, 1, 1, P, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_model_decode_step(None, P, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_model_hidden_states(None, None, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_model_destroy(None) == eet.EET_OK
+    assert L.eet_stack_destroy(st) == eet.EET_OK
+    lens = (C.c_int32 * 2)(3, 9)
+    assert L.eet_op_embedding(P, lens, 2, 8, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG        # len 9 > S 8
+    assert L.eet_op_embedding(P, lens, 2, 16, 60, 100, 16, P, P, P, None) == eet.EET_ERR_UNSUPPORTED_SHAPE # hidden % 8
+    assert L.eet_op_embedding(P, lens, 2, 16, 64, 100, 16, P, P + 4, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_embedding(None, lens, 2, 16, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_embedding_decode(P, None, 2, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_embedding_decode(P, P, 2, 64, 0, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_argmax(P, 2, 100, 96, P, None) == eet.EET_ERR_INVALID_ARG                              # stride < vocab
+    assert L.eet_op_argmax(P, 2, 100, 100, P, None) == eet.EET_ERR_INVALID_ARG                             # stride % 8
+    assert L.eet_op_argmax(P, 2, 100, 104, None, None) == eet.EET_ERR_INVALID_ARG
