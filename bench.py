@@ -57,6 +57,9 @@ def parse():
     p.add_argument("--warmup", type=int, default=1)
     p.add_argument("--workload", default="cfg2")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--model", action="store_true",
+                   help="run the pass through the model entry points (embedding, the stack, final LayerNorm, output "
+                        "projection over GPT-2's vocabulary, greedy choice fed back on the device) instead of the stack's")
     p.add_argument("--no-graph", action="store_true", help="launch decode kernels directly instead of replaying a graph")
     p.add_argument("--kernel-reps", type=int, default=200, help="launches per kernel in the roofline measurement")
     p.add_argument("--roofline-only", action="store_true",
@@ -107,6 +110,35 @@ class Stack:
     def one_pass(self):
         self.prefill()
         self.decode()
+
+
+class ModelStack(Stack):
+    """The same layers behind the model entry points at GPT-2's vocabulary: token ids in, one call per prefill and one
+    per decode step, the greedy token of a step fed to the next step on the device (no host round trip)."""
+    VOCAB = 50257
+
+    def __init__(self, w, eet, torch, wl, use_graph=True):
+        self.w, self.eet, self.torch = w, eet, torch
+        cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+        weights = [{k: torch.from_numpy(v) for k, v in wl.layer_weights(w, li).items()} for li in range(w.layers)]
+        head = {k: torch.from_numpy(v) for k, v in wl.model_head(w, self.VOCAB, w.max_seq).items()}
+        self.model = eet.DecoderModel(cfg, weights, head, self.VOCAB, use_graph=use_graph)
+        self.stack = self.model.stack
+        self.n_layers = w.layers
+        self.lens = [int(v) for v in wl.lengths(w)]
+        self.ids = torch.from_numpy(wl.prompt_ids(w, self.VOCAB)).to("cuda:0")
+        self.stream = torch.cuda.Stream()
+        self.nxt = None
+
+    def prefill(self):
+        with self.torch.cuda.stream(self.stream):
+            _, self.nxt = self.model.prefill(self.ids, self.lens, stream=self.stream)
+
+    def decode(self):
+        with self.torch.cuda.stream(self.stream):
+            nxt = self.nxt
+            for _ in range(self.w.decode_steps):
+                _, nxt = self.model.decode_step(nxt, stream=self.stream)
 
 
 class EncoderStack:
@@ -283,6 +315,33 @@ def _kernel_candidates(stack, torch, eet, reps):
     out.append({"kernel": f"softmax_maskfree_vec: stand-alone mask-free softmax (Algorithm 1), {nh} head(s), not on the layer path",
                 "bound": "hbm", "work": nh * (2.0 * 2 * tri + 2.0 * sum(L * S - L * (L + 1) / 2 for L in stack.lens)),
                 "ms": ms, "launches": 0})
+    # (7) the operators around the stack at GPT-2's vocabulary (50257, padded to 50304 columns): not on the layer pass
+    # that the metric counts, measured for their own roofline rows.  Skipped where the table would pass 512 MB.
+    V, Vp = 50257, 50304
+    if w.decode_steps and 2 * Vp * H <= (512 << 20):
+        wte = torch.randn(Vp, H, device="cuda:0").half().mul_(0.02)
+        wpe = torch.randn(w.max_seq, H, device="cuda:0").half().mul_(0.01)
+        ids = torch.randint(0, V, (B, S), dtype=torch.int32, device="cuda:0")
+        emb = torch.empty(B, S, H, device="cuda:0", dtype=torch.float16)
+        ms = time_launches(torch, lambda: eet.eet_op_embedding(ids, stack.lens, wte, wpe, emb, vocab=V), 8, replays=2)
+        out.append({"kernel": "embed_tokens: token + position embedding of the prompts (pad rows zero-filled), not on the layer path",
+                    "bound": "hbm", "work": 6.0 * T * H + 2.0 * (B * S - T) * H + 4.0 * T, "ms": ms, "launches": 0})
+        xh = torch.randn(B, H, device="cuda:0").half()
+        zb = torch.zeros(Vp, device="cuda:0", dtype=torch.float16)
+        lg = torch.empty(B, Vp, device="cuda:0", dtype=torch.float16)
+        tables = [wte] + [wte.clone() for _ in range(3)]      # four copies in turn: none is still in a cache when its turn comes
+        st7 = {"i": 0}
+
+        def run_head():
+            st7["i"] += 1
+            eet.eet_op_linear(xh, tables[st7["i"] % 4], zb, lg)
+        ms = time_launches(torch, run_head, 8, replays=2)
+        out.append({"kernel": f"decode output projection over the vocabulary (weight stream, M = {B} rows, N = {Vp}), not on the layer path",
+                    "bound": "hbm", "work": 2.0 * (Vp * H + B * H + Vp + B * Vp), "ms": ms, "launches": 0})
+        nxt = torch.empty(B, device="cuda:0", dtype=torch.int32)
+        ms = time_launches(torch, lambda: eet.eet_op_argmax(lg, nxt, vocab=V), 16, replays=2)
+        out.append({"kernel": f"argmax_rows: greedy choice over {B} rows of {V} logits, not on the layer path",
+                    "bound": "hbm", "work": 2.0 * B * V + 4.0 * B, "ms": ms, "launches": 0})
     return out
 
 
@@ -377,7 +436,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = wl.WORKLOADS[a.workload]
-    stack = EncoderStack(w, eet, torch, wl) if w.encoder else Stack(w, eet, torch, wl, use_graph=not a.no_graph)
+    if a.model and (w.encoder or not w.decode_steps):
+        print("bench.py: --model needs a decoder workload with decode steps", file=sys.stderr)
+        sys.exit(2)
+    stack = EncoderStack(w, eet, torch, wl) if w.encoder else \
+        (ModelStack if a.model else Stack)(w, eet, torch, wl, use_graph=not a.no_graph)
     tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
 
     if a.roofline_only:
@@ -414,7 +477,9 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.layers} layer(s), hidden {w.hidden}, heads {w.heads}, ffn {w.ffn}, "
                                f"batch {w.batch}, prompts {w.len_lo}-{w.len_hi} padded to {w.padded_len}, "
-                               f"{w.decode_steps} decode steps, cache {w.max_seq}",
+                               f"{w.decode_steps} decode steps, cache {w.max_seq}" +
+                               (f"; through the model entry points: token ids in, embedding, final LayerNorm, output projection "
+                                f"over {ModelStack.VOCAB} tokens and greedy choice per step, fed back on the device" if a.model else ""),
                    "valid_tokens_per_step": tokens, "prefill_tokens": sum(stack.lens),
                    "decode_tokens": w.batch * w.decode_steps,
                    "prefill_ms": ms_prefill, "decode_ms": ms_decode,
@@ -423,7 +488,7 @@ def main():
     }
     rec["roofline"], rec["roofline_other_kernels"] = roofline_for(stack, torch, eet, a.kernel_reps)
     rec["hbm_reference"] = hbm_reference(torch)
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and not a.model:      # the timed oracle sample is the layer stack's, not the model's
         rec["cpu_baseline"] = cpu_baseline(w, wl)
     print(json.dumps(rec))
 

@@ -60,19 +60,22 @@ hipError_t launch_embedding(const int32_t* ids, const SeqLens& lens, const int32
     return hipGetLastError();
 }
 
-// Greedy choice: out[r] = index of the first maximum of logits[r*ld + 0 .. vocab).  One workgroup per row; a thread
+// Greedy choice: out[r] = index of the first maximum of logits[r*ld + 0 .. vocab).  One workgroup of 16 waves per row
+// (a decode step has few rows, so a row's 100 KB must come through as many lanes as one workgroup can hold); a thread
 // walks its 8-wide chunks in increasing order, so `>` keeps the first of equal values; pairs are merged by
 // (larger value, then smaller index).  NaN compares false and never wins; a row with nothing above -inf gives 0.
-__global__ __launch_bounds__(256) void argmax_rows(const half_t* __restrict__ logits, int vocab, int ld,
+constexpr int kArgmaxThreads = 1024;
+__global__ __launch_bounds__(kArgmaxThreads) void argmax_rows(const half_t* __restrict__ logits, int vocab, int ld,
                                                    int32_t* __restrict__ out) {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+    constexpr int NW = kArgmaxThreads / kWave;
+    __shared__ float sv[NW];
+    __shared__ int si[NW];
     const half_t* row = logits + (size_t)blockIdx.x * ld;
     const int tid = threadIdx.x;
     float best = -__builtin_inff();
     int bi = INT_MAX;
     const int full = vocab >> 3;                                   // whole 8-wide chunks (rows start 16-byte aligned: ld % 8 == 0)
-    for (int c = tid; c < full; c += 256) {
+    for (int c = tid; c < full; c += kArgmaxThreads) {
         const half8v v = reinterpret_cast<const half8v*>(row)[c];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(256) void argmax_rows(const half_t* __restrict__ lo
             if (f > best) { best = f; bi = c * 8 + e; }
         }
     }
-    for (int j = full * 8 + tid; j < vocab; j += 256) {             // tail: at most 7 columns, one per thread
+    for (int j = full * 8 + tid; j < vocab; j += kArgmaxThreads) {             // tail: at most 7 columns, one per thread
         const float f = (float)row[j];
         if (f > best) { best = f; bi = j; }
     }
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(256) void argmax_rows(const half_t* __restrict__ lo
     __syncthreads();
     if (tid == 0) {
 #pragma unroll
-        for (int w = 1; w < 4; ++w)
+        for (int w = 1; w < NW; ++w)
             if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
         out[blockIdx.x] = bi == INT_MAX ? 0 : bi;
     }
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(256) void argmax_rows(const half_t* __restrict__ lo
 
 hipError_t launch_argmax(const half_t* logits, int rows, int vocab, int ld, int32_t* out, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(argmax_rows, dim3(rows), dim3(256), 0, s, logits, vocab, ld, out);
+    hipLaunchKernelGGL(argmax_rows, dim3(rows), dim3(kArgmaxThreads), 0, s, logits, vocab, ld, out);
     return hipGetLastError();
 }
 
