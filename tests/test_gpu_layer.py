@@ -94,6 +94,15 @@ def test_small_workloads_elementwise(eet, name):
     full_parity(eet, wl.WORKLOADS[name])
 
 
+@pytest.mark.parametrize("B", [17, 40, 128])
+def test_batches_above_16_up_to_the_largest(eet, B):
+    """More than 16 sequences: a decode step's projections leave the weight-streaming kernels for the tile kernels
+    (the new token's K/V rows go to slot n_b from their epilogue), the LayerNorms run as row kernels and the second
+    one advances the lengths.  128 is the largest batch the interface takes."""
+    w = wl.Workload(f"batch{B}", 19, 256, 4, 1024, 1, B, 48, 1, 48, 4, 56)
+    full_parity(eet, w)
+
+
 @pytest.mark.parametrize("name", ["tiny", "small64", "small128", "bert1024"])
 def test_encoder_use_elementwise(eet, name):
     """eet_layer_encode against the oracle's encoder use of the same layer (no sequence mask):
