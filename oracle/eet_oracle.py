@@ -349,20 +349,23 @@ class DecoderModelOracle:
         self.hidden_in = None        # input of layer 0 and output of the last layer of the latest call (for per-part checks)
         self.hidden_out = None
 
-    def prefill(self, ids: np.ndarray, q_lens: Sequence[int]) -> np.ndarray:
-        """ids [B, S] (right-padded; pad entries are never read), q_lens[b] valid tokens.  Returns the logits
-        [B, vocab] of the LAST valid token of every sequence (the ones the first generated token is drawn from)."""
+    def prefill(self, ids: np.ndarray, q_lens: Sequence[int], left_padded: bool = False) -> np.ndarray:
+        """ids [B, S], q_lens[b] valid tokens: ids[b, :L_b] (right-padded) or, with left_padded, ids[b, S-L_b:] (the
+        layout Algorithm 1 is printed for); pad entries are never read.  Token t of a sequence has position t in
+        either layout.  Returns the logits [B, vocab] of the LAST valid token of every sequence (the ones the first
+        generated token is drawn from)."""
         B, S = ids.shape
         H = self.head["wte"].shape[1]
         x = np.zeros((B, S, H), F64)
+        first = [S - int(L) if left_padded else 0 for L in q_lens]
         for b in range(B):
             L = int(q_lens[b])
-            x[b, :L] = embedding(ids[b, :L], range(L), self.head["wte"], self.head["wpe"])
+            x[b, first[b]: first[b] + L] = embedding(ids[b, first[b]: first[b] + L], range(L), self.head["wte"], self.head["wpe"])
         self.hidden_in = x
         for layer in self.layers:
-            x = layer.prefill(x, q_lens)
+            x = layer.prefill(x, q_lens, left_padded=left_padded)
         self.hidden_out = x
-        last = np.stack([x[b, int(q_lens[b]) - 1] for b in range(B)])
+        last = np.stack([x[b, first[b] + int(q_lens[b]) - 1] for b in range(B)])
         return lm_head(last, self.head["lnf_g"], self.head["lnf_b"], self.head["wte"], self.eps)
 
     def decode_step(self, ids: Sequence[int]) -> np.ndarray:

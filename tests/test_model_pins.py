@@ -139,6 +139,30 @@ def test_position_embedding_matters_and_is_sequence_relative():
     assert np.array_equal(m.hidden_in[0], head["wte"][7] + head["wpe"][1])
 
 
+def test_left_padded_model_equals_the_right_padded_one():
+    # same tokens, pads in front: embedding rows move to the end of each row block with the same values (positions are
+    # sequence-relative), logits, cache and lengths are bitwise those of the right-padded call
+    w, LW, head = small_model()
+    lens = [int(v) for v in wl.lengths(w)]
+    B, S = w.batch, w.padded_len
+    ids = wl.prompt_ids(w, 19, pad_value=-1)
+    left = np.full_like(ids, -1)
+    for b, L in enumerate(lens):
+        left[b, S - L:] = ids[b, :L]
+    a = orc.DecoderModelOracle(LW, head, w.heads, B, w.max_seq)
+    c = orc.DecoderModelOracle(LW, head, w.heads, B, w.max_seq)
+    la, lc = a.prefill(ids, lens), c.prefill(left, lens, left_padded=True)
+    assert np.array_equal(la, lc)
+    for b, L in enumerate(lens):
+        assert np.array_equal(a.hidden_in[b, :L], c.hidden_in[b, S - L:])
+        assert np.all(c.hidden_in[b, :S - L] == 0) and np.all(c.hidden_out[b, :S - L] == 0)
+        assert np.array_equal(a.hidden_out[b, :L], c.hidden_out[b, S - L:])
+        assert np.array_equal(c.hidden_in[b, S - L], head["wte"][ids[b, 0]] + head["wpe"][0])     # first token: position 0
+    nxt = wl.decode_ids(w, 0, 19)
+    assert np.array_equal(a.decode_step(nxt), c.decode_step(nxt))
+    assert a.layers[0].lens.tolist() == c.layers[0].lens.tolist()
+
+
 # ------------------------------------------------------------------ planted mistakes must fail a pin
 def test_planted_mistakes_in_the_model_fail_the_pins(monkeypatch):
     w, LW, head = small_model(B=1, S=6, lo=3, hi=3)
