@@ -155,6 +155,11 @@ int eet_stack_create(const eet_layer_config *cfg, int32_t n_layers, const eet_la
  * the input of layer l+1; `out` receives the last layer's output. */
 int eet_stack_prefill(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                       const void *tokens, void *out, void *kv_cache, void *hip_stream);
+/* As eet_prefill_left_padded through all layers: tokens and out hold sequence b at rows
+ * padded_len - q_lens[b] .. padded_len - 1 of its block (the layout Algorithm 1 is printed for);
+ * cache, lengths and every following decode step are those of eet_stack_prefill. */
+int eet_stack_prefill_left_padded(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                                  const void *tokens, void *out, void *kv_cache, void *hip_stream);
 int eet_stack_decode_step(eet_stack_t *stack, const void *tokens, void *out, void *kv_cache,
                           void *hip_stream);
 int eet_stack_cache_lens(eet_stack_t *stack, int32_t *out_host, void *hip_stream);
@@ -207,6 +212,13 @@ int eet_model_create(eet_stack_t *stack, const eet_layer_config *cfg, const eet_
  * Arguments, errors and cache behaviour otherwise as eet_stack_prefill. */
 int eet_model_prefill(eet_model_t *model, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                       const int32_t *ids, void *logits, int32_t *next_ids, void *kv_cache, void *hip_stream);
+
+/* The same with the pads in front: the valid ids of sequence b are ids[b, padded_len - q_lens[b] ..
+ * padded_len - 1]; token t of a sequence still has position t.  Logits, next_ids, cache and
+ * lengths are those of eet_model_prefill on the same tokens. */
+int eet_model_prefill_left_padded(eet_model_t *model, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                                  const int32_t *ids, void *logits, int32_t *next_ids, void *kv_cache,
+                                  void *hip_stream);
 
 /* One new token per sequence, at position n_b (read on the device).  ids: DEVICE int32 [batch];
  * it may be the next_ids buffer of the previous call, so generation needs no host round trip.
@@ -297,6 +309,11 @@ int eet_op_attention_unfused(const void *q, const void *k_cache, const void *v_c
 int eet_op_embedding(const int32_t *ids, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                      int32_t hidden, int32_t vocab, int32_t max_pos, const void *wte, const void *wpe,
                      void *out, void *hip_stream);
+/* The same with the pads in front: row (b, i) = wte[ids[b, i]] + wpe[i - (padded_len - q_lens[b])]
+ * for i >= padded_len - q_lens[b], zeros before. */
+int eet_op_embedding_left_padded(const int32_t *ids, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                                 int32_t hidden, int32_t vocab, int32_t max_pos, const void *wte,
+                                 const void *wpe, void *out, void *hip_stream);
 /* Embedding of one token per sequence: out[b] = wte[ids[b]] + wpe[positions[b]]; ids and positions
  * DEVICE int32 [batch]. */
 int eet_op_embedding_decode(const int32_t *ids, const int32_t *positions, int32_t batch, int32_t hidden,

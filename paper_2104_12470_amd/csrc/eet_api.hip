@@ -480,21 +480,20 @@ int eet_stack_create(const eet_layer_config* cfg, int32_t n_layers, const eet_la
     return EET_OK;
 }
 
-int eet_stack_prefill(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
-                      void* out, void* kv_cache, void* hip_stream) {
-    if (!st) return fail(EET_ERR_INVALID_ARG, "eet_stack_prefill: null argument");
+static int stack_prefill(const char* who, bool left_padded, eet_stack_t* st, const int32_t* q_lens, int32_t batch,
+                         int32_t padded_len, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
+    if (!st) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
     SeqLens lens;
     int64_t T;
     int max_len;
-    if (const int rc = check_prefill("eet_stack_prefill", st->cfg, q_lens, batch, padded_len, tokens, out, kv_cache,
-                                     lens, T, max_len))
+    if (const int rc = check_prefill(who, st->cfg, q_lens, batch, padded_len, tokens, out, kv_cache, lens, T, max_len))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const void* in = tokens;
     for (int l = 0; l < st->n_layers; ++l) {
         void* o = (l == st->n_layers - 1) ? out : static_cast<void*>(st->ws + st->act[l & 1]);
         char* kv = static_cast<char*>(kv_cache) + (size_t)l * st->layer_cache_bytes;
-        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv, s);
+        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv, s, true, left_padded);
         if (rc != EET_OK) return rc;
         st->layers[l]->batch = batch;
         in = o;
@@ -502,6 +501,16 @@ int eet_stack_prefill(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int
     st->batch = batch;
     for (int b = 0; b < batch; ++b) st->host_lens[b] = q_lens[b];
     return EET_OK;
+}
+
+int eet_stack_prefill(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                      void* out, void* kv_cache, void* hip_stream) {
+    return stack_prefill("eet_stack_prefill", false, st, q_lens, batch, padded_len, tokens, out, kv_cache, hip_stream);
+}
+
+int eet_stack_prefill_left_padded(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int32_t padded_len,
+                                  const void* tokens, void* out, void* kv_cache, void* hip_stream) {
+    return stack_prefill("eet_stack_prefill_left_padded", true, st, q_lens, batch, padded_len, tokens, out, kv_cache, hip_stream);
 }
 
 static int stack_enqueue_decode(eet_stack* st, const void* tokens, void* out, void* kv_cache, hipStream_t s) {
@@ -667,26 +676,37 @@ static int model_head(eet_model* m, const void* hidden, const int32_t* row_map, 
     return EET_OK;
 }
 
-int eet_model_prefill(eet_model_t* m, const int32_t* q_lens, int32_t batch, int32_t padded_len, const int32_t* ids,
-                      void* logits, int32_t* next_ids, void* kv_cache, void* hip_stream) {
-    if (!m || !ids || !logits) return fail(EET_ERR_INVALID_ARG, "eet_model_prefill: null argument");
-    if (!aligned16(logits)) return fail(EET_ERR_INVALID_ARG, "eet_model_prefill: logits must be 16-byte aligned");
+static int model_prefill(const char* who, bool left_padded, eet_model_t* m, const int32_t* q_lens, int32_t batch,
+                         int32_t padded_len, const int32_t* ids, void* logits, int32_t* next_ids, void* kv_cache,
+                         void* hip_stream) {
+    if (!m || !ids || !logits) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!aligned16(logits)) return fail(EET_ERR_INVALID_ARG, "%s: logits must be 16-byte aligned", who);
     eet_stack* st = m->st;
     void* x0 = st->ws + st->act[1];                              // embedding -> one activation cache ...
     void* xn = st->ws + st->act[(st->n_layers - 1) & 1];         // ... final output -> where the last layer's turn falls
     SeqLens lens;
     int64_t T;
     int max_len;
-    if (const int rc = check_prefill("eet_model_prefill", st->cfg, q_lens, batch, padded_len, x0, xn, kv_cache, lens, T, max_len))
-        return rc;
+    if (const int rc = check_prefill(who, st->cfg, q_lens, batch, padded_len, x0, xn, kv_cache, lens, T, max_len)) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     int32_t* last_row = reinterpret_cast<int32_t*>(m->ws + m->last_row);
     EET_LAUNCH(launch_embedding(ids, lens, nullptr, batch, padded_len, st->cfg.hidden, m->mc.vocab, m->mc.max_pos,
-                                (const half_t*)m->w.wte, (const half_t*)m->w.wpe, (half_t*)x0, last_row, s), "embedding");
-    if (const int rc = eet_stack_prefill(st, q_lens, batch, padded_len, x0, xn, kv_cache, hip_stream)) return rc;
+                                (const half_t*)m->w.wte, (const half_t*)m->w.wpe, (half_t*)x0, last_row, s, left_padded), "embedding");
+    if (const int rc = stack_prefill(who, left_padded, st, q_lens, batch, padded_len, x0, xn, kv_cache, hip_stream)) return rc;
     m->hidden_in = x0 == xn ? nullptr : x0;      // an even number of layers ends in the buffer the embedding was in
     m->hidden_out = xn;
     return model_head(m, xn, last_row, batch, logits, next_ids, s);
+}
+
+int eet_model_prefill(eet_model_t* m, const int32_t* q_lens, int32_t batch, int32_t padded_len, const int32_t* ids,
+                      void* logits, int32_t* next_ids, void* kv_cache, void* hip_stream) {
+    return model_prefill("eet_model_prefill", false, m, q_lens, batch, padded_len, ids, logits, next_ids, kv_cache, hip_stream);
+}
+
+int eet_model_prefill_left_padded(eet_model_t* m, const int32_t* q_lens, int32_t batch, int32_t padded_len,
+                                  const int32_t* ids, void* logits, int32_t* next_ids, void* kv_cache, void* hip_stream) {
+    return model_prefill("eet_model_prefill_left_padded", true, m, q_lens, batch, padded_len, ids, logits, next_ids, kv_cache,
+                         hip_stream);
 }
 
 int eet_model_decode_step(eet_model_t* m, const int32_t* ids, void* logits, int32_t* next_ids, void* kv_cache,
@@ -874,9 +894,9 @@ int eet_op_attention_unfused(const void* q, const void* k_cache, const void* v_c
     return EET_OK;
 }
 
-int eet_op_embedding(const int32_t* ids, const int32_t* q_lens, int32_t batch, int32_t padded_len, int32_t hidden,
-                     int32_t vocab, int32_t max_pos, const void* wte, const void* wpe, void* out, void* hip_stream) {
-    const char* who = "eet_op_embedding";
+static int op_embedding(const char* who, bool left_padded, const int32_t* ids, const int32_t* q_lens, int32_t batch,
+                        int32_t padded_len, int32_t hidden, int32_t vocab, int32_t max_pos, const void* wte, const void* wpe,
+                        void* out, void* hip_stream) {
     if (!ids || !q_lens || !wte || !wpe || !out) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
     if (batch < 1 || padded_len < 1 || hidden < 1 || vocab < 1 || max_pos < 1) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
     if (hidden % 8 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: hidden must be a multiple of 8", who);
@@ -891,8 +911,19 @@ int eet_op_embedding(const int32_t* ids, const int32_t* q_lens, int32_t batch, i
         lens.len[b] = q_lens[b];
     }
     EET_LAUNCH(launch_embedding(ids, lens, nullptr, batch, padded_len, hidden, vocab, max_pos, (const half_t*)wte,
-                                (const half_t*)wpe, (half_t*)out, nullptr, (hipStream_t)hip_stream), "embedding");
+                                (const half_t*)wpe, (half_t*)out, nullptr, (hipStream_t)hip_stream, left_padded), "embedding");
     return EET_OK;
+}
+
+int eet_op_embedding(const int32_t* ids, const int32_t* q_lens, int32_t batch, int32_t padded_len, int32_t hidden,
+                     int32_t vocab, int32_t max_pos, const void* wte, const void* wpe, void* out, void* hip_stream) {
+    return op_embedding("eet_op_embedding", false, ids, q_lens, batch, padded_len, hidden, vocab, max_pos, wte, wpe, out, hip_stream);
+}
+
+int eet_op_embedding_left_padded(const int32_t* ids, const int32_t* q_lens, int32_t batch, int32_t padded_len, int32_t hidden,
+                                 int32_t vocab, int32_t max_pos, const void* wte, const void* wpe, void* out, void* hip_stream) {
+    return op_embedding("eet_op_embedding_left_padded", true, ids, q_lens, batch, padded_len, hidden, vocab, max_pos, wte, wpe, out,
+                        hip_stream);
 }
 
 int eet_op_embedding_decode(const int32_t* ids, const int32_t* positions, int32_t batch, int32_t hidden, int32_t vocab,

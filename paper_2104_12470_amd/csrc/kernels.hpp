@@ -112,12 +112,13 @@ size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits);
 hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s);
 
 // ---- operators around the stack (model.hip) ------------------------------------------------------
-// out[b*S + i] = wte[ids[b*S + i]] + wpe[i] for i < lens.len[b], zeros for pad rows (positions == nullptr);
+// out[b*S + i] = wte[ids[b*S + i]] + wpe[i - first] for first <= i < first + lens.len[b] (first = 0, or S - lens.len[b]
+// when left_padded), zeros for pad rows (positions == nullptr);
 // or, with S == 1, out[b] = wte[ids[b]] + wpe[positions[b]] (positions on the DEVICE).  Rows whose id or position
 // is outside its table become NaN.  last_row (optional, DEVICE [batch]): row index of each sequence's last valid token.
 hipError_t launch_embedding(const int32_t* ids, const SeqLens& lens, const int32_t* positions, int batch, int S, int width,
                             int vocab, int max_pos, const half_t* wte, const half_t* wpe, half_t* out, int32_t* last_row,
-                            hipStream_t s);
+                            hipStream_t s, bool left_padded = false);
 // out[r] = first maximum of logits[r*ld + 0 .. vocab)   (ld % 8 == 0)
 hipError_t launch_argmax(const half_t* logits, int rows, int vocab, int ld, int32_t* out, hipStream_t s);
 

@@ -8,8 +8,9 @@
 
 namespace eet {
 
-// One workgroup per padded row.  Prompt form (positions == nullptr): row r = b*S + i holds token i of sequence b when
-// i < len[b] (position i), otherwise it is a pad row and is written as zeros; its id is never read.  Decode form:
+// One workgroup per padded row.  Prompt form (positions == nullptr): with first = 0 (right-padded) or S - len[b]
+// (left-padded, the layout Algorithm 1 is printed for), row r = b*S + i holds token i - first of sequence b when
+// first <= i < first + len[b] (position i - first), otherwise it is a pad row and is written as zeros; its id is never read.  Decode form:
 // S == 1, row b holds the new token of sequence b at position positions[b] (the device-side cache length).
 // An id outside [0, vocab) or a position outside [0, max_pos) indexes nothing: the row becomes NaN, which every later
 // step propagates to the logits.  last_row[b] (optional) receives the row index of the last valid token.
@@ -17,22 +18,23 @@ __global__ __launch_bounds__(128) void embed_tokens(const int32_t* __restrict__ 
                                                     const int32_t* __restrict__ positions, int S, int width, int vocab,
                                                     int max_pos, const half_t* __restrict__ wte,
                                                     const half_t* __restrict__ wpe, half_t* __restrict__ out,
-                                                    int32_t* __restrict__ last_row) {
+                                                    int32_t* __restrict__ last_row, int left) {
     const int r = blockIdx.x;
     const int b = r / S, i = r % S;
     const int nvec = width >> 3;
     half8v* o = reinterpret_cast<half8v*>(out + (size_t)r * width);
-    int pos = i;
+    const int first = (positions == nullptr && left) ? S - lens.len[b] : 0;
+    int pos = i - first;
     if (positions != nullptr) {
         pos = positions[b];
-    } else if (i >= lens.len[b]) {
+    } else if (pos < 0 || pos >= lens.len[b]) {
         half8v z;
 #pragma unroll
         for (int e = 0; e < 8; ++e) z[e] = (half_t)0.f;
         for (int c = threadIdx.x; c < nvec; c += 128) o[c] = z;
         return;
     }
-    if (last_row != nullptr && threadIdx.x == 0 && (positions != nullptr || i == lens.len[b] - 1)) last_row[b] = r;
+    if (last_row != nullptr && threadIdx.x == 0 && (positions != nullptr || pos == lens.len[b] - 1)) last_row[b] = r;
     const int id = ids[r];
     if (id < 0 || id >= vocab || pos < 0 || pos >= max_pos) {
         half8v n;
@@ -54,9 +56,9 @@ __global__ __launch_bounds__(128) void embed_tokens(const int32_t* __restrict__ 
 
 hipError_t launch_embedding(const int32_t* ids, const SeqLens& lens, const int32_t* positions, int batch, int S, int width,
                             int vocab, int max_pos, const half_t* wte, const half_t* wpe, half_t* out, int32_t* last_row,
-                            hipStream_t s) {
+                            hipStream_t s, bool left_padded) {
     hipLaunchKernelGGL(embed_tokens, dim3(batch * S), dim3(128), 0, s, ids, lens, positions, S, width, vocab, max_pos, wte,
-                       wpe, out, last_row);
+                       wpe, out, last_row, left_padded ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
             "eet_stack_workspace_bytes": (sz, [cfgp, i32]),
             "eet_stack_create": (i32, [cfgp, i32, C.POINTER(LayerWeights), vp, i32, C.POINTER(vp)]),
             "eet_stack_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_stack_prefill_left_padded": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_stack_decode_step": (i32, [vp, vp, vp, vp, vp]),
             "eet_stack_cache_lens": (i32, [vp, i32p, vp]),
             "eet_stack_destroy": (i32, [vp]),
@@ -105,10 +106,12 @@ def lib() -> C.CDLL:
             "eet_model_workspace_bytes": (sz, [cfgp, C.POINTER(ModelConfig)]),
             "eet_model_create": (i32, [vp, cfgp, C.POINTER(ModelConfig), C.POINTER(ModelWeights), vp, C.POINTER(vp)]),
             "eet_model_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp, vp]),
+            "eet_model_prefill_left_padded": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp, vp]),
             "eet_model_decode_step": (i32, [vp, vp, vp, vp, vp, vp]),
             "eet_model_hidden_states": (i32, [vp, C.POINTER(vp), C.POINTER(vp)]),
             "eet_model_destroy": (i32, [vp]),
             "eet_op_embedding": (i32, [vp, i32p, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
+            "eet_op_embedding_left_padded": (i32, [vp, i32p, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
             "eet_op_embedding_decode": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "eet_op_argmax": (i32, [vp, i32, i32, i32, vp, vp]),
             "eet_bufmgr_create": (i32, [vp, sz, C.POINTER(vp)]),
@@ -133,7 +136,8 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
            "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
-           "eet_op_embedding_decode", "eet_op_argmax")
+           "eet_op_embedding_decode", "eet_op_argmax", "eet_stack_prefill_left_padded", "eet_model_prefill_left_padded",
+           "eet_op_embedding_left_padded")
 
 
 def _check(code: int) -> None:
@@ -231,6 +235,12 @@ def eet_stack_prefill(stack: int, q_lens: Sequence[int], batch: int, padded_len:
                                    _ptr(kv_cache), _stream(stream)))
 
 
+def eet_stack_prefill_left_padded(stack: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens, out, kv_cache,
+                                  stream=None) -> None:
+    _check(lib().eet_stack_prefill_left_padded(stack, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
+                                               _ptr(kv_cache), _stream(stream)))
+
+
 def eet_stack_decode_step(stack: int, tokens, out, kv_cache, stream=None) -> None:
     _check(lib().eet_stack_decode_step(stack, _ptr(tokens), _ptr(out), _ptr(kv_cache), _stream(stream)))
 
@@ -320,6 +330,14 @@ def eet_op_embedding(ids, q_lens, wte, wpe, out, vocab: Optional[int] = None, st
                                   wpe.shape[0], _ptr(wte), _ptr(wpe), _ptr(out), _stream(stream)))
 
 
+def eet_op_embedding_left_padded(ids, q_lens, wte, wpe, out, vocab: Optional[int] = None, stream=None) -> None:
+    B, S = ids.shape
+    assert ids.dtype == torch.int32 and ids.is_cuda
+    _check(lib().eet_op_embedding_left_padded(_ptr(ids), _lens_array(q_lens), B, S, wte.shape[1],
+                                              wte.shape[0] if vocab is None else vocab, wpe.shape[0], _ptr(wte), _ptr(wpe),
+                                              _ptr(out), _stream(stream)))
+
+
 def eet_op_embedding_decode(ids, positions, wte, wpe, out, vocab: Optional[int] = None, stream=None) -> None:
     assert ids.dtype == torch.int32 and positions.dtype == torch.int32 and ids.is_cuda and positions.is_cuda
     _check(lib().eet_op_embedding_decode(_ptr(ids), _ptr(positions), ids.shape[0], wte.shape[1],
@@ -348,6 +366,12 @@ def eet_model_prefill(model: int, q_lens: Sequence[int], batch: int, padded_len:
                       stream=None) -> None:
     _check(lib().eet_model_prefill(model, _lens_array(q_lens), batch, padded_len, _ptr(ids), _ptr(logits), _ptr(next_ids),
                                    _ptr(kv_cache), _stream(stream)))
+
+
+def eet_model_prefill_left_padded(model: int, q_lens: Sequence[int], batch: int, padded_len: int, ids, logits, next_ids,
+                                  kv_cache, stream=None) -> None:
+    _check(lib().eet_model_prefill_left_padded(model, _lens_array(q_lens), batch, padded_len, _ptr(ids), _ptr(logits),
+                                               _ptr(next_ids), _ptr(kv_cache), _stream(stream)))
 
 
 def eet_model_decode_step(model: int, ids, logits, next_ids, kv_cache, stream=None) -> None:
@@ -470,6 +494,12 @@ class DecoderStack:
         eet_stack_prefill(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
         return out
 
+    def prefill_left_padded(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_stack_prefill_left_padded(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
     def decode_step(self, tokens: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):
         out = torch.empty_like(tokens) if out is None else out
         eet_stack_decode_step(self.handle, tokens, out, self.kv_cache, stream)
@@ -508,11 +538,12 @@ class DecoderModel:
         self.handle = eet_model_create(self.stack.handle, cfg, self.mcfg, self.head, self.workspace)
         self.batch = 0
 
-    def prefill(self, ids: torch.Tensor, q_lens: Sequence[int], stream=None):
+    def prefill(self, ids: torch.Tensor, q_lens: Sequence[int], stream=None, left_padded: bool = False):
         B, S = ids.shape
         logits = torch.empty((B, self.mcfg.vocab_padded), dtype=torch.float16, device=ids.device)
         nxt = torch.empty((B,), dtype=torch.int32, device=ids.device)
-        eet_model_prefill(self.handle, q_lens, B, S, ids, logits, nxt, self.stack.kv_cache, stream)
+        (eet_model_prefill_left_padded if left_padded else eet_model_prefill)(
+            self.handle, q_lens, B, S, ids, logits, nxt, self.stack.kv_cache, stream)
         self.batch, self.padded_len = B, S
         return logits, nxt
 

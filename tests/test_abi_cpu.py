@@ -189,6 +189,9 @@ def test_model_and_its_operators_validate(eet):
     assert L.eet_op_embedding(P, lens, 2, 16, 60, 100, 16, P, P, P, None) == eet.EET_ERR_UNSUPPORTED_SHAPE # hidden % 8
     assert L.eet_op_embedding(P, lens, 2, 16, 64, 100, 16, P, P + 4, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_embedding(None, lens, 2, 16, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_op_embedding_left_padded(P, lens, 2, 8, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG   # len 9 > S 8
+    assert L.eet_model_prefill_left_padded(None, None, 1, 1, P, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_stack_prefill_left_padded(None, lens, 2, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_embedding_decode(P, None, 2, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_embedding_decode(P, P, 2, 64, 0, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_argmax(P, 2, 100, 96, P, None) == eet.EET_ERR_INVALID_ARG                              # stride < vocab

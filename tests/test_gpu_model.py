@@ -51,6 +51,25 @@ def test_embedding_op_is_bit_exact_and_skips_pad_ids(eet, H, S, lens):
         assert np.all(got[b, L:] == 0)
 
 
+def test_left_padded_embedding_op(eet):
+    V, P, H, S, lens = 300, 40, 128, 33, [33, 1, 20, 32]
+    B = len(lens)
+    w = wl.Workload("e", 45, H, 1, 64, 1, B, S, 1, S, 0, P)
+    head = wl.model_head(w, V, P)
+    ids = np.full((B, S), -3, np.int32)                              # pad ids in front: out of range, never read
+    tok = wl.uniform_int(45, 9, B * S, 0, V - 1).reshape(B, S)
+    for b, L in enumerate(lens):
+        ids[b, S - L:] = tok[b, :L]
+    out = torch.full((B, S, H), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_embedding_left_padded(dev(ids), lens, dev(head["wte"]), dev(head["wpe"]), out)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b, L in enumerate(lens):
+        want = fp16_sum(head["wte"], head["wpe"], tok[b, :L], range(L))     # token t of the sequence: position t
+        assert np.array_equal(got[b, S - L:].view(np.uint16), want.view(np.uint16)), f"sequence {b}"
+        assert np.all(got[b, :S - L] == 0)
+
+
 def test_embedding_rows_with_an_id_or_position_outside_the_tables_become_nan(eet):
     V, P, H, S = 50, 6, 64, 8
     w = wl.Workload("e", 43, H, 1, 64, 1, 2, S, 1, S, 0, P)
@@ -191,6 +210,49 @@ def test_generation_feeds_the_chosen_tokens_back_on_the_device(eet):
     assert gpu.stack.cache_lens(w.batch) == [L + w.decode_steps for L in lens]
     print(f"\n[generation] GPU and oracle chose the same token in {agree} of {total} steps")
     gpu.close()
+
+
+@pytest.mark.parametrize("layers", [1, 2])
+def test_left_padded_model_prefill(eet, layers):
+    """Pads in front: logits, greedy tokens, caches and lengths are bit for bit those of the right-padded call on the same
+    tokens (and so within tolerance of the oracle's left-padded model), and generation continues identically."""
+    w = replace(wl.WORKLOADS["small64"], layers=layers, decode_steps=2)
+    V = 1000
+    right, ora, head = build(eet, w, V)
+    left, _, _ = build(eet, w, V)
+    lens = [int(v) for v in wl.lengths(w)]
+    ids = wl.prompt_ids(w, V, pad_value=-1)
+    B, S = ids.shape
+    ids_l = np.full_like(ids, -1)
+    for b, L in enumerate(lens):
+        ids_l[b, S - L:] = ids[b, :L]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        lr, nr = right.prefill(dev(ids), lens, stream=stream)
+        ll, nl = left.prefill(dev(ids_l), lens, stream=stream, left_padded=True)
+    stream.synchronize()
+    assert np.array_equal(host(ll).view(np.uint16), host(lr).view(np.uint16)) and host(nl).tolist() == host(nr).tolist()
+    gate(host(ll)[:, :V], ora.prefill(ids_l, lens, left_padded=True), "left-padded model: logits")
+    h_in, h_out = left.hidden_states(decode=False)
+    if layers % 2:                                                    # the embedding is still in its activation cache
+        for b, L in enumerate(lens):
+            assert np.array_equal(host(h_in)[b, S - L:].view(np.uint16),
+                                  fp16_sum(head["wte"], head["wpe"], ids[b, :L], range(L)).view(np.uint16))
+            assert np.all(host(h_in)[b, :S - L] == 0)
+    else:
+        assert h_in is None
+    for b, L in enumerate(lens):
+        assert np.all(host(h_out)[b, :S - L] == 0)
+    assert torch.equal(left.stack.kv_cache, right.stack.kv_cache)
+    assert left.stack.cache_lens(B) == right.stack.cache_lens(B) == lens
+    with torch.cuda.stream(stream):
+        for _ in range(w.decode_steps):
+            lr, nr = right.decode_step(nr, stream=stream)
+            ll, nl = left.decode_step(nl, stream=stream)
+    stream.synchronize()
+    assert np.array_equal(host(ll).view(np.uint16), host(lr).view(np.uint16)) and host(nl).tolist() == host(nr).tolist()
+    left.close()
+    right.close()
 
 
 def test_model_errors_and_poisoned_ids(eet):

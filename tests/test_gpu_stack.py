@@ -117,3 +117,51 @@ def test_stack_capacity(eet):
         assert e.value.code == eet.EET_ERR_CAPACITY
         assert stack.cache_lens(3) == [32, 11, 9]
     stack.close()
+
+
+def shift_to_the_end(x, lens):
+    """Right-padded [B, S, ...] -> left-padded: the valid rows of sequence b moved to the end of its block, NaN in front."""
+    out = np.full_like(x, np.nan)
+    S = x.shape[1]
+    for b, L in enumerate(lens):
+        out[b, S - int(L):] = x[b, :int(L)]
+    return out
+
+
+@pytest.mark.parametrize("name,n_layers", [("small64", 2), ("small128", 3)])
+def test_left_padded_stack_prefill(eet, name, n_layers):
+    """Pads in front (the layout Algorithm 1 is printed for), through every layer: the valid rows are bit for bit those
+    of the right-padded call, shifted; the caches and lengths are identical, and so is the decode step that follows;
+    the pad rows (NaN on input) are zeros on output; against the oracle's left-padded stack within the layer tolerance."""
+    w = wl.WORKLOADS[name]
+    cfg, Ws, right = build(eet, w, n_layers, use_graph=False)
+    _, _, left = build(eet, w, n_layers, use_graph=True)
+    lens, x = wl.lengths(w), wl.prompt_embeddings(w)
+    B, S = w.batch, w.padded_len
+    xl = shift_to_the_end(x, lens)
+    stream = torch.cuda.Stream()
+    got_r = right.prefill(dev(x), lens)
+    with torch.cuda.stream(stream):
+        got_l = left.prefill_left_padded(dev(xl), lens, stream=stream)
+    torch.cuda.synchronize()
+    ho = xl.astype(np.float64)
+    oracles = [orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps) for W in Ws]
+    for o in oracles:
+        ho = o.prefill(ho, lens, left_padded=True)
+    gr, gl = host(got_r), host(got_l)
+    for b, L in enumerate(lens):
+        L = int(L)
+        assert np.array_equal(gl[b, S - L:].view(np.uint16), gr[b, :L].view(np.uint16))
+        assert np.all(gl[b, :S - L] == 0)
+        gate(gl[b, S - L:], ho[b, S - L:], f"{name} left-padded stack b={b}")
+    assert left.cache_lens(B) == right.cache_lens(B) == [int(v) for v in lens]
+    assert torch.equal(left.kv_cache, right.kv_cache)
+    xs = wl.decode_embeddings(w, 0)
+    d_r = right.decode_step(dev(xs))
+    with torch.cuda.stream(stream):
+        d_l = left.decode_step(dev(xs), stream=stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d_l).view(np.uint16), host(d_r).view(np.uint16))
+    assert torch.equal(left.kv_cache, right.kv_cache)
+    left.close()
+    right.close()
