@@ -74,6 +74,61 @@ __global__ __launch_bounds__(256) void layernorm_cached(const half_t* __restrict
     if (bump_lens != nullptr && tid == 0 && row < bump_count) bump_lens[row] += 1;
 }
 
+// Many narrow rows (width <= 2048, width % 8 == 0): one wave per row, four rows per workgroup.  The row sits in NV
+// 16-byte vectors per lane, both reductions are lane exchanges, and there is no barrier and no LDS, so a prompt's few
+// thousand rows are all in flight at once instead of queueing behind 256-thread workgroups that each wait twice.
+template <int NV>
+__global__ __launch_bounds__(256) void layernorm_wave(const half_t* __restrict__ x, const int32_t* __restrict__ in_row_map,
+                                                      const half_t* __restrict__ gamma, const half_t* __restrict__ beta,
+                                                      half_t* __restrict__ y, int rows, int width, float eps,
+                                                      int32_t* bump_lens, int bump_count) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;                                  // whole waves leave; nothing below synchronises
+    const int64_t src = in_row_map ? (int64_t)in_row_map[row] : (int64_t)row;
+    const half8v* xr = reinterpret_cast<const half8v*>(x + src * width);
+    const int nvec = width >> 3;
+    half8v v[NV];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            v[i] = xr[idx];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += (float)v[i][e];
+        }
+    }
+    const float mean = wave_sum(sum) / (float)width;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (lane + i * 64 < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dlt = (float)v[i][e] - mean;
+                sq += dlt * dlt;
+            }
+        }
+    }
+    const float rstd = rsqrtf(wave_sum(sq) / (float)width + eps);
+    const half8v* g8 = reinterpret_cast<const half8v*>(gamma);
+    const half8v* b8 = reinterpret_cast<const half8v*>(beta);
+    half8v* yr = reinterpret_cast<half8v*>(y + (int64_t)row * width);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            const half8v g = g8[idx], b = b8[idx];
+            half8v o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (half_t)(((float)v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
+            yr[idx] = o;
+        }
+    }
+    if (bump_lens != nullptr && lane == 0 && row < bump_count) bump_lens[row] += 1;
+}
+
 // Any width, any alignment: three scalar passes over the row (re-read through L2).
 __global__ __launch_bounds__(256) void layernorm_generic(const half_t* __restrict__ x,
                                                          const int32_t* __restrict__ in_row_map,
@@ -111,7 +166,12 @@ hipError_t launch_layernorm(const half_t* x, const int32_t* in_row_map, const ha
     const dim3 grid((unsigned)rows), block(256);
     const bool vec = (width % 8 == 0) && aligned16(x) && aligned16(y) && aligned16(gamma) && aligned16(beta);
 #define EET_LN(NV) hipLaunchKernelGGL(layernorm_cached<NV>, grid, block, 0, s, x, in_row_map, gamma, beta, y, width, eps, bump_lens, bump_count)
-    if (vec && width <= 2048) EET_LN(1);
+#define EET_LNW(NV) hipLaunchKernelGGL(layernorm_wave<NV>, dim3((unsigned)((rows + 3) / 4)), block, 0, s, x, in_row_map, gamma, beta, y, (int)rows, width, eps, bump_lens, bump_count)
+    if (vec && width <= 2048 && rows >= 64) {                 // a prompt's rows: one wave each
+        if (width <= 512) EET_LNW(1);
+        else if (width <= 1024) EET_LNW(2);
+        else EET_LNW(4);
+    } else if (vec && width <= 2048) EET_LN(1);
     else if (vec && width <= 4096) EET_LN(2);
     else if (vec && width <= 8192) EET_LN(4);
     else if (vec && width <= 16384) EET_LN(8);
@@ -119,6 +179,7 @@ hipError_t launch_layernorm(const half_t* x, const int32_t* in_row_map, const ha
         hipLaunchKernelGGL(layernorm_generic, grid, block, 0, s, x, in_row_map, gamma, beta, y, width, eps,
                            bump_lens, bump_count);
 #undef EET_LN
+#undef EET_LNW
     return hipGetLastError();
 }
 

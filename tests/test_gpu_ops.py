@@ -25,7 +25,9 @@ OP_MAX, OP_MEAN = 6e-3, 6e-4
 
 
 @pytest.mark.parametrize("rows,width", [(7, 64), (5, 768), (3, 1024), (3, 1280), (2, 2048), (3, 4096), (2, 12288),
-                                        (2, 16384), (2, 49152), (4, 100), (3, 1283), (300, 1024)])
+                                        (2, 16384), (2, 49152), (4, 100), (3, 1283), (300, 1024),
+                                        # 64 rows and more, up to 2048 wide: one wave per row, four rows per workgroup
+                                        (67, 64), (301, 768), (130, 1280), (65, 2048), (64, 8), (3150, 1024)])
 def test_layernorm(eet, rows, width):
     x = (wl.normal(101, width, (rows, width)).astype(np.float32) * 1.7 + 0.3).astype(np.float16)
     g = wl.normal(102, width, (width,), 0.1, 1.0)
