@@ -314,7 +314,8 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     // 24-layer hidden-1024 stack, one call: 346 -> 324 ms for 512 decode steps.  Prefetching during the attention or
     // the QKV projection, other workgroup counts (64, 96, 112, 192, 256) and the first feed-forward matrix instead
     // of the second were all slower: the attention streams from HBM itself, and 128 keeps main plus extra
-    // workgroups at one per CU.
+    // workgroups at one per CU.  Moving any share of the K/V rows (a quarter to all) from FFN-2's extra workgroups to
+    // the output projection's was slower too (324 -> 361-367 ms).
     constexpr int kPrefetchBlocks = 128;
     const bool prefetch = fuse_ln;
     auto lines = [](size_t bytes) { return (uint32_t)(bytes / 128); };
