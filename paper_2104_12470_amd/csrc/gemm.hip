@@ -1101,9 +1101,10 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
-        // 256x256 direct-to-LDS tiles once they can fill the chip, 128x128 register-staged tiles below that
+        // 256x256 direct-to-LDS tiles once they cover about 60 % of the CUs, 128x128 register-staged tiles below that
+        // (measured: 156 tiles 592 vs 514 TFLOP/s in favour of the large tiles, 112 tiles 563 vs 673 against them)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-        if (big_tiles >= 192) launch_dma64_cfg<2, 4>(a, epi, s);
+        if (big_tiles >= 150) launch_dma64_cfg<2, 4>(a, epi, s);
         else launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
     }
     return hipGetLastError();
