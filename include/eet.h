@@ -117,7 +117,13 @@ int eet_layer_encode(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, i
  * The token of sequence b is written to cache slot n_b, attends to slots 0..n_b, and n_b
  * becomes n_b + 1 (the lengths live in device memory and are advanced on the stream, so a
  * step has no host-varying argument).
- * Errors: STATE (no prefill yet), CAPACITY (some n_b + 1 > max_seq). */
+ * Errors: STATE (no prefill yet), CAPACITY (some n_b + 1 > max_seq).
+ * The capacity check uses a host-side count of the calls.  A caller that captures this call into
+ * a HIP graph of its own and replays it advances the device-side lengths once per replay without
+ * the host seeing it, and must keep count itself; the kernels never touch memory outside a
+ * sequence's max_seq slots whatever the device-side length says (a token past the capacity is
+ * not stored and the attention stops at max_seq keys: that sequence's results are then
+ * meaningless, nothing else is affected).  The same holds for the stack and model entry points. */
 int eet_decode_step(eet_layer_t *layer, const void *tokens, void *out, void *kv_cache,
                     void *hip_stream);
 

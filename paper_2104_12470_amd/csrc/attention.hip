@@ -776,7 +776,8 @@ __global__ __launch_bounds__(NW * 64) void attn_decode(AttnDecodeArgs a) {
     const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kslot = lane / LPK, chunk = lane % LPK;
-    const int n = a.lens[b] + a.len_bias;                // visible keys
+    int n = a.lens[b] + a.len_bias;                      // visible keys
+    n = n < 0 ? 0 : (n > a.capacity ? a.capacity : n);   // whatever the device-side length says, never outside the pair's slots
     const int splits = a.splits;
     int per = (n + splits - 1) / splits;
     per = (per + 15) & ~15;

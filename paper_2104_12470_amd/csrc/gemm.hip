@@ -72,6 +72,7 @@ __device__ __forceinline__ void epilogue_apply(const GemmArgs& a, int m, int n, 
                 b_ = m;
                 pos = e.pos;
             }
+            if (pos < 0 || pos >= a.max_seq) return;   // device-side lengths advanced past the capacity (replays the host never saw): drop, never write outside the slots
             const int g = c / a.d, dd = c - g * a.d;
             half_t* cache = which == 1 ? a.k_cache : a.v_cache;
             *reinterpret_cast<half4v*>(cache + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd) = o;
@@ -169,6 +170,7 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float1
                     b_ = m;
                     pos = a.lens[m];
                 }
+                if (pos < 0 || pos >= a.max_seq) continue;   // see epilogue_apply: never outside the sequence's slots
                 const int g = c / a.d, dd = c - g * a.d;
                 dst = (which == 1 ? a.k_cache : a.v_cache) + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd;
             }

@@ -220,6 +220,53 @@ def test_capacity_is_enforced_before_launch(eet):
     layer.close()
 
 
+@pytest.mark.parametrize("name,lens", [("tiny", [24, 1, 7]), ("small64", [200, 3, 150, 64, 199])])
+def test_replays_the_host_never_saw_stay_inside_the_slots(eet, name, lens):
+    """A caller records one decode step into a graph of its own and replays it more often than the cache has room for.
+    The host-side capacity check saw one call; the device-side lengths keep counting.  Whatever they say, no kernel
+    writes or reads outside a sequence's max_seq slots: the sequences that still fit are exactly what the oracle gives
+    for the same steps, the slots of the sequence that ran over hold its prompt and the tokens that fitted, and every
+    other slot still holds the sentinel."""
+    w = wl.WORKLOADS[name]
+    W = wl.layer_weights(w, 0, True)
+    B = len(lens)
+    layer = make_gpu_layer(eet, w, W, max_batch=B)
+    oracle = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps)
+    x = wl.prompt_embeddings(w)[:B]
+    layer.prefill(dev(poison_pads(x, lens)), lens)
+    oracle.prefill(x, lens)
+    xs = wl.decode_embeddings(w, 0)[:B]
+    tok = dev(xs)
+    out = torch.empty_like(tok)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):                         # the caller's capture: the library's launches join it
+        layer.decode_step(tok, out)
+    room = w.max_seq - max(lens)
+    replays = room + 5                                # the longest sequence runs over by five steps
+    for _ in range(replays):
+        g.replay()
+    torch.cuda.synchronize()
+    assert layer.cache_lens(B) == [L + replays for L in lens]          # the device-side count, unchecked by the host
+    kc, vc = layer.cache_views()
+    kc, vc = host(kc), host(vc)
+    fit = [b for b, L in enumerate(lens) if L + replays <= w.max_seq]
+    over = [b for b, L in enumerate(lens) if L + replays > w.max_seq]
+    assert fit and over
+    for _ in range(replays):
+        want = oracle.decode_step(xs, seqs=fit)
+    gate(host(out)[fit], want[fit], f"{name}: sequences that fit")
+    for b in fit:
+        n = lens[b] + replays
+        gate(kc[b, :, :n], oracle.k_cache[b, :, :n], f"{name}: K of sequence {b}", 1e-2, 1e-3)
+        gate(vc[b, :, :n], oracle.v_cache[b, :, :n], f"{name}: V of sequence {b}", 1e-2, 1e-3)
+        assert np.all(kc[b, :, n:] == SENTINEL) and np.all(vc[b, :, n:] == SENTINEL)
+    for b in over:                                    # full to the brim with finite rows, prompt part as the oracle has it
+        assert np.all(np.isfinite(kc[b])) and np.all(kc[b] != SENTINEL) and np.all(np.isfinite(vc[b]))
+        gate(kc[b, :, :lens[b]], oracle.k_cache[b, :, :lens[b]], f"{name}: prompt K of sequence {b}", 1e-2, 1e-3)
+    layer.close()
+
+
 def test_runs_are_bitwise_reproducible(eet):
     w = wl.WORKLOADS["small128"]
     W = wl.layer_weights(w)
