@@ -8,16 +8,22 @@
  * maximum length); generation is incremental over a K/V cache that is sized once for the
  * maximum batch and sequence length (Section 3.1).  Row-wise kernels (softmax, LayerNorm,
  * add-bias/GELU/residual) handle rows of any width (the goal of Section 2.2).
+ * Around the layer: a stack of layers driven by one call per step, the model around the stack
+ * (token ids in, logits and the greedy next token out), the operators one by one, and the buffer
+ * manager of Section 3.2.
  *
  * Conventions
  *   - All tensors are fp16 (IEEE binary16) in DEVICE memory unless a parameter says HOST.
  *     Accumulation and statistics are fp32.  Row-major, innermost dimension contiguous,
  *     base pointers 16-byte aligned.
  *   - Sequences are right-padded: sequence b has q_lens[b] valid rows [0, q_lens[b]) out of
- *     padded_len; the paper's per-sequence padding length is padded_len - q_lens[b].
+ *     padded_len; the paper's per-sequence padding length is padded_len - q_lens[b].  The entry
+ *     points named *_left_padded take the layout Algorithm 1 is printed for instead (valid rows
+ *     padded_len - q_lens[b] .. padded_len - 1).
  *   - The library never allocates, frees or synchronises device memory: workspace, K/V cache,
  *     weights, inputs and outputs are the caller's.  Every call only enqueues work on the
- *     given hipStream_t (passed as void*; NULL = default stream), except eet_cache_lens.
+ *     given hipStream_t (passed as void*; NULL = default stream), except eet_cache_lens (and
+ *     eet_model_create, which clears a few KB of its workspace with a blocking memset).
  *   - Return value: EET_OK or a negative error code.  On error nothing has been enqueued and
  *     no state has changed; eet_last_error() describes the failure (thread-local storage).
  *   - Calls on one layer handle must not overlap in time (one stream at a time).
