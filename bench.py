@@ -145,31 +145,29 @@ class ModelStack(Stack):
 
 
 class EncoderStack:
-    """The workload's layers used as a bidirectional encoder (no sequence mask, no decode): one
-    eet_layer_encode call per layer, activations ping-ponged between two buffers."""
+    """The workload's layers used as a bidirectional encoder (no sequence mask, no decode): one eet_stack_encode call
+    per pass, activations in the stack's two activation caches, one layer's K/V region as the scratch of every layer."""
 
     def __init__(self, w, eet, torch, wl):
         self.w, self.eet, self.torch = w, eet, torch
         cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
-        self.layers = [eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in wl.layer_weights(w, li).items()})
-                       for li in range(w.layers)]
+        self.stack = eet.DecoderStack(cfg, [{k: torch.from_numpy(v) for k, v in wl.layer_weights(w, li).items()}
+                                            for li in range(w.layers)], use_graph=False)
         self.n_layers = w.layers
         self.lens = [int(v) for v in wl.lengths(w)]
         self.x0 = torch.from_numpy(wl.prompt_embeddings(w)).to("cuda:0")
-        self.buf = [torch.empty_like(self.x0), torch.empty_like(self.x0)]
+        self.out = torch.empty_like(self.x0)
         self.stream = torch.cuda.Stream()
 
     def weights(self, layer):
-        return self.layers[layer].weights
+        return self.stack.weights[layer]
 
     def cache_views(self, layer):
-        return self.layers[layer].cache_views()
+        return self.stack.cache_views(layer)
 
     def prefill(self):
         with self.torch.cuda.stream(self.stream):
-            x = self.x0
-            for li, layer in enumerate(self.layers):
-                x = layer.encode(x, self.lens, self.buf[li & 1])
+            self.stack.encode(self.x0, self.lens, self.out)
 
     def decode(self):
         pass

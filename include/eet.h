@@ -172,6 +172,12 @@ int eet_stack_prefill(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, 
  * cache, lengths and every following decode step are those of eet_stack_prefill. */
 int eet_stack_prefill_left_padded(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, int32_t padded_len,
                                   const void *tokens, void *out, void *kv_cache, void *hip_stream);
+/* As eet_layer_encode through all layers (the encoder use of Section 4's Bert experiment: padding
+ * skipped, no sequence mask, no decode afterwards).  kv_scratch: DEVICE memory of ONE layer's
+ * eet_kv_cache_bytes(cfg), reused by every layer in turn for the keys and values of its pass.
+ * Any prefill / decode state of the stack is dropped.  Errors as eet_prefill. */
+int eet_stack_encode(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, int32_t padded_len,
+                     const void *tokens, void *out, void *kv_scratch, void *hip_stream);
 int eet_stack_decode_step(eet_stack_t *stack, const void *tokens, void *out, void *kv_cache,
                           void *hip_stream);
 int eet_stack_cache_lens(eet_stack_t *stack, int32_t *out_host, void *hip_stream);

@@ -514,6 +514,28 @@ int eet_stack_prefill_left_padded(eet_stack_t* st, const int32_t* q_lens, int32_
     return stack_prefill("eet_stack_prefill_left_padded", true, st, q_lens, batch, padded_len, tokens, out, kv_cache, hip_stream);
 }
 
+int eet_stack_encode(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int32_t padded_len, const void* tokens,
+                     void* out, void* kv_scratch, void* hip_stream) {
+    if (!st) return fail(EET_ERR_INVALID_ARG, "eet_stack_encode: null argument");
+    SeqLens lens;
+    int64_t T;
+    int max_len;
+    if (const int rc = check_prefill("eet_stack_encode", st->cfg, q_lens, batch, padded_len, tokens, out, kv_scratch, lens, T, max_len))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    st->batch = 0;                                   // the pass overwrites the device-side lengths: no decode state afterwards
+    const void* in = tokens;
+    for (int l = 0; l < st->n_layers; ++l) {
+        void* o = (l == st->n_layers - 1) ? out : static_cast<void*>(st->ws + st->act[l & 1]);
+        st->layers[l]->batch = 0;
+        // every layer's keys and values of this pass go to the same scratch: the layers run one after another
+        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv_scratch, s, false);
+        if (rc != EET_OK) return rc;
+        in = o;
+    }
+    return EET_OK;
+}
+
 static int stack_enqueue_decode(eet_stack* st, const void* tokens, void* out, void* kv_cache, hipStream_t s) {
     const void* in = tokens;
     for (int l = 0; l < st->n_layers; ++l) {

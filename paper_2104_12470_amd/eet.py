@@ -89,6 +89,7 @@ def lib() -> C.CDLL:
             "eet_stack_create": (i32, [cfgp, i32, C.POINTER(LayerWeights), vp, i32, C.POINTER(vp)]),
             "eet_stack_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_stack_prefill_left_padded": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
+            "eet_stack_encode": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_stack_decode_step": (i32, [vp, vp, vp, vp, vp]),
             "eet_stack_cache_lens": (i32, [vp, i32p, vp]),
             "eet_stack_destroy": (i32, [vp]),
@@ -137,7 +138,7 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
            "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
            "eet_op_embedding_decode", "eet_op_argmax", "eet_stack_prefill_left_padded", "eet_model_prefill_left_padded",
-           "eet_op_embedding_left_padded")
+           "eet_op_embedding_left_padded", "eet_stack_encode")
 
 
 def _check(code: int) -> None:
@@ -239,6 +240,11 @@ def eet_stack_prefill_left_padded(stack: int, q_lens: Sequence[int], batch: int,
                                   stream=None) -> None:
     _check(lib().eet_stack_prefill_left_padded(stack, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out),
                                                _ptr(kv_cache), _stream(stream)))
+
+
+def eet_stack_encode(stack: int, q_lens: Sequence[int], batch: int, padded_len: int, tokens, out, kv_scratch, stream=None) -> None:
+    _check(lib().eet_stack_encode(stack, _lens_array(q_lens), batch, padded_len, _ptr(tokens), _ptr(out), _ptr(kv_scratch),
+                                  _stream(stream)))
 
 
 def eet_stack_decode_step(stack: int, tokens, out, kv_cache, stream=None) -> None:
@@ -498,6 +504,13 @@ class DecoderStack:
         B, S, _ = tokens.shape
         out = torch.empty_like(tokens) if out is None else out
         eet_stack_prefill_left_padded(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
+        return out
+
+    def encode(self, tokens: torch.Tensor, q_lens: Sequence[int], out: Optional[torch.Tensor] = None, stream=None):
+        """All layers as a bidirectional encoder; the first layer's share of the K/V cache serves as the scratch."""
+        B, S, _ = tokens.shape
+        out = torch.empty_like(tokens) if out is None else out
+        eet_stack_encode(self.handle, q_lens, B, S, tokens, out, self.kv_cache, stream)
         return out
 
     def decode_step(self, tokens: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):

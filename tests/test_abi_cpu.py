@@ -149,6 +149,8 @@ def test_stack_sizes_and_validation(eet):
     assert L.eet_stack_prefill(h, lens, 2, 512, P, P, P, None) == eet.EET_ERR_INVALID_ARG     # 600 > 512
     assert L.eet_stack_prefill(h, lens, 9, 512, P, P, P, None) == eet.EET_ERR_CAPACITY
     assert L.eet_stack_cache_lens(h, lens, None) == eet.EET_ERR_STATE
+    assert L.eet_stack_encode(h, lens, 2, 512, P, P, P, None) == eet.EET_ERR_INVALID_ARG      # 600 > 512
+    assert L.eet_stack_encode(h, lens, 2, 1024, P, P, P, None) == eet.EET_ERR_CAPACITY        # padded_len > max_prompt
     assert L.eet_stack_destroy(h) == eet.EET_OK
     bad = (eet.LayerWeights * 2)(eet.LayerWeights(*[0x10000] * 12), eet.LayerWeights(*[0x10000] * 11, 0))
     assert L.eet_stack_create(C.byref(cfg), 2, bad, 0x100000, 1, C.byref(h)) == eet.EET_ERR_INVALID_ARG and not h.value
@@ -192,6 +194,7 @@ def test_model_and_its_operators_validate(eet):
     assert L.eet_op_embedding_left_padded(P, lens, 2, 8, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG   # len 9 > S 8
     assert L.eet_model_prefill_left_padded(None, None, 1, 1, P, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_stack_prefill_left_padded(None, lens, 2, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_stack_encode(None, lens, 2, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_embedding_decode(P, None, 2, 64, 100, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_embedding_decode(P, P, 2, 64, 0, 16, P, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_op_argmax(P, 2, 100, 96, P, None) == eet.EET_ERR_INVALID_ARG                              # stride < vocab

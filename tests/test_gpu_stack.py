@@ -165,3 +165,39 @@ def test_left_padded_stack_prefill(eet, name, n_layers):
     assert torch.equal(left.kv_cache, right.kv_cache)
     left.close()
     right.close()
+
+
+@pytest.mark.parametrize("name,n_layers", [("small64", 2), ("small128", 3)])
+def test_stack_encode_equals_layer_chain_and_oracle(eet, name, n_layers):
+    """All layers as a bidirectional encoder in one call: bit for bit the chain of eet_layer_encode calls, within the
+    layer tolerance of the oracle's chain, pad rows zero, and no decode state afterwards."""
+    w = wl.WORKLOADS[name]
+    cfg, Ws, stack = build(eet, w, n_layers, use_graph=True)
+    lens, x = wl.lengths(w), wl.prompt_embeddings(w)
+    B = w.batch
+    xp = x.copy()
+    for b, L in enumerate(lens):
+        xp[b, int(L):] = np.nan                      # pad rows are never read
+    got = stack.encode(dev(xp), lens)
+    layers = [eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in W.items()}) for W in Ws]
+    h, ho = dev(xp), x.astype(np.float64)
+    for layer, W in zip(layers, Ws):
+        h = layer.encode(h, lens)
+        ho = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps).encode(ho, lens)
+    torch.cuda.synchronize()
+    g = host(got)
+    assert np.array_equal(g.view(np.uint16), host(h).view(np.uint16))
+    for b, L in enumerate(lens):
+        L = int(L)
+        gate(g[b, :L], ho[b, :L], f"{name} stack encode b={b}")
+        assert np.all(g[b, L:] == 0)
+    with pytest.raises(eet.EETError) as e:
+        stack.decode_step(dev(wl.decode_embeddings(w, 0)))
+    assert e.value.code == eet.EET_ERR_STATE
+    stack.prefill(dev(x), lens)                      # the stack is usable as a decoder again
+    stack.decode_step(dev(wl.decode_embeddings(w, 0)))
+    torch.cuda.synchronize()
+    assert stack.cache_lens(B) == [int(v) + 1 for v in lens]
+    stack.close()
+    for layer in layers:
+        layer.close()
