@@ -325,3 +325,52 @@ def test_gpt2_sized_vocabulary_on_the_cfg2_layer_shape(eet):
         nxt = nxt2
     assert gpu.stack.cache_lens(B) == [L + w.decode_steps for L in lens]
     gpu.close()
+
+
+def test_cfg2_model_at_full_size_is_embedding_then_stack_then_head(eet):
+    """The benchmark's --model configuration (24 layers, batch 8, prompts of 256-512 tokens, vocabulary 50257, decode
+    steps replayed from the stack's graph): the model call is bit for bit the embedding operator, then the stack entry
+    points on a second stack with the same weights, and its logits are the output projection of its own last-layer rows
+    within tolerance, with the exact greedy choice -- each of those parts is compared with the oracle on its own
+    (embedding: above; stack: layer by layer in test_gpu_layer.py; head: check_head)."""
+    w = replace(wl.WORKLOADS["cfg2"], decode_steps=3)
+    V = 50257
+    LW = [{k: torch.from_numpy(v) for k, v in wl.layer_weights(w, l).items()} for l in range(w.layers)]
+    head = wl.model_head(w, V, w.max_seq)
+    cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+    model = eet.DecoderModel(cfg, LW, {k: torch.from_numpy(v) for k, v in head.items()}, V)
+    other = eet.DecoderStack(cfg, LW, use_graph=False)
+    head64 = {k: v.astype(np.float64) for k, v in head.items()}
+    lens = [int(v) for v in wl.lengths(w)]
+    ids = dev(wl.prompt_ids(w, V))
+    B, S = ids.shape
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        logits, nxt = model.prefill(ids, lens, stream=stream)
+    stream.synchronize()
+    h_in, h_out = model.hidden_states(decode=False)
+    assert h_in is None                                             # 24 layers: the final output replaced the embedding
+    emb = torch.empty((B, S, w.hidden), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_embedding(ids, lens, model.head["wte"], model.head["wpe"], emb, vocab=V)
+    ref = other.prefill(emb, lens)
+    torch.cuda.synchronize()
+    assert torch.equal(h_out, ref)
+    last = np.stack([host(h_out[b, L - 1]) for b, L in enumerate(lens)])
+    check_head(model, head64, last, logits, nxt, V, "cfg2 model prefill")
+    for k in range(w.decode_steps):
+        fed = nxt
+        with torch.cuda.stream(stream):
+            logits, nxt = model.decode_step(fed, stream=stream)
+        stream.synchronize()
+        d_in, d_out = model.hidden_states(decode=True)
+        pos = torch.tensor([L + k for L in lens], dtype=torch.int32, device="cuda:0")
+        x = torch.empty((B, w.hidden), dtype=torch.float16, device="cuda:0")
+        eet.eet_op_embedding_decode(fed, pos, model.head["wte"], model.head["wpe"], x, vocab=V)
+        y = other.decode_step(x)
+        torch.cuda.synchronize()
+        assert torch.equal(d_in, x) and torch.equal(d_out, y)
+        check_head(model, head64, host(d_out), logits, nxt, V, f"cfg2 model decode {k}")
+    assert model.stack.cache_lens(B) == other.cache_lens(B) == [L + w.decode_steps for L in lens]
+    assert torch.equal(model.stack.kv_cache, other.kv_cache)
+    model.close()
+    other.close()
