@@ -290,7 +290,7 @@ def _kernel_candidates(stack, torch, eet, reps):
         st4["i"] += 1
         attn_op(qp, kc, vc, cp, stack.lens, w.heads)
     ms = time_launches(torch, run_pattn, max(4, min(reps, 24)), replays=2)
-    pname = "attn_prefill_wide" if d == 128 and max(stack.lens) > 128 else "attn_prefill"      # the library's own choice
+    pname = "attn_prefill_wide" if d == 128 and max(stack.lens) > 512 else "attn_prefill"      # the library's own choice
     if w.encoder:       # every valid row sees all L valid keys: 2 * (2 * L * L * H) flop per sequence
         out.append({"kernel": f"{pname}<{d}, false>: padding-skipping attention without sequence mask (matrix cores)",
                     "bound": "mfma", "work": sum(4.0 * H * L * L for L in stack.lens), "ms": ms, "launches": nl})
