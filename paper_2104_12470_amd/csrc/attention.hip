@@ -273,11 +273,16 @@ __device__ __forceinline__ void wait_vmem() {
     if (N == 4) asm volatile("s_waitcnt vmcnt(4)");
 }
 // lane ^ 32 maximum without the LDS: v_permlane32_swap exchanges the upper half of its first operand
-// with the lower half of its second
+// with the lower half of its second, so the two results hold, for every lane, its own value and its partner's.
+// The two elements are copied into scalars before the bit casts: __builtin_bit_cast applied to the vector element
+// r[1] directly reads element 0 with this compiler, which silently turned the maximum into "the value of the lower
+// lane" (a reference of the exponentials that ignored half of each row's keys: exact results until a row's scores
+// span more than the 16 bits of headroom fp16 has above one, then infinities).
 __device__ __forceinline__ float max_xor32(float x) {
     const unsigned u = __builtin_bit_cast(unsigned, x);
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    const unsigned r0 = r[0], r1 = r[1];
+    return fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
 }
 
 template <int D, bool CAUSAL>

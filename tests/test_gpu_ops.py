@@ -185,6 +185,40 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
 
 
 @pytest.mark.parametrize("d,heads,S,cap,lens", [
+    (128, 2, 1100, 1104, [1100, 700]),        # 256-row kernel
+    (128, 2, 500, 512, [500, 257]),           # 128-row kernel, heads of 128
+    (64, 2, 700, 704, [700, 130]),            # 128-row kernel, heads of 64
+])
+def test_attention_prefill_with_a_wide_score_range_and_a_rising_maximum(eet, d, heads, S, cap, lens):
+    """Scores with a standard deviation of about 12 whose magnitude grows with the key position: the running maximum
+    keeps rising from key tile to key tile by more than the slack the kernels allow before they move the reference of
+    their exponentials, so the rescaling path runs many times per row, and the softmax is close to one-hot."""
+    B, H = len(lens), heads * d
+    q = (wl.normal(430 + d, 1, (B, S, heads, d)).astype(np.float32) * 4.0).astype(np.float16)
+    ramp = (1.0 + 2.0 * np.arange(S, dtype=np.float32) / S)[None, :, None, None]
+    k = (wl.normal(430 + d, 2, (B, S, heads, d)).astype(np.float32) * ramp).astype(np.float16)
+    v = wl.normal(430 + d, 3, (B, S, heads, d))
+    want = orc.attention_prefill(q, k, v, lens)
+    kc = np.full((B, heads, cap, d), np.nan, np.float16)
+    vc = np.full((B, heads, cap, d), np.nan, np.float16)
+    for b, L in enumerate(lens):
+        kc[b, :, :L] = k[b, :L].transpose(1, 0, 2)
+        vc[b, :, :L] = v[b, :L].transpose(1, 0, 2)
+    ctx = torch.zeros((B, S, H), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_prefill(dev(q.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads)
+    nk = torch.tensor(lens, dtype=torch.int32, device="cuda:0")
+    last_q = np.stack([q[b, L - 1] for b, L in enumerate(lens)]).reshape(B, H)
+    dctx = torch.zeros((B, H), dtype=torch.float16, device="cuda:0")
+    scratch = torch.empty(eet.eet_op_attention_decode_scratch_bytes(B, heads, d, cap), dtype=torch.uint8, device="cuda:0")
+    eet.eet_op_attention_decode(dev(last_q), dev(kc), dev(vc), dctx, nk, scratch)      # the last row again, as a decode step
+    torch.cuda.synchronize()
+    got = host(ctx).reshape(B, S, heads, d)
+    for b, L in enumerate(lens):
+        gate(got[b, :L], want[b, :L], f"wide-range attention prefill b={b} L={L}", OP_MAX, OP_MEAN)
+        gate(host(dctx)[b].reshape(heads, d), want[b, L - 1], f"wide-range attention decode b={b}", OP_MAX, OP_MEAN)
+
+
+@pytest.mark.parametrize("d,heads,S,cap,lens", [
     (64, 2, 24, 32, [24, 1, 7]),
     (64, 3, 200, 224, [200, 3, 129, 64, 65]),
     (128, 2, 333, 352, [333, 40, 129, 128]),
