@@ -267,6 +267,42 @@ def test_replays_the_host_never_saw_stay_inside_the_slots(eet, name, lens):
     layer.close()
 
 
+@pytest.mark.parametrize("name", ["small64", "cfg2-2seq"])
+def test_inputs_with_a_common_offset_and_an_outlier_channel(eet, name):
+    """Hidden states as real models have them: every row shifted by a common offset of several standard deviations and
+    one channel (the first: the pivot of the LayerNorm statistics fused into the small-layer decode projections) ten
+    times larger than the rest.  Prefill (row-kernel LayerNorm) and decode steps (fused LayerNorm) against the oracle."""
+    from dataclasses import replace
+    w = wl.WORKLOADS["small64"] if name == "small64" else replace(wl.WORKLOADS["cfg2"], batch=2, decode_steps=3)
+    W = wl.layer_weights(w, 0, True)
+    lens = wl.lengths(w)
+    B = w.batch
+
+    def skew(a):
+        a = a.astype(np.float32) + 6.0
+        a[..., 0] = a[..., 0] * 10.0
+        return a.astype(np.float16)
+    x = skew(wl.prompt_embeddings(w))
+    layer = make_gpu_layer(eet, w, W)
+    oracle = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps)
+    rows = None if name == "small64" else {b: [0, int(L) // 2, int(L) - 1] for b, L in enumerate(lens)}
+    got = host(layer.prefill(dev(poison_pads(x, lens)), lens))
+    want = oracle.prefill(x, lens, rows)
+    for b, L in enumerate(lens):
+        idx = range(int(L)) if rows is None else rows[b]
+        for i in idx:
+            ref = want[b, i]
+            tol = np.maximum(MAX_ABS, np.abs(ref) * 2.0 ** -10)        # the outlier channel is ~60: an fp16 ulp there is 0.03
+            assert np.all(np.abs(got[b, i].astype(np.float64) - ref) <= tol), (name, b, i)
+    for k in range(3):
+        xs = skew(wl.decode_embeddings(w, k))
+        got_d = host(layer.decode_step(dev(xs))).astype(np.float64)
+        ref = oracle.decode_step(xs)
+        tol = np.maximum(MAX_ABS, np.abs(ref) * 2.0 ** -10)
+        assert np.all(np.abs(got_d - ref) <= tol), (name, "decode", k, float(np.abs(got_d - ref).max()))
+    layer.close()
+
+
 def test_runs_are_bitwise_reproducible(eet):
     w = wl.WORKLOADS["small128"]
     W = wl.layer_weights(w)

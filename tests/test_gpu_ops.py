@@ -38,6 +38,33 @@ def test_layernorm(eet, rows, width):
     gate(host(y), orc.layernorm(x, g, b, 1e-5), f"layernorm {rows}x{width}", OP_MAX, OP_MEAN)
 
 
+@pytest.mark.parametrize("rows,width", [(5, 1024), (130, 1024), (3, 4096), (2, 12288), (3, 1283)])
+def test_layernorm_of_rows_with_a_large_mean_and_an_outlier(eet, rows, width):
+    """Rows whose mean is a hundred standard deviations away from zero (a one-pass variance would cancel), and rows with
+    one element a thousand times the others (the statistics are then that element's)."""
+    base = wl.normal(105, width, (rows, width)).astype(np.float32)
+    shifted = (base + 100.0).astype(np.float16)
+    spiked = base.copy()
+    spiked[:, 0] = 1000.0
+    spiked[1:, 0] = 0.1
+    spiked[1:, width // 2] = -3000.0
+    spiked = spiked.astype(np.float16)
+    g = np.ones(width, np.float16)
+    b = np.zeros(width, np.float16)
+    for name, x in (("mean 100", shifted), ("spike", spiked)):
+        y = torch.full((rows, width), float("nan"), dtype=torch.float16, device="cuda:0")
+        eet.eet_op_layernorm(dev(x), dev(g), dev(b), y, 1e-5)
+        torch.cuda.synchronize()
+        want = orc.layernorm(x, g, b, 1e-5)
+        got = host(y).astype(np.float64)
+        assert np.all(np.isfinite(got))
+        # O(1) outputs to the operator tolerance; the spike itself is sqrt(width) large: half an ulp of fp16 there
+        small = np.abs(want) < 4.0
+        gate(np.where(small, got, 0.0), np.where(small, want, 0.0), f"layernorm {name} {rows}x{width}", OP_MAX, OP_MEAN)
+        rel = np.abs(got - want)[~small] / np.abs(want[~small]) if (~small).any() else np.zeros(1)
+        assert rel.max() <= 2e-3, (name, rel.max())
+
+
 @pytest.mark.parametrize("rows,width", [(5, 3072), (3, 49152), (4, 100), (2, 16392), (70000, 64)])
 def test_bias_gelu_and_bias_residual(eet, rows, width):
     x = (wl.normal(111, width, (rows, width)).astype(np.float32) * 2.0).astype(np.float16)
