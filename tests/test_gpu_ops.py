@@ -38,6 +38,35 @@ def test_layernorm(eet, rows, width):
     gate(host(y), orc.layernorm(x, g, b, 1e-5), f"layernorm {rows}x{width}", OP_MAX, OP_MEAN)
 
 
+@pytest.mark.parametrize("S,lens", [(64, [64, 17]), (520, [333, 520]), (9, [9, 4])])
+def test_softmax_maskfree_with_scores_that_leave_one_key_standing(eet, S, lens):
+    """Scores with a standard deviation of 30 and a scale of 1: every row is close to one-hot, most probabilities
+    underflow, none may overflow or turn into NaN, and rows still sum to one."""
+    B = len(lens)
+    s = (wl.scores(29, B, 2, S).astype(np.float32) * 15.0).astype(np.float16)
+    sd = dev(s)
+    eet.eet_op_softmax_maskfree(sd, lens, 1.0)
+    torch.cuda.synchronize()
+    got, want = host(sd), orc.softmax_maskfree(s, lens, 1.0)
+    for b, L in enumerate(lens):
+        gate(got[b, :, :L], want[b, :, :L], f"one-hot softmax b={b}", 1e-3, 1e-4)
+        np.testing.assert_allclose(got[b, :, :L].astype(np.float64).sum(-1), 1.0, atol=2e-3)
+
+
+@pytest.mark.parametrize("rows,width", [(3, 1024), (70, 768), (2, 4096), (3, 1283)])
+def test_layernorm_of_constant_rows_gives_beta(eet, rows, width):
+    """Zero variance: the result is beta exactly (the deviations are exact zeros; eps keeps the scale finite)."""
+    x = np.full((rows, width), 0.1, np.float16)
+    x[1] = 1.5
+    x[-1] = -7.0
+    g = wl.normal(102, width, (width,), 0.1, 1.0)
+    b = wl.normal(103, width, (width,), 0.1, 0.0)
+    y = torch.full((rows, width), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_layernorm(dev(x), dev(g), dev(b), y, 1e-5)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(y), np.broadcast_to(b, (rows, width)))
+
+
 @pytest.mark.parametrize("rows,width", [(5, 1024), (130, 1024), (3, 4096), (2, 12288), (3, 1283)])
 def test_layernorm_of_rows_with_a_large_mean_and_an_outlier(eet, rows, width):
     """Rows whose mean is a hundred standard deviations away from zero (a one-pass variance would cancel), and rows with
@@ -216,7 +245,8 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
     (128, 2, 500, 512, [500, 257]),           # 128-row kernel, heads of 128
     (64, 2, 700, 704, [700, 130]),            # 128-row kernel, heads of 64
 ])
-def test_attention_prefill_with_a_wide_score_range_and_a_rising_maximum(eet, d, heads, S, cap, lens):
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_prefill_with_a_wide_score_range_and_a_rising_maximum(eet, d, heads, S, cap, lens, causal):
     """Scores with a standard deviation of about 12 whose magnitude grows with the key position: the running maximum
     keeps rising from key tile to key tile by more than the slack the kernels allow before they move the reference of
     their exponentials, so the rescaling path runs many times per row, and the softmax is close to one-hot."""
@@ -225,14 +255,15 @@ def test_attention_prefill_with_a_wide_score_range_and_a_rising_maximum(eet, d, 
     ramp = (1.0 + 2.0 * np.arange(S, dtype=np.float32) / S)[None, :, None, None]
     k = (wl.normal(430 + d, 2, (B, S, heads, d)).astype(np.float32) * ramp).astype(np.float16)
     v = wl.normal(430 + d, 3, (B, S, heads, d))
-    want = orc.attention_prefill(q, k, v, lens)
+    want = orc.attention_prefill(q, k, v, lens, causal=causal)
     kc = np.full((B, heads, cap, d), np.nan, np.float16)
     vc = np.full((B, heads, cap, d), np.nan, np.float16)
     for b, L in enumerate(lens):
         kc[b, :, :L] = k[b, :L].transpose(1, 0, 2)
         vc[b, :, :L] = v[b, :L].transpose(1, 0, 2)
     ctx = torch.zeros((B, S, H), dtype=torch.float16, device="cuda:0")
-    eet.eet_op_attention_prefill(dev(q.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads)
+    op = eet.eet_op_attention_prefill if causal else eet.eet_op_attention_encoder
+    op(dev(q.reshape(B, S, H)), dev(kc), dev(vc), ctx, lens, heads)
     nk = torch.tensor(lens, dtype=torch.int32, device="cuda:0")
     last_q = np.stack([q[b, L - 1] for b, L in enumerate(lens)]).reshape(B, H)
     dctx = torch.zeros((B, H), dtype=torch.float16, device="cuda:0")
@@ -241,8 +272,8 @@ def test_attention_prefill_with_a_wide_score_range_and_a_rising_maximum(eet, d, 
     torch.cuda.synchronize()
     got = host(ctx).reshape(B, S, heads, d)
     for b, L in enumerate(lens):
-        gate(got[b, :L], want[b, :L], f"wide-range attention prefill b={b} L={L}", OP_MAX, OP_MEAN)
-        gate(host(dctx)[b].reshape(heads, d), want[b, L - 1], f"wide-range attention decode b={b}", OP_MAX, OP_MEAN)
+        gate(got[b, :L], want[b, :L], f"wide-range attention (causal={causal}) b={b} L={L}", OP_MAX, OP_MEAN)
+        gate(host(dctx)[b].reshape(heads, d), want[b, L - 1], f"wide-range attention decode b={b}", OP_MAX, OP_MEAN)   # the last row sees all keys either way
 
 
 @pytest.mark.parametrize("d,heads,S,cap,lens", [
