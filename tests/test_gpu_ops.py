@@ -109,6 +109,30 @@ def test_bias_gelu_and_bias_residual(eet, rows, width):
     gate(host(y), orc.bias_residual(x, b, r), f"bias_residual {rows}x{width}", OP_MAX, OP_MEAN)
 
 
+def test_gelu_at_the_ends_of_the_fp16_range(eet):
+    """Arguments from the smallest to the largest fp16 magnitudes: exact limits (x for large x, -0 for very negative x),
+    no NaN from an overflowing exponential, and the operator tolerance relative to the size of the value in between."""
+    vals = [0.0, -0.0, 6e-8, -6e-8, 1e-4, -1e-4, 0.5, -0.5, 1.0, -1.0, 3.0, -3.0, 5.0, -5.0, 8.0, -8.0, 12.0, -12.0, 30.0, -30.0,
+            100.0, -100.0, 1000.0, -1000.0, 30000.0, -30000.0, 65504.0, -65504.0]
+    width = 64
+    x = np.zeros((len(vals), width), np.float16)
+    for r, v in enumerate(vals):
+        x[r, :] = v
+    b = np.zeros(width, np.float16)
+    y = torch.full(x.shape, float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_bias_gelu(dev(x), dev(b), y)
+    torch.cuda.synchronize()
+    got = host(y).astype(np.float64)
+    want = orc.gelu_tanh(x.astype(np.float64))
+    assert np.all(np.isfinite(got))
+    assert np.all(np.abs(got - want) <= np.maximum(2e-3, np.abs(want) * 2.0 ** -10)), np.abs(got - want).max(axis=1)
+    for r, v in enumerate(vals):
+        if v >= 12.0:
+            assert np.all(got[r] == np.float64(np.float16(v)))          # gelu(x) = x to fp16 precision
+        if v <= -12.0:
+            assert np.all(got[r] == 0.0)
+
+
 @pytest.mark.parametrize("B,nh,S,lens", [
     (3, 2, 9, [9, 1, 5]),              # scalar path (S % 8 != 0)
     (4, 1, 10, [5, 2, 4, 10]),         # the uneven batch of the paper's Section 4.1 example
