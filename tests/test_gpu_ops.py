@@ -383,6 +383,32 @@ def test_attention_unfused(eet, d, heads, S, cap, lens):
 
 
 @pytest.mark.parametrize("d,heads,cap,n_keys", [
+    (64, 16, 640, [640, 1, 63, 64, 65, 300, 511, 129]),     # 128 (sequence, head) pairs: one key range each, no merge launch
+    (128, 32, 520, [520, 257, 32, 33]),
+])
+@pytest.mark.parametrize("peaked", [False, True])
+def test_attention_decode_with_one_range_per_pair(eet, d, heads, cap, n_keys, peaked):
+    B = len(n_keys)
+    q = wl.normal(520 + d, 1, (B, heads, d))
+    kc = wl.normal(520 + d, 2, (B, heads, cap, d))
+    vc = wl.normal(520 + d, 3, (B, heads, cap, d))
+    if peaked:        # scores with a standard deviation of about 12 that grow with the slot: the running maximum keeps moving
+        q = (q.astype(np.float32) * 4.0).astype(np.float16)
+        kc = (kc.astype(np.float32) * (1.0 + 2.0 * np.arange(cap, dtype=np.float32) / cap)[None, None, :, None]).astype(np.float16)
+    assert eet.eet_op_attention_decode_scratch_bytes(B, heads, d, cap) <= 256      # nothing to merge
+    want = orc.attention_decode(q, kc, vc, n_keys)
+    kp, vp = kc.copy(), vc.copy()
+    for b, n in enumerate(n_keys):
+        kp[b, :, n:] = np.nan
+        vp[b, :, n:] = np.nan
+    scratch = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    ctx = torch.full((B, heads * d), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_decode(dev(q.reshape(B, heads * d)), dev(kp), dev(vp), ctx, dev(np.asarray(n_keys, np.int32)), scratch)
+    torch.cuda.synchronize()
+    gate(host(ctx).reshape(B, heads, d), want, f"attention decode, one range, d={d} peaked={peaked}", OP_MAX, OP_MEAN)
+
+
+@pytest.mark.parametrize("d,heads,cap,n_keys", [
     (64, 4, 600, [1, 17, 600]),
     (128, 4, 600, [600, 16, 33]),
     (64, 2, 2048, [2048, 100]),        # several key ranges per (sequence, head), one of them empty for the short one
