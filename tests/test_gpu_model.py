@@ -374,3 +374,33 @@ def test_cfg2_model_at_full_size_is_embedding_then_stack_then_head(eet):
     assert torch.equal(model.stack.kv_cache, other.kv_cache)
     model.close()
     other.close()
+
+
+def test_model_sized_for_more_sequences_serves_smaller_batches_one_after_another(eet):
+    """A model created for 6 sequences runs a batch of 4, generates, then a batch of 2 with other prompts, generates again
+    (the recorded decode graph is re-recorded for the new batch): every call against a fresh oracle model."""
+    w = replace(wl.WORKLOADS["small64"], batch=6, decode_steps=3)
+    V = 333
+    gpu, _, head = build(eet, w, V)
+    LW = [wl.layer_weights(w, l, random_affine=True) for l in range(w.layers)]
+    all_ids = wl.prompt_ids(w, V)
+    all_lens = [int(v) for v in wl.lengths(w)]
+    stream = torch.cuda.Stream()
+    for rows in ([0, 1, 2, 3], [5, 4]):
+        ids = np.ascontiguousarray(all_ids[rows]); lens = [all_lens[r] for r in rows]
+        ora = orc.DecoderModelOracle(LW, head, w.heads, len(rows), w.max_seq, w.ln_eps)
+        with torch.cuda.stream(stream):
+            logits, nxt = gpu.prefill(dev(ids), lens, stream=stream)
+        stream.synchronize()
+        want = ora.prefill(ids, lens)
+        gate(host(logits)[:, :V], want, f"batch of {len(rows)}: prefill logits")
+        for k in range(w.decode_steps):
+            fed = host(nxt)
+            with torch.cuda.stream(stream):
+                logits, nxt = gpu.decode_step(nxt, stream=stream)
+            stream.synchronize()
+            want = ora.decode_step(fed)
+            gate(host(logits)[:, :V], want, f"batch of {len(rows)}: decode {k} logits")
+            assert host(nxt).tolist() == orc.greedy_token(host(logits).astype(np.float64), V).tolist()
+        assert gpu.stack.cache_lens(len(rows)) == [L + w.decode_steps for L in lens]
+    gpu.close()
