@@ -137,6 +137,14 @@ int eet_decode_step(eet_layer_t *layer, const void *tokens, void *out, void *kv_
  * Synchronises the stream.  Errors: STATE, HIP. */
 int eet_cache_lens(eet_layer_t *layer, int32_t *out_host, void *hip_stream);
 
+/* Resume from a saved state.  The resumable state of a layer is its K/V cache (the caller's memory) and the
+ * lengths n_b (eet_cache_lens): with a cache that holds tokens [0, cache_lens[b]) of sequence b in its slots, this
+ * call sets the lengths (device side, by a small kernel on the stream, and the host-side count) and the batch, after
+ * which eet_decode_step continues exactly where the saved run stopped -- on this layer or on another one created
+ * with the same configuration and weights.  cache_lens: HOST int32[batch], 1 <= cache_lens[b] <= max_seq.
+ * Errors: INVALID_ARG, CAPACITY (batch > max_batch). */
+int eet_restore(eet_layer_t *layer, const int32_t *cache_lens, int32_t batch, void *hip_stream);
+
 /* Release the handle (host memory only). */
 int eet_layer_destroy(eet_layer_t *layer);
 
@@ -181,6 +189,8 @@ int eet_stack_encode(eet_stack_t *stack, const int32_t *q_lens, int32_t batch, i
 int eet_stack_decode_step(eet_stack_t *stack, const void *tokens, void *out, void *kv_cache,
                           void *hip_stream);
 int eet_stack_cache_lens(eet_stack_t *stack, int32_t *out_host, void *hip_stream);
+/* As eet_restore for all layers (they share the lengths): kv_cache holds every layer's saved region. */
+int eet_stack_restore(eet_stack_t *stack, const int32_t *cache_lens, int32_t batch, void *hip_stream);
 int eet_stack_destroy(eet_stack_t *stack);
 
 /* ---------------------------------------------------------------------------------------------

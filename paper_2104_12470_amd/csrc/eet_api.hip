@@ -393,6 +393,30 @@ int eet_decode_step(eet_layer_t* L, const void* tokens, void* out, void* kv_cach
     return EET_OK;
 }
 
+static int check_restore(const char* who, const eet_layer_config& c, const int32_t* lens_host, int32_t batch, SeqLens& lens) {
+    if (!lens_host) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1) return fail(EET_ERR_INVALID_ARG, "%s: batch must be >= 1", who);
+    if (batch > c.max_batch) return fail(EET_ERR_CAPACITY, "%s: batch %d > max_batch %d", who, batch, c.max_batch);
+    std::memset(&lens, 0, sizeof(lens));
+    for (int b = 0; b < batch; ++b) {
+        if (lens_host[b] < 1 || lens_host[b] > c.max_seq)
+            return fail(EET_ERR_INVALID_ARG, "%s: cache_lens[%d] = %d outside [1, %d]", who, b, lens_host[b], c.max_seq);
+        lens.len[b] = lens_host[b];
+    }
+    return EET_OK;
+}
+
+int eet_restore(eet_layer_t* L, const int32_t* cache_lens, int32_t batch, void* hip_stream) {
+    if (!L) return fail(EET_ERR_INVALID_ARG, "eet_restore: null argument");
+    SeqLens lens;
+    if (const int rc = check_restore("eet_restore", L->cfg, cache_lens, batch, lens)) return rc;
+    EET_LAUNCH(launch_set_cache_lens(lens, batch, reinterpret_cast<int32_t*>(L->ws + L->lay.lens), static_cast<hipStream_t>(hip_stream)),
+               "set cache lengths");
+    L->batch = batch;
+    for (int b = 0; b < batch; ++b) L->host_lens[b] = cache_lens[b];
+    return EET_OK;
+}
+
 int eet_cache_lens(eet_layer_t* L, int32_t* out_host, void* hip_stream) {
     if (!L || !out_host) return fail(EET_ERR_INVALID_ARG, "eet_cache_lens: null argument");
     if (L->batch == 0) return fail(EET_ERR_STATE, "eet_cache_lens: no prefill has been run on this layer");
@@ -597,6 +621,19 @@ int eet_stack_decode_step(eet_stack_t* st, const void* tokens, void* out, void* 
         EET_LAUNCH(hipGraphLaunch(st->exec, s), "graph launch");
     }
     for (int b = 0; b < B; ++b) st->host_lens[b] += 1;
+    return EET_OK;
+}
+
+int eet_stack_restore(eet_stack_t* st, const int32_t* cache_lens, int32_t batch, void* hip_stream) {
+    if (!st) return fail(EET_ERR_INVALID_ARG, "eet_stack_restore: null argument");
+    SeqLens lens;
+    if (const int rc = check_restore("eet_stack_restore", st->cfg, cache_lens, batch, lens)) return rc;
+    eet_layer* L0 = st->layers[0];                       // the layers share one set of device-side lengths
+    EET_LAUNCH(launch_set_cache_lens(lens, batch, reinterpret_cast<int32_t*>(L0->ws + L0->lay.lens), static_cast<hipStream_t>(hip_stream)),
+               "set cache lengths");
+    for (int l = 0; l < st->n_layers; ++l) st->layers[l]->batch = batch;
+    st->batch = batch;
+    for (int b = 0; b < batch; ++b) st->host_lens[b] = cache_lens[b];
     return EET_OK;
 }
 

@@ -26,6 +26,9 @@ hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width
                                 int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s,
                                 bool left_padded = false);
 
+// cache_lens[b] = lens.len[b] for b < batch (DEVICE array of the layer's workspace)
+hipError_t launch_set_cache_lens(const SeqLens& lens, int batch, int32_t* cache_lens, hipStream_t s);
+
 // ---- operands of the launches that follow, pulled towards the memory-side cache -------------
 // A latency-bound decode projection leaves CUs idle (64-128 workgroups on 256 CUs).  Extra workgroups of the same
 // launch use them to touch one word of every 128-byte line of what the NEXT launches will read (weights; the K/V

@@ -389,6 +389,17 @@ __global__ __launch_bounds__(64) void prefill_setup(SeqLens lens, int batch, int
     }
 }
 
+// The device-side cache lengths set from the host (resuming from a saved K/V cache): one small fill kernel, so the
+// call can sit in a stream or a captured graph like every other.
+__global__ __launch_bounds__(kMaxBatch) void set_cache_lens(SeqLens lens, int batch, int32_t* __restrict__ cache_lens) {
+    if ((int)threadIdx.x < batch) cache_lens[threadIdx.x] = lens.len[threadIdx.x];
+}
+
+hipError_t launch_set_cache_lens(const SeqLens& lens, int batch, int32_t* cache_lens, hipStream_t s) {
+    hipLaunchKernelGGL(set_cache_lens, dim3(1), dim3(kMaxBatch), 0, s, lens, batch, cache_lens);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefill_setup(const SeqLens& lens, int batch, int S, int width, int32_t* cache_lens,
                                 int32_t* cu_seqlens, int32_t* row_map, half_t* out, hipStream_t s, bool left_padded) {
     hipLaunchKernelGGL(prefill_setup, dim3(batch * S), dim3(64), 0, s, lens, batch, S, width, cache_lens,

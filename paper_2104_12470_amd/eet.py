@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
             "eet_layer_encode": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp]),
             "eet_decode_step": (i32, [vp, vp, vp, vp, vp]),
             "eet_cache_lens": (i32, [vp, i32p, vp]),
+            "eet_restore": (i32, [vp, i32p, i32, vp]),
+            "eet_stack_restore": (i32, [vp, i32p, i32, vp]),
             "eet_layer_destroy": (i32, [vp]),
             "eet_last_error": (C.c_char_p, []),
             "eet_stack_kv_cache_bytes": (sz, [cfgp, i32]),
@@ -138,7 +140,7 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
            "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
            "eet_op_embedding_decode", "eet_op_argmax", "eet_stack_prefill_left_padded", "eet_model_prefill_left_padded",
-           "eet_op_embedding_left_padded", "eet_stack_encode")
+           "eet_op_embedding_left_padded", "eet_stack_encode", "eet_restore", "eet_stack_restore")
 
 
 def _check(code: int) -> None:
@@ -208,6 +210,14 @@ def eet_cache_lens(layer: int, batch: int, stream=None):
     out = (C.c_int32 * batch)()
     _check(lib().eet_cache_lens(layer, out, _stream(stream)))
     return list(out)
+
+
+def eet_restore(layer: int, cache_lens: Sequence[int], stream=None) -> None:
+    _check(lib().eet_restore(layer, _lens_array(cache_lens), len(cache_lens), _stream(stream)))
+
+
+def eet_stack_restore(stack: int, cache_lens: Sequence[int], stream=None) -> None:
+    _check(lib().eet_stack_restore(stack, _lens_array(cache_lens), len(cache_lens), _stream(stream)))
 
 
 def eet_layer_destroy(layer: int) -> None:

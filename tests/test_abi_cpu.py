@@ -98,6 +98,13 @@ def test_prefill_and_decode_validate_before_any_launch(eet):
     assert L.eet_prefill(h, lens, 4, 10, None, P, P, None) == eet.EET_ERR_INVALID_ARG
     assert L.eet_prefill(h, lens, 4, 10, P + 2, P, P, None) == eet.EET_ERR_INVALID_ARG   # alignment
     assert L.eet_decode_step(h, P, P, P, None) == eet.EET_ERR_STATE                  # failures changed no state
+    assert L.eet_restore(h, None, 4, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_restore(h, lens, 5, None) == eet.EET_ERR_CAPACITY                   # batch > max_batch
+    assert L.eet_restore(h, (C.c_int32 * 4)(5, 2, 4, 81), 4, None) == eet.EET_ERR_INVALID_ARG   # 81 > max_seq 80
+    assert L.eet_restore(h, (C.c_int32 * 4)(5, 0, 4, 10), 4, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_restore(None, lens, 4, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_stack_restore(None, lens, 4, None) == eet.EET_ERR_INVALID_ARG
+    assert L.eet_decode_step(h, P, P, P, None) == eet.EET_ERR_STATE                  # ... still none
     assert L.eet_layer_destroy(h) == 0
 
 

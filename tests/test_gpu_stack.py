@@ -201,3 +201,56 @@ def test_stack_encode_equals_layer_chain_and_oracle(eet, name, n_layers):
     stack.close()
     for layer in layers:
         layer.close()
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_resume_from_a_saved_cache(eet, use_graph):
+    """The resumable state is the K/V cache and the lengths: a second stack (same configuration and weights) that is
+    handed a copy of the cache and eet_stack_restore(lengths) continues bit for bit where the first one was, and so does
+    a single layer with eet_restore."""
+    w = wl.WORKLOADS["small64"]
+    cfg, Ws, first = build(eet, w, 2, use_graph=use_graph)
+    _, _, second = build(eet, w, 2, use_graph=use_graph)
+    lens, x = wl.lengths(w), wl.prompt_embeddings(w)
+    B = w.batch
+    stream = torch.cuda.Stream()
+    steps = [dev(wl.decode_embeddings(w, k)) for k in range(6)]
+    with torch.cuda.stream(stream):
+        first.prefill(dev(x), lens, stream=stream)
+        for k in range(3):
+            first.decode_step(steps[k], stream=stream)
+    stream.synchronize()
+    saved_lens = first.cache_lens(B)
+    assert saved_lens == [int(v) + 3 for v in lens]
+    second.kv_cache.copy_(first.kv_cache)                               # the checkpoint: cache bytes + lengths
+    torch.cuda.synchronize()
+    with pytest.raises(eet.EETError) as e:
+        second.decode_step(steps[3])
+    assert e.value.code == eet.EET_ERR_STATE                            # nothing restored yet
+    eet.eet_stack_restore(second.handle, saved_lens, stream=stream)
+    with torch.cuda.stream(stream):
+        a = [first.decode_step(steps[k], stream=stream) for k in range(3, 6)]
+        b = [second.decode_step(steps[k], stream=stream) for k in range(3, 6)]
+    stream.synchronize()
+    for ya, yb in zip(a, b):
+        assert torch.equal(ya, yb)
+    assert torch.equal(first.kv_cache, second.kv_cache)
+    assert first.cache_lens(B) == second.cache_lens(B) == [int(v) + 6 for v in lens]
+    with pytest.raises(eet.EETError) as e:
+        eet.eet_stack_restore(second.handle, [w.max_seq + 1] + saved_lens[1:])
+    assert e.value.code == eet.EET_ERR_INVALID_ARG
+    first.close()
+    second.close()
+    # one layer
+    la = eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in Ws[0].items()}, cache_fill=SENTINEL)
+    lb = eet.DecoderLayer(cfg, {k: torch.from_numpy(v) for k, v in Ws[0].items()}, cache_fill=SENTINEL)
+    la.prefill(dev(x), lens)
+    la.decode_step(steps[0])
+    torch.cuda.synchronize()
+    lb.kv_cache.copy_(la.kv_cache)
+    eet.eet_restore(lb.handle, la.cache_lens(B))
+    ya, yb = la.decode_step(steps[1]), lb.decode_step(steps[1])
+    torch.cuda.synchronize()
+    assert torch.equal(ya, yb) and torch.equal(la.kv_cache, lb.kv_cache) and la.cache_lens(B) == lb.cache_lens(B)
+    la.close()
+    lb.close()
