@@ -254,3 +254,70 @@ def test_resume_from_a_saved_cache(eet, use_graph):
     assert torch.equal(ya, yb) and torch.equal(la.kv_cache, lb.kv_cache) and la.cache_lens(B) == lb.cache_lens(B)
     la.close()
     lb.close()
+
+
+class Guarded:
+    """A device buffer with a megabyte of 0xA5 on either side: nothing may ever write there."""
+    GUARD = 1 << 20
+
+    def __init__(self, nbytes):
+        self.nbytes = nbytes
+        self.raw = torch.full((nbytes + 2 * self.GUARD,), 0xA5, dtype=torch.uint8, device="cuda:0")
+        self.mid = self.raw[self.GUARD: self.GUARD + nbytes]
+        assert self.mid.data_ptr() % 256 == 0
+
+    def intact(self):
+        return bool((self.raw[: self.GUARD] == 0xA5).all()) and bool((self.raw[self.GUARD + self.nbytes:] == 0xA5).all())
+
+
+@pytest.mark.parametrize("name,n_layers", [("small64", 2), ("small128", 1), ("wide1280", 2)])
+def test_nothing_is_written_outside_the_sizes_the_library_asks_for(eet, name, n_layers):
+    """Workspace, K/V cache, model workspace, outputs and logits are handed over with guard regions around exactly the
+    number of bytes the size queries name; prefill, decode steps, the encoder pass and the model calls leave every
+    guard untouched (and still agree with a run on ordinary buffers)."""
+    w = wl.WORKLOADS[name]
+    V = 200
+    cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
+    Ws = [{k: dev(v) for k, v in wl.layer_weights(w, li, random_affine=True).items()} for li in range(n_layers)]
+    head = {k: dev(v) for k, v in wl.model_head(w, 256, w.max_seq).items()}           # 256 rows: the padded vocabulary
+    mcfg = eet.ModelConfig(V, 256, w.max_seq)
+    ws = Guarded(eet.eet_stack_workspace_bytes(cfg, n_layers))
+    kv = Guarded(eet.eet_stack_kv_cache_bytes(cfg, n_layers))
+    mws = Guarded(eet.eet_model_workspace_bytes(cfg, mcfg))
+    lens, x = wl.lengths(w), wl.prompt_embeddings(w)
+    B, S, H = x.shape
+    out = Guarded(2 * B * S * H)
+    dout = Guarded(2 * B * H)
+    logits = Guarded(2 * B * 256)
+    nxt = Guarded(4 * B)
+    stack = eet.eet_stack_create(cfg, Ws, ws.mid, use_graph=True)
+    model = eet.eet_model_create(stack, cfg, mcfg, head, mws.mid)
+    stream = torch.cuda.Stream()
+    ids = dev(np.where(wl.prompt_ids(w, V) < 0, 0, wl.prompt_ids(w, V)).astype(np.int32))
+    ref = eet.DecoderStack(cfg, [{k: v for k, v in W.items()} for W in Ws], use_graph=False)
+    with torch.cuda.stream(stream):
+        eet.eet_stack_prefill(stack, lens, B, S, dev(x), out.mid, kv.mid, stream)
+        for k in range(3):
+            eet.eet_stack_decode_step(stack, dev(wl.decode_embeddings(w, k)), dout.mid, kv.mid, stream)
+    stream.synchronize()
+    want = ref.prefill(dev(x), lens)
+    for k in range(3):
+        want_d = ref.decode_step(dev(wl.decode_embeddings(w, k)))
+    torch.cuda.synchronize()
+    assert torch.equal(out.mid.view(torch.float16).view(B, S, H), want)
+    assert torch.equal(dout.mid.view(torch.float16).view(B, H), want_d)
+    with torch.cuda.stream(stream):
+        eet.eet_stack_encode(stack, lens, B, S, dev(x), out.mid, kv.mid, stream)
+        eet.eet_stack_prefill_left_padded(stack, lens, B, S, dev(x), out.mid, kv.mid, stream)
+        eet.eet_model_prefill(model, lens, B, S, ids, logits.mid, nxt.mid, kv.mid, stream)
+        for k in range(3):
+            eet.eet_model_decode_step(model, nxt.mid.view(torch.int32), logits.mid, nxt.mid, kv.mid, stream)
+        eet.eet_model_prefill_left_padded(model, lens, B, S, ids, logits.mid, nxt.mid, kv.mid, stream)
+    stream.synchronize()
+    for g, what in ((ws, "workspace"), (kv, "K/V cache"), (mws, "model workspace"), (out, "prefill output"), (dout, "decode output"),
+                    (logits, "logits"), (nxt, "next ids")):
+        assert g.intact(), what
+    assert bool(torch.isfinite(logits.mid.view(torch.float16)).all())
+    eet.eet_model_destroy(model)
+    eet.eet_stack_destroy(stack)
+    ref.close()
