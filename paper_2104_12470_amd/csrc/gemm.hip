@@ -654,8 +654,32 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-template <int NW, int UPW, int TN, int EPI, bool LN>
+// A launch of the weight-streaming kernels with gridDim.y > 1 (template flag SL) cuts the rows into slices of 16: the
+// workgroups of row blockIdx.y see rows [16 y, 16 y + 16) as a problem of their own (a decode step of 17 to 64
+// sequences: the slices run side by side and all but the first find the weights in L2).  Used without row maps, fused
+// LayerNorm, prefetch workgroups or length bump.  A flag of its own because even this much scalar arithmetic shows in
+// the launch-bound decode of small layers (0.2 % of the 24-layer pass).
+template <int EPI>
+__device__ __forceinline__ void take_row_slice(GemmArgs& a) {
+    const int m0 = (int)blockIdx.y * 16;
+    const int rows = a.M - m0;
+    a.M = rows < 16 ? rows : 16;
+    a.x += (size_t)m0 * a.K;
+    if (EPI == EPI_QKV) {                       // decode: row m is sequence m, its token goes to slot lens[m] of its own cache
+        a.y += (size_t)m0 * a.hidden;
+        a.lens += m0;
+        const size_t seq = (size_t)a.heads * a.max_seq * a.d;
+        a.k_cache += (size_t)m0 * seq;
+        a.v_cache += (size_t)m0 * seq;
+    } else {
+        a.y += (size_t)m0 * a.N;
+        if (EPI == EPI_BIAS_RES) a.res += (size_t)m0 * a.N;
+    }
+}
+
+template <int NW, int UPW, int TN, int EPI, bool LN, bool SL>
 __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
+    if (SL) take_row_slice<EPI>(a);
     constexpr int NT = NW * 64;
     constexpr int K = 64 * NW * UPW, KV = K / 8, LDX = K + 8;   // LDX: 16-byte reads of 16 rows spread over all banks
     constexpr int SA = flat_stage_areas(NW, UPW);
@@ -833,8 +857,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 //   * the four partial tiles are summed through LDS once, at the end.
 constexpr int kStreamStagedUnits = 2;
 
-template <int NF, int EPI, int XH>
+template <int NF, int EPI, int XH, bool SL>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
+    if (SL) take_row_slice<EPI>(a);
     constexpr int UQ = 4;                                   // units per group
     constexpr int SU = kStreamStagedUnits;                  // units staged at a time
     constexpr int AREAS = SU * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
@@ -1019,15 +1044,20 @@ static void launch_flat_kernel(void (*kernel)(GemmArgs), const GemmArgs& a, dim3
     hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
 }
 
+template <int NW, int UPW, int TN, bool LN, bool SL>
+static void launch_flat_sl(const GemmArgs& a, Epilogue epi, int lds, hipStream_t s) {
+    const dim3 grid(a.N / TN + (a.pf.blocks > 0 ? a.pf.blocks : 0), SL ? (a.M + 15) / 16 : 1), block(NW * 64);
+    switch (epi) {
+        case EPI_BIAS: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS, LN, SL>, a, grid, block, lds, s); break;
+        case EPI_BIAS_GELU: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_GELU, LN, SL>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, LN, SL>, a, grid, block, lds, s); break;
+        case EPI_QKV: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_QKV, LN, SL>, a, grid, block, lds, s); break;
+    }
+}
 template <int NW, int UPW, int TN, bool LN>
 static void launch_flat_epi(const GemmArgs& a, Epilogue epi, int lds, hipStream_t s) {
-    const dim3 grid(a.N / TN + (a.pf.blocks > 0 ? a.pf.blocks : 0)), block(NW * 64);
-    switch (epi) {
-        case EPI_BIAS: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS, LN>, a, grid, block, lds, s); break;
-        case EPI_BIAS_GELU: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_GELU, LN>, a, grid, block, lds, s); break;
-        case EPI_BIAS_RES: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, LN>, a, grid, block, lds, s); break;
-        case EPI_QKV: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_QKV, LN>, a, grid, block, lds, s); break;
-    }
+    if (!LN && a.M > 16) launch_flat_sl<NW, UPW, TN, false, true>(a, epi, lds, s);     // never with the fused LayerNorm
+    else launch_flat_sl<NW, UPW, TN, LN, false>(a, epi, lds, s);
 }
 template <int NW, int TN, bool LN>
 static void launch_flat(const GemmArgs& a, int upw, Epilogue epi, int lds, hipStream_t s) {
@@ -1071,13 +1101,24 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 
 template <int NF, int XH>
 static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const dim3 grid(a.N / (16 * NF)), block(256);
     const int lds = 4 * kStreamStagedUnits * (NF + 1) * 16 * kFlatStageRow * 2;
+    const dim3 block(256);
+    if (a.M > 16) {                                           // rows in slices of 16 along gridDim.y
+        const dim3 grid(a.N / (16 * NF), (a.M + 15) / 16);
+        switch (epi) {
+            case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH, true>, a, grid, block, lds, s); break;
+            case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, true>, a, grid, block, lds, s); break;
+            case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, true>, a, grid, block, lds, s); break;
+            case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH, true>, a, grid, block, lds, s); break;
+        }
+        return;
+    }
+    const dim3 grid(a.N / (16 * NF));
     switch (epi) {
-        case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH>, a, grid, block, lds, s); break;
-        case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH>, a, grid, block, lds, s); break;
-        case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH>, a, grid, block, lds, s); break;
-        case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH>, a, grid, block, lds, s); break;
+        case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH, false>, a, grid, block, lds, s); break;
+        case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false>, a, grid, block, lds, s); break;
+        case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH, false>, a, grid, block, lds, s); break;
     }
 }
 // true when the streaming kernel took the problem: K a multiple of 256, whole column tiles, no LayerNorm
@@ -1096,32 +1137,14 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
     // A few more rows than the weight-streaming kernels take at once (a decode step of 17 to 64 sequences, a very short
-    // prompt): slices of 16 rows, one launch each.  The weights are read once from HBM and again out of L2 for the other
-    // slices, which beats a tile kernel that would run a handful of workgroups through the whole K loop (decode layer-step
-    // of the hidden-1024 layer at 32 sequences: 91 -> 51 us; hidden 4096: 416 -> 215 us; from 96 rows on the tile kernels win).
+    // prompt): the same kernels with the rows cut into slices of 16 along gridDim.y.  The weights come from HBM once and out
+    // of L2 for the other slices, which beats a tile kernel that would run a handful of workgroups through the whole K loop
+    // (decode layer-step of the hidden-1024 layer at 32 sequences: 91 us with the tile kernels, 38 us so; 64 sequences:
+    // 99 -> 49 us; hidden 4096 at 32: 416 -> 192 us).
     constexpr int kSliceRowsMax = 64;
-    if (a.M > 16 && a.M <= kSliceRowsMax && a.res_row_map == nullptr && a.out_row_map == nullptr && a.tok_row_map == nullptr &&
-        a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0) {
-        for (int m0 = 0; m0 < a.M; m0 += 16) {
-            GemmArgs t = a;
-            t.M = a.M - m0 < 16 ? a.M - m0 : 16;
-            t.x = a.x + (size_t)m0 * a.K;
-            if (epi == EPI_QKV) {                       // decode: row m is sequence m, its token goes to slot lens[m] of its own cache
-                t.y = a.y + (size_t)m0 * a.hidden;
-                t.lens = a.lens + m0;
-                const size_t seq = (size_t)a.heads * a.max_seq * a.d;
-                t.k_cache = a.k_cache + (size_t)m0 * seq;
-                t.v_cache = a.v_cache + (size_t)m0 * seq;
-            } else {
-                t.y = a.y + (size_t)m0 * a.N;
-                if (a.res != nullptr) t.res = a.res + (size_t)m0 * a.N;
-            }
-            const hipError_t e = launch_gemm(t, epi, s);
-            if (e != hipSuccess) return e;
-        }
-        return hipSuccess;
-    }
-    if (a.M <= 16) {
+    const bool sliced = a.M > 16 && a.M <= kSliceRowsMax && a.res_row_map == nullptr && a.out_row_map == nullptr &&
+                        a.tok_row_map == nullptr && a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0;
+    if (a.M <= 16 || sliced) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
         if (try_flat(a, epi, s)) return hipGetLastError();
         if (try_stream(a, epi, s)) return hipGetLastError();
