@@ -1139,10 +1139,10 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // A few more rows than the weight-streaming kernels take at once (a decode step of 17 to 64 sequences, a very short
     // prompt): the same kernels with the rows cut into slices of 16 along gridDim.y.  The weights come from HBM once and out
     // of L2 for the other slices, which beats a tile kernel that would run a handful of workgroups through the whole K loop
-    // (decode layer-step of the hidden-1024 layer at 32 sequences: 91 us with the tile kernels, 38 us so; 64 sequences:
-    // 99 -> 49 us; hidden 4096 at 32: 416 -> 192 us).
-    constexpr int kSliceRowsMax = 64;
-    const bool sliced = a.M > 16 && a.M <= kSliceRowsMax && a.res_row_map == nullptr && a.out_row_map == nullptr &&
+    // (decode layer-step of the hidden-1024 layer at 32 sequences: 91 us with the tile kernels, 38 us so; 128 sequences:
+    // 136 -> 73 us; hidden 4096 at 32: 416 -> 192 us, at 128 the tile kernels win there: 486 against 581 us).
+    const int slice_rows_max = (int64_t)a.N * a.K * 2 > ((int64_t)64 << 20) ? 96 : 128;
+    const bool sliced = a.M > 16 && a.M <= slice_rows_max && a.res_row_map == nullptr && a.out_row_map == nullptr &&
                         a.tok_row_map == nullptr && a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0;
     if (a.M <= 16 || sliced) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
