@@ -202,16 +202,19 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     tile_m = gm0 + in_grp - tile_n * gsz;
 }
 
-constexpr int kBK = 64;          // K depth of one LDS stage
-constexpr int kLdk = kBK + 8;    // padded LDS row (144 B): 16-byte fragment reads hit distinct banks
-
-template <int BM, int BN, int WGM, int WGN, int EPI>
+// BK is the K depth of one LDS stage.  The next stage is fetched into registers while the current one is multiplied, so
+// a K step cannot take less than one trip to memory: with few tiles on the chip that trip, not the arithmetic, sets the
+// time, and the small tiles take 128 columns a step where K allows it (half as many trips, twice the bytes in flight).
+template <int BM, int BN, int WGM, int WGN, int EPI, int BK>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles_m, int tiles_n) {
     constexpr int NT = WGM * WGN * 64;
+    constexpr int kBK = BK;
+    constexpr int kLdk = BK + 8;                      // padded LDS row: 16-byte fragment reads hit distinct banks
+    constexpr int CH = BK / 8;                        // 16-byte chunks of a staged row
     constexpr int WM = BM / WGM, WN = BN / WGN;       // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;         // 32x32 fragments per wave
-    constexpr int AV = BM * 8 / NT, WV = BN * 8 / NT; // 16-byte vectors each thread stages per K step
-    static_assert(AV >= 1 && WV >= 1 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    constexpr int AV = BM * CH / NT, WV = BN * CH / NT; // 16-byte vectors each thread stages per K step
+    static_assert(AV >= 1 && WV >= 1 && BM * CH % NT == 0 && BN * CH % NT == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
 
     __shared__ __attribute__((aligned(16))) half_t As[2][BM * kLdk];
     __shared__ __attribute__((aligned(16))) half_t Ws[2][BN * kLdk];
@@ -228,14 +231,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
     auto gload = [&](int kt) {
 #pragma unroll
         for (int v = 0; v < AV; ++v) {
-            const int idx = tid + v * NT, row = idx >> 3, ch = idx & 7;
+            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
             int gr = m0 + row;
             gr = gr < M ? gr : M - 1;                                  // rows past the tail: clamp, never stored
             ra[v] = *reinterpret_cast<const half8v*>(a.x + (int64_t)gr * K + kt * kBK + ch * 8);
         }
 #pragma unroll
         for (int v = 0; v < WV; ++v) {
-            const int idx = tid + v * NT, row = idx >> 3, ch = idx & 7;
+            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
             int gr = n0 + row;
             gr = gr < N ? gr : N - 1;
             rw[v] = *reinterpret_cast<const half8v*>(a.w + (int64_t)gr * K + kt * kBK + ch * 8);
@@ -244,12 +247,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
     auto sstore = [&](int st) {
 #pragma unroll
         for (int v = 0; v < AV; ++v) {
-            const int idx = tid + v * NT, row = idx >> 3, ch = idx & 7;
+            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
             *reinterpret_cast<half8v*>(&As[st][row * kLdk + ch * 8]) = ra[v];
         }
 #pragma unroll
         for (int v = 0; v < WV; ++v) {
-            const int idx = tid + v * NT, row = idx >> 3, ch = idx & 7;
+            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
             *reinterpret_cast<half8v*>(&Ws[st][row * kLdk + ch * 8]) = rw[v];
         }
     };
@@ -989,15 +992,15 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int BK = 64>
 static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS, BK>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_GELU, BK>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_RES, BK>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_QKV, BK>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1125,7 +1128,7 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
     if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
-    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU                       // 32 columns per workgroup once that still leaves four workgroups per CU
+    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU
     if (a.M <= 8) {
         if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
     } else {
@@ -1134,16 +1137,36 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     return true;
 }
 
+// Row slices of the weight-streaming kernels against the tile kernels for a problem of 17 to 512 rows, from two cost
+// estimates in microseconds whose constants are measured (projections of 2 to 400 MB, 17 to 1024 rows).  Slices: the
+// first reads the weights at about 4 TB/s, every further one reads them again out of L2 or the memory-side cache at about
+// 7.5 TB/s.  Tiles: the time does not depend on the row count while all workgroups are resident at once; it is the larger
+// of the weights at about 3 TB/s and of the K loop, every step of which costs one trip to memory (0.5 us for 64 columns,
+// 0.85 us for 128; longer in proportion once the tiles no longer fit the chip at once).  Wide outputs with a short K go
+// to the tiles from about 33 rows on, narrow outputs with a long K (the output and second feed-forward projections)
+// stay with the slices for up to a few hundred rows.
+static bool slices_beat_tiles(const GemmArgs& a) {
+    const int slices = (a.M + 15) / 16;
+    if (slices > 32) return false;
+    const double w_mb = (double)a.N * a.K * 2e-6;
+    const bool streams = a.K % 256 == 0 && a.N % 32 == 0;        // else the slower general kernel: 2.5 and 4.5 TB/s
+    const double again = w_mb / (streams ? 7.5 : 4.5);
+    const double est_slices = 2.0 + w_mb / (streams ? 4.0 : 2.5) + (slices - 1) * (again > 0.1 ? again : 0.1);
+    const bool deep = a.K % 128 == 0;
+    const double wg64 = (double)((a.M + 63) / 64) * ((a.N + 63) / 64);
+    const double k_loop = (deep ? (a.K / 128) * 0.85 : (a.K / 64) * 0.5) * (wg64 > 512.0 ? wg64 / 512.0 : 1.0);
+    const double est_tiles = 3.0 + (w_mb / 3.0 > k_loop ? w_mb / 3.0 : k_loop);
+    return est_slices < est_tiles;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
-    // A few more rows than the weight-streaming kernels take at once (a decode step of 17 to 64 sequences, a very short
-    // prompt): the same kernels with the rows cut into slices of 16 along gridDim.y.  The weights come from HBM once and out
-    // of L2 for the other slices, which beats a tile kernel that would run a handful of workgroups through the whole K loop
-    // (decode layer-step of the hidden-1024 layer at 32 sequences: 91 us with the tile kernels, 38 us so; 128 sequences:
-    // 136 -> 73 us; hidden 4096 at 32: 416 -> 192 us, at 128 the tile kernels win there: 486 against 581 us).
-    const int slice_rows_max = (int64_t)a.N * a.K * 2 > ((int64_t)64 << 20) ? 96 : 128;
-    const bool sliced = a.M > 16 && a.M <= slice_rows_max && a.res_row_map == nullptr && a.out_row_map == nullptr &&
-                        a.tok_row_map == nullptr && a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0;
+    // A few more rows than the weight-streaming kernels take at once (a decode step of more than 16 sequences, a very
+    // short prompt): the same kernels with the rows cut into slices of 16 along gridDim.y, where that beats a tile kernel
+    // that would run a handful of workgroups through the whole K loop (decode layer-step of the hidden-1024 layer at 32
+    // sequences: 91 us with the tile kernels, 38 us so; 128 sequences: 136 -> 73 us).
+    const bool sliced = a.M > 16 && a.res_row_map == nullptr && a.out_row_map == nullptr && a.tok_row_map == nullptr &&
+                        a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0 && slices_beat_tiles(a);
     if (a.M <= 16 || sliced) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
         if (try_flat(a, epi, s)) return hipGetLastError();
@@ -1159,11 +1182,17 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else {
             // few tiles (short prompts, narrow layers): smaller tiles put more workgroups on the chip; the K loop of
             // each is a chain of dependent steps, so what counts there is how many run side by side
-            // (160 x 768 x 768: 12.0 -> 7.9 us; 1500 x 1024 x 1024: 15.7 -> 11.5 us; 300 x 4096 x 1024: 15.2 -> 11.5 us)
+            // (160 x 768 x 768: 12.0 -> 7.9 us; 1500 x 1024 x 1024: 15.7 -> 11.5 us; 300 x 4096 x 1024: 15.2 -> 11.5 us).
+            // K steps of 128 while every workgroup is resident with the larger LDS stages (two 64x64 tiles or one
+            // 128x64 tile per CU): 128 x 4096 x 16384 61 -> 45 us, 256 x 16384 x 4096 203 -> 115 us (rows x K x N).
             const int tm = (a.M + 127) / 128;
-            if (tm * ((a.N + 63) / 64) < 64) launch_mfma_cfg<64, 64, 2, 1>(a, epi, s);
-            else if (tm * ((a.N + 127) / 128) < 256) launch_mfma_cfg<128, 64, 4, 1>(a, epi, s);
-            else launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
+            const bool deep = a.K % 128 == 0;
+            const int wg64 = ((a.M + 63) / 64) * ((a.N + 63) / 64), wg128 = tm * ((a.N + 63) / 64);
+            if (wg128 < 192) {
+                if (deep && wg64 <= 512) launch_mfma_cfg<64, 64, 2, 1, 128>(a, epi, s); else launch_mfma_cfg<64, 64, 2, 1>(a, epi, s);
+            } else if (tm * ((a.N + 127) / 128) < 256) {
+                if (deep && wg128 <= 256) launch_mfma_cfg<128, 64, 4, 1, 128>(a, epi, s); else launch_mfma_cfg<128, 64, 4, 1>(a, epi, s);
+            } else launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
         }
     }
     return hipGetLastError();

@@ -104,9 +104,8 @@ def test_batches_above_16_up_to_the_largest(eet, B):
 
 
 def test_decode_of_100_sequences_on_a_layer_with_large_projections(eet):
-    """Hidden 4096 (QKV and feed-forward matrices of 100-134 MB) with 100 sequences: the decode projections of more than
-    64 MB take the tile kernels (the new token's K/V rows go to slot n_b from their epilogue), the attention output
-    projection (32 MB) the row slices of the weight-streaming kernel."""
+    """Hidden 4096 (QKV and feed-forward matrices of 100-134 MB) with 100 sequences: the decode projections take the tile
+    kernels with K steps of 128 (the new token's K/V rows go to slot n_b from their epilogue)."""
     w = wl.Workload("b100h4096", 23, 4096, 32, 16384, 1, 100, 16, 1, 16, 2, 24)
     full_parity(eet, w, random_affine=False)
 

@@ -193,7 +193,7 @@ def test_softmax_maskfree_left_padded(eet, B, nh, S, lens):
         np.testing.assert_allclose(got[b, :, pad:].astype(np.float64).sum(-1), 1.0, atol=4e-3)
 
 
-@pytest.mark.parametrize("M", [1, 5, 16, 17, 130, 300])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 130, 200, 300, 513])
 @pytest.mark.parametrize("K,N", [(64, 64), (256, 192), (1024, 3072), (4096, 1024), (1088, 1216), (1024, 2048), (4608, 3072), (512, 32832), (1280, 1280)])
 def test_linear(eet, M, K, N):
     x = wl.normal(300 + M, K, (M, K))
