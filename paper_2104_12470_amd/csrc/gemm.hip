@@ -300,7 +300,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
 // --------------------------------------------------------------------------------------------
 // MFMA tile kernel with direct global->LDS loads
 // --------------------------------------------------------------------------------------------
-// 256x256 tile, WGM x WGN waves, K steps of 64 through two LDS stages filled by
+// BM x BN tile (256x256 for the large problems, 128x128 and 128x64 for fewer tiles), WGM x WGN waves with wave tiles
+// of 64 columns, K steps of 64 through two LDS stages filled by
 // global_load_lds_dwordx4 (no staging registers, no ds_write): the loads of K step kt+1 are issued
 // at the start of step kt.  An LDS row is the 128 bytes of one operand row, and a wave-level load
 // covers 8 rows x 128 bytes, i.e. whole cache lines.  Instead of padding, the eight 16-byte chunks
@@ -321,8 +322,10 @@ __device__ __forceinline__ void load_lds_16B(const half_t* gptr, half_t* lds) {
 
 template <int N>
 __device__ __forceinline__ void wait_lgkm() {
-    static_assert(N == 0 || N == 6 || N == 8, "add the count");
+    static_assert(N == 0 || N == 3 || N == 4 || N == 6 || N == 8, "add the count");
     if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)");
+    if (N == 3) asm volatile("s_waitcnt lgkmcnt(3)");
+    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)");
     if (N == 6) asm volatile("s_waitcnt lgkmcnt(6)");
     if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)");
 }
@@ -334,12 +337,13 @@ __device__ __forceinline__ void wait_vm() {
     if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
 }
 
-template <int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
-    constexpr int BM = 256, BN = 256, NW = WGM * WGN, BK = 64;
+    constexpr int NW = WGM * WGN, BK = 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
-    constexpr int LR = 256 / NW;          // rows of each operand tile a wave loads per K step
-    constexpr int LI = LR / 8;            // wave-level load instructions per operand per K step
+    constexpr int LRA = BM / NW, LRW = BN / NW;   // rows of each operand tile a wave loads per K step
+    constexpr int LIA = LRA / 8, LIW = LRW / 8;   // wave-level load instructions per operand per K step
+    static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && FM >= 1 && FM <= 4 && FN >= 1 && FN <= 4, "tile shape");
     __shared__ __attribute__((aligned(1024))) half_t As[2][BM * BK];
     __shared__ __attribute__((aligned(1024))) half_t Ws[2][BN * BK];
 
@@ -351,16 +355,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
     const int M = a.M, N = a.N, K = a.K;
     const int nk = K / BK;
 
-    const half_t* pa[LI];
-    const half_t* pw[LI];
+    const half_t* pa[LIA];
+    const half_t* pw[LIW];
 #pragma unroll
-    for (int v = 0; v < LI; ++v) {
-        const int row = wave * LR + v * 8 + (lane >> 3);
+    for (int v = 0; v < LIA; ++v) {
+        const int row = wave * LRA + v * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         int gr = m0 + row;
         gr = gr < M ? gr : M - 1;
         pa[v] = a.x + (int64_t)gr * K + c * 8;
-        gr = n0 + row;
+    }
+#pragma unroll
+    for (int v = 0; v < LIW; ++v) {
+        const int row = wave * LRW + v * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        int gr = n0 + row;
         gr = gr < N ? gr : N - 1;
         pw[v] = a.w + (int64_t)gr * K + c * 8;
     }
@@ -382,10 +391,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 
 #define EET_DLOAD(T, ST)                                                                                 \
     do {                                                                                                 \
-        _Pragma("unroll") for (int v = 0; v < LI; ++v) {                                                 \
-            load_lds_16B(pa[v] + (int64_t)(T) * BK, &As[ST][(wave * LR + v * 8) * BK]);                  \
-            load_lds_16B(pw[v] + (int64_t)(T) * BK, &Ws[ST][(wave * LR + v * 8) * BK]);                  \
-        }                                                                                                \
+        _Pragma("unroll") for (int v = 0; v < LIA; ++v)                                                  \
+            load_lds_16B(pa[v] + (int64_t)(T) * BK, &As[ST][(wave * LRA + v * 8) * BK]);                 \
+        _Pragma("unroll") for (int v = 0; v < LIW; ++v)                                                  \
+            load_lds_16B(pw[v] + (int64_t)(T) * BK, &Ws[ST][(wave * LRW + v * 8) * BK]);                 \
     } while (0)
 #define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
 #define EET_DFRAG(FS, ST, KS)                                                                            \
@@ -447,8 +456,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 
     static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
-    epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * 16384,
-                                  m0 + wm0, n0 + wn0, lane);
+    constexpr int EB = FM * 32 * 128;                      // bytes of a wave's turn-around area
+    if constexpr (NW * EB <= (int)sizeof(As)) {
+        epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
+    } else {
+        static_assert(NW == 8 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
+        epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
+                                      m0 + wm0, n0 + wn0, lane);
+    }
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1004,15 +1019,15 @@ static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
 }
 
-template <int WGM, int WGN>
+template <int WGM, int WGN, int BM = 256, int BN = 256>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
+    const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1191,8 +1206,10 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             if (wg128 < 192) {
                 if (deep && wg64 <= 512) launch_mfma_cfg<64, 64, 2, 1, 128>(a, epi, s); else launch_mfma_cfg<64, 64, 2, 1>(a, epi, s);
             } else if (tm * ((a.N + 127) / 128) < 256) {
-                if (deep && wg128 <= 256) launch_mfma_cfg<128, 64, 4, 1, 128>(a, epi, s); else launch_mfma_cfg<128, 64, 4, 1>(a, epi, s);
-            } else launch_mfma_cfg<128, 128, 2, 2>(a, epi, s);
+                // resident at once: K steps of 128 through registers; more tiles than that: the direct-to-LDS loads
+                if (deep && wg128 <= 256) launch_mfma_cfg<128, 64, 4, 1, 128>(a, epi, s);
+                else launch_dma64_cfg<4, 1, 128, 64>(a, epi, s);
+            } else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);
         }
     }
     return hipGetLastError();
