@@ -301,9 +301,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles
 // MFMA tile kernel with direct global->LDS loads
 // --------------------------------------------------------------------------------------------
 // BM x BN tile (256x256 for the large problems, 128x128 and 128x64 for fewer tiles), WGM x WGN waves with wave tiles
-// of 64 columns, K steps of 64 through two LDS stages filled by
-// global_load_lds_dwordx4 (no staging registers, no ds_write): the loads of K step kt+1 are issued
-// at the start of step kt.  An LDS row is the 128 bytes of one operand row, and a wave-level load
+// of 64 columns, K steps of 64 through NS LDS stages filled by
+// global_load_lds_dwordx4 (no staging registers, no ds_write): with two stages the loads of K step kt+1 are issued
+// at the start of step kt, with three (the small tiles, where few workgroups share a CU and nothing else hides the
+// trip to memory) those of step kt+2.  An LDS row is the 128 bytes of one operand row, and a wave-level load
 // covers 8 rows x 128 bytes, i.e. whole cache lines.  Instead of padding, the eight 16-byte chunks
 // of a row are XOR-permuted by (row/2)%8 -- applied on the global address of each lane when loading
 // and on the LDS address when reading fragments -- which spreads consecutive rows over all banks.
@@ -331,21 +332,23 @@ __device__ __forceinline__ void wait_lgkm() {
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
-    static_assert(N == 0 || N == 8 || N == 16, "add the count");
+    static_assert(N == 0 || N == 6 || N == 8 || N == 16, "add the count");
     if (N == 0) asm volatile("s_waitcnt vmcnt(0)");
+    if (N == 6) asm volatile("s_waitcnt vmcnt(6)");
     if (N == 8) asm volatile("s_waitcnt vmcnt(8)");
     if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
     constexpr int NW = WGM * WGN, BK = 64;
+    static_assert(NS == 2 || NS == 3, "LDS stages");
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int LRA = BM / NW, LRW = BN / NW;   // rows of each operand tile a wave loads per K step
     constexpr int LIA = LRA / 8, LIW = LRW / 8;   // wave-level load instructions per operand per K step
     static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && FM >= 1 && FM <= 4 && FN >= 1 && FN <= 4, "tile shape");
-    __shared__ __attribute__((aligned(1024))) half_t As[2][BM * BK];
-    __shared__ __attribute__((aligned(1024))) half_t Ws[2][BN * BK];
+    __shared__ __attribute__((aligned(1024))) half_t As[NS][BM * BK];
+    __shared__ __attribute__((aligned(1024))) half_t Ws[NS][BN * BK];
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -425,27 +428,62 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
         __builtin_amdgcn_sched_barrier(0);                                                               \
     } while (0)
 
-    EET_DLOAD(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)");
-    __syncthreads();
-    EET_DFRAG(0, 0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int st = kt & 1;
-        if (kt + 1 < nk) EET_DLOAD(kt + 1, st ^ 1);   // stage st^1 was released by the barrier of the previous step
-        EET_DFRAG(1, st, 1);
-        EET_DWAIT(0, FM + FN);
-        EET_DMMA(0);
-        EET_DFRAG(0, st, 2);
-        EET_DWAIT(1, FM + FN);
-        EET_DMMA(1);
-        EET_DFRAG(1, st, 3);
-        EET_DWAIT(0, FM + FN);
-        EET_DMMA(0);
-        EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
-        asm volatile("s_waitcnt vmcnt(0)");   // this wave's part of tile kt+1 has landed
-        __builtin_amdgcn_s_barrier();         // ... and everybody else's
-        EET_DFRAG(0, st ^ 1, 0);              // (past the last tile: stale data, never used)
-        EET_DMMA(1);
+    if constexpr (NS == 2) {
+        EET_DLOAD(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)");
+        __syncthreads();
+        EET_DFRAG(0, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st = kt & 1;
+            if (kt + 1 < nk) EET_DLOAD(kt + 1, st ^ 1);   // stage st^1 was released by the barrier of the previous step
+            EET_DFRAG(1, st, 1);
+            EET_DWAIT(0, FM + FN);
+            EET_DMMA(0);
+            EET_DFRAG(0, st, 2);
+            EET_DWAIT(1, FM + FN);
+            EET_DMMA(1);
+            EET_DFRAG(1, st, 3);
+            EET_DWAIT(0, FM + FN);
+            EET_DMMA(0);
+            EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
+            asm volatile("s_waitcnt vmcnt(0)");   // this wave's part of tile kt+1 has landed
+            __builtin_amdgcn_s_barrier();         // ... and everybody else's
+            EET_DFRAG(0, st ^ 1, 0);              // (past the last tile: stale data, never used)
+            EET_DMMA(1);
+        }
+    } else {
+        // ring of three stages: tile kt+2 is requested at the start of step kt, into the stage that step kt-1 read and
+        // the barrier at its end released; at the end of step kt only the newest request may still be in flight
+        EET_DLOAD(0, 0);
+        if (nk > 1) {
+            EET_DLOAD(1, 1);
+            wait_vm<LIA + LIW>();
+        } else {
+            wait_vm<0>();
+        }
+        __builtin_amdgcn_s_barrier();             // nothing but the loads above has touched LDS so far
+        EET_DFRAG(0, 0, 0);
+        int st = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
+            const bool more = kt + 2 < nk;
+            if (more) EET_DLOAD(kt + 2, st2);
+            EET_DFRAG(1, st, 1);
+            EET_DWAIT(0, FM + FN);
+            EET_DMMA(0);
+            EET_DFRAG(0, st, 2);
+            EET_DWAIT(1, FM + FN);
+            EET_DMMA(1);
+            EET_DFRAG(1, st, 3);
+            EET_DWAIT(0, FM + FN);
+            EET_DMMA(0);
+            EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
+            if (more) wait_vm<LIA + LIW>(); else wait_vm<0>();   // this wave's part of tile kt+1 has landed
+            __builtin_amdgcn_s_barrier();         // ... and everybody else's
+            EET_DFRAG(0, st1, 0);                 // (past the last tile: stale data, never used)
+            EET_DMMA(1);
+            st = st1;
+        }
     }
     EET_DWAIT(0, 0);
 #undef EET_DLOAD
@@ -1019,15 +1057,15 @@ static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
 }
 
-template <int WGM, int WGN, int BM = 256, int BN = 256>
+template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1208,8 +1246,9 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             } else if (tm * ((a.N + 127) / 128) < 256) {
                 // resident at once: K steps of 128 through registers; more tiles than that: the direct-to-LDS loads
                 if (deep && wg128 <= 256) launch_mfma_cfg<128, 64, 4, 1, 128>(a, epi, s);
-                else launch_dma64_cfg<4, 1, 128, 64>(a, epi, s);
-            } else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);
+                else launch_dma64_cfg<4, 1, 128, 64, 3>(a, epi, s);
+            } else if (tm * ((a.N + 127) / 128) <= 256) launch_dma64_cfg<2, 2, 128, 128, 3>(a, epi, s);   // one per CU
+            else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);                                              // two per CU
         }
     }
     return hipGetLastError();
