@@ -2,13 +2,13 @@
 // add-bias+GELU, add-bias+residual with optional row scatter back to the padded layout).
 //
 // The paper leaves these to library GEMM calls followed by separate bias/activation kernels
-// (Section 3.2: "kernels are not always fused, especially ... GEMM calls").  Here the epilogue
+// (Section 3.2 notes that fusion stops at the GEMM calls).  Here the epilogue
 // runs on the accumulators, so the intermediate never visits HBM.
 //
 // Kernels:
-//   gemm_mfma_dma64  prefill (M = valid tokens of the batch, packed), large problems: 256x256 tiles,
-//                    direct global->LDS loads, v_mfma_f32_32x32x16_f16; bound by the matrix cores.
-//   gemm_mfma        prefill, small problems: 128x128 register-staged tiles (128x64 and 64x64 when there are few).
+//   gemm_mfma_dma64  prefill (M = valid tokens of the batch, packed) and decode steps of many sequences: 256x256 tiles
+//                    for the large problems, 128x128, 128x64 and 64x64 when there are few; direct global->LDS loads,
+//                    v_mfma_f32_32x32x16_f16; bound by the matrix cores.
 //   gemm_flat        decode (M <= 16 rows), small layers: one memory round trip, few instructions.
 //   gemm_stream      decode, large layers: every weight is read from HBM exactly once per step, so
 //                    the kernel is a weight stream; v_mfma_f32_16x16x32_f16 does the 16-row contraction.
@@ -200,101 +200,6 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     const int gsz = tiles_m - gm0 < GM ? tiles_m - gm0 : GM;    // last group may be shorter
     tile_n = in_grp / gsz;
     tile_m = gm0 + in_grp - tile_n * gsz;
-}
-
-// BK is the K depth of one LDS stage.  The next stage is fetched into registers while the current one is multiplied, so
-// a K step cannot take less than one trip to memory: with few tiles on the chip that trip, not the arithmetic, sets the
-// time, and the small tiles take 128 columns a step where K allows it (half as many trips, twice the bytes in flight).
-template <int BM, int BN, int WGM, int WGN, int EPI, int BK>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma(GemmArgs a, int tiles_m, int tiles_n) {
-    constexpr int NT = WGM * WGN * 64;
-    constexpr int kBK = BK;
-    constexpr int kLdk = BK + 8;                      // padded LDS row: 16-byte fragment reads hit distinct banks
-    constexpr int CH = BK / 8;                        // 16-byte chunks of a staged row
-    constexpr int WM = BM / WGM, WN = BN / WGN;       // wave tile
-    constexpr int FM = WM / 32, FN = WN / 32;         // 32x32 fragments per wave
-    constexpr int AV = BM * CH / NT, WV = BN * CH / NT; // 16-byte vectors each thread stages per K step
-    static_assert(AV >= 1 && WV >= 1 && BM * CH % NT == 0 && BN * CH % NT == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
-
-    __shared__ __attribute__((aligned(16))) half_t As[2][BM * kLdk];
-    __shared__ __attribute__((aligned(16))) half_t Ws[2][BN * kLdk];
-
-    int tile_m, tile_n;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-    const int M = a.M, N = a.N, K = a.K;
-
-    half8v ra[AV], rw[WV];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int v = 0; v < AV; ++v) {
-            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
-            int gr = m0 + row;
-            gr = gr < M ? gr : M - 1;                                  // rows past the tail: clamp, never stored
-            ra[v] = *reinterpret_cast<const half8v*>(a.x + (int64_t)gr * K + kt * kBK + ch * 8);
-        }
-#pragma unroll
-        for (int v = 0; v < WV; ++v) {
-            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
-            int gr = n0 + row;
-            gr = gr < N ? gr : N - 1;
-            rw[v] = *reinterpret_cast<const half8v*>(a.w + (int64_t)gr * K + kt * kBK + ch * 8);
-        }
-    };
-    auto sstore = [&](int st) {
-#pragma unroll
-        for (int v = 0; v < AV; ++v) {
-            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
-            *reinterpret_cast<half8v*>(&As[st][row * kLdk + ch * 8]) = ra[v];
-        }
-#pragma unroll
-        for (int v = 0; v < WV; ++v) {
-            const int idx = tid + v * NT, row = idx / CH, ch = idx % CH;
-            *reinterpret_cast<half8v*>(&Ws[st][row * kLdk + ch * 8]) = rw[v];
-        }
-    };
-
-    float16v acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int nk = K / kBK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    const int frow = lane & 31, fk = (lane >> 5) * 8;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int st = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
-#pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            half8v fa[FM], fw[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                fa[i] = *reinterpret_cast<const half8v*>(&As[st][(wm0 + i * 32 + frow) * kLdk + ks * 16 + fk]);
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                fw[j] = *reinterpret_cast<const half8v*>(&Ws[st][(wn0 + j * 32 + frow) * kLdk + ks * 16 + fk]);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[j], fa[i], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) sstore(st ^ 1);
-        __syncthreads();
-    }
-
-    // the loop ended on a barrier: every wave is done with the operand stages
-    static_assert(WN == 64 && FM * 32 * 128 * WGM * WGN <= (int)sizeof(As), "LDS epilogue: 64-column wave tiles staged in As");
-    epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * (FM * 32 * 128), m0 + wm0, n0 + wn0, lane);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1045,18 +950,6 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int BK = 64>
-static void launch_mfma_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-    const dim3 grid(tm * tn), block(WGM * WGN * 64);
-    switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS, BK>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_GELU, BK>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_BIAS_RES, BK>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma<BM, BN, WGM, WGN, EPI_QKV, BK>), grid, block, 0, s, a, tm, tn); break;
-    }
-}
-
 template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
@@ -1194,8 +1087,8 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 // estimates in microseconds whose constants are measured (projections of 2 to 400 MB, 17 to 1024 rows).  Slices: the
 // first reads the weights at about 4 TB/s, every further one reads them again out of L2 or the memory-side cache at about
 // 7.5 TB/s.  Tiles: the time does not depend on the row count while all workgroups are resident at once; it is the larger
-// of the weights at about 3 TB/s and of the K loop, every step of which costs one trip to memory (0.5 us for 64 columns,
-// 0.85 us for 128; longer in proportion once the tiles no longer fit the chip at once).  Wide outputs with a short K go
+// of the weights at about 3 TB/s and of the K loop (0.33 us per step of 64 columns; longer in proportion once the tiles
+// no longer fit the chip at once).  Wide outputs with a short K go
 // to the tiles from about 33 rows on, narrow outputs with a long K (the output and second feed-forward projections)
 // stay with the slices for up to a few hundred rows.
 static bool slices_beat_tiles(const GemmArgs& a) {
@@ -1205,9 +1098,8 @@ static bool slices_beat_tiles(const GemmArgs& a) {
     const bool streams = a.K % 256 == 0 && a.N % 32 == 0;        // else the slower general kernel: 2.5 and 4.5 TB/s
     const double again = w_mb / (streams ? 7.5 : 4.5);
     const double est_slices = 2.0 + w_mb / (streams ? 4.0 : 2.5) + (slices - 1) * (again > 0.1 ? again : 0.1);
-    const bool deep = a.K % 128 == 0;
     const double wg64 = (double)((a.M + 63) / 64) * ((a.N + 63) / 64);
-    const double k_loop = (deep ? (a.K / 128) * 0.85 : (a.K / 64) * 0.5) * (wg64 > 512.0 ? wg64 / 512.0 : 1.0);
+    const double k_loop = (a.K / 64) * 0.33 * (wg64 > 768.0 ? wg64 / 768.0 : 1.0);
     const double est_tiles = 3.0 + (w_mb / 3.0 > k_loop ? w_mb / 3.0 : k_loop);
     return est_slices < est_tiles;
 }
@@ -1228,27 +1120,22 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else if (a.N >= 32 * 1024) launch_skinny_cfg<2>(a, epi, s);
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
-        // 256x256 direct-to-LDS tiles once they cover about 60 % of the CUs, 128x128 register-staged tiles below that
+        // 256x256 tiles once they cover about 60 % of the CUs, smaller tiles below that
         // (measured: 156 tiles 592 vs 514 TFLOP/s in favour of the large tiles, 112 tiles 563 vs 673 against them)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
         if (big_tiles >= 150) launch_dma64_cfg<2, 4>(a, epi, s);
         else {
             // few tiles (short prompts, narrow layers): smaller tiles put more workgroups on the chip; the K loop of
-            // each is a chain of dependent steps, so what counts there is how many run side by side
-            // (160 x 768 x 768: 12.0 -> 7.9 us; 1500 x 1024 x 1024: 15.7 -> 11.5 us; 300 x 4096 x 1024: 15.2 -> 11.5 us).
-            // K steps of 128 while every workgroup is resident with the larger LDS stages (two 64x64 tiles or one
-            // 128x64 tile per CU): 128 x 4096 x 16384 61 -> 45 us, 256 x 16384 x 4096 203 -> 115 us (rows x K x N).
+            // each is a chain of dependent steps, so what counts there is how many run side by side and how far ahead
+            // the loads run: three LDS stages for the tiles that share a CU with few others
+            // (rows x K x N, against two-stage register-staged tiles of the same sizes: 256 x 4096 x 4096 29.9 -> 23.8 us,
+            // 2048 x 4096 x 1024 37.6 -> 28.5 us, 768 x 8192 x 2048 69.5 -> 51.9 us, 128 x 1600 x 6400 16.3 -> 11.8 us)
             const int tm = (a.M + 127) / 128;
-            const bool deep = a.K % 128 == 0;
-            const int wg64 = ((a.M + 63) / 64) * ((a.N + 63) / 64), wg128 = tm * ((a.N + 63) / 64);
-            if (wg128 < 192) {
-                if (deep && wg64 <= 512) launch_mfma_cfg<64, 64, 2, 1, 128>(a, epi, s); else launch_mfma_cfg<64, 64, 2, 1>(a, epi, s);
-            } else if (tm * ((a.N + 127) / 128) < 256) {
-                // resident at once: K steps of 128 through registers; more tiles than that: the direct-to-LDS loads
-                if (deep && wg128 <= 256) launch_mfma_cfg<128, 64, 4, 1, 128>(a, epi, s);
-                else launch_dma64_cfg<4, 1, 128, 64, 3>(a, epi, s);
-            } else if (tm * ((a.N + 127) / 128) <= 256) launch_dma64_cfg<2, 2, 128, 128, 3>(a, epi, s);   // one per CU
-            else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);                                              // two per CU
+            const int tiles128 = tm * ((a.N + 127) / 128);
+            if (tm * ((a.N + 63) / 64) < 128) launch_dma64_cfg<2, 1, 64, 64, 3>(a, epi, s);
+            else if (tiles128 < 256) launch_dma64_cfg<4, 1, 128, 64, 3>(a, epi, s);
+            else if (tiles128 == 256) launch_dma64_cfg<2, 2, 128, 128, 3>(a, epi, s);      // one per CU
+            else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);                               // two per CU
         }
     }
     return hipGetLastError();
