@@ -158,9 +158,11 @@ int eet_layer_destroy(eet_layer_t* layer) {
     } while (0)
 
 // Enqueue the kernels of one layer's prefill (arguments already validated).
+// index_setup = false: a layer of a stack whose workspace already holds this prefill's lengths, prefix sums and row map
+// and whose output buffer already has its pad rows zeroed (an earlier layer of the same call did both).
 static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int padded_len, int64_t T, int max_len,
                            const void* tokens, void* out, void* kv_cache, hipStream_t s, bool causal = true,
-                           bool left_padded = false) {
+                           bool left_padded = false, bool index_setup = true) {
     const eet_layer_config& c = L->cfg;
     const int H = c.hidden, F = c.ffn;
     int32_t* d_lens = reinterpret_cast<int32_t*>(L->ws + L->lay.lens);
@@ -177,8 +179,9 @@ static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int pad
     // a1: padding offsets -> integers on the device; pad rows of `out` zeroed
     // (left_padded: the packed->padded row map starts each sequence at row S - L_b; every kernel below works on
     // the packed rows and never sees the difference, except the cache scatter, which needs the position)
-    EET_LAUNCH(launch_prefill_setup(lens, batch, padded_len, H, d_lens, d_cu, d_map, static_cast<half_t*>(out), s,
-                                    left_padded), "prefill_setup");
+    if (index_setup)
+        EET_LAUNCH(launch_prefill_setup(lens, batch, padded_len, H, d_lens, d_cu, d_map, static_cast<half_t*>(out), s,
+                                        left_padded), "prefill_setup");
     // a2: LN1 over valid rows only (gathered into the packed layout)
     EET_LAUNCH(launch_layernorm(x, d_map, (const half_t*)L->w.ln1_g, (const half_t*)L->w.ln1_b, bufA, T, H, c.ln_eps,
                                 nullptr, 0, s), "layernorm 1");
@@ -505,6 +508,12 @@ int eet_stack_create(const eet_layer_config* cfg, int32_t n_layers, const eet_la
     return EET_OK;
 }
 
+// The layers of a stack share one workspace, so the index set-up of layer 0 (lengths, prefix sums, row map) serves them
+// all; what is left per layer is zeroing the pad rows of its output buffer.  Layers 0 and 1 do that for the two
+// activation buffers the stack alternates between (nothing writes a pad row afterwards: the last projection of a layer
+// scatters valid rows only), the last layer for the caller's buffer; the layers in between skip the launch.
+static bool stack_layer_needs_setup(int l, int n_layers) { return l < 2 || l == n_layers - 1; }
+
 static int stack_prefill(const char* who, bool left_padded, eet_stack_t* st, const int32_t* q_lens, int32_t batch,
                          int32_t padded_len, const void* tokens, void* out, void* kv_cache, void* hip_stream) {
     if (!st) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
@@ -518,7 +527,8 @@ static int stack_prefill(const char* who, bool left_padded, eet_stack_t* st, con
     for (int l = 0; l < st->n_layers; ++l) {
         void* o = (l == st->n_layers - 1) ? out : static_cast<void*>(st->ws + st->act[l & 1]);
         char* kv = static_cast<char*>(kv_cache) + (size_t)l * st->layer_cache_bytes;
-        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv, s, true, left_padded);
+        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv, s, true, left_padded,
+                                       stack_layer_needs_setup(l, st->n_layers));
         if (rc != EET_OK) return rc;
         st->layers[l]->batch = batch;
         in = o;
@@ -553,7 +563,8 @@ int eet_stack_encode(eet_stack_t* st, const int32_t* q_lens, int32_t batch, int3
         void* o = (l == st->n_layers - 1) ? out : static_cast<void*>(st->ws + st->act[l & 1]);
         st->layers[l]->batch = 0;
         // every layer's keys and values of this pass go to the same scratch: the layers run one after another
-        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv_scratch, s, false);
+        const int rc = enqueue_prefill(st->layers[l], lens, batch, padded_len, T, max_len, in, o, kv_scratch, s, false, false,
+                                       stack_layer_needs_setup(l, st->n_layers));
         if (rc != EET_OK) return rc;
         in = o;
     }
