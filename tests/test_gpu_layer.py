@@ -274,13 +274,17 @@ def test_replays_the_host_never_saw_stay_inside_the_slots(eet, name, lens):
     layer.close()
 
 
-@pytest.mark.parametrize("name", ["small64", "cfg2-2seq"])
+@pytest.mark.parametrize("name", ["small64", "cfg2-2seq", "h2048"])
 def test_inputs_with_a_common_offset_and_an_outlier_channel(eet, name):
     """Hidden states as real models have them: every row shifted by a common offset of several standard deviations and
-    one channel (the first: the pivot of the LayerNorm statistics fused into the small-layer decode projections) ten
-    times larger than the rest.  Prefill (row-kernel LayerNorm) and decode steps (fused LayerNorm) against the oracle."""
+    one channel (the first: the pivot of the LayerNorm statistics fused into the decode projections) ten times larger
+    than the rest.  Prefill (row-kernel LayerNorm) and decode steps (LayerNorm fused into the small-layer kernel for
+    the first two, row kernel + weight-streaming kernel for the hidden-2048 layer) against the oracle."""
     from dataclasses import replace
-    w = wl.WORKLOADS["small64"] if name == "small64" else replace(wl.WORKLOADS["cfg2"], batch=2, decode_steps=3)
+    if name == "h2048":
+        w = wl.Workload("h2048", 29, 2048, 16, 8192, 1, 3, 24, 8, 24, 3, 32)
+    else:
+        w = wl.WORKLOADS["small64"] if name == "small64" else replace(wl.WORKLOADS["cfg2"], batch=2, decode_steps=3)
     W = wl.layer_weights(w, 0, True)
     lens = wl.lengths(w)
     B = w.batch
@@ -292,7 +296,7 @@ def test_inputs_with_a_common_offset_and_an_outlier_channel(eet, name):
     x = skew(wl.prompt_embeddings(w))
     layer = make_gpu_layer(eet, w, W)
     oracle = orc.DecoderLayerOracle(W, w.heads, B, w.max_seq, w.ln_eps)
-    rows = None if name == "small64" else {b: [0, int(L) // 2, int(L) - 1] for b, L in enumerate(lens)}
+    rows = None if name != "cfg2-2seq" else {b: [0, int(L) // 2, int(L) - 1] for b, L in enumerate(lens)}
     got = host(layer.prefill(dev(poison_pads(x, lens)), lens))
     want = oracle.prefill(x, lens, rows)
     for b, L in enumerate(lens):
