@@ -194,7 +194,7 @@ def test_softmax_maskfree_left_padded(eet, B, nh, S, lens):
 
 
 @pytest.mark.parametrize("M", [1, 5, 16, 17, 130, 200, 300, 513])
-@pytest.mark.parametrize("K,N", [(64, 64), (256, 192), (1024, 3072), (4096, 1024), (1088, 1216), (1024, 2048), (4608, 3072), (512, 32832), (1280, 1280)])
+@pytest.mark.parametrize("K,N", [(64, 64), (128, 320), (256, 192), (1024, 3072), (4096, 1024), (1088, 1216), (1024, 2048), (4608, 3072), (512, 32832), (1280, 1280)])
 def test_linear(eet, M, K, N):
     x = wl.normal(300 + M, K, (M, K))
     w = wl.normal(301, K * 7 + N, (N, K), 1.0 / np.sqrt(K))
