@@ -1121,9 +1121,11 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         else launch_skinny_cfg<1>(a, epi, s);
     } else {
         // 256x256 tiles once they cover about 60 % of the CUs, smaller tiles below that
-        // (measured: 156 tiles 592 vs 514 TFLOP/s in favour of the large tiles, 112 tiles 563 vs 673 against them)
+        // (measured: 156 tiles 592 vs 514 TFLOP/s in favour of the large tiles, 112 tiles 563 vs 673 against them), and
+        // never for at most 128 rows, where half of every large tile would be idle (a decode step of many sequences
+        // over a very wide output, e.g. the vocabulary: 128 x 1024 x 50304 39.7 -> 30.9 us with 128x128 tiles)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-        if (big_tiles >= 150) launch_dma64_cfg<2, 4>(a, epi, s);
+        if (big_tiles >= 150 && a.M > 128) launch_dma64_cfg<2, 4>(a, epi, s);
         else {
             // few tiles (short prompts, narrow layers): smaller tiles put more workgroups on the chip; the K loop of
             // each is a chain of dependent steps, so what counts there is how many run side by side and how far ahead
