@@ -244,24 +244,30 @@ __device__ __forceinline__ void wait_vm() {
     if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS>
+__global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
+    // KS > 1: KS groups of WGM x WGN waves share the tile and take every KS-th K step each, through LDS stages of their
+    // own; the other groups' accumulators are added to the first's through LDS at the end.  For the few
+    // tiles of a narrow output with a long K, where nothing else puts more loads in flight per CU.
     constexpr int NW = WGM * WGN, BK = 64;
     static_assert(NS == 2 || NS == 3, "LDS stages");
+    static_assert(KS == 1 || KS == 2, "K groups");
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int LRA = BM / NW, LRW = BN / NW;   // rows of each operand tile a wave loads per K step
     constexpr int LIA = LRA / 8, LIW = LRW / 8;   // wave-level load instructions per operand per K step
     static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && FM >= 1 && FM <= 4 && FN >= 1 && FN <= 4, "tile shape");
-    __shared__ __attribute__((aligned(1024))) half_t As[NS][BM * BK];
-    __shared__ __attribute__((aligned(1024))) half_t Ws[NS][BN * BK];
+    __shared__ __attribute__((aligned(1024))) half_t As[KS * NS][BM * BK];
+    __shared__ __attribute__((aligned(1024))) half_t Ws[KS * NS][BN * BK];
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int kg = KS == 1 ? 0 : (tid >> 6) / NW;            // K group of this wave
+    const int wave = KS == 1 ? tid >> 6 : (tid >> 6) % NW;   // wave inside its group
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int M = a.M, N = a.N, K = a.K;
-    const int nk = K / BK;
+    const int nk = K / (BK * KS);                            // steps of this group (the host sends whole multiples)
 
     const half_t* pa[LIA];
     const half_t* pw[LIW];
@@ -282,8 +288,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
         pw[v] = a.w + (int64_t)gr * K + c * 8;
     }
     const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 1) & 7;
-    const unsigned a_lds = (unsigned)(uintptr_t)&As[0][(wm0 + frow) * BK];
-    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[0][(wn0 + frow) * BK];
+    const unsigned a_lds = (unsigned)(uintptr_t)&As[kg * NS][(wm0 + frow) * BK];
+    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[kg * NS][(wn0 + frow) * BK];
     unsigned foff[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) foff[ks] = (unsigned)(((ks * 2 + fG) ^ fsw) * 16);
@@ -300,9 +306,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 #define EET_DLOAD(T, ST)                                                                                 \
     do {                                                                                                 \
         _Pragma("unroll") for (int v = 0; v < LIA; ++v)                                                  \
-            load_lds_16B(pa[v] + (int64_t)(T) * BK, &As[ST][(wave * LRA + v * 8) * BK]);                 \
+            load_lds_16B(pa[v] + (int64_t)((T) * KS + kg) * BK, &As[kg * NS + (ST)][(wave * LRA + v * 8) * BK]); \
         _Pragma("unroll") for (int v = 0; v < LIW; ++v)                                                  \
-            load_lds_16B(pw[v] + (int64_t)(T) * BK, &Ws[ST][(wave * LRW + v * 8) * BK]);                 \
+            load_lds_16B(pw[v] + (int64_t)((T) * KS + kg) * BK, &Ws[kg * NS + (ST)][(wave * LRW + v * 8) * BK]); \
     } while (0)
 #define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
 #define EET_DFRAG(FS, ST, KS)                                                                            \
@@ -399,6 +405,31 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_dma64(GemmArgs a, int
 
     static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
+    if constexpr (KS > 1) {
+        // the other groups' partial tiles go over the weight stages, lane-major (no bank conflicts), to the first
+        constexpr int PT = FM * FN * 16 * 64;                 // floats of one wave's partial tile
+        static_assert((KS - 1) * NW * PT * 4 <= (int)sizeof(Ws), "partial tiles over the weight stages");
+        float* red = reinterpret_cast<float*>(&Ws[0][0]) + wave * PT + lane;
+        if (kg > 0) {
+            float* mine = red + (kg - 1) * (NW * PT);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mine[((i * FN + j) * 16 + r) * 64] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 0; g < KS - 1; ++g)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += red[g * (NW * PT) + ((i * FN + j) * 16 + r) * 64];
+    }
     constexpr int EB = FM * 32 * 128;                      // bytes of a wave's turn-around area
     if constexpr (NW * EB <= (int)sizeof(As)) {
         epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
@@ -950,15 +981,15 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
-template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2>
+template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2, int KS = 1>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+    const dim3 grid(tm * tn), block(WGM * WGN * KS * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS, KS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS, KS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS, KS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS, KS>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1087,8 +1118,8 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 // estimates in microseconds whose constants are measured (projections of 2 to 400 MB, 17 to 1024 rows).  Slices: the
 // first reads the weights at about 4 TB/s, every further one reads them again out of L2 or the memory-side cache at about
 // 7.5 TB/s.  Tiles: the time does not depend on the row count while all workgroups are resident at once; it is the larger
-// of the weights at about 3 TB/s and of the K loop (0.33 us per step of 64 columns; longer in proportion once the tiles
-// no longer fit the chip at once).  Wide outputs with a short K go
+// of the weights at about 3 TB/s and of the K loop (0.33 us per step of 64 columns, 0.23 us where two groups of waves
+// share it; longer in proportion once the tiles no longer fit the chip at once).  Wide outputs with a short K go
 // to the tiles from about 33 rows on, narrow outputs with a long K (the output and second feed-forward projections)
 // stay with the slices for up to a few hundred rows.
 static bool slices_beat_tiles(const GemmArgs& a) {
@@ -1099,7 +1130,8 @@ static bool slices_beat_tiles(const GemmArgs& a) {
     const double again = w_mb / (streams ? 7.5 : 4.5);
     const double est_slices = 2.0 + w_mb / (streams ? 4.0 : 2.5) + (slices - 1) * (again > 0.1 ? again : 0.1);
     const double wg64 = (double)((a.M + 63) / 64) * ((a.N + 63) / 64);
-    const double k_loop = (a.K / 64) * 0.33 * (wg64 > 768.0 ? wg64 / 768.0 : 1.0);
+    const bool k_split = a.K % 128 == 0 && a.K >= 1024 && wg64 <= 256.0;     // two groups of waves share the K loop
+    const double k_loop = (a.K / 64) * (k_split ? 0.23 : 0.33) * (wg64 > 768.0 ? wg64 / 768.0 : 1.0);
     const double est_tiles = 3.0 + (w_mb / 3.0 > k_loop ? w_mb / 3.0 : k_loop);
     return est_slices < est_tiles;
 }
@@ -1134,7 +1166,16 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             // 2048 x 4096 x 1024 37.6 -> 28.5 us, 768 x 8192 x 2048 69.5 -> 51.9 us, 128 x 1600 x 6400 16.3 -> 11.8 us)
             const int tm = (a.M + 127) / 128;
             const int tiles128 = tm * ((a.N + 127) / 128);
-            if (tm * ((a.N + 63) / 64) < 128) launch_dma64_cfg<2, 1, 64, 64, 3>(a, epi, s);
+            // A long K with all tiles resident at one workgroup per CU: two groups of waves per tile, each with half
+            // of the K steps and LDS stages of its own, put twice the loads in flight (rows x K x N: 128 x 4096 x 4096
+            // 23.8 -> 16.5 us, 96 x 16384 x 4096 101.7 -> 67.7 us, 512 x 4096 x 1024 23.3 -> 16.5 us; four groups with
+            // two stages each were slower than two with three).
+            const bool k_split = a.K % 128 == 0 && a.K >= 1024;
+            const int wg128 = tm * ((a.N + 63) / 64), wg64 = ((a.M + 63) / 64) * ((a.N + 63) / 64);
+            if (wg128 < 128) {
+                if (k_split && wg64 <= 256) launch_dma64_cfg<2, 1, 64, 64, 3, 2>(a, epi, s);
+                else launch_dma64_cfg<2, 1, 64, 64, 3>(a, epi, s);
+            } else if (tiles128 < 256 && k_split && wg128 <= 256) launch_dma64_cfg<4, 1, 128, 64, 3, 2>(a, epi, s);
             else if (tiles128 < 256) launch_dma64_cfg<4, 1, 128, 64, 3>(a, epi, s);
             else if (tiles128 == 256) launch_dma64_cfg<2, 2, 128, 128, 3>(a, epi, s);      // one per CU
             else launch_dma64_cfg<2, 2, 128, 128>(a, epi, s);                               // two per CU
