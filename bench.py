@@ -44,12 +44,21 @@ MEASURED_TRAFFIC = {
 
 
 # Average duration of the same kernel's launches INSIDE the timed pass, from the last `rocprofv3 --kernel-trace` run of
-# the default command (profiles/cfg2_whole_pass_kernel_trace.txt).  The live figure above times launches of the
+# the workload's bench command (cfg2: profiles/cfg2_whole_pass_kernel_trace.txt).  The live figure above times launches of the
 # operator on its own, back to back; inside a decode step of a small layer the preceding FFN-2 launch has already
 # pulled the K/V rows towards the memory-side cache, so the same kernel runs faster there.  Reported beside the live
 # figure, never instead of it.
 IN_PASS_LAUNCH_US = {
-    "cfg2": {"attn_decode<64, 4>": 5.47},
+    "cfg2": {"attn_decode<64, 4>": (5.47,
+             "live figure: the operator launched on its own, operands cold.  Inside a decode step the extra "
+             "workgroups of the preceding FFN-2 launch fetch this kernel's K/V rows ahead of it, so part of its "
+             "fetch time shows up there in a kernel trace of the pass (FFN-2 7.7 us instead of 5.2, this kernel "
+             "5.2-5.5 instead of 8.0)")},
+    # profiles/cfg3_cfg5a_cfg4_bert1024_whole_pass_kernel_trace.txt
+    "cfg4": {"attn_decode<128, 4>": (9.40,
+             "live figure: the operator, whose 8 key ranges per (sequence, head) are merged by a second launch "
+             "(attn_decode_combine, about 4 us).  Inside a decode step of the layer the output projection merges the "
+             "ranges while it loads its activations, so there the attention is this one kernel")},
 }
 
 
@@ -362,14 +371,11 @@ def roofline_for(stack, torch, eet, reps):
                      "traffic": next((v for k, v in measured.items() if c["kernel"].startswith(k)), None),
                      "avg_launch_us": c["ms"] * 1e3,
                      "algorithmic_work_per_launch": c["work"], "share_ms_per_pass": c["ms"] * c["launches"]})
-        us = next((v for k, v in in_pass.items() if c["kernel"].startswith(k)), None)
-        if us is not None:      # same work per launch, the profiled in-pass duration
-            recs[-1]["in_pass_avg_launch_us_profiled"] = us
-            recs[-1]["in_pass_frac_profiled"] = c["work"] / (us * 1e-6) / 1e9 / peak
-            recs[-1]["note"] = ("live figure: the operator launched on its own, operands cold.  Inside a decode step the extra "
-                                "workgroups of the preceding FFN-2 launch fetch this kernel's K/V rows ahead of it, so part of its "
-                                "fetch time shows up there in a kernel trace of the pass (FFN-2 7.7 us instead of 5.2, this kernel "
-                                "5.2 instead of 8.0)")
+        prof = next((v for k, v in in_pass.items() if c["kernel"].startswith(k)), None)
+        if prof is not None:    # same work per launch, the profiled in-pass duration
+            recs[-1]["in_pass_avg_launch_us_profiled"] = prof[0]
+            recs[-1]["in_pass_frac_profiled"] = c["work"] / (prof[0] * 1e-6) / 1e9 / peak
+            recs[-1]["note"] = prof[1]
     recs.sort(key=lambda r: -r["share_ms_per_pass"])
     return recs[0], recs[1:]
 

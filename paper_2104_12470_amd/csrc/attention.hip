@@ -973,7 +973,7 @@ hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s) {
     const dim3 grid(a.splits, a.heads, a.batch), block(256);
     if (a.d == 128) hipLaunchKernelGGL((attn_decode<128, 4>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((attn_decode<64, 4>), grid, block, 0, s, a);
-    if (a.splits > 1) {
+    if (a.splits > 1 && !a.leave_ranges) {
         const int pairs = a.batch * a.heads;
         if (a.d == 128) hipLaunchKernelGGL(attn_decode_combine<128>, dim3((pairs + 1) / 2), dim3(256), 0, s, a);
         else hipLaunchKernelGGL(attn_decode_combine<64>, dim3((pairs + 3) / 4), dim3(256), 0, s, a);

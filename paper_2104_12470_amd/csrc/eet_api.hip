@@ -341,12 +341,20 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     at.splits = attention_decode_splits(B, c.heads, c.max_seq);
     at.part_acc = reinterpret_cast<float*>(L->ws + L->lay.part);
     at.part_ml = at.part_acc + (size_t)B * c.heads * at.splits * L->d;
-    EET_LAUNCH(launch_attention_decode(at, s), "decode attention");
     // output projection + bias + residual; its first workgroup also advances n_b: every reader of
     // n_b in this step (cache append, attention) is already ordered before it on the stream
     GemmArgs o{};
     o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
     o.M = B; o.N = H; o.K = H; o.res = x;
+    o.heads = c.heads; o.d = L->d;
+    // With the key range split (few (sequence, head) pairs) the ranges need merging.  Where the output projection goes to
+    // the small-layer kernel, that kernel merges them while it loads its activations, and the merge launch (4 us, the
+    // floor of a dependent launch) is gone; otherwise attn_decode_combine runs.
+    if (at.splits > 1 && gemm_merges_attention_ranges(o)) {
+        at.leave_ranges = 1;
+        o.x_part_acc = at.part_acc; o.x_part_ml = at.part_ml; o.x_splits = at.splits;
+    }
+    EET_LAUNCH(launch_attention_decode(at, s), "decode attention");
     const bool bump_in_gemm = B <= 16;
     if (bump && bump_in_gemm) { o.bump_lens = d_lens; o.bump_count = B; }
     if (prefetch) {                                       // during the output projection (64 workgroups): the second feed-forward matrix

@@ -669,8 +669,9 @@ __device__ __forceinline__ void take_row_slice(GemmArgs& a) {
     }
 }
 
-template <int NW, int UPW, int TN, int EPI, bool LN, bool SL>
+template <int NW, int UPW, int TN, int EPI, bool LN, bool SL, bool XM = false>
 __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
+    static_assert(!XM || (EPI == EPI_BIAS_RES && !LN && !SL), "merging attention ranges: the output projection of a decode step");
     if (SL) take_row_slice<EPI>(a);
     constexpr int NT = NW * 64;
     constexpr int K = 64 * NW * UPW, KV = K / 8, LDX = K + 8;   // LDX: 16-byte reads of 16 rows spread over all banks
@@ -717,8 +718,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
             }
         }
     };
-    request_x(0);
-    if (M > 8) request_x(1);
+    if (!XM) {
+        request_x(0);
+        if (M > 8) request_x(1);
+    }
     // weights: per unit, lane l takes 16 bytes (chunk l%8) of rows l/8 and 8 + l/8
     const int wrow = lane >> 3, wchunk = lane & 7;
     half8v wreg[UPW][WA];
@@ -739,6 +742,62 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
         eo.bias = *reinterpret_cast<const half4v*>(a.bias + en);
         if (EPI == EPI_BIAS_RES) eo.res = *reinterpret_cast<const half4v*>(a.res + (uint32_t)(eml * a.N + en));
         if (EPI == EPI_QKV) eo.pos = a.lens[eml];
+    }
+
+    // ---- XM: the activations are the attention output of this step, one partial per key range; merge them ----
+    // (what attn_decode_combine does in a launch of its own: common maximum, rescaled sums, one division)
+    if constexpr (XM) {
+        constexpr int MAXS = NW >= 16 ? 2 : 8;                  // ranges in flight at a time (1024 threads: 128 VGPRs each)
+        const int splits = a.x_splits;
+        auto merge_x = [&](int h) {
+#pragma unroll
+            for (int i = 0; i < UPW; ++i) {
+                const int row = (tid + NT * i) / KV, col = (tid + NT * i) % KV;
+                const int src = 8 * h + row;
+                xdst[i] = row * LDX + col * 8;
+                half8v o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (half_t)0.f;
+                if (src < M) {                                  // rows past M feed outputs nobody writes
+                    const int g = (col * 8) / a.d, dd = (col * 8) % a.d;
+                    const int64_t bh = (int64_t)src * a.heads + g;
+                    const float* ml = a.x_part_ml + bh * splits * 2;
+                    const float* pa = a.x_part_acc + bh * splits * a.d + dd;
+                    float mx = -INFINITY;
+                    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml[s * 2]);      // range 0 is never empty
+                    float lsum = 0.f, av[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) av[e] = 0.f;
+                    for (int s0 = 0; s0 < splits; s0 += MAXS) {
+                        float2v mlv[MAXS];
+                        float4v lo[MAXS], hi[MAXS];
+#pragma unroll
+                        for (int u = 0; u < MAXS; ++u) {
+                            const int s = s0 + u < splits ? s0 + u : splits - 1;
+                            mlv[u] = *reinterpret_cast<const float2v*>(ml + s * 2);
+                            lo[u] = *reinterpret_cast<const float4v*>(pa + (int64_t)s * a.d);
+                            hi[u] = *reinterpret_cast<const float4v*>(pa + (int64_t)s * a.d + 4);
+                        }
+#pragma unroll
+                        for (int u = 0; u < MAXS; ++u) {
+                            const float sc = s0 + u < splits ? exp2f(mlv[u][0] - mx) : 0.f;
+                            lsum += mlv[u][1] * sc;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                av[e] += lo[u][e] * sc;
+                                av[4 + e] += hi[u][e] * sc;
+                            }
+                        }
+                    }
+                    const float inv = 1.0f / lsum;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = (half_t)(av[e] * inv);
+                }
+                xv[h][i] = o;
+            }
+        };
+        merge_x(0);
+        if (M > 8) merge_x(1);
     }
 
     // ---- activations -> LDS (normalised when LN) ----------------------------------------------
@@ -1030,7 +1089,15 @@ static void launch_flat_sl(const GemmArgs& a, Epilogue epi, int lds, hipStream_t
     switch (epi) {
         case EPI_BIAS: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS, LN, SL>, a, grid, block, lds, s); break;
         case EPI_BIAS_GELU: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_GELU, LN, SL>, a, grid, block, lds, s); break;
-        case EPI_BIAS_RES: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, LN, SL>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES:
+            if constexpr (!LN && !SL) {
+                if (a.x_splits > 1) {
+                    launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, false, false, true>, a, grid, block, lds, s);
+                    break;
+                }
+            }
+            launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_BIAS_RES, LN, SL>, a, grid, block, lds, s);
+            break;
         case EPI_QKV: launch_flat_kernel(gemm_flat<NW, UPW, TN, EPI_QKV, LN, SL>, a, grid, block, lds, s); break;
     }
 }
@@ -1050,7 +1117,7 @@ static void launch_flat(const GemmArgs& a, int upw, Epilogue epi, int lds, hipSt
 }
 // true when the flat kernel took the problem: a few MB of weights, K = 64 * NW * UPW with
 // NW in {4, 8, 16} and UPW in 1..4, N a multiple of 16, no row maps
-static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s, bool ask_only = false) {
     constexpr int tn8_wgs = 128;                              // fewer 16-column workgroups than this: 8-column ones
     if ((int64_t)a.N * a.K * 2 > (16 << 20) || a.N % 16 != 0 || a.K % 64 != 0) return false;
     if (a.res_row_map != nullptr || a.out_row_map != nullptr || a.tok_row_map != nullptr) return false;
@@ -1067,6 +1134,7 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int upw = units / nw;
     const int lds = flat_lds_bytes(nw, upw, a.M <= 8 ? 8 : 16);
     if (lds > kFlatLdsLimit) return false;
+    if (ask_only) return true;
     if (nw == 4) {
         if (ln) launch_flat<4, 16, true>(a, upw, epi, lds, s); else launch_flat<4, 16, false>(a, upw, epi, lds, s);
     } else if (nw == 8) {
@@ -1136,8 +1204,14 @@ static bool slices_beat_tiles(const GemmArgs& a) {
     return est_slices < est_tiles;
 }
 
+bool gemm_merges_attention_ranges(const GemmArgs& a) {
+    return a.M >= 1 && a.M <= 16 && a.ln_gamma == nullptr && a.d >= 8 && a.d % 8 == 0 && a.heads * a.d == a.K &&
+           try_flat(a, EPI_BIAS_RES, nullptr, true);
+}
+
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
+    if (a.x_splits > 1 && (epi != EPI_BIAS_RES || !gemm_merges_attention_ranges(a))) return hipErrorInvalidValue;
     // A few more rows than the weight-streaming kernels take at once (a decode step of more than 16 sequences, a very
     // short prompt): the same kernels with the rows cut into slices of 16 along gridDim.y, where that beats a tile kernel
     // that would run a handful of workgroups through the whole K loop (decode layer-step of the hidden-1024 layer at 32

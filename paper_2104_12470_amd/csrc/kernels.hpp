@@ -74,7 +74,16 @@ struct GemmArgs {
     int32_t* bump_lens;
     int bump_count;
     PrefetchArgs pf;              // gemm_flat only
+    // gemm_flat with EPI_BIAS_RES only (x_splits > 1): the activations are the decode attention's output still split
+    // over key ranges, and the kernel merges the ranges while it loads them (x is not read).  Row m, head g = column
+    // / d, range s: weighted values x_part_acc[((m*heads + g)*x_splits + s)*d ..+d], (maximum, sum) in the exp2
+    // domain x_part_ml[((m*heads + g)*x_splits + s)*2 ..+2]; heads and d above give the layout.
+    const float* x_part_acc;
+    const float* x_part_ml;
+    int x_splits;
 };
+// true when launch_gemm would give this bias+residual projection to the kernel that can merge the key ranges itself
+bool gemm_merges_attention_ranges(const GemmArgs& a);
 
 // M > 16: MFMA tile kernel.  M <= 16 (decode): weight-streaming kernel.
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
@@ -109,6 +118,7 @@ struct AttnDecodeArgs {
     int splits;             // key-range splits per (sequence, head)
     float* part_acc;        // [batch*heads*splits, d]   (splits > 1)
     float* part_ml;         // [batch*heads*splits, 2]
+    int leave_ranges;       // 1: no merge launch, the projection that follows merges the ranges (GemmArgs::x_splits)
 };
 int attention_decode_splits(int batch, int heads, int capacity);
 size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits);
