@@ -763,14 +763,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
                     const int64_t bh = (int64_t)src * a.heads + g;
                     const float* ml = a.x_part_ml + bh * splits * 2;
                     const float* pa = a.x_part_acc + bh * splits * a.d + dd;
-                    float mx = -INFINITY;
-                    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml[s * 2]);      // range 0 is never empty
                     float lsum = 0.f, av[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) av[e] = 0.f;
-                    for (int s0 = 0; s0 < splits; s0 += MAXS) {
-                        float2v mlv[MAXS];
-                        float4v lo[MAXS], hi[MAXS];
+                    auto fetch = [&](int s0, float2v (&mlv)[MAXS], float4v (&lo)[MAXS], float4v (&hi)[MAXS]) {
 #pragma unroll
                         for (int u = 0; u < MAXS; ++u) {
                             const int s = s0 + u < splits ? s0 + u : splits - 1;
@@ -778,6 +774,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
                             lo[u] = *reinterpret_cast<const float4v*>(pa + (int64_t)s * a.d);
                             hi[u] = *reinterpret_cast<const float4v*>(pa + (int64_t)s * a.d + 4);
                         }
+                    };
+                    auto add = [&](int s0, float mx, const float2v (&mlv)[MAXS], const float4v (&lo)[MAXS], const float4v (&hi)[MAXS]) {
 #pragma unroll
                         for (int u = 0; u < MAXS; ++u) {
                             const float sc = s0 + u < splits ? exp2f(mlv[u][0] - mx) : 0.f;
@@ -787,6 +785,22 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
                                 av[e] += lo[u][e] * sc;
                                 av[4 + e] += hi[u][e] * sc;
                             }
+                        }
+                    };
+                    float2v mlv[MAXS];
+                    float4v lo[MAXS], hi[MAXS];
+                    if (splits <= MAXS) {                       // the usual case: everything in one trip to memory
+                        fetch(0, mlv, lo, hi);
+                        float mx = mlv[0][0];                   // range 0 is never empty (clamped slots repeat the last range)
+#pragma unroll
+                        for (int u = 1; u < MAXS; ++u) mx = fmaxf(mx, mlv[u][0]);
+                        add(0, mx, mlv, lo, hi);
+                    } else {
+                        float mx = -INFINITY;
+                        for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml[s * 2]);
+                        for (int s0 = 0; s0 < splits; s0 += MAXS) {
+                            fetch(s0, mlv, lo, hi);
+                            add(s0, mx, mlv, lo, hi);
                         }
                     }
                     const float inv = 1.0f / lsum;
