@@ -110,6 +110,15 @@ def test_decode_of_100_sequences_on_a_layer_with_large_projections(eet):
     full_parity(eet, w, random_affine=False)
 
 
+@pytest.mark.parametrize("heads,B,max_seq,lo,hi", [(4, 3, 512, 300, 500), (2, 1, 4096, 3900, 4000)])
+def test_decode_with_the_key_range_split_and_merged_by_the_output_projection(eet, heads, B, max_seq, lo, hi):
+    """Few (sequence, head) pairs and a long cache: the decode attention splits the key range (4 ranges per pair in the
+    first case, 32 in the second: more than the projection keeps in flight at once), and the output projection of
+    these small layers merges the ranges while it loads its activations.  Every element against the oracle."""
+    w = wl.Workload(f"ranges{heads}x{B}", 31, 256, heads, 1024, 1, B, hi, lo, hi, 3, max_seq)
+    full_parity(eet, w, random_affine=False)
+
+
 @pytest.mark.parametrize("name", ["tiny", "small64", "small128", "bert1024"])
 def test_encoder_use_elementwise(eet, name):
     """eet_layer_encode against the oracle's encoder use of the same layer (no sequence mask):
