@@ -327,6 +327,18 @@ def test_gpt2_sized_vocabulary_on_the_cfg2_layer_shape(eet):
     gpu.close()
 
 
+def differs(what, a, b):
+    """Message for a failed bit-for-bit comparison: how many elements differ, where the first one is, by how much."""
+    a, b = a.reshape(-1), b.reshape(-1)
+    ne = (a != b) & ~(torch.isnan(a.float()) & torch.isnan(b.float()))
+    idx = torch.nonzero(ne).reshape(-1)
+    if idx.numel() == 0:
+        return f"{what}: NaN patterns differ"
+    i = int(idx[0])
+    return (f"{what}: {idx.numel()} of {a.numel()} elements differ, first at flat index {i} ({float(a[i])} vs {float(b[i])}), "
+            f"largest difference {float((a.float() - b.float()).abs()[idx].max())}")
+
+
 def test_cfg2_model_at_full_size_is_embedding_then_stack_then_head(eet):
     """The benchmark's --model configuration (24 layers, batch 8, prompts of 256-512 tokens, vocabulary 50257, decode
     steps replayed from the stack's graph): the model call is bit for bit the embedding operator, then the stack entry
@@ -354,7 +366,7 @@ def test_cfg2_model_at_full_size_is_embedding_then_stack_then_head(eet):
     eet.eet_op_embedding(ids, lens, model.head["wte"], model.head["wpe"], emb, vocab=V)
     ref = other.prefill(emb, lens)
     torch.cuda.synchronize()
-    assert torch.equal(h_out, ref)
+    assert torch.equal(h_out, ref), differs("prefill: last-layer rows, model against embedding operator + stack", h_out, ref)
     last = np.stack([host(h_out[b, L - 1]) for b, L in enumerate(lens)])
     check_head(model, head64, last, logits, nxt, V, "cfg2 model prefill")
     for k in range(w.decode_steps):
@@ -368,10 +380,11 @@ def test_cfg2_model_at_full_size_is_embedding_then_stack_then_head(eet):
         eet.eet_op_embedding_decode(fed, pos, model.head["wte"], model.head["wpe"], x, vocab=V)
         y = other.decode_step(x)
         torch.cuda.synchronize()
-        assert torch.equal(d_in, x) and torch.equal(d_out, y)
+        assert torch.equal(d_in, x), differs(f"decode {k}: embedded rows", d_in, x)
+        assert torch.equal(d_out, y), differs(f"decode {k}: last-layer rows", d_out, y)
         check_head(model, head64, host(d_out), logits, nxt, V, f"cfg2 model decode {k}")
     assert model.stack.cache_lens(B) == other.cache_lens(B) == [L + w.decode_steps for L in lens]
-    assert torch.equal(model.stack.kv_cache, other.kv_cache)
+    assert torch.equal(model.stack.kv_cache, other.kv_cache), differs("K/V caches", model.stack.kv_cache, other.kv_cache)
     model.close()
     other.close()
 
