@@ -1150,7 +1150,11 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s, bool ask_on
     if (lds > kFlatLdsLimit) return false;
     if (ask_only) return true;
     if (nw == 4) {
-        if (ln) launch_flat<4, 16, true>(a, upw, epi, lds, s); else launch_flat<4, 16, false>(a, upw, epi, lds, s);
+        // few columns: 8 per workgroup put twice the workgroups on the chip (hidden-1024 output projection: 64 -> 128
+        // beside its 128 prefetch workgroups; 512 decode steps of the 24-layer stack 324.9 -> 322.6 ms, same call)
+        if (ln) launch_flat<4, 16, true>(a, upw, epi, lds, s);
+        else if (a.N / 16 < tn8_wgs) launch_flat<4, 8, false>(a, upw, epi, lds, s);
+        else launch_flat<4, 16, false>(a, upw, epi, lds, s);
     } else if (nw == 8) {
         if (ln) launch_flat<8, 16, true>(a, upw, epi, lds, s); else launch_flat<8, 16, false>(a, upw, epi, lds, s);
     } else if (a.N / 16 < tn8_wgs) {
