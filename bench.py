@@ -49,7 +49,7 @@ MEASURED_TRAFFIC = {
 # pulled the K/V rows towards the memory-side cache, so the same kernel runs faster there.  Reported beside the live
 # figure, never instead of it.
 IN_PASS_LAUNCH_US = {
-    "cfg2": {"attn_decode<64, 4>": (5.47,
+    "cfg2": {"attn_decode<64, 4>": (5.19,
              "live figure: the operator launched on its own, operands cold.  Inside a decode step the extra "
              "workgroups of the preceding FFN-2 launch fetch this kernel's K/V rows ahead of it, so part of its "
              "fetch time shows up there in a kernel trace of the pass (FFN-2 7.7 us instead of 5.2, this kernel "
