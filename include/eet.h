@@ -48,6 +48,7 @@ extern "C" {
 #define EET_MAX_BATCH 128                /* per-sequence lengths travel as kernel arguments        */
 
 typedef struct eet_layer eet_layer_t;    /* opaque, host memory owned by the library               */
+typedef struct eet_bufmgr eet_bufmgr_t;  /* buffer manager of Section 3.2 (declared at the end of this header) */
 
 /* Layer shape and capacity: the paper's h, n, and maximum b, p, s (Section 3.1 notation). */
 typedef struct {
@@ -82,9 +83,12 @@ size_t eet_kv_cache_bytes(const eet_layer_config *cfg);
  * Section 3).  Returns 0 on a bad config. */
 size_t eet_workspace_bytes(const eet_layer_config *cfg);
 
-/* Create a layer.  `workspace` is DEVICE memory of eet_workspace_bytes(cfg), 256-byte aligned,
- * owned by the caller and used exclusively by this layer until eet_layer_destroy.  Nothing is
- * enqueued.  Errors: INVALID_ARG (null), UNSUPPORTED_SHAPE. */
+/* Create a layer (Section 3.1: everything a pass needs is sized once, for the maximum batch, prompt and
+ * sequence length, before the first call, so that no call allocates).  `workspace` is DEVICE memory of
+ * eet_workspace_bytes(cfg), 256-byte aligned, owned by the caller and used exclusively by this layer until
+ * eet_layer_destroy; weights are borrowed.  All of it must be ready (filled, uploaded) on the stream a later
+ * call is given: the library orders nothing against other streams.  Nothing is enqueued.
+ * Errors: INVALID_ARG (null, misaligned), UNSUPPORTED_SHAPE. */
 int eet_layer_create(const eet_layer_config *cfg, const eet_layer_weights *weights,
                      void *workspace, eet_layer_t **out_layer);
 
@@ -133,8 +137,9 @@ int eet_layer_encode(eet_layer_t *layer, const int32_t *q_lens, int32_t batch, i
 int eet_decode_step(eet_layer_t *layer, const void *tokens, void *out, void *kv_cache,
                     void *hip_stream);
 
-/* Copy the device-side cache lengths n_b of the current batch to HOST int32[batch].
- * Synchronises the stream.  Errors: STATE, HIP. */
+/* Copy the device-side cache lengths n_b of the current batch to HOST int32[batch] (Section 3.1: the
+ * number of keys and values kept per sequence; with the padding offsets of Section 2.1 these are the
+ * integers that must match exactly).  Synchronises the stream.  Errors: STATE, HIP. */
 int eet_cache_lens(eet_layer_t *layer, int32_t *out_host, void *hip_stream);
 
 /* Resume from a saved state.  The resumable state of a layer is its K/V cache (the caller's memory) and the
@@ -145,10 +150,12 @@ int eet_cache_lens(eet_layer_t *layer, int32_t *out_host, void *hip_stream);
  * Errors: INVALID_ARG, CAPACITY (batch > max_batch). */
 int eet_restore(eet_layer_t *layer, const int32_t *cache_lens, int32_t batch, void *hip_stream);
 
-/* Release the handle (host memory only). */
+/* Release the handle: host memory only; workspace, cache and weights stay the caller's (Section 3.1's
+ * buffers live as long as the caller keeps them).  NULL is accepted. */
 int eet_layer_destroy(eet_layer_t *layer);
 
-/* Message for the last error on this thread ("" if none). */
+/* Message for the last error on this thread ("" if none); static thread-local storage, valid until the
+ * next failing call on the thread.  Not from the paper: part of the C-ABI conventions above. */
 const char *eet_last_error(void);
 
 /* ---------------------------------------------------------------------------------------------
@@ -287,17 +294,25 @@ int eet_op_softmax_maskfree(void *scores, const int32_t *q_lens, int32_t batch, 
 int eet_op_softmax_maskfree_left_padded(void *scores, const int32_t *q_lens, int32_t batch, int32_t heads,
                                         int32_t padded_len, float scale, void *hip_stream);
 
-/* y = gelu_tanh(x + bias); x, y [rows, width], bias [width]. */
+/* Add-bias + GELU as a kernel of its own, the form the paper's layer has between its library GEMM calls
+ * (Section 3.2: fusion stops at the GEMMs), for rows of any width (Section 2.2's goal; the layer's own pass
+ * runs it as the epilogue of the first feed-forward projection).  y = gelu_tanh(x + bias), fp32 arithmetic;
+ * x, y [rows, width], bias [width]; y may be x.  Errors: INVALID_ARG (null, rows < 0, width < 1). */
 int eet_op_bias_gelu(const void *x, const void *bias, void *y, int64_t rows, int32_t width,
                      void *hip_stream);
 
-/* y = x + bias + residual; x, residual, y [rows, width], bias [width]. */
+/* Add-bias + residual as a kernel of its own (Section 3.1 names the residual connection; Section 3.2 and 2.2
+ * as above).  y = x + bias + residual, summed in fp32 and rounded once; x, residual, y [rows, width],
+ * bias [width]; y may be x.  Errors as eet_op_bias_gelu. */
 int eet_op_bias_residual(const void *x, const void *bias, const void *residual, void *y,
                          int64_t rows, int32_t width, void *hip_stream);
 
-/* Dense projection y = act(x W^T + bias) (+ residual): x [rows, in], W [out, in], y [rows, out];
- * in and out multiples of 64.  act: 0 = identity, 1 = gelu_tanh.  residual may be NULL.
- * rows <= 16 takes the weight-streaming path used by decode, otherwise the MFMA tile path. */
+/* Dense projection with its epilogue, the four matrix products of a layer that the paper leaves to library
+ * GEMM calls (Section 3.2): y = act(x W^T + bias) (+ residual), fp32 accumulation, one rounding.
+ * x [rows, in], W [out, in], y [rows, out], bias [out], residual [rows, out] or NULL; in and out multiples of
+ * 64; act: 0 = identity, 1 = gelu_tanh (not together with a residual).  rows <= 16 takes the weight-streaming
+ * path of a decode step, more rows the MFMA tile path of a prefill (or row slices, by a cost estimate).
+ * Errors: INVALID_ARG (null, bad size, misaligned), UNSUPPORTED_SHAPE. */
 int eet_op_linear(const void *x, const void *w, const void *bias, const void *residual, void *y,
                   int64_t rows, int32_t in, int32_t out, int32_t act, void *hip_stream);
 
@@ -323,13 +338,9 @@ int eet_op_attention_encoder(const void *q, const void *k_cache, const void *v_c
  * must be a multiple of 8.  Adds EET_ERR_CAPACITY when the manager's arena cannot hold the scores. */
 int eet_op_attention_unfused(const void *q, const void *k_cache, const void *v_cache, void *ctx,
                              const int32_t *q_lens, int32_t batch, int32_t padded_len, int32_t heads,
-                             int32_t d, int32_t capacity, struct eet_bufmgr *buffers, int32_t module,
+                             int32_t d, int32_t capacity, eet_bufmgr_t *buffers, int32_t module,
                              void *hip_stream);
 
-/* Incremental attention: q, ctx [batch, heads*d]; sequence b attends to slots 0..n_keys[b]-1.
- * n_keys is DEVICE int32[batch], each 1..capacity.  scratch: DEVICE, at least
- * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes (partial results of the
- * key ranges; contents on entry do not matter). */
 /* Embedding of whole prompts: out [batch, padded_len, hidden] fp16; row (b, i) = wte[ids[b, i]] +
  * wpe[i] (sum in fp32, rounded once) for i < q_lens[b], zeros for pad rows, whose ids are never
  * read.  ids: DEVICE int32; q_lens: HOST.  hidden must be a multiple of 8.  A row whose id is
@@ -353,6 +364,15 @@ int eet_op_embedding_decode(const int32_t *ids, const int32_t *positions, int32_
 int eet_op_argmax(const void *logits, int32_t rows, int32_t vocab, int32_t row_stride, int32_t *out,
                   void *hip_stream);
 
+/* Incremental attention over the K/V cache (Section 3.1: the keys and values of every step are kept for the
+ * next step's attention; the padding offset of Section 2.1 is the loop bound).  q, ctx [batch, heads*d];
+ * k_cache, v_cache [batch, heads, capacity, d]; sequence b attends to slots 0..n_keys[b]-1.
+ * n_keys is DEVICE int32[batch], each 1..capacity (a value above capacity is clamped to it; a sequence with
+ * n_keys[b] < 1 sees no key and its ctx rows are written as 0).  scratch: DEVICE, 16-byte aligned, at least
+ * eet_op_attention_decode_scratch_bytes(batch, heads, d, capacity) bytes, owned by the caller: partial results
+ * of the key ranges when a (sequence, head) pair is split over several workgroups; contents on entry do not
+ * matter, calls that share it must not overlap.  Errors: INVALID_ARG (null, size < 1, misaligned),
+ * UNSUPPORTED_SHAPE (d not 64 or 128, batch or heads above 65535). */
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity);
 int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_cache, void *ctx,
                             const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,
@@ -375,7 +395,7 @@ int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_ca
  * EET_ERR_CAPACITY (the request does not fit in what is left of the arena), EET_ERR_STATE (release
  * of a buffer that is already idle).  On error nothing changes.
  * ------------------------------------------------------------------------------------------- */
-typedef struct eet_bufmgr eet_bufmgr_t;   /* opaque, host memory owned by the library */
+/* eet_bufmgr_t: opaque, host memory owned by the library (typedef at the top of this header) */
 typedef struct {
     uint64_t arena_bytes;        /* size of the arena                                        */
     uint64_t footprint_bytes;    /* bytes of all buffers created so far                      */

@@ -5,25 +5,41 @@ import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeet.so")
+OBJ = os.path.join(os.path.dirname(HERE), "_build", "obj")      # object files: ignored by git, never shipped
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
          "-Wall", "-Wno-unused-function"]
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every kernel source into one shared library; always recompiles."""
+def build_library(verbose: bool = True, lib: str = LIB, extra_flags=()) -> str:
+    """Compile every kernel source (one hipcc process per file, side by side) and link them into one shared library;
+    always recompiles."""
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    cmd = [HIPCC, *FLAGS, *srcs, "-o", LIB]
+    objdir = os.path.join(OBJ, os.path.basename(lib))
+    os.makedirs(objdir, exist_ok=True)
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        cmd = [HIPCC, *FLAGS, *extra_flags, "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        objs = list(pool.map(compile_one, srcs))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -1028,6 +1028,18 @@ int eet_op_argmax(const void* logits, int32_t rows, int32_t vocab, int32_t row_s
     return EET_OK;
 }
 
+// Shared argument checks of the two decode-attention operators.
+static int check_attention_decode(const char* who, const void* q, const void* k_cache, const void* v_cache, const void* ctx,
+                                  const int32_t* n_keys, int32_t batch, int32_t heads, int32_t d, int32_t capacity) {
+    if (!q || !k_cache || !v_cache || !ctx || !n_keys) return fail(EET_ERR_INVALID_ARG, "%s: null argument", who);
+    if (batch < 1 || heads < 1 || capacity < 1) return fail(EET_ERR_INVALID_ARG, "%s: bad size", who);
+    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: head size must be 64 or 128", who);
+    if (batch > 65535 || heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: batch or heads > 65535", who);
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx))
+        return fail(EET_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+    return EET_OK;
+}
+
 size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32_t d, int32_t capacity) {
     if (batch < 1 || heads < 1 || d < 1 || capacity < 1) return 0;
     const size_t n = attention_decode_scratch_bytes(batch, heads, d, attention_decode_splits(batch, heads, capacity));
@@ -1036,13 +1048,9 @@ size_t eet_op_attention_decode_scratch_bytes(int32_t batch, int32_t heads, int32
 
 int eet_op_attention_decode(const void* q, const void* k_cache, const void* v_cache, void* ctx, const int32_t* n_keys,
                             int32_t batch, int32_t heads, int32_t d, int32_t capacity, void* scratch, void* hip_stream) {
-    if (!q || !k_cache || !v_cache || !ctx || !n_keys || !scratch)
-        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: null argument");
-    if (batch < 1 || heads < 1 || capacity < 1) return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: bad size");
-    if (d != 64 && d != 128) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_decode: head size must be 64 or 128");
-    if (batch > 65535 || heads > 65535) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_attention_decode: batch or heads > 65535");
-    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(ctx) || !aligned16(scratch))
-        return fail(EET_ERR_INVALID_ARG, "eet_op_attention_decode: pointers must be 16-byte aligned");
+    const char* who = "eet_op_attention_decode";
+    if (const int rc = check_attention_decode(who, q, k_cache, v_cache, ctx, n_keys, batch, heads, d, capacity)) return rc;
+    if (!scratch || !aligned16(scratch)) return fail(EET_ERR_INVALID_ARG, "%s: scratch is null or not 16-byte aligned", who);
     AttnDecodeArgs a{};
     a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
     a.lens = n_keys; a.len_bias = 0; a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity;

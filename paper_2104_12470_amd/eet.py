@@ -433,6 +433,13 @@ def eet_bufmgr_destroy(handle) -> None:
     _check(lib().eet_bufmgr_destroy(handle))
 
 
+def _buffers_ready() -> None:
+    """The holders below fill the K/V cache and upload the weights on torch's current stream, and their calls accept
+    any stream: the library orders nothing across streams (include/eet.h), so the holder waits here, once, until what
+    it allocated is in place."""
+    torch.cuda.current_stream().synchronize()
+
+
 class DecoderLayer:
     """Owns the torch buffers a layer handle borrows.  No arithmetic here."""
 
@@ -442,6 +449,7 @@ class DecoderLayer:
         self.workspace = torch.empty(eet_workspace_bytes(cfg), dtype=torch.uint8, device=device)
         self.kv_cache = torch.full((eet_kv_cache_bytes(cfg) // 2,), cache_fill, dtype=torch.float16, device=device)
         self.handle = eet_layer_create(cfg, self.weights, self.workspace)
+        _buffers_ready()
 
     def cache_views(self):
         c = self.cfg
@@ -498,6 +506,7 @@ class DecoderStack:
         self.kv_cache = torch.full((eet_stack_kv_cache_bytes(cfg, self.n_layers) // 2,), cache_fill,
                                    dtype=torch.float16, device=device)
         self.handle = eet_stack_create(cfg, self.weights, self.workspace, use_graph)
+        _buffers_ready()
 
     def cache_views(self, layer: int):
         c = self.cfg
@@ -559,6 +568,7 @@ class DecoderModel:
         self.mcfg = ModelConfig(vocab, vp, self.head["wpe"].shape[0])
         self.workspace = torch.empty(eet_model_workspace_bytes(cfg, self.mcfg), dtype=torch.uint8, device=device)
         self.handle = eet_model_create(self.stack.handle, cfg, self.mcfg, self.head, self.workspace)
+        _buffers_ready()
         self.batch = 0
 
     def prefill(self, ids: torch.Tensor, q_lens: Sequence[int], stream=None, left_padded: bool = False):

@@ -207,3 +207,30 @@ def test_model_and_its_operators_validate(eet):
     assert L.eet_op_argmax(P, 2, 100, 96, P, None) == eet.EET_ERR_INVALID_ARG                              # stride < vocab
     assert L.eet_op_argmax(P, 2, 100, 100, P, None) == eet.EET_ERR_INVALID_ARG                             # stride % 8
     assert L.eet_op_argmax(P, 2, 100, 104, None, None) == eet.EET_ERR_INVALID_ARG
+
+
+def test_header_compiles_as_plain_c_and_links(eet, tmp_path):
+    """include/eet.h is a C header: a C99 translation unit that includes it compiles without a warning under
+    -Wall -Werror -pedantic, links against the library and gets the K/V cache size of Section 3.1 from it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "eet.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '    eet_layer_config c = {1024, 16, 4096, 8, 512, 1024, 1e-5f};\n'
+        '    eet_bufmgr_t *m = 0;\n'
+        '    (void)m;\n'
+        '    printf("%lu %s\\n", (unsigned long)eet_kv_cache_bytes(&c), eet_last_error());\n'
+        '    return eet_layer_destroy(0);\n'
+        '}\n')
+    exe = tmp_path / "use_header"
+    libdir = os.path.dirname(eet.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.dirname(HEADER), str(src),
+                    "-o", str(exe), "-L", libdir, "-l:libeet.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == 2 * orc.kv_cache_elements(8, 1024, 1024, 1)
