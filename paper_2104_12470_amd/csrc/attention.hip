@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <type_traits>
 #include "kernels.hpp"
+#include "pipeline.hpp"
 
 namespace eet {
 
@@ -261,16 +262,16 @@ __device__ __forceinline__ void load_lds_16B(const char* gptr, char* lds) {
 template <int N>
 __device__ __forceinline__ void wait_lds() {
     static_assert(N == 0 || N == 4 || N == 8 || N == 16, "add the count");
-    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)");
-    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)");
-    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)");
-    if (N == 16) asm volatile("s_waitcnt lgkmcnt(15)");   // the counter saturates at 15: one read more than needed is waited for
+    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");
+    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)" ::: "memory");
+    if (N == 16) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");   // the counter saturates at 15: one read more than needed is waited for
 }
 template <int N>
 __device__ __forceinline__ void wait_vmem() {
     static_assert(N == 2 || N == 4, "add the count");
-    if (N == 2) asm volatile("s_waitcnt vmcnt(2)");
-    if (N == 4) asm volatile("s_waitcnt vmcnt(4)");
+    if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
 }
 // lane ^ 32 maximum without the LDS: v_permlane32_swap exchanges the upper half of its first operand
 // with the lower half of its second, so the two results hold, for every lane, its own value and its partner's.
@@ -284,6 +285,25 @@ __device__ __forceinline__ float max_xor32(float x) {
     const unsigned r0 = r[0], r1 = r[1];
     return fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
 }
+
+// Executor of pipe::attn_kv_loop for the kernel below: the tile loads and the arithmetic of a step are the kernel's
+// own lambdas, the waits and the barrier are the instructions themselves.  PAIR = load instructions of one
+// load_k + load_v pair of a wave.
+template <int PAIR, class LoadK, class LoadV, class First, class Step>
+struct AttnRingExec {
+    LoadK& load_k_;
+    LoadV& load_v_;
+    First& first_;
+    Step& step_;
+    __device__ __forceinline__ void load_k(int tile, int stage) { load_k_(tile, stage); }
+    __device__ __forceinline__ void load_v(int tile, int stage) { load_v_(tile, stage); }
+    __device__ __forceinline__ void wait_loads_but_newest_pair() { wait_vmem<PAIR>(); }
+    __device__ __forceinline__ void wait_loads_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+    __device__ __forceinline__ void barrier() { __builtin_amdgcn_s_barrier(); }
+    __device__ __forceinline__ void first_scores() { first_(); }
+    __device__ __forceinline__ void step(int jt, int v_stage, int k_stage) { step_(jt, v_stage, k_stage); }
+    __device__ __forceinline__ void wait_reads() { wait_lds<0>(); }
+};
 
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqLens lens) {
@@ -403,7 +423,7 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
     auto read_k = [](half8v (&dst)[KK], const unsigned (&ka)[KK], auto jb) __attribute__((always_inline)) {
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
-            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[kk]) : "v"(ka[kk]), "n"(decltype(jb)::value * 32 * ROWB));
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[kk]) : "v"(ka[kk]), "n"(decltype(jb)::value * 32 * ROWB) : "memory");
     };
     auto landed_k = [&]() __attribute__((always_inline)) {     // after a wait: the fragments are now defined
 #pragma unroll
@@ -451,8 +471,8 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16) * ROWB));
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16 + 8) * ROWB));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16) * ROWB) : "memory");
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[hf][db]) : "v"(va[db]), "n"((JB * 32 + hf * 16 + 8) * ROWB) : "memory");
             }
         if constexpr (decltype(has_next)::value) {
             wait_lds<4 * DB>();                                   // the K fragments requested one region ago
@@ -507,48 +527,33 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
     constexpr std::integral_constant<int, 0> jb0{};
     constexpr std::integral_constant<int, 1> jb1{};
 
-    // Rings: tile t lives in stage t%3.  During step jt the waves read V(jt) and K(jt+1) while K(jt+2), V(jt+1)
-    // (requested during step jt-1) and K(jt+3), V(jt+2) (requested now, into the stages step jt-1 was reading)
-    // are in flight.  Requests past the last tile re-read clamped rows into stages nobody reads: the number of
-    // loads per step stays fixed, which keeps the wait counts fixed.
+    // Rings: tile t lives in stage t%3.  Which stage is loaded, read, waited for and released when is
+    // pipe::attn_kv_loop (pipeline.hpp), shared with the host-side audit of the hand-over; the lambdas below are
+    // the instructions of its steps.
     float16v sa, sb;
-    load_k(0, 0);
-    load_k(1, 1);
-    load_v(0, 0);
-    load_k(2, 2);
-    load_v(1, 1);
-    wait_vmem<2 * NV>();                                  // K(0), K(1), V(0) of this wave have landed ...
-    __builtin_amdgcn_s_barrier();                         // ... and everybody else's
-    if (nh_w > 0) {
-        read_k(kf, kaddr, jb0);
-        wait_lds<0>();
-        landed_k();
-        scores(sa);
-        if (nh_w == 1) row_max(sa, 0, yes);
-        else row_max(sa, 0, no);                          // alpha = 0 and the accumulators are zero: nothing to rescale
-        if (nh_w > 1) read_k(kf, kaddr, jb1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    wait_lds<0>();
-    __builtin_amdgcn_s_barrier();                         // step 0 refills the stage of K(0)
-    int s0 = 0;                                           // stage of tile jt
-    for (int jt = 0; jt < nt_wg; ++jt) {
-        const int s1 = s0 == 2 ? 0 : s0 + 1, s2 = s0 == 0 ? 2 : s0 - 1;
-        load_k(jt + 3, s0);                               // K(jt) was last read during step jt-1
-        load_v(jt + 2, s2);                               // V(jt-1) was last read during step jt-1
+    auto first_scores = [&]() __attribute__((always_inline)) {
+        if (nh_w > 0) {
+            read_k(kf, kaddr, jb0);
+            wait_lds<0>();
+            landed_k();
+            scores(sa);
+            if (nh_w == 1) row_max(sa, 0, yes);
+            else row_max(sa, 0, no);                      // alpha = 0 and the accumulators are zero: nothing to rescale
+            if (nh_w > 1) read_k(kf, kaddr, jb1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto step = [&](int jt, int v_stage, int k_stage) __attribute__((always_inline)) {
         unsigned ka2[KK], va[DB];                         // fragment addresses in the stages of K(jt+1) and V(jt)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) ka2[kk] = kaddr[kk] + s1 * TILEB;
+        for (int kk = 0; kk < KK; ++kk) ka2[kk] = kaddr[kk] + k_stage * TILEB;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) va[db] = vaddr[db] + s0 * TILEB;
+        for (int db = 0; db < DB; ++db) va[db] = vaddr[db] + v_stage * TILEB;
         wave_half(2 * jt, jb0, sa, sb, va, ka2);          // requests the K fragments of half 2*jt+2: tile jt+1, jb 0
         wave_half(2 * jt + 1, jb1, sb, sa, va, ka2);      // ... of half 2*jt+3: tile jt+1, jb 1
-        wait_lds<0>();                                    // this wave is done reading the stages of this step
-        wait_vmem<2 * NV>();                              // K(jt+2), V(jt+1) of this wave have landed ...
-        __builtin_amdgcn_s_barrier();                     // ... and everybody else's
-        s0 = s1;
-    }
-    asm volatile("s_waitcnt vmcnt(0)");                   // no load may still be writing LDS when the workgroup ends
+    };
+    AttnRingExec<2 * NV, decltype(load_k), decltype(load_v), decltype(first_scores), decltype(step)> ring{load_k, load_v, first_scores, step};
+    pipe::attn_kv_loop(ring, nt_wg);
 
     l += __shfl_xor(l, 32, kWave);
     if (i >= L) return;
@@ -905,7 +910,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode(AttnDecodeArgs a) {
         }
     }
     if (splits == 1) {
-        if (tid < D) a.ctx[bh * D + tid] = (half_t)(A / Lsum);
+        if (tid < D) a.ctx[bh * D + tid] = (half_t)(Lsum > 0.f ? A / Lsum : 0.f);   // a pair that sees no key: zeros, not 0/0
         return;
     }
     if (tid < D) a.part_acc[(bh * splits + sp) * D + tid] = A;
@@ -931,7 +936,7 @@ __global__ __launch_bounds__(256) void attn_decode_combine(AttnDecodeArgs a) {
     const float* ml = a.part_ml + bh * splits * 2;
     const float* pa = a.part_acc + bh * splits * D + dd;
     float M = -INFINITY;
-    for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[s * 2]);     // range 0 is never empty
+    for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[s * 2]);     // an empty range reports the finite kEmpty and a zero sum
     float Lsum = 0.f, A = 0.f;
     for (int s0 = 0; s0 < splits; s0 += MAXS) {
         float mv[MAXS], lv[MAXS], av[MAXS];
@@ -949,7 +954,7 @@ __global__ __launch_bounds__(256) void attn_decode_combine(AttnDecodeArgs a) {
             A += av[u] * sc;
         }
     }
-    a.ctx[bh * D + dd] = (half_t)(A / Lsum);
+    a.ctx[bh * D + dd] = (half_t)(Lsum > 0.f ? A / Lsum : 0.f);                 // every range empty: zeros, not 0/0
 }
 
 int attention_decode_splits(int batch, int heads, int capacity) {

@@ -22,6 +22,7 @@
 #include <utility>
 
 #include "kernels.hpp"
+#include "pipeline.hpp"
 
 namespace eet {
 
@@ -185,23 +186,7 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float1
 // --------------------------------------------------------------------------------------------
 // MFMA tile kernel
 // --------------------------------------------------------------------------------------------
-// Tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x is
-// given a contiguous range of a tile sequence in which any 32 consecutive tiles (one per CU of the
-// XCD) form a block of 8 row-tiles x 4 column-tiles: 12 operand panels are shared by 32 tiles.
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-    constexpr int GM = 8;
-    const int nb = tiles_m * tiles_n;
-    const int xcd = pid & 7, local = pid >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    const int t = xcd * q + (xcd < rem ? xcd : rem) + local;   // position in the sequence
-    const int per_group = GM * tiles_n;
-    const int grp = t / per_group, in_grp = t - grp * per_group;
-    const int gm0 = grp * GM;
-    const int gsz = tiles_m - gm0 < GM ? tiles_m - gm0 : GM;    // last group may be shorter
-    tile_n = in_grp / gsz;
-    tile_m = gm0 + in_grp - tile_n * gsz;
-}
-
+// Tile order: pipe::tile_of_block (pipeline.hpp; the host-side audit checks that it visits every tile exactly once).
 // --------------------------------------------------------------------------------------------
 // MFMA tile kernel with direct global->LDS loads
 // --------------------------------------------------------------------------------------------
@@ -229,20 +214,84 @@ __device__ __forceinline__ void load_lds_16B(const half_t* gptr, half_t* lds) {
 template <int N>
 __device__ __forceinline__ void wait_lgkm() {
     static_assert(N == 0 || N == 3 || N == 4 || N == 6 || N == 8, "add the count");
-    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)");
-    if (N == 3) asm volatile("s_waitcnt lgkmcnt(3)");
-    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)");
-    if (N == 6) asm volatile("s_waitcnt lgkmcnt(6)");
-    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)");
+    if (N == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (N == 3) asm volatile("s_waitcnt lgkmcnt(3)" ::: "memory");
+    if (N == 4) asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");
+    if (N == 6) asm volatile("s_waitcnt lgkmcnt(6)" ::: "memory");
+    if (N == 8) asm volatile("s_waitcnt lgkmcnt(8)" ::: "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
     static_assert(N == 0 || N == 6 || N == 8 || N == 16, "add the count");
-    if (N == 0) asm volatile("s_waitcnt vmcnt(0)");
-    if (N == 6) asm volatile("s_waitcnt vmcnt(6)");
-    if (N == 8) asm volatile("s_waitcnt vmcnt(8)");
-    if (N == 16) asm volatile("s_waitcnt vmcnt(16)");
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
+
+// The instructions of the tile kernel's K loop.  The loop itself -- which stage is loaded, read, waited for and released
+// when -- is pipe::gemm_k_loop (pipeline.hpp), shared with the host-side audit of the hand-over; this executor supplies the
+// instructions, all forced inline.  (Namespace scope because a local class cannot have member templates.)
+template <int BM, int BN, int NW, int NS, int KS, int FM, int FN>
+struct GemmTileExec {
+    static constexpr int BK = 64;
+    static constexpr int LRA = BM / NW, LRW = BN / NW, LIA = LRA / 8, LIW = LRW / 8;
+    const half_t* pa[LIA];                 // this lane's source of each load instruction, K tile 0
+    const half_t* pw[LIW];
+    half_t* as_base;                       // stage 0 of this wave's K group: As[kg * NS], Ws[kg * NS]
+    half_t* ws_base;
+    unsigned a_lds, w_lds;                 // LDS byte address of this lane's fragment row in stage 0
+    unsigned foff[4];                      // byte offset of sub-step s inside the (permuted) row
+    int kg, wave;
+    half8v fa[2][FM], fw[2][FN];
+    float16v acc[FM][FN];
+
+    __device__ __forceinline__ void load(int tile, int stage) {
+#pragma unroll
+        for (int v = 0; v < LIA; ++v)
+            load_lds_16B(pa[v] + (int64_t)(tile * KS + kg) * BK, as_base + stage * (BM * BK) + (wave * LRA + v * 8) * BK);
+#pragma unroll
+        for (int v = 0; v < LIW; ++v)
+            load_lds_16B(pw[v] + (int64_t)(tile * KS + kg) * BK, ws_base + stage * (BN * BK) + (wave * LRW + v * 8) * BK);
+    }
+    __device__ __forceinline__ void wait_loads_all() { wait_vm<0>(); }
+    __device__ __forceinline__ void wait_loads_but_newest() { wait_vm<LIA + LIW>(); }
+    __device__ __forceinline__ void barrier() { __builtin_amdgcn_s_barrier(); }
+#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR) : "memory")
+    template <int BUF, int SUB>
+    __device__ __forceinline__ void frag(int stage) {
+        const unsigned va_ = a_lds + stage * (BM * BK * 2) + foff[SUB];
+        const unsigned vw_ = w_lds + stage * (BN * BK * 2) + foff[SUB];
+        EET_DREAD(fa[BUF][0], va_, 0);
+        if (FM > 1) EET_DREAD(fa[BUF][1 % FM], va_, 4096);
+        if (FM > 2) EET_DREAD(fa[BUF][2 % FM], va_, 8192);
+        if (FM > 3) EET_DREAD(fa[BUF][3 % FM], va_, 12288);
+        EET_DREAD(fw[BUF][0], vw_, 0);
+        if (FN > 1) EET_DREAD(fw[BUF][1 % FN], vw_, 4096);
+        if (FN > 2) EET_DREAD(fw[BUF][2 % FN], vw_, 8192);
+        if (FN > 3) EET_DREAD(fw[BUF][3 % FN], vw_, 12288);
+    }
+#undef EET_DREAD
+    // `newer`: frag() calls issued after the one being waited for (FM + FN reads each) that may stay in flight
+    template <int BUF>
+    __device__ __forceinline__ void wait_frag(int newer) {
+        if (newer) wait_lgkm<FM + FN>(); else wait_lgkm<0>();
+#pragma unroll
+        for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[BUF][i]));      // the fragments are defined from here on
+#pragma unroll
+        for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[BUF][j]));
+    }
+    template <int BUF>
+    __device__ __forceinline__ void mma() {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[BUF][j], fa[BUF][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+};
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS>
 __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
@@ -260,7 +309,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     __shared__ __attribute__((aligned(1024))) half_t Ws[KS * NS][BN * BK];
 
     int tile_m, tile_n;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    pipe::tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int kg = KS == 1 ? 0 : (tid >> 6) / NW;            // K group of this wave
@@ -269,15 +318,19 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     const int M = a.M, N = a.N, K = a.K;
     const int nk = K / (BK * KS);                            // steps of this group (the host sends whole multiples)
 
-    const half_t* pa[LIA];
-    const half_t* pw[LIW];
+    GemmTileExec<BM, BN, NW, NS, KS, FM, FN> ex;
+    static_assert(decltype(ex)::LIA == LIA && decltype(ex)::LIW == LIW, "load instructions per K step");
+    ex.kg = kg;
+    ex.wave = wave;
+    ex.as_base = &As[kg * NS][0];
+    ex.ws_base = &Ws[kg * NS][0];
 #pragma unroll
     for (int v = 0; v < LIA; ++v) {
         const int row = wave * LRA + v * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         int gr = m0 + row;
         gr = gr < M ? gr : M - 1;
-        pa[v] = a.x + (int64_t)gr * K + c * 8;
+        ex.pa[v] = a.x + (int64_t)gr * K + c * 8;
     }
 #pragma unroll
     for (int v = 0; v < LIW; ++v) {
@@ -285,123 +338,22 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         int gr = n0 + row;
         gr = gr < N ? gr : N - 1;
-        pw[v] = a.w + (int64_t)gr * K + c * 8;
+        ex.pw[v] = a.w + (int64_t)gr * K + c * 8;
     }
     const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 1) & 7;
-    const unsigned a_lds = (unsigned)(uintptr_t)&As[kg * NS][(wm0 + frow) * BK];
-    const unsigned w_lds = (unsigned)(uintptr_t)&Ws[kg * NS][(wn0 + frow) * BK];
-    unsigned foff[4];
+    ex.a_lds = (unsigned)(uintptr_t)&As[kg * NS][(wm0 + frow) * BK];
+    ex.w_lds = (unsigned)(uintptr_t)&Ws[kg * NS][(wn0 + frow) * BK];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) foff[ks] = (unsigned)(((ks * 2 + fG) ^ fsw) * 16);
+    for (int ks = 0; ks < 4; ++ks) ex.foff[ks] = (unsigned)(((ks * 2 + fG) ^ fsw) * 16);
 
-    half8v fa[2][FM], fw[2][FN];
-    float16v acc[FM][FN];
+    float16v (&acc)[FM][FN] = ex.acc;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-#define EET_DLOAD(T, ST)                                                                                 \
-    do {                                                                                                 \
-        _Pragma("unroll") for (int v = 0; v < LIA; ++v)                                                  \
-            load_lds_16B(pa[v] + (int64_t)((T) * KS + kg) * BK, &As[kg * NS + (ST)][(wave * LRA + v * 8) * BK]); \
-        _Pragma("unroll") for (int v = 0; v < LIW; ++v)                                                  \
-            load_lds_16B(pw[v] + (int64_t)((T) * KS + kg) * BK, &Ws[kg * NS + (ST)][(wave * LRW + v * 8) * BK]); \
-    } while (0)
-#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR))
-#define EET_DFRAG(FS, ST, KS)                                                                            \
-    do {                                                                                                 \
-        const unsigned va_ = a_lds + (ST) * (BM * BK * 2) + foff[KS];                                    \
-        const unsigned vw_ = w_lds + (ST) * (BN * BK * 2) + foff[KS];                                    \
-        EET_DREAD(fa[FS][0], va_, 0);                                                                    \
-        if (FM > 1) EET_DREAD(fa[FS][1 % FM], va_, 4096);                                                \
-        if (FM > 2) EET_DREAD(fa[FS][2 % FM], va_, 8192);                                                \
-        if (FM > 3) EET_DREAD(fa[FS][3 % FM], va_, 12288);                                               \
-        EET_DREAD(fw[FS][0], vw_, 0);                                                                    \
-        if (FN > 1) EET_DREAD(fw[FS][1 % FN], vw_, 4096);                                                \
-        if (FN > 2) EET_DREAD(fw[FS][2 % FN], vw_, 8192);                                                \
-        if (FN > 3) EET_DREAD(fw[FS][3 % FN], vw_, 12288);                                               \
-    } while (0)
-#define EET_DWAIT(FS, CNT)                                                                               \
-    do {                                                                                                 \
-        wait_lgkm<CNT>();                                                                                \
-        _Pragma("unroll") for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[FS][i]));              \
-        _Pragma("unroll") for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[FS][j]));              \
-    } while (0)
-#define EET_DMMA(FS)                                                                                     \
-    do {                                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                               \
-        _Pragma("unroll") for (int i = 0; i < FM; ++i)                          \
-            _Pragma("unroll") for (int j = 0; j < FN; ++j)                      \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[FS][j], fa[FS][i], acc[i][j], 0, 0, 0); \
-        __builtin_amdgcn_sched_barrier(0);                                                               \
-    } while (0)
-
-    if constexpr (NS == 2) {
-        EET_DLOAD(0, 0);
-        asm volatile("s_waitcnt vmcnt(0)");
-        __syncthreads();
-        EET_DFRAG(0, 0, 0);
-        for (int kt = 0; kt < nk; ++kt) {
-            const int st = kt & 1;
-            if (kt + 1 < nk) EET_DLOAD(kt + 1, st ^ 1);   // stage st^1 was released by the barrier of the previous step
-            EET_DFRAG(1, st, 1);
-            EET_DWAIT(0, FM + FN);
-            EET_DMMA(0);
-            EET_DFRAG(0, st, 2);
-            EET_DWAIT(1, FM + FN);
-            EET_DMMA(1);
-            EET_DFRAG(1, st, 3);
-            EET_DWAIT(0, FM + FN);
-            EET_DMMA(0);
-            EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
-            asm volatile("s_waitcnt vmcnt(0)");   // this wave's part of tile kt+1 has landed
-            __builtin_amdgcn_s_barrier();         // ... and everybody else's
-            EET_DFRAG(0, st ^ 1, 0);              // (past the last tile: stale data, never used)
-            EET_DMMA(1);
-        }
-    } else {
-        // ring of three stages: tile kt+2 is requested at the start of step kt, into the stage that step kt-1 read and
-        // the barrier at its end released; at the end of step kt only the newest request may still be in flight
-        EET_DLOAD(0, 0);
-        if (nk > 1) {
-            EET_DLOAD(1, 1);
-            wait_vm<LIA + LIW>();
-        } else {
-            wait_vm<0>();
-        }
-        __builtin_amdgcn_s_barrier();             // nothing but the loads above has touched LDS so far
-        EET_DFRAG(0, 0, 0);
-        int st = 0;
-        for (int kt = 0; kt < nk; ++kt) {
-            const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
-            const bool more = kt + 2 < nk;
-            if (more) EET_DLOAD(kt + 2, st2);
-            EET_DFRAG(1, st, 1);
-            EET_DWAIT(0, FM + FN);
-            EET_DMMA(0);
-            EET_DFRAG(0, st, 2);
-            EET_DWAIT(1, FM + FN);
-            EET_DMMA(1);
-            EET_DFRAG(1, st, 3);
-            EET_DWAIT(0, FM + FN);
-            EET_DMMA(0);
-            EET_DWAIT(1, 0);                      // all of this wave's reads of stage st are done
-            if (more) wait_vm<LIA + LIW>(); else wait_vm<0>();   // this wave's part of tile kt+1 has landed
-            __builtin_amdgcn_s_barrier();         // ... and everybody else's
-            EET_DFRAG(0, st1, 0);                 // (past the last tile: stale data, never used)
-            EET_DMMA(1);
-            st = st1;
-        }
-    }
-    EET_DWAIT(0, 0);
-#undef EET_DLOAD
-#undef EET_DREAD
-#undef EET_DFRAG
-#undef EET_DWAIT
-#undef EET_DMMA
+    pipe::gemm_k_loop<NS>(ex, nk);
 
     static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
@@ -431,6 +383,9 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
                     for (int r = 0; r < 16; ++r) acc[i][j][r] += red[g * (NW * PT) + ((i * FN + j) * 16 + r) * 64];
     }
     constexpr int EB = FM * 32 * 128;                      // bytes of a wave's turn-around area
+    // with K groups the partial tiles above sit in the weight stages and group 0 may still be summing them while a faster
+    // wave of the group already turns its tile around: that must then happen in the activation stages only
+    static_assert(KS == 1 || NW * EB <= (int)sizeof(As), "turn-around areas must not touch the partial tiles");
     if constexpr (NW * EB <= (int)sizeof(As)) {
         epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
     } else {
@@ -791,7 +746,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
                     float4v lo[MAXS], hi[MAXS];
                     if (splits <= MAXS) {                       // the usual case: everything in one trip to memory
                         fetch(0, mlv, lo, hi);
-                        float mx = mlv[0][0];                   // range 0 is never empty (clamped slots repeat the last range)
+                        float mx = mlv[0][0];                   // empty ranges report a finite maximum and a zero sum (clamped slots repeat the last range)
 #pragma unroll
                         for (int u = 1; u < MAXS; ++u) mx = fmaxf(mx, mlv[u][0]);
                         add(0, mx, mlv, lo, hi);
@@ -803,7 +758,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
                             add(s0, mx, mlv, lo, hi);
                         }
                     }
-                    const float inv = 1.0f / lsum;
+                    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;     // a pair that saw no key at all: zeros, not 0/0
 #pragma unroll
                     for (int e = 0; e < 8; ++e) o[e] = (half_t)(av[e] * inv);
                 }

@@ -1,0 +1,167 @@
+// The LDS hand-over schedules of the two pipelined kernels, written once.
+//
+// gemm_mfma_dma64 (gemm.hip) and attn_prefill_wide (attention.hip) move operand tiles from global memory
+// straight into rings of LDS stages while other waves still read earlier tiles out of the same ring.  What
+// makes that correct is only the ORDER in which a wave issues tile loads, fragment reads, counter waits and
+// barriers.  That order lives here, as templates over an executor:
+//   * in the kernels the executor issues the instructions (its methods are forced inline: the generated code
+//     is the same as if the loop were written out in the kernel);
+//   * in tests/pipeline_audit.cpp, a host program, the executor records them, and a checker replays the
+//     record for all waves of a workgroup and asserts that no stage is overwritten while a read of it can be
+//     outstanding, that no fragment is consumed before its tile has landed for every wave, that every
+//     (K tile, K sub-step) is multiplied exactly once, and that nothing is in flight when the loop is left.
+// This header is plain C++ (no HIP types), so the host program includes the very text the kernels compile.
+#pragma once
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define EET_PIPE_FN __host__ __device__ __forceinline__
+#else
+#define EET_PIPE_FN inline
+#endif
+
+namespace eet {
+namespace pipe {
+
+// ---------------------------------------------------------------------------------------------------------
+// Tile order of the MFMA tile kernel.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
+// XCD x is given a contiguous range of a tile sequence in which any 32 consecutive tiles (one per CU of the XCD)
+// form a block of 8 row-tiles x 4 column-tiles: 12 operand panels are shared by 32 tiles.  Every workgroup
+// index in [0, tiles_m * tiles_n) maps to a different tile (checked on the host for all small grids).
+// ---------------------------------------------------------------------------------------------------------
+EET_PIPE_FN void tile_of_block(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    constexpr int GM = 8;
+    const int nb = tiles_m * tiles_n;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int q = nb >> 3, rem = nb & 7;
+    const int t = xcd * q + (xcd < rem ? xcd : rem) + local;   // position in the sequence
+    const int per_group = GM * tiles_n;
+    const int grp = t / per_group, in_grp = t - grp * per_group;
+    const int gm0 = grp * GM;
+    const int gsz = tiles_m - gm0 < GM ? tiles_m - gm0 : GM;    // last group may be shorter
+    tile_n = in_grp / gsz;
+    tile_m = gm0 + in_grp - tile_n * gsz;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K loop of the MFMA tile kernel: K tiles of 64 columns through NS LDS stages (tile t in stage t % NS), four
+// sub-steps of 16 columns per tile, fragments double-buffered in registers.
+//
+// Executor interface (BUF = register buffer 0/1, SUB = sub-step 0..3, stage = ring slot):
+//   load(tile, stage)            issue this wave's global->LDS loads of K tile `tile`           (vector-memory counter)
+//   wait_loads_all()             every load of this wave has landed in LDS
+//   wait_loads_but_newest()      ... every load except those of the newest load() call
+//   barrier()                    workgroup barrier
+//   frag<BUF, SUB>(stage)        issue the LDS reads of sub-step SUB of the tile in `stage` into buffer BUF
+//   wait_frag<BUF>(newer)        the reads into BUF have landed; `newer` frag() calls issued after them may still fly
+//   mma<BUF>()                   multiply-accumulate from buffer BUF
+// ---------------------------------------------------------------------------------------------------------
+template <int NS, class Ops>
+EET_PIPE_FN void gemm_k_loop(Ops& op, int nk) {
+    static_assert(NS == 2 || NS == 3, "LDS stages");
+    if (NS == 2) {
+        // two stages: tile kt+1 is requested at the start of step kt into the stage that step kt-1 read and that the
+        // barrier at its end released; the end of step kt waits for it
+        op.load(0, 0);
+        op.wait_loads_all();
+        op.barrier();
+        op.template frag<0, 0>(0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st = kt & 1;
+            if (kt + 1 < nk) op.load(kt + 1, st ^ 1);
+            op.template frag<1, 1>(st);
+            op.template wait_frag<0>(1);
+            op.template mma<0>();
+            op.template frag<0, 2>(st);
+            op.template wait_frag<1>(1);
+            op.template mma<1>();
+            op.template frag<1, 3>(st);
+            op.template wait_frag<0>(1);
+            op.template mma<0>();
+            op.template wait_frag<1>(0);          // all of this wave's reads of stage st are done
+            op.wait_loads_all();                  // this wave's part of tile kt+1 has landed
+            op.barrier();                         // ... and everybody else's; stage st is free
+            op.template frag<0, 0>(st ^ 1);       // (past the last tile: stale data, never multiplied)
+            op.template mma<1>();
+        }
+    } else {
+        // ring of three stages: tile kt+2 is requested at the start of step kt, into the stage that step kt-1 read and
+        // the barrier at its end released; at the end of step kt only that newest request may still be in flight
+        op.load(0, 0);
+        if (nk > 1) {
+            op.load(1, 1);
+            op.wait_loads_but_newest();
+        } else {
+            op.wait_loads_all();
+        }
+        op.barrier();                             // nothing but the loads above has touched LDS so far
+        op.template frag<0, 0>(0);
+        int st = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
+            const bool more = kt + 2 < nk;
+            if (more) op.load(kt + 2, st2);
+            op.template frag<1, 1>(st);
+            op.template wait_frag<0>(1);
+            op.template mma<0>();
+            op.template frag<0, 2>(st);
+            op.template wait_frag<1>(1);
+            op.template mma<1>();
+            op.template frag<1, 3>(st);
+            op.template wait_frag<0>(1);
+            op.template mma<0>();
+            op.template wait_frag<1>(0);          // all of this wave's reads of stage st are done
+            if (more) op.wait_loads_but_newest(); else op.wait_loads_all();   // this wave's part of tile kt+1 has landed
+            op.barrier();                         // ... and everybody else's; stage st is free
+            op.template frag<0, 0>(st1);          // (past the last tile: stale data, never multiplied)
+            op.template mma<1>();
+            st = st1;
+        }
+    }
+    op.template wait_frag<0>(0);                  // the stale reads too: the epilogue reuses the stages
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Key-tile loop of the 256-row prefill attention: K and V tiles of 64 keys through two rings of three stages
+// (tile t in stage t % 3 of its ring).  During step jt the waves read V(jt) and K(jt+1) -- the scores of tile
+// jt were formed during step jt-1 -- while K(jt+2), V(jt+1) (requested during step jt-1) and K(jt+3), V(jt+2)
+// (requested at the start of this step, into the stages step jt-1 was reading) are in flight.  Requests past
+// the last tile are still issued (the kernel clamps their rows): the number of loads per step, and with it
+// every wait count, stays fixed.
+//
+// Executor interface:
+//   load_k(tile, stage), load_v(tile, stage)   issue this wave's global->LDS loads of a key / value tile
+//   wait_loads_but_newest_pair()               every load except those of the newest load_k + load_v pair has landed
+//   wait_loads_all()
+//   barrier()
+//   first_scores()                             reads K(0) out of K stage 0 and waits for them (scores of tile 0)
+//   step(jt, v_stage, k_stage)                 reads V(jt) from v_stage and K(jt+1) from k_stage, multiplies
+//   wait_reads()                               every LDS read of this wave has landed
+// ---------------------------------------------------------------------------------------------------------
+template <class Ops>
+EET_PIPE_FN void attn_kv_loop(Ops& op, int nt) {
+    op.load_k(0, 0);
+    op.load_k(1, 1);
+    op.load_v(0, 0);
+    op.load_k(2, 2);
+    op.load_v(1, 1);
+    op.wait_loads_but_newest_pair();              // K(0), K(1), V(0) of this wave have landed ...
+    op.barrier();                                 // ... and everybody else's
+    op.first_scores();
+    op.wait_reads();
+    op.barrier();                                 // step 0 refills the stage of K(0)
+    int s0 = 0;                                   // stage of tile jt
+    for (int jt = 0; jt < nt; ++jt) {
+        const int s1 = s0 == 2 ? 0 : s0 + 1, s2 = s0 == 0 ? 2 : s0 - 1;
+        op.load_k(jt + 3, s0);                    // K(jt) was last read during step jt-1
+        op.load_v(jt + 2, s2);                    // V(jt-1) was last read during step jt-1
+        op.step(jt, s0, s1);
+        op.wait_reads();                          // this wave is done reading the stages of this step
+        op.wait_loads_but_newest_pair();          // K(jt+2), V(jt+1) of this wave have landed ...
+        op.barrier();                             // ... and everybody else's
+        s0 = s1;
+    }
+    op.wait_loads_all();                          // no load may still be writing LDS when the workgroup ends
+}
+
+}  // namespace pipe
+}  // namespace eet
