@@ -378,6 +378,20 @@ int eet_op_attention_decode(const void *q, const void *k_cache, const void *v_ca
                             const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,
                             int32_t capacity, void *scratch, void *hip_stream);
 
+/* eet_op_attention_decode for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * `scratch`, same kernels, same results bit for bit: the partial results of a split key range live in a
+ * 512 KiB device array inside the library (EET_STATIC_SCRATCH_BYTES; one copy per GPU, held until the process
+ * ends), whose address is looked up on the first call on each device -- make that first call outside a capture.
+ * The call allocates nothing.  Every call on a GPU shares that GPU's array: calls that overlap in time on one
+ * GPU (two streams, two threads) race; calls on one stream are ordered by the stream.  Nothing has to be
+ * cleared between calls.  Adds EET_ERR_CAPACITY when eet_op_attention_decode_scratch_bytes(batch, heads, d,
+ * capacity) exceeds the array (it never does for d <= 128: the split count keeps it below 300 KB). */
+#define EET_STATIC_SCRATCH_BYTES (512 * 1024)
+int eet_op_attention_decode_static(const void *q, const void *k_cache, const void *v_cache, void *ctx,
+                                   const int32_t *n_keys, int32_t batch, int32_t heads, int32_t d,
+                                   int32_t capacity, void *hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Dynamic buffer manager (Section 3.2): the result buffers of operators that are not fused are
  * requested by size and marked idle when no longer needed; the manager decides what to reuse.

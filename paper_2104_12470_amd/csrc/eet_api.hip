@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "kernels.hpp"
@@ -1062,3 +1063,59 @@ int eet_op_attention_decode(const void* q, const void* k_cache, const void* v_ca
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------------
+// decode attention for callers that cannot allocate
+// ------------------------------------------------------------------------------------------------
+// The partial results of a split key range live in a device array that is part of the library's code object instead
+// of caller memory: every GPU the library runs on holds its own copy, at its own address, until the process ends.
+// `scratch` below is only the host-side name of that array: its device address is looked up once per device
+// (hipGetSymbolAddress, with that device current) and kept; host code passes the looked-up pointer, never the name.
+constexpr size_t kStaticScratchBytes = EET_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device; looked up on the first call per device.
+int static_scratch(const char* who, void** out) {
+    int dev = -1;
+    const hipError_t eg = hipGetDevice(&dev);
+    if (eg != hipSuccess) return hip_fail(eg, who);
+    if (dev < 0 || dev >= kMaxDevices) return fail(EET_ERR_UNSUPPORTED_SHAPE, "%s: device index %d beyond %d", who, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "address of the library's scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return EET_OK;
+}
+}  // namespace
+
+extern "C" int eet_op_attention_decode_static(const void* q, const void* k_cache, const void* v_cache, void* ctx,
+                                              const int32_t* n_keys, int32_t batch, int32_t heads, int32_t d,
+                                              int32_t capacity, void* hip_stream) {
+    const char* who = "eet_op_attention_decode_static";
+    if (const int rc = check_attention_decode(who, q, k_cache, v_cache, ctx, n_keys, batch, heads, d, capacity)) return rc;
+    const int splits = attention_decode_splits(batch, heads, capacity);
+    const size_t need = attention_decode_scratch_bytes(batch, heads, d, splits);
+    if (need > kStaticScratchBytes)
+        return fail(EET_ERR_CAPACITY, "%s: %zu bytes of partial results exceed the library's %zu-byte scratch array "
+                    "(use eet_op_attention_decode with a scratch buffer of your own)", who, need, kStaticScratchBytes);
+    void* ptr = nullptr;
+    if (const int rc = static_scratch(who, &ptr)) return rc;
+    AttnDecodeArgs a{};
+    a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
+    a.lens = n_keys; a.len_bias = 0; a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity;
+    a.splits = splits;
+    // every slot the merge reads is written by the attention launch in front of it: nothing has to start at zero
+    a.part_acc = static_cast<float*>(ptr);
+    a.part_ml = a.part_acc + (size_t)batch * heads * splits * d;
+    EET_LAUNCH(launch_attention_decode(a, (hipStream_t)hip_stream), "decode attention");
+    return EET_OK;
+}

@@ -106,6 +106,7 @@ def lib() -> C.CDLL:
             "eet_op_attention_unfused": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp, i32, vp]),
             "eet_op_attention_decode_scratch_bytes": (sz, [i32, i32, i32, i32]),
             "eet_op_attention_decode": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
+            "eet_op_attention_decode_static": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]),
             "eet_model_workspace_bytes": (sz, [cfgp, C.POINTER(ModelConfig)]),
             "eet_model_create": (i32, [vp, cfgp, C.POINTER(ModelConfig), C.POINTER(ModelWeights), vp, C.POINTER(vp)]),
             "eet_model_prefill": (i32, [vp, i32p, i32, i32, vp, vp, vp, vp, vp]),
@@ -136,7 +137,7 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
            "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
-           "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_bufmgr_create", "eet_bufmgr_request",
+           "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_op_attention_decode_static", "eet_bufmgr_create", "eet_bufmgr_request",
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
            "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
            "eet_op_embedding_decode", "eet_op_argmax", "eet_stack_prefill_left_padded", "eet_model_prefill_left_padded",
@@ -337,6 +338,13 @@ def eet_op_attention_decode(q, k_cache, v_cache, ctx, n_keys, scratch, stream=No
     assert n_keys.dtype == torch.int32 and n_keys.is_cuda
     _check(lib().eet_op_attention_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _ptr(n_keys), B, nh, d,
                                          cap, _ptr(scratch), _stream(stream)))
+
+
+def eet_op_attention_decode_static(q, k_cache, v_cache, ctx, n_keys, stream=None) -> None:
+    B, nh, cap, d = k_cache.shape
+    assert n_keys.dtype == torch.int32 and n_keys.is_cuda
+    _check(lib().eet_op_attention_decode_static(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(ctx), _ptr(n_keys), B, nh, d,
+                                                cap, _stream(stream)))
 
 
 def eet_op_embedding(ids, q_lens, wte, wpe, out, vocab: Optional[int] = None, stream=None) -> None:
