@@ -6,7 +6,11 @@ whole-prompt prefill through every layer, then every incremental decode step thr
 layer (K/V caches filled by the prefill and extended by each step).  Inputs, weights and caches
 are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5b] [--also cfg2,cfg3,cfg4,cfg5a]
+
+The line's metric, value and roofline are those of --workload (default: cfg5b, the largest configuration, where the
+60 % HBM / 50 % MFMA targets are defined); the workloads of --also are timed the same way, with fewer passes, and
+reported under "other_workloads" in the same line, each with its own roofline records.
 """
 from __future__ import annotations
 
@@ -23,43 +27,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
 
-# HBM bytes per launch from the last `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of
-# `bench.py --roofline-only` (counters scaled by the plain copy kernel of the same run: x 2.000 and
-# x 1.000; summary in profiles/cfg2_hbm_traffic_counters.txt), keyed by workload and by the start of
-# the record's kernel name.  Workloads that were not profiled report null.
-MEASURED_TRAFFIC = {
-    "cfg2": {
-        "attn_decode<64, 4>": 21.44e6,
-        "decode FFN-2 projection": 9.13e6,
-        "decode attention output projection": 2.35e6,
-        "prefill FFN-1 projection": 74.73e6,
-        "attn_prefill<64, true>": 25.89e6,
-        "layernorm_wave": 12.99e6,
-        "embed_tokens": 16.10e6,
-        "decode output projection over the vocabulary": 104.55e6,
-        "argmax_rows": 0.863e6,
-        "softmax_maskfree_vec": 75.65e6,
-    },
-}
+PROFILES = os.path.join(ROOT, "profiles")
 
 
-# Average duration of the same kernel's launches INSIDE the timed pass, from the last `rocprofv3 --kernel-trace` run of
-# the workload's bench command (cfg2: profiles/cfg2_whole_pass_kernel_trace.txt).  The live figure above times launches of the
-# operator on its own, back to back; inside a decode step of a small layer the preceding FFN-2 launch has already
-# pulled the K/V rows towards the memory-side cache, so the same kernel runs faster there.  Reported beside the live
-# figure, never instead of it.
-IN_PASS_LAUNCH_US = {
-    "cfg2": {"attn_decode<64, 4>": (5.19,
-             "live figure: the operator launched on its own, operands cold.  Inside a decode step the extra "
-             "workgroups of the preceding FFN-2 launch fetch this kernel's K/V rows ahead of it, so part of its "
-             "fetch time shows up there in a kernel trace of the pass (FFN-2 7.7 us instead of 5.2, this kernel "
-             "5.2-5.5 instead of 8.0)")},
-    # profiles/cfg3_cfg5a_cfg4_bert1024_whole_pass_kernel_trace.txt
-    "cfg4": {"attn_decode<128, 4>": (9.35,
-             "live figure: the operator, whose 8 key ranges per (sequence, head) are merged by a second launch "
-             "(attn_decode_combine, about 4 us).  Inside a decode step of the layer the output projection merges the "
-             "ranges while it loads its activations, so there the attention is this one kernel")},
-}
+def profiled_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 hardware counters (two --pmc runs, FETCH_SIZE and WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size), read from the committed summary
+    profiles/<workload>_hbm_traffic_counters.txt: lines of the form
+        traffic | <start of the record's kernel name> | <bytes per launch>
+    and one line `measured: <commit, date, command>`.  Returns ({prefix: bytes}, source string); workloads without a
+    summary report null.  Nothing here is measured by this run: the record says where the figure comes from."""
+    path = os.path.join(PROFILES, f"{workload}_hbm_traffic_counters.txt")
+    table, measured = {}, ""
+    if os.path.exists(path):
+        for line in open(path):
+            parts = [t.strip() for t in line.split("|")]
+            if len(parts) == 3 and parts[0] == "traffic":
+                try:
+                    table[parts[1]] = float(parts[2])
+                except ValueError:
+                    pass
+            elif line.startswith("measured:"):
+                measured = line[len("measured:"):].strip()
+    return table, (f"profiles/{os.path.basename(path)}" + (f" ({measured})" if measured else "")) if table else None
 
 
 def parse():
@@ -67,7 +57,9 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=3)
     p.add_argument("--warmup", type=int, default=1)
-    p.add_argument("--workload", default="cfg2")
+    p.add_argument("--workload", default="cfg5b")
+    p.add_argument("--also", default="cfg2,cfg3,cfg4,cfg5a",
+                   help="comma-separated workloads reported under other_workloads (two timed passes each); '' for none")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--model", action="store_true",
                    help="run the pass through the model entry points (embedding, the stack, final LayerNorm, output "
@@ -84,14 +76,13 @@ class Stack:
     """The workload's layers behind the stack entry points (one call per prefill, one per decode
     step; decode steps are replayed from a HIP graph recorded by the library), on its own stream."""
 
-    def __init__(self, w, eet, torch, wl, use_graph=True):
+    def __init__(self, w, eet, torch, wl, use_graph=True, device_weights=None):
         self.w, self.eet, self.torch = w, eet, torch
         cfg = eet.make_config(w.hidden, w.heads, w.ffn, w.batch, w.padded_len, w.max_seq, w.ln_eps)
-        weights = []
-        for li in range(w.layers):
-            W = wl.layer_weights(w, li)
-            weights.append({k: torch.from_numpy(v) for k, v in W.items()})
-        self.stack = eet.DecoderStack(cfg, weights, use_graph=use_graph)
+        if device_weights is None:        # fp16 weights of every layer, uploaded once
+            device_weights = [{k: torch.from_numpy(v).to("cuda:0") for k, v in wl.layer_weights(w, li).items()}
+                              for li in range(w.layers)]
+        self.stack = eet.DecoderStack(cfg, device_weights, use_graph=use_graph)
         self.n_layers = w.layers
         self.lens = [int(v) for v in wl.lengths(w)]
         dev = "cuda:0"
@@ -225,11 +216,12 @@ def time_launches(torch, fn, calls, replays=5):
     return e0.elapsed_time(e1) / (replays * calls)
 
 
-def _kernel_candidates(stack, torch, eet, reps):
+def _kernel_candidates(stack, torch, eet, reps, full=True):
     """Time the kernels that can dominate a pass, each through its operator-level entry point on
     the stack's own weights and caches, cycling over the layers so that nothing is served from a
     cache the real pass would not have.  Returns a list of records with the algorithmic bytes or
-    flops of one launch, the average launch duration and the launches per pass."""
+    flops of one launch, the average launch duration and the launches per pass.  full = False leaves
+    out the operators that are not on the layer's path (stand-alone softmax, add-bias kernels, model head)."""
     w = stack.w
     B, H, F, nl = w.batch, w.hidden, w.ffn, stack.n_layers
     d = H // w.heads
@@ -275,18 +267,29 @@ def _kernel_candidates(stack, torch, eet, reps):
                         "launches": w.decode_steps * nl})
         projection("FFN-2 projection", "w_fc2", "b_fc2", H, F)
         projection("attention output projection", "w_o", "b_o", H, H)
-    # (3) prefill projection on the matrix cores: FFN-1 over all valid tokens
+    # (3) prefill projections on the matrix cores, all valid tokens: the four shapes of a layer (the QKV shape through
+    # the plain-bias epilogue: the cache scatter exists only inside the layer call)
     xp = torch.randn(T, H, device="cuda:0").half()
     yp = torch.empty(T, F, device="cuda:0", dtype=torch.float16)
+    yq = torch.empty(T, 3 * H, device="cuda:0", dtype=torch.float16)
+    yh = torch.empty(T, H, device="cuda:0", dtype=torch.float16)
+    rh = torch.randn(T, H, device="cuda:0").half()
     st3 = {"i": 0}
 
-    def run_pre():
-        wts = stack.weights(st3["i"] % nl)
-        st3["i"] += 1
-        eet.eet_op_linear(xp, wts["w_fc1"], wts["b_fc1"], yp, act=1)
-    ms = time_launches(torch, run_pre, max(4, min(reps, 24)), replays=2)
-    out.append({"kernel": "prefill FFN-1 projection + bias + GELU (MFMA tile kernel)", "bound": "mfma",
-                "work": 2.0 * T * H * F, "ms": ms, "launches": nl})
+    def prefill_projection(name, wkey, bkey, x, y, n_out, n_in, act=0, residual=None):
+        def run():
+            wts = stack.weights(st3["i"] % nl)
+            st3["i"] += 1
+            eet.eet_op_linear(x, wts[wkey], wts[bkey], y, residual=residual, act=act)
+        ms = time_launches(torch, run, max(4, min(reps, 24)), replays=2)
+        out.append({"kernel": f"prefill {name} (MFMA tile kernel, {T} x {n_out} x {n_in})", "bound": "mfma",
+                    "work": 2.0 * T * n_out * n_in, "ms": ms, "launches": nl})
+    prefill_projection("FFN-1 projection + bias + GELU", "w_fc1", "b_fc1", xp, yp, F, H, act=1)
+    yp.normal_()                                    # FFN-2 reads what FFN-1 wrote: keep it finite and O(1)
+    prefill_projection("FFN-2 projection + bias + residual", "w_fc2", "b_fc2", yp, yh, H, F, residual=rh)
+    prefill_projection("QKV-shaped projection + bias", "w_qkv", "b_qkv", xp, yq, 3 * H, H)
+    prefill_projection("attention output projection + bias + residual", "w_o", "b_o", xp, yh, H, H, residual=rh)
+    del yq
     # (4) prefill attention: QK^T and PV over the valid causal triangle of every sequence
     qp = torch.randn(B, w.padded_len, H, device="cuda:0").half()
     cp = torch.empty_like(qp)
@@ -314,6 +317,8 @@ def _kernel_candidates(stack, torch, eet, reps):
     lname = "layernorm_wave" if H % 8 == 0 and H <= 2048 and T >= 64 else "layernorm_cached"      # the library's own choice
     out.append({"kernel": f"{lname}: LayerNorm over the valid prompt rows (row kernel)", "bound": "hbm",
                 "work": 4.0 * T * H + 4.0 * H, "ms": ms, "launches": 2 * nl})
+    if not full:
+        return out
     # (6) stand-alone mask-free softmax (Algorithm 1) over [B, heads', S, S] scores, in place: the valid
     # causal triangle is read and written, the strip i < j < S of valid rows is zero-filled.  Not on the
     # layer's path (the fused attention never materialises scores): measured for its own roofline row,
@@ -326,6 +331,21 @@ def _kernel_candidates(stack, torch, eet, reps):
     out.append({"kernel": f"softmax_maskfree_vec: stand-alone mask-free softmax (Algorithm 1), {nh} head(s), not on the layer path",
                 "bound": "hbm", "work": nh * (2.0 * 2 * tri + 2.0 * sum(L * S - L * (L + 1) / 2 for L in stack.lens)),
                 "ms": ms, "launches": 0})
+    # (6b) stand-alone add-bias + GELU over [T, F] rows and add-bias + residual over [T, H] rows (the kernels the paper
+    # runs between its library GEMM calls; here they are epilogues, so these launches are not on the layer path):
+    # 4F resp. 6H bytes per token (+ the bias row)
+    del sc
+    yp.normal_()
+    go = torch.empty_like(yp)
+    ms = time_launches(torch, lambda: eet.eet_op_bias_gelu(yp, stack.weights(0)["b_fc1"], go), max(4, min(reps, 16)), replays=2)
+    out.append({"kernel": f"bias_act_vec<false>: stand-alone add-bias + GELU over {T} rows of {F}, not on the layer path",
+                "bound": "hbm", "work": 4.0 * T * F + 2.0 * F, "ms": ms, "launches": 0})
+    del go
+    ro = torch.empty_like(rh)
+    ms = time_launches(torch, lambda: eet.eet_op_bias_residual(xp, stack.weights(0)["b_o"], rh, ro), max(4, min(reps, 16)), replays=2)
+    out.append({"kernel": f"bias_act_vec<true>: stand-alone add-bias + residual over {T} rows of {H}, not on the layer path",
+                "bound": "hbm", "work": 6.0 * T * H + 2.0 * H, "ms": ms, "launches": 0})
+    del ro
     # (7) the operators around the stack at GPT-2's vocabulary (50257, padded to 50304 columns): not on the layer pass
     # that the metric counts, measured for their own roofline rows.  Skipped where the table would pass 512 MB.
     V, Vp = 50257, 50304
@@ -356,26 +376,22 @@ def _kernel_candidates(stack, torch, eet, reps):
     return out
 
 
-def roofline_for(stack, torch, eet, reps):
-    """Roofline record of the dominant kernel (largest share of the pass) and of the others."""
+def roofline_for(stack, torch, eet, reps, full=True):
+    """Roofline record of the dominant kernel (largest share of the pass) and of the others.  `achieved` divides the
+    algorithmic work of one launch by the launch duration measured live in this run; `traffic` is the profiled HBM bytes
+    per launch from the committed counter summary of the workload (null when there is none), with its source."""
     recs = []
-    measured = MEASURED_TRAFFIC.get(stack.w.name, {})
-    in_pass = IN_PASS_LAUNCH_US.get(stack.w.name, {})
-    for c in _kernel_candidates(stack, torch, eet, reps):
+    measured, source = profiled_traffic(stack.w.name)
+    for c in _kernel_candidates(stack, torch, eet, reps, full):
         if c["bound"] == "hbm":
             ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
             ach, peak, unit = c["work"] / (c["ms"] * 1e-3) / 1e12, MFMA_FP16_PEAK_TFLOPS, "TFLOP/s"
+        traffic = next((v for k, v in measured.items() if c["kernel"].startswith(k)), None)
         recs.append({"kernel": c["kernel"], "bound": c["bound"], "achieved": ach, "peak": peak, "unit": unit,
-                     "frac": ach / peak,
-                     "traffic": next((v for k, v in measured.items() if c["kernel"].startswith(k)), None),
+                     "frac": ach / peak, "traffic": traffic, "traffic_source": source if traffic is not None else None,
                      "avg_launch_us": c["ms"] * 1e3,
                      "algorithmic_work_per_launch": c["work"], "share_ms_per_pass": c["ms"] * c["launches"]})
-        prof = next((v for k, v in in_pass.items() if c["kernel"].startswith(k)), None)
-        if prof is not None:    # same work per launch, the profiled in-pass duration
-            recs[-1]["in_pass_avg_launch_us_profiled"] = prof[0]
-            recs[-1]["in_pass_frac_profiled"] = c["work"] / (prof[0] * 1e-6) / 1e9 / peak
-            recs[-1]["note"] = prof[1]
     recs.sort(key=lambda r: -r["share_ms_per_pass"])
     return recs[0], recs[1:]
 
@@ -398,12 +414,18 @@ def cpu_baseline(w, wl, budget_s=25.0, min_s=10.0):
     import numpy as np
 
     from oracle import eet_oracle as orc
+    flop_budget = 1.5e12                                          # about ten seconds of float64 matrix products per layer
     lens_all = wl.lengths(w)
     flops_seq = 24.0 * lens_all.astype(np.float64) * w.hidden * w.hidden
     nseq = 1
-    while nseq < w.batch and flops_seq[: nseq + 1].sum() <= 1.5e12:
+    while nseq < w.batch and flops_seq[: nseq + 1].sum() <= flop_budget:
         nseq += 1
-    lens = lens_all[:nseq]
+    lens = lens_all[:nseq].copy()
+    cut = ""
+    if flops_seq[0] > flop_budget:        # one prompt alone is beyond the budget: its causal prefix is a smaller prompt of the same kind
+        keep = max(64, int(flop_budget / (24.0 * w.hidden * w.hidden)) // 64 * 64)
+        cut = f", prompt cut to its first {keep} of {int(lens[0])} tokens"
+        lens[0] = keep
     weights = [{k: v.astype(np.float64) for k, v in wl.layer_weights(w, li).items()} for li in range(min(w.layers, 4))]
     x = wl.prompt_embeddings(w)[:nseq]
     dec = [wl.decode_embeddings(w, k)[:nseq] for k in range(w.decode_steps)]
@@ -430,8 +452,39 @@ def cpu_baseline(w, wl, budget_s=25.0, min_s=10.0):
     return {"value": per_layer_tokens / (total / layers_done * w.layers), "unit": "tokens/s",
             "cores": min(cores, nthreads), "kind": "oracle",
             "sample": f"float64 oracle, {layers_done} of {w.layers} layer(s) (time per layer scaled by {w.layers}), "
-                      f"{nseq} of {w.batch} sequences (lengths {lens.tolist()}), prefill + {steps_done[0]} of "
+                      f"{nseq} of {w.batch} sequences (lengths {lens.tolist()}{cut}), prefill + {steps_done[0]} of "
                       f"{w.decode_steps} decode steps each; {total:.1f} s of CPU work, {tokens} layer-tokens"}
+
+
+def workload_text(w, model=False):
+    return (f"{w.name}: {w.layers} layer(s), hidden {w.hidden}, heads {w.heads}, ffn {w.ffn}, batch {w.batch}, prompts "
+            f"{w.len_lo}-{w.len_hi} padded to {w.padded_len}, {w.decode_steps} decode steps, cache {w.max_seq}" +
+            (f"; through the model entry points: token ids in, embedding, final LayerNorm, output projection over "
+             f"{ModelStack.VOCAB} tokens and greedy choice per step, fed back on the device" if model else ""))
+
+
+def measure(stack, a, torch, eet, steps, warmup, full):
+    """Whole-pass timing (host clock around `steps` passes, everything resident), phase split (HIP events on the launch
+    stream) and per-kernel roofline records of one workload."""
+    w = stack.w
+    tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
+    for _ in range(warmup):
+        stack.one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        stack.one_pass()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_prefill = time_region(torch, stack.prefill, 2, stack.stream)
+    ms_decode = time_region(torch, stack.decode, 1, stack.stream) if w.decode_steps else 0.0
+    rec = {"value": tokens / (dt / steps), "unit": "tokens/s", "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3,
+           "config": {"workload": workload_text(w, a.model), "valid_tokens_per_step": tokens, "prefill_tokens": sum(stack.lens),
+                      "decode_tokens": w.batch * w.decode_steps, "prefill_ms": ms_prefill, "decode_ms": ms_decode,
+                      "prefill_tokens_per_s": sum(stack.lens) / (ms_prefill * 1e-3),
+                      "decode_tokens_per_s": (w.batch * w.decode_steps) / (ms_decode * 1e-3) if ms_decode else None}}
+    rec["roofline"], rec["roofline_other_kernels"] = roofline_for(stack, torch, eet, a.kernel_reps, full)
+    return rec
 
 
 def main():
@@ -451,10 +504,20 @@ def main():
     if a.model and (w.encoder or not w.decode_steps):
         print("bench.py: --model needs a decoder workload with decode steps", file=sys.stderr)
         sys.exit(2)
-    stack = EncoderStack(w, eet, torch, wl) if w.encoder else \
-        (ModelStack if a.model else Stack)(w, eet, torch, wl, use_graph=not a.no_graph)
-    tokens = sum(stack.lens) + w.batch * w.decode_steps       # valid tokens only
+    shared = {}                              # device weights by (seed, shape): cfg5a and cfg5b are one layer on two batches
 
+    def build(wk, model=False):
+        if wk.encoder:
+            return EncoderStack(wk, eet, torch, wl)
+        if model:
+            return ModelStack(wk, eet, torch, wl, use_graph=not a.no_graph)
+        key = (wk.seed, wk.hidden, wk.heads, wk.ffn, wk.layers, wk.sigma_w)
+        if key not in shared:
+            shared[key] = [{k: torch.from_numpy(v).to("cuda:0") for k, v in wl.layer_weights(wk, li).items()}
+                           for li in range(wk.layers)]
+        return Stack(wk, eet, torch, wl, use_graph=not a.no_graph, device_weights=shared[key])
+
+    stack = build(w, a.model)
     if a.roofline_only:
         stack.one_pass() if w.decode_steps <= 64 else stack.prefill()   # caches hold real keys/values
         # plain copy kernel of known size under a name nothing else in the run uses: x + 0 over
@@ -464,42 +527,33 @@ def main():
         torch.add(src, 0, out=dst)
         torch.cuda.synchronize()
         main_rec, others = roofline_for(stack, torch, eet, a.kernel_reps)
-        print(json.dumps({"roofline": main_rec, "roofline_other_kernels": others, "copy_bytes": 256 << 20}))
+        print(json.dumps({"workload": w.name, "roofline": main_rec, "roofline_other_kernels": others, "copy_bytes": 256 << 20}))
         return
 
-    for _ in range(a.warmup):
-        stack.one_pass()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        stack.one_pass()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / a.steps * 1e3
-
-    # phase split (informative): prefill alone and decode alone, HIP events
-    ms_prefill = time_region(torch, stack.prefill, 2, stack.stream)
-    ms_decode = time_region(torch, stack.decode, 1, stack.stream) if w.decode_steps else 0.0
-
+    m = measure(stack, a, torch, eet, a.steps, a.warmup, full=True)
     rec = {
         "metric": ("encoder-layer tokens/s (one pass, no sequence mask) fp16; % of HBM/MFMA roofline" if w.encoder else
                    "decoder-layer tokens/s (prefill+decode) fp16; % of HBM/MFMA roofline"),
-        "value": tokens / (dt / a.steps), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.layers} layer(s), hidden {w.hidden}, heads {w.heads}, ffn {w.ffn}, "
-                               f"batch {w.batch}, prompts {w.len_lo}-{w.len_hi} padded to {w.padded_len}, "
-                               f"{w.decode_steps} decode steps, cache {w.max_seq}" +
-                               (f"; through the model entry points: token ids in, embedding, final LayerNorm, output projection "
-                                f"over {ModelStack.VOCAB} tokens and greedy choice per step, fed back on the device" if a.model else ""),
-                   "valid_tokens_per_step": tokens, "prefill_tokens": sum(stack.lens),
-                   "decode_tokens": w.batch * w.decode_steps,
-                   "prefill_ms": ms_prefill, "decode_ms": ms_decode,
-                   "prefill_tokens_per_s": sum(stack.lens) / (ms_prefill * 1e-3),
-                   "decode_tokens_per_s": (w.batch * w.decode_steps) / (ms_decode * 1e-3) if ms_decode else None},
+        "value": m["value"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic", "config": m["config"],
+        "roofline": m["roofline"], "roofline_other_kernels": m["roofline_other_kernels"],
     }
-    rec["roofline"], rec["roofline_other_kernels"] = roofline_for(stack, torch, eet, a.kernel_reps)
     rec["hbm_reference"] = hbm_reference(torch)
+    del stack
+    torch.cuda.empty_cache()
+    # the other workloads, same measurement, two timed passes each
+    others = {}
+    for name in [n for n in a.also.split(",") if n and n != a.workload]:
+        wk = wl.WORKLOADS[name]
+        st = build(wk)
+        others[name] = measure(st, a, torch, eet, 2, 1, full=False)
+        del st
+        torch.cuda.empty_cache()
+    if others:
+        rec["other_workloads"] = others
+    shared.clear()
+    torch.cuda.empty_cache()
     if not a.no_cpu_baseline and not a.model:      # the timed oracle sample is the layer stack's, not the model's
         rec["cpu_baseline"] = cpu_baseline(w, wl)
     print(json.dumps(rec))
