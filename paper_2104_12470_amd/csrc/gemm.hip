@@ -96,22 +96,23 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
 // --------------------------------------------------------------------------------------------
 // The accumulator layout gives a lane one row and 4 consecutive columns: stored like that, a wave-level store
 // touches 32 rows with 16 bytes each, and the output (as large as an operand) leaves the chip at a fraction of
-// the memory rate.  Instead each wave turns its (FM*32) x 64 tile around in a private piece of the operand
+// the memory rate.  Instead each wave turns its (AM*16) x 64 tile around in a private piece of the operand
 // stages, which are free after the main loop: the residual tile comes in with whole-line loads, the epilogue
 // arithmetic runs in fp32 on the accumulators, the rounded tile goes out with whole-line stores (8 rows x 128
 // bytes per instruction).  Rows are 128 bytes; their sixteen 8-byte units are XOR-permuted by (row/2)%16 so that
-// both access patterns spread over all banks.  `stage`: FM*32*128 bytes of LDS no other wave touches; mw, nw:
+// both access patterns spread over all banks.  `stage`: AM*16*128 bytes of LDS no other wave touches; mw, nw:
 // first row and column of the wave tile (its 64 columns are inside N or outside as a whole: N % 64 == 0).
-template <int FM, int FN, int EPI>
-__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float16v (&acc)[FM][FN], char* stage, int mw, int nw,
+template <int AM, int AN, int EPI>
+__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][AN], char* stage, int mw, int nw,
                                                  int lane) {
-    static_assert(FN == 2, "64 columns per wave tile");
+    static_assert(AN == 4, "64 columns per wave tile");
+    constexpr int ROWS = AM * 16;                         // rows of the wave tile
     const int M = a.M, N = a.N;
     if (nw >= N) return;
     const int r8 = lane >> 3, c8 = lane & 7;              // whole-line pattern: row it*8 + r8, 16-byte chunk c8
     if (EPI == EPI_BIAS_RES) {
 #pragma unroll 4
-        for (int it = 0; it < FM * 4; ++it) {
+        for (int it = 0; it < ROWS / 8; ++it) {
             const int row = it * 8 + r8, m = mw + row;
             if (m < M) {
                 const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
@@ -122,32 +123,30 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float1
             }
         }
     }
-    // arithmetic on the accumulators: acc[i][j][rg*4 ..+4] = row i*32 + lane%32, columns j*32 + rg*8 + (lane/32)*4 ..+4
+    // arithmetic on the accumulators: acc[i][j][0..3] = row i*16 + lane%16, columns j*16 + (lane/16)*4 ..+4
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int j = 0; j < AN; ++j) {
+        const int unit = j * 4 + (lane >> 4);             // 8-byte unit of the 128-byte row
+        const half4v bias = *reinterpret_cast<const half4v*>(a.bias + nw + unit * 4);
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int unit = j * 8 + rg * 2 + (lane >> 5);
-            const half4v bias = *reinterpret_cast<const half4v*>(a.bias + nw + unit * 4);
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int row = i * 32 + (lane & 31);
-                half4v* slot = reinterpret_cast<half4v*>(stage + row * 128 + ((unit ^ ((row >> 1) & 15)) * 8));
-                float v0 = acc[i][j][rg * 4 + 0] + (float)bias[0], v1 = acc[i][j][rg * 4 + 1] + (float)bias[1];
-                float v2 = acc[i][j][rg * 4 + 2] + (float)bias[2], v3 = acc[i][j][rg * 4 + 3] + (float)bias[3];
-                if (EPI == EPI_BIAS_GELU) {
-                    v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
-                }
-                if (EPI == EPI_BIAS_RES) {
-                    const half4v r = *slot;
-                    v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
-                }
-                *slot = half4v{(half_t)v0, (half_t)v1, (half_t)v2, (half_t)v3};
+        for (int i = 0; i < AM; ++i) {
+            const int row = i * 16 + (lane & 15);
+            half4v* slot = reinterpret_cast<half4v*>(stage + row * 128 + ((unit ^ ((row >> 1) & 15)) * 8));
+            float v0 = acc[i][j][0] + (float)bias[0], v1 = acc[i][j][1] + (float)bias[1];
+            float v2 = acc[i][j][2] + (float)bias[2], v3 = acc[i][j][3] + (float)bias[3];
+            if (EPI == EPI_BIAS_GELU) {
+                v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
             }
+            if (EPI == EPI_BIAS_RES) {
+                const half4v r = *slot;
+                v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
+            }
+            *slot = half4v{(half_t)v0, (half_t)v1, (half_t)v2, (half_t)v3};
         }
+    }
     // whole lines out
 #pragma unroll 4
-    for (int it = 0; it < FM * 4; ++it) {
+    for (int it = 0; it < ROWS / 8; ++it) {
         const int row = it * 8 + r8, m = mw + row;
         if (m >= M) continue;
         const int sw = (row >> 1) & 15;
@@ -232,19 +231,29 @@ __device__ __forceinline__ void wait_vm() {
 // The instructions of the tile kernel's K loop.  The loop itself -- which stage is loaded, read, waited for and released
 // when -- is pipe::gemm_k_loop (pipeline.hpp), shared with the host-side audit of the hand-over; this executor supplies the
 // instructions, all forced inline.  (Namespace scope because a local class cannot have member templates.)
-template <int BM, int BN, int NW, int NS, int KS, int FM, int FN>
+//
+// Matrix instruction: v_mfma_f32_16x16x32_f16.  Under this part's power management the 16x16x32 form sustains about a
+// sixth more than 32x32x16 (measured with bare loops of either: 2.08 against 1.79 PFLOP/s over tens of milliseconds): per
+// flop it reads and writes half the accumulator registers.  Weights are the A operand (16 output columns x 32 k), the
+// activations the B operand (32 k x 16 rows): a lane holds 4 consecutive output columns of one row.
+// A wave tile of WM x 64 is AM = WM/16 by AN = 4 accumulator blocks.  A K tile of 64 is walked in four sub-steps
+// s = 2h + mh: k half h (32 columns) times row half mh (AM/2 blocks).  The weight fragments of a k half (AN reads of 16
+// bytes per lane) serve both row halves and are read with the first; every sub-step reads AM/2 activation fragments; both
+// kinds are double-buffered in registers, so the reads of sub-step s+1 fly during the AM/2 * AN multiplies of sub-step s.
+template <int BM, int BN, int NW, int NS, int KS, int AM, int AN>
 struct GemmTileExec {
-    static constexpr int BK = 64;
+    static constexpr int BK = 64, AH = AM / 2;
     static constexpr int LRA = BM / NW, LRW = BN / NW, LIA = LRA / 8, LIW = LRW / 8;
+    static_assert(AM % 2 == 0 && AH >= 1 && AH <= 4 && AN == 4, "wave tile shape");
     const half_t* pa[LIA];                 // this lane's source of each load instruction, K tile 0
     const half_t* pw[LIW];
     half_t* as_base;                       // stage 0 of this wave's K group: As[kg * NS], Ws[kg * NS]
     half_t* ws_base;
-    unsigned a_lds, w_lds;                 // LDS byte address of this lane's fragment row in stage 0
-    unsigned foff[4];                      // byte offset of sub-step s inside the (permuted) row
+    unsigned a_lds, w_lds;                 // LDS byte address of row lane%16 of the wave tile's first block, stage 0
+    unsigned foff[2];                      // byte offset of this lane's 16 bytes of k half h inside the (permuted) row
     int kg, wave;
-    half8v fa[2][FM], fw[2][FN];
-    float16v acc[FM][FN];
+    half8v fa[2][AH], fw[2][AN];           // fa[s & 1]: activations of sub-step s; fw[h & 1]: weights of k half h
+    float4v acc[AM][AN];
 
     __device__ __forceinline__ void load(int tile, int stage) {
 #pragma unroll
@@ -254,57 +263,114 @@ struct GemmTileExec {
         for (int v = 0; v < LIW; ++v)
             load_lds_16B(pw[v] + (int64_t)(tile * KS + kg) * BK, ws_base + stage * (BN * BK) + (wave * LRW + v * 8) * BK);
     }
-    __device__ __forceinline__ void wait_loads_all() { wait_vm<0>(); }
-    __device__ __forceinline__ void wait_loads_but_newest() { wait_vm<LIA + LIW>(); }
+    template <int L>
+    __device__ __forceinline__ void wait_vmem() {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L * (LIA + LIW)) : "memory");
+    }
     __device__ __forceinline__ void barrier() { __builtin_amdgcn_s_barrier(); }
-#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=&v"(DST) : "v"(ADDR) : "memory")
+    // LDS reads of sub-step SUB: 16 bytes per lane per fragment, blocks 2 KB apart
+    static constexpr int reads_of(int sub) { return AH + ((sub & 1) == 0 ? AN : 0); }
+#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(DST) : "v"(ADDR), "n"(OFF) : "memory")
     template <int BUF, int SUB>
     __device__ __forceinline__ void frag(int stage) {
-        const unsigned va_ = a_lds + stage * (BM * BK * 2) + foff[SUB];
-        const unsigned vw_ = w_lds + stage * (BN * BK * 2) + foff[SUB];
-        EET_DREAD(fa[BUF][0], va_, 0);
-        if (FM > 1) EET_DREAD(fa[BUF][1 % FM], va_, 4096);
-        if (FM > 2) EET_DREAD(fa[BUF][2 % FM], va_, 8192);
-        if (FM > 3) EET_DREAD(fa[BUF][3 % FM], va_, 12288);
-        EET_DREAD(fw[BUF][0], vw_, 0);
-        if (FN > 1) EET_DREAD(fw[BUF][1 % FN], vw_, 4096);
-        if (FN > 2) EET_DREAD(fw[BUF][2 % FN], vw_, 8192);
-        if (FN > 3) EET_DREAD(fw[BUF][3 % FN], vw_, 12288);
+        static_assert(BUF == (SUB & 1), "activation buffer of a sub-step");
+        constexpr int H = SUB >> 1, MH = SUB & 1;
+        const unsigned va_ = a_lds + stage * (BM * BK * 2) + foff[H];
+        EET_DREAD(fa[BUF][0], va_, (MH * AH + 0) * 2048);
+        if (AH > 1) EET_DREAD(fa[BUF][1 % AH], va_, (MH * AH + 1) * 2048);
+        if (AH > 2) EET_DREAD(fa[BUF][2 % AH], va_, (MH * AH + 2) * 2048);
+        if (AH > 3) EET_DREAD(fa[BUF][3 % AH], va_, (MH * AH + 3) * 2048);
+        if (MH == 0) {
+            const unsigned vw_ = w_lds + stage * (BN * BK * 2) + foff[H];
+            EET_DREAD(fw[H][0], vw_, 0);
+            EET_DREAD(fw[H][1], vw_, 2048);
+            EET_DREAD(fw[H][2], vw_, 4096);
+            EET_DREAD(fw[H][3], vw_, 6144);
+        }
     }
 #undef EET_DREAD
-    // `newer`: frag() calls issued after the one being waited for (FM + FN reads each) that may stay in flight
-    template <int BUF>
-    __device__ __forceinline__ void wait_frag(int newer) {
-        if (newer) wait_lgkm<FM + FN>(); else wait_lgkm<0>();
+    // The reads of sub-step SUB have landed; those of sub-step NEWER (issued after them; -1: none) may stay in flight.
+    template <int BUF, int SUB, int NEWER>
+    __device__ __forceinline__ void wait_frag() {
+        static_assert(BUF == (SUB & 1), "activation buffer of a sub-step");
+        asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(NEWER < 0 ? 0 : reads_of(NEWER & 3)) : "memory");
 #pragma unroll
-        for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(fa[BUF][i]));      // the fragments are defined from here on
+        for (int i = 0; i < AH; ++i) asm volatile("" : "+v"(fa[BUF][i]));      // the fragments are defined from here on
+        if ((SUB & 1) == 0) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(fw[BUF][j]));
+            for (int j = 0; j < AN; ++j) asm volatile("" : "+v"(fw[SUB >> 1][j]));
+        }
     }
-    template <int BUF>
-    __device__ __forceinline__ void mma() {
+    // ---- the two-group schedule (pipe::gemm_k_loop_pingpong): a whole k half at a time, single-buffered ----------
+    __device__ __forceinline__ bool second_group() const { return wave >= NW / 2; }
+#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(DST) : "v"(ADDR), "n"(OFF) : "memory")
+    template <int H>
+    __device__ __forceinline__ void read_half(int stage) {
+        const unsigned vw_ = w_lds + stage * (BN * BK * 2) + foff[H];
+        EET_DREAD(fw[0][0], vw_, 0);
+        EET_DREAD(fw[0][1], vw_, 2048);
+        EET_DREAD(fw[0][2], vw_, 4096);
+        EET_DREAD(fw[0][3], vw_, 6144);
+        const unsigned va_ = a_lds + stage * (BM * BK * 2) + foff[H];
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            EET_DREAD(fa[mh][0], va_, (mh * AH + 0) * 2048);
+            if (AH > 1) EET_DREAD(fa[mh][1 % AH], va_, (mh * AH + 1) * 2048);
+            if (AH > 2) EET_DREAD(fa[mh][2 % AH], va_, (mh * AH + 2) * 2048);
+            if (AH > 3) EET_DREAD(fa[mh][3 % AH], va_, (mh * AH + 3) * 2048);
+        }
+    }
+#undef EET_DREAD
+    __device__ __forceinline__ void wait_reads() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < AN; ++j) asm volatile("" : "+v"(fw[0][j]));
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+            for (int i = 0; i < AH; ++i) asm volatile("" : "+v"(fa[mh][i]));
+    }
+    template <int H>
+    __device__ __forceinline__ void mma_half() {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[BUF][j], fa[BUF][i], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < AH; ++i)
+#pragma unroll
+                for (int j = 0; j < AN; ++j)
+                    acc[mh * AH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[0][j], fa[mh][i], acc[mh * AH + i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    template <int BUF, int SUB>
+    __device__ __forceinline__ void mma() {
+        static_assert(BUF == (SUB & 1), "activation buffer of a sub-step");
+        constexpr int H = SUB >> 1, MH = SUB & 1;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < AH; ++i)
+#pragma unroll
+            for (int j = 0; j < AN; ++j)
+                acc[MH * AH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[H][j], fa[BUF][i], acc[MH * AH + i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 };
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS>
+// SCHED: 0 = the schedule of pipe::gemm_k_loop<NS>, 1 = its early-release form (two stages), 2 = two wave groups in
+// alternation (pipe::gemm_k_loop_pingpong; two stages, eight waves, one K group)
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS, int SCHED>
 __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
+    static_assert(SCHED == 0 || (NS == 2 && KS == 1 && (SCHED == 1 || WGM * WGN == 8)), "schedule");
     // KS > 1: KS groups of WGM x WGN waves share the tile and take every KS-th K step each, through LDS stages of their
     // own; the other groups' accumulators are added to the first's through LDS at the end.  For the few
     // tiles of a narrow output with a long K, where nothing else puts more loads in flight per CU.
     constexpr int NW = WGM * WGN, BK = 64;
     static_assert(NS == 2 || NS == 3, "LDS stages");
     static_assert(KS == 1 || KS == 2, "K groups");
-    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+    constexpr int WM = BM / WGM, WN = BN / WGN, AM = WM / 16, AN = WN / 16;   // wave tile in 16 x 16 accumulator blocks
     constexpr int LRA = BM / NW, LRW = BN / NW;   // rows of each operand tile a wave loads per K step
     constexpr int LIA = LRA / 8, LIW = LRW / 8;   // wave-level load instructions per operand per K step
-    static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && FM >= 1 && FM <= 4 && FN >= 1 && FN <= 4, "tile shape");
+    static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && WM % 32 == 0 && WN == 64, "tile shape");
     __shared__ __attribute__((aligned(1024))) half_t As[KS * NS][BM * BK];
     __shared__ __attribute__((aligned(1024))) half_t Ws[KS * NS][BN * BK];
 
@@ -312,13 +378,14 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     pipe::tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int kg = KS == 1 ? 0 : (tid >> 6) / NW;            // K group of this wave
-    const int wave = KS == 1 ? tid >> 6 : (tid >> 6) % NW;   // wave inside its group
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keeps LDS bases in scalar registers
+    const int kg = KS == 1 ? 0 : wv / NW;                    // K group of this wave
+    const int wave = KS == 1 ? wv : wv % NW;                 // wave inside its group
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int M = a.M, N = a.N, K = a.K;
     const int nk = K / (BK * KS);                            // steps of this group (the host sends whole multiples)
 
-    GemmTileExec<BM, BN, NW, NS, KS, FM, FN> ex;
+    GemmTileExec<BM, BN, NW, NS, KS, AM, AN> ex;
     static_assert(decltype(ex)::LIA == LIA && decltype(ex)::LIW == LIW, "load instructions per K step");
     ex.kg = kg;
     ex.wave = wave;
@@ -340,57 +407,58 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
         gr = gr < N ? gr : N - 1;
         ex.pw[v] = a.w + (int64_t)gr * K + c * 8;
     }
-    const int frow = lane & 31, fG = lane >> 5, fsw = (frow >> 1) & 7;
+    // fragment rows: lane l reads row l%16 of a block, the 16 bytes (l/16) of k half h; rows are 128 bytes with their
+    // 16-byte chunks XOR-permuted by (row/2)%8, and blocks start at multiples of 16 rows, so the permutation is the lane's own
+    const int frow = lane & 15, fG = lane >> 4, fsw = frow >> 1;
     ex.a_lds = (unsigned)(uintptr_t)&As[kg * NS][(wm0 + frow) * BK];
     ex.w_lds = (unsigned)(uintptr_t)&Ws[kg * NS][(wn0 + frow) * BK];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ex.foff[ks] = (unsigned)(((ks * 2 + fG) ^ fsw) * 16);
+    for (int h = 0; h < 2; ++h) ex.foff[h] = (unsigned)(((h * 4 + fG) ^ fsw) * 16);
 
-    float16v (&acc)[FM][FN] = ex.acc;
+    float4v (&acc)[AM][AN] = ex.acc;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < AM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    pipe::gemm_k_loop<NS>(ex, nk);
+        for (int j = 0; j < AN; ++j) acc[i][j] = float4v{0.f, 0.f, 0.f, 0.f};
+    if constexpr (SCHED == 2) pipe::gemm_k_loop_pingpong(ex, nk);
+    else pipe::gemm_k_loop<NS, SCHED == 1>(ex, nk);
 
     static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
     if constexpr (KS > 1) {
         // the other groups' partial tiles go over the weight stages, lane-major (no bank conflicts), to the first
-        constexpr int PT = FM * FN * 16 * 64;                 // floats of one wave's partial tile
+        constexpr int PT = AM * AN * 4 * 64;                  // floats of one wave's partial tile
         static_assert((KS - 1) * NW * PT * 4 <= (int)sizeof(Ws), "partial tiles over the weight stages");
         float* red = reinterpret_cast<float*>(&Ws[0][0]) + wave * PT + lane;
         if (kg > 0) {
             float* mine = red + (kg - 1) * (NW * PT);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < AM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < AN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mine[((i * FN + j) * 16 + r) * 64] = acc[i][j][r];
+                    for (int r = 0; r < 4; ++r) mine[((i * AN + j) * 4 + r) * 64] = acc[i][j][r];
         }
         __syncthreads();
         if (kg > 0) return;
 #pragma unroll
         for (int g = 0; g < KS - 1; ++g)
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < AM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < AN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] += red[g * (NW * PT) + ((i * FN + j) * 16 + r) * 64];
+                    for (int r = 0; r < 4; ++r) acc[i][j][r] += red[g * (NW * PT) + ((i * AN + j) * 4 + r) * 64];
     }
-    constexpr int EB = FM * 32 * 128;                      // bytes of a wave's turn-around area
+    constexpr int EB = WM * 128;                           // bytes of a wave's turn-around area
     // with K groups the partial tiles above sit in the weight stages and group 0 may still be summing them while a faster
     // wave of the group already turns its tile around: that must then happen in the activation stages only
     static_assert(KS == 1 || NW * EB <= (int)sizeof(As), "turn-around areas must not touch the partial tiles");
     if constexpr (NW * EB <= (int)sizeof(As)) {
-        epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
+        epilogue_via_lds<AM, AN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
     } else {
         static_assert(NW == 8 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
-        epilogue_via_lds<FM, FN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
+        epilogue_via_lds<AM, AN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
                                       m0 + wm0, n0 + wn0, lane);
     }
 }
@@ -1009,15 +1077,15 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
-template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2, int KS = 1>
+template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2, int KS = 1, int SCHED = 0>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * KS * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS, KS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS, KS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS, KS>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS, KS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1204,7 +1272,13 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         // never for at most 128 rows, where half of every large tile would be idle (a decode step of many sequences
         // over a very wide output, e.g. the vocabulary: 128 x 1024 x 50304 39.7 -> 30.9 us with 128x128 tiles)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-        if (big_tiles >= 150 && a.M > 128) launch_dma64_cfg<2, 4>(a, epi, s);
+        if (big_tiles >= 150 && a.M > 128) {
+            // two wave groups in alternation, except for very long K, where the single-phase schedule with the early
+            // release of the stage is ahead (25082 x 12288 x 49152: 1.11 against 1.04 PFLOP/s; at K of 4096 to 16384 the
+            // alternation leads by 2-6 %, measured in one call)
+            if (a.K >= 32768) launch_dma64_cfg<2, 4, 256, 256, 2, 1, 1>(a, epi, s);
+            else launch_dma64_cfg<2, 4, 256, 256, 2, 1, 2>(a, epi, s);
+        }
         else {
             // few tiles (short prompts, narrow layers): smaller tiles put more workgroups on the chip; the K loop of
             // each is a chain of dependent steps, so what counts there is how many run side by side and how far ahead

@@ -44,44 +44,73 @@ EET_PIPE_FN void tile_of_block(int pid, int tiles_m, int tiles_n, int& tile_m, i
 
 // ---------------------------------------------------------------------------------------------------------
 // K loop of the MFMA tile kernel: K tiles of 64 columns through NS LDS stages (tile t in stage t % NS), four
-// sub-steps of 16 columns per tile, fragments double-buffered in registers.
+// sub-steps per tile, fragments double-buffered in registers (buffer = sub-step % 2).
 //
-// Executor interface (BUF = register buffer 0/1, SUB = sub-step 0..3, stage = ring slot):
+// Executor interface (SUB = sub-step 0..3 of a tile, BUF = SUB % 2 its register buffer, stage = ring slot):
 //   load(tile, stage)            issue this wave's global->LDS loads of K tile `tile`           (vector-memory counter)
-//   wait_loads_all()             every load of this wave has landed in LDS
-//   wait_loads_but_newest()      ... every load except those of the newest load() call
+//   wait_vmem<L>()               the loads of this wave have landed, except those of the newest L load() calls (the
+//                                vector-memory queue retires in issue order)
 //   barrier()                    workgroup barrier
 //   frag<BUF, SUB>(stage)        issue the LDS reads of sub-step SUB of the tile in `stage` into buffer BUF
-//   wait_frag<BUF>(newer)        the reads into BUF have landed; `newer` frag() calls issued after them may still fly
-//   mma<BUF>()                   multiply-accumulate from buffer BUF
+//   wait_frag<BUF, SUB, NEWER>() the reads of sub-step SUB have landed; those of sub-step NEWER, issued after them, may
+//                                still fly (NEWER = -1: none: every read of this wave has landed)
+//   mma<BUF, SUB>()              multiply-accumulate sub-step SUB from buffer BUF
 // ---------------------------------------------------------------------------------------------------------
-template <int NS, class Ops>
+// the three sub-steps in the middle of a tile, common to every schedule: on entry the reads of sub-step 0 are in flight
+template <class Ops>
+EET_PIPE_FN void gemm_tile_front(Ops& op, int st) {
+    op.template frag<1, 1>(st);
+    op.template wait_frag<0, 0, 1>();
+    op.template mma<0, 0>();
+    op.template frag<0, 2>(st);
+    op.template wait_frag<1, 1, 2>();
+    op.template mma<1, 1>();
+    op.template frag<1, 3>(st);
+}
+
+template <int NS, bool EARLY = false, class Ops = void>
 EET_PIPE_FN void gemm_k_loop(Ops& op, int nk) {
     static_assert(NS == 2 || NS == 3, "LDS stages");
-    if (NS == 2) {
+    static_assert(!EARLY || NS == 2, "early release: two-stage schedule only");
+    if (NS == 2 && EARLY) {
+        // two stages, early release: the reads of a tile's last sub-step are issued after the multiplies of its second,
+        // and the barrier that hands the stage over sits before the multiplies of the last two sub-steps; the request of
+        // tile kt+2 follows the barrier at once, while the fetch of tile kt+1 is still completing
+        op.load(0, 0);
+        op.template wait_vmem<0>();
+        op.barrier();
+        if (nk > 1) op.load(1, 1);
+        op.template frag<0, 0>(0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st = kt & 1;
+            gemm_tile_front(op, st);
+            op.template wait_frag<1, 3, -1>();    // every read of stage st has landed (sub-steps 2 and 3 sit in the buffers)
+            op.template wait_frag<0, 2, -1>();
+            op.template wait_vmem<0>();        // this wave's part of tile kt+1 has landed
+            op.barrier();                         // ... and everybody else's; stage st is free
+            if (kt + 2 < nk) op.load(kt + 2, st);
+            op.template mma<0, 2>();
+            op.template frag<0, 0>(st ^ 1);       // (past the last tile: stale data, never multiplied)
+            op.template mma<1, 3>();
+        }
+    } else if (NS == 2) {
         // two stages: tile kt+1 is requested at the start of step kt into the stage that step kt-1 read and that the
         // barrier at its end released; the end of step kt waits for it
         op.load(0, 0);
-        op.wait_loads_all();
+        op.template wait_vmem<0>();
         op.barrier();
         op.template frag<0, 0>(0);
         for (int kt = 0; kt < nk; ++kt) {
             const int st = kt & 1;
             if (kt + 1 < nk) op.load(kt + 1, st ^ 1);
-            op.template frag<1, 1>(st);
-            op.template wait_frag<0>(1);
-            op.template mma<0>();
-            op.template frag<0, 2>(st);
-            op.template wait_frag<1>(1);
-            op.template mma<1>();
-            op.template frag<1, 3>(st);
-            op.template wait_frag<0>(1);
-            op.template mma<0>();
-            op.template wait_frag<1>(0);          // all of this wave's reads of stage st are done
-            op.wait_loads_all();                  // this wave's part of tile kt+1 has landed
+            gemm_tile_front(op, st);
+            op.template wait_frag<0, 2, 3>();
+            op.template mma<0, 2>();
+            op.template wait_frag<1, 3, -1>();    // all of this wave's reads of stage st are done
+            op.template wait_vmem<0>();           // this wave's part of tile kt+1 has landed
             op.barrier();                         // ... and everybody else's; stage st is free
             op.template frag<0, 0>(st ^ 1);       // (past the last tile: stale data, never multiplied)
-            op.template mma<1>();
+            op.template mma<1, 3>();
         }
     } else {
         // ring of three stages: tile kt+2 is requested at the start of step kt, into the stage that step kt-1 read and
@@ -89,9 +118,9 @@ EET_PIPE_FN void gemm_k_loop(Ops& op, int nk) {
         op.load(0, 0);
         if (nk > 1) {
             op.load(1, 1);
-            op.wait_loads_but_newest();
+            op.template wait_vmem<1>();
         } else {
-            op.wait_loads_all();
+            op.template wait_vmem<0>();
         }
         op.barrier();                             // nothing but the loads above has touched LDS so far
         op.template frag<0, 0>(0);
@@ -100,24 +129,64 @@ EET_PIPE_FN void gemm_k_loop(Ops& op, int nk) {
             const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
             const bool more = kt + 2 < nk;
             if (more) op.load(kt + 2, st2);
-            op.template frag<1, 1>(st);
-            op.template wait_frag<0>(1);
-            op.template mma<0>();
-            op.template frag<0, 2>(st);
-            op.template wait_frag<1>(1);
-            op.template mma<1>();
-            op.template frag<1, 3>(st);
-            op.template wait_frag<0>(1);
-            op.template mma<0>();
-            op.template wait_frag<1>(0);          // all of this wave's reads of stage st are done
-            if (more) op.wait_loads_but_newest(); else op.wait_loads_all();   // this wave's part of tile kt+1 has landed
+            gemm_tile_front(op, st);
+            op.template wait_frag<0, 2, 3>();
+            op.template mma<0, 2>();
+            op.template wait_frag<1, 3, -1>();    // all of this wave's reads of stage st are done
+            if (more) op.template wait_vmem<1>(); else op.template wait_vmem<0>();   // this wave's part of tile kt+1 has landed
             op.barrier();                         // ... and everybody else's; stage st is free
             op.template frag<0, 0>(st1);          // (past the last tile: stale data, never multiplied)
-            op.template mma<1>();
+            op.template mma<1, 3>();
             st = st1;
         }
     }
-    op.template wait_frag<0>(0);                  // the stale reads too: the epilogue reuses the stages
+    op.template wait_frag<0, 0, -1>();            // the stale reads too: the epilogue reuses the stages
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K loop of the MFMA tile kernel, two wave groups in alternation ("ping-pong"), two LDS stages.
+//
+// The waves of a workgroup form two groups; a SIMD hosts one wave of each.  A K tile is handled in four phases
+// separated by workgroup barriers: M0 (request tile kt+1, read the fragments of k half 0, wait for them), C0 (multiply
+// k half 0), M1 (wait for the own part of tile kt+1, read the fragments of k half 1, wait), C1 (multiply k half 1).
+// The second group enters one barrier later, so whenever one group multiplies the other does its memory work: the
+// matrix pipe of a SIMD always has exactly one wave feeding it back to back, and no wave's loads or LDS waits stand
+// between two multiplies.  Both groups run this same code; the second executes one extra barrier in front of the
+// loop and the first one behind it, so every wave passes the same number of barriers.
+//
+// Hand-over (group A's phase p coincides with group B's phase p-1): when A requests tile kt+1 in M0(kt), the stage it
+// goes to held tile kt-1, whose last reads are B's M1(kt-1), finished before the barrier that opens A's M0(kt).  B's
+// part of tile kt+1 is requested in B's M0(kt) and waited for in B's M1(kt), which ends with the barrier that opens
+// A's M0(kt+1), the first read of that tile.
+//
+// Executor interface: load(tile, stage), wait_vmem<0>(), barrier() as above, and
+//   second_group()              wave-uniform: this wave belongs to the group that runs one phase behind
+//   read_half<H>(stage)         issue the LDS reads of k half H of the tile in `stage` (all fragments of the half)
+//   wait_reads()                every LDS read of this wave has landed
+//   mma_half<H>()               multiply-accumulate k half H
+// ---------------------------------------------------------------------------------------------------------
+template <class Ops>
+EET_PIPE_FN void gemm_k_loop_pingpong(Ops& op, int nk) {
+    op.load(0, 0);
+    op.template wait_vmem<0>();
+    op.barrier();
+    if (op.second_group()) op.barrier();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int st = kt & 1;
+        if (kt + 1 < nk) op.load(kt + 1, st ^ 1);     // M0
+        op.template read_half<0>(st);
+        op.wait_reads();
+        op.barrier();
+        op.template mma_half<0>();                    // C0
+        op.barrier();
+        op.template wait_vmem<0>();                // M1: this wave's part of tile kt+1 has landed
+        op.template read_half<1>(st);
+        op.wait_reads();
+        op.barrier();
+        op.template mma_half<1>();                    // C1
+        op.barrier();
+    }
+    if (!op.second_group()) op.barrier();
 }
 
 // ---------------------------------------------------------------------------------------------------------

@@ -103,6 +103,34 @@ struct Trace {
             }
         }
     }
+    // The same rules between the waves of two groups that run different records (x reads, y loads): nothing orders two
+    // waves inside a segment, so every read / load pair on a stage must be a whole barrier apart, the load that a consumed
+    // read depends on -- the last one y issued before the read's segment -- must carry the read's tile, and both records
+    // must pass the same number of barriers.
+    static void check_across(const char* what, Trace& x, const Trace& y) {
+        char buf[256];
+        if (x.seg != y.seg) x.fail(std::string(what) + ": the two groups pass different numbers of barriers");
+        for (const Read& r : x.reads) {
+            if (r.retire_pos < 0) continue;
+            const Load* latest = nullptr;
+            for (const Load& g : y.loads) {
+                if (g.ring != r.ring || g.stage != r.stage || g.retire_pos < 0) continue;
+                const bool load_first = g.retire_seg < r.issue_seg, read_first = r.retire_seg < g.issue_seg;
+                if (!load_first && !read_first) {
+                    snprintf(buf, sizeof buf, "%s: R1/R2 ring %d stage %d: a read of tile %d (segments %d..%d) and the other group's load of tile %d "
+                             "(segments %d..%d) are not a barrier apart", what, r.ring, r.stage, r.tile, r.issue_seg, r.retire_seg, g.tile,
+                             g.issue_seg, g.retire_seg);
+                    x.fail(buf);
+                }
+                if (load_first && (!latest || g.issue_seg > latest->issue_seg)) latest = &g;
+            }
+            if (r.consumed && (!latest || latest->tile != r.tile)) {
+                snprintf(buf, sizeof buf, "%s: R2 ring %d stage %d: a consumed read expects tile %d, the other group's part of the stage holds tile %d",
+                         what, r.ring, r.stage, r.tile, latest ? latest->tile : -1);
+                x.fail(buf);
+            }
+        }
+    }
 };
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -117,28 +145,35 @@ struct GemmRecorder {
     explicit GemmRecorder(int nk_) : nk(nk_) {}
 
     void load(int tile, int stage) { t.issue_load(0, stage, tile); }
-    void wait_loads_all() { t.retire_loads(0); }
-    void wait_loads_but_newest() { t.retire_loads(1); }
+    template <int L>
+    void wait_vmem() { t.retire_loads((size_t)L); }       // the queue retires in issue order: the newest L load() calls stay
     void barrier() { t.barrier(); }
     template <int BUF, int SUB>
     void frag(int stage) {
         // the i-th frag() call feeds the i-th mma(): K tile i / 4, sub-step i % 4 (the call past the last tile feeds none)
         const int idx = issued++;
         if (SUB != idx % 4) t.fail("R4 fragment reads do not walk the sub-steps 0..3 in order");
+        if (BUF != (SUB & 1)) t.fail("R3 a sub-step is read into the other sub-steps' buffer");
         if (buf_read[BUF] >= 0 && !t.reads[buf_read[BUF]].consumed && t.reads[buf_read[BUF]].tile < nk)
             t.fail("R3 a register buffer is refilled before its fragments were multiplied");
         buf_read[BUF] = t.issue_read(0, stage, idx / 4, SUB);
     }
-    template <int BUF>
-    void wait_frag(int newer) {
-        t.retire_reads((size_t)newer);
-        if (buf_read[BUF] >= 0 && t.reads[buf_read[BUF]].retire_pos < 0) t.fail("R3 wait_frag leaves the buffer it waits for in flight");
+    template <int BUF, int SUB, int NEWER>
+    void wait_frag() {
+        // reads retire in issue order: what stays in flight is the newest frag() call, which must be sub-step NEWER's
+        const int n = (int)t.reads_in_flight.size();
+        if (NEWER >= 0 && n > 0 && t.reads[t.reads_in_flight[n - 1]].sub != NEWER)
+            t.fail("R3 an LDS wait count does not match the order the reads were issued in");
+        t.retire_reads(NEWER >= 0 ? 1 : 0);
+        if (buf_read[BUF] < 0 || t.reads[buf_read[BUF]].sub != SUB) t.fail("R3 wait_frag names a sub-step that is not in its buffer");
+        else if (t.reads[buf_read[BUF]].retire_pos < 0) t.fail("R3 wait_frag leaves the buffer it waits for in flight");
     }
-    template <int BUF>
+    template <int BUF, int SUB>
     void mma() {
         ++t.pos;
         if (buf_read[BUF] < 0) { t.fail("R3 mma on a buffer that was never read into"); return; }
         Read& r = t.reads[buf_read[BUF]];
+        if (r.sub != SUB) t.fail("R3 mma names a sub-step that is not in its buffer");
         if (r.retire_pos < 0) t.fail("R3 mma consumes a buffer whose reads have not been waited for");
         if (r.consumed) t.fail("R4 a fragment is multiplied twice");
         r.consumed = true;
@@ -152,6 +187,49 @@ struct GemmRecorder {
         for (const Read& r : t.reads)
             if (!r.consumed && r.tile < nk) t.fail(std::string(what) + ": R4 a fragment of a real tile is read and never multiplied");
         return t.error;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------------------------
+// recorder for pipe::gemm_k_loop_pingpong: one record per wave group
+// ------------------------------------------------------------------------------------------------------------------
+struct PingPongRecorder {
+    Trace t;
+    int nk;
+    bool second;
+    int half_read = -1;                                    // the read group sitting in the (single) fragment buffer
+    int issued = 0;
+    std::vector<int> consumed;
+    PingPongRecorder(int nk_, bool second_) : nk(nk_), second(second_) {}
+    bool second_group() const { return second; }
+    void load(int tile, int stage) { t.issue_load(0, stage, tile); }
+    template <int L>
+    void wait_vmem() { static_assert(L == 0, "the two-group schedule waits for everything"); t.retire_loads(0); }
+    void barrier() { t.barrier(); }
+    template <int H>
+    void read_half(int stage) {
+        const int idx = issued++;
+        if (H != idx % 2) t.fail("R4 fragment reads do not alternate between the two k halves");
+        if (half_read >= 0 && !t.reads[half_read].consumed) t.fail("R3 the fragment buffer is refilled before it was multiplied");
+        half_read = t.issue_read(0, stage, idx / 2, H);
+    }
+    void wait_reads() { t.retire_reads(0); }
+    template <int H>
+    void mma_half() {
+        ++t.pos;
+        if (half_read < 0) { t.fail("R3 multiply before any fragment was read"); return; }
+        Read& r = t.reads[half_read];
+        if (r.sub != H) t.fail("R3 multiply names a k half that is not in the buffer");
+        if (r.retire_pos < 0) t.fail("R3 multiply consumes fragments that have not been waited for");
+        if (r.consumed) t.fail("R4 a k half is multiplied twice");
+        r.consumed = true;
+        consumed.push_back(r.tile * 2 + r.sub);
+    }
+    void finish(const char* what) {
+        t.check(what);
+        if ((int)consumed.size() != 2 * nk) t.fail(std::string(what) + ": R4 number of multiply phases is not 2 per K tile");
+        for (int i = 0; i < (int)consumed.size() && i < 2 * nk; ++i)
+            if (consumed[i] != i) t.fail(std::string(what) + ": R4 k halves are not consumed once each, in order");
     }
 };
 
@@ -201,7 +279,7 @@ enum Mistake { kWrongStage, kNoBarrier, kShortWait, kLateLoadWait };
 template <class Ops>
 void mutant_gemm_loop(Ops& op, int nk, Mistake what) {
     op.load(0, 0);
-    if (nk > 1) { op.load(1, 1); op.wait_loads_but_newest(); } else { op.wait_loads_all(); }
+    if (nk > 1) { op.load(1, 1); op.template wait_vmem<1>(); } else { op.template wait_vmem<0>(); }
     op.barrier();
     op.template frag<0, 0>(0);
     int st = 0;
@@ -209,26 +287,28 @@ void mutant_gemm_loop(Ops& op, int nk, Mistake what) {
         const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
         const bool more = kt + 2 < nk;
         if (more) op.load(kt + 2, what == kWrongStage ? st1 : st2);   // kWrongStage: over the tile that is read next
-        op.template frag<1, 1>(st);
-        op.template wait_frag<0>(1);
-        op.template mma<0>();
-        op.template frag<0, 2>(st);
-        op.template wait_frag<1>(1);
-        op.template mma<1>();
-        op.template frag<1, 3>(st);
-        op.template wait_frag<0>(1);
-        op.template mma<0>();
-        op.template wait_frag<1>(what == kShortWait ? 1 : 0);           // kShortWait: nothing waited for (one request may fly)
-        if (what == kLateLoadWait) { if (more) op.wait_loads_but_newest(); }   // kLateLoadWait: the last tiles are never waited for
-        else { if (more) op.wait_loads_but_newest(); else op.wait_loads_all(); }
+        eet::pipe::gemm_tile_front(op, st);
+        op.template wait_frag<0, 2, 3>();
+        op.template mma<0, 2>();
+        if (what == kShortWait) op.template wait_frag<1, 3, 3>();       // kShortWait: the last reads may still fly at the barrier
+        else op.template wait_frag<1, 3, -1>();
+        if (what == kLateLoadWait) { if (more) op.template wait_vmem<1>(); }   // kLateLoadWait: the last tiles are never waited for
+        else { if (more) op.template wait_vmem<1>(); else op.template wait_vmem<0>(); }
         if (what != kNoBarrier) op.barrier();
         op.template frag<0, 0>(st1);
-        op.template mma<1>();
+        op.template mma<1, 3>();
         st = st1;
     }
-    op.template wait_frag<0>(0);
-    if (what == kLateLoadWait) op.wait_loads_all();
+    op.template wait_frag<0, 0, -1>();
+    if (what == kLateLoadWait) op.template wait_vmem<0>();
 }
+
+// planted mistake for the two-group schedule: waves that never wait for their own tile loads after the prologue
+struct NoWait : PingPongRecorder {
+    using PingPongRecorder::PingPongRecorder;
+    template <int L>
+    void wait_vmem() { if (t.seg < 2) t.retire_loads(0); }
+};
 
 int failures = 0;
 
@@ -256,10 +336,35 @@ int main() {
         }
         {
             GemmRecorder r(nk);
+            eet::pipe::gemm_k_loop<2, true>(r, nk);
+            snprintf(name, sizeof name, "tile kernel, two LDS stages with early release, %d K tiles", nk);
+            expect_ok(r.verdict(name), name);
+        }
+        {
+            GemmRecorder r(nk);
             eet::pipe::gemm_k_loop<3>(r, nk);
             snprintf(name, sizeof name, "tile kernel, three LDS stages, %d K tiles", nk);
             expect_ok(r.verdict(name), name);
         }
+    }
+    for (int nk : {1, 2, 3, 4, 5, 16, 192, 768}) {
+        PingPongRecorder a(nk, false), b(nk, true);
+        eet::pipe::gemm_k_loop_pingpong(a, nk);
+        eet::pipe::gemm_k_loop_pingpong(b, nk);
+        snprintf(name, sizeof name, "tile kernel, two wave groups in alternation, %d K tiles", nk);
+        a.finish(name); b.finish(name);
+        Trace::check_across(name, a.t, b.t);
+        Trace::check_across(name, b.t, a.t);
+        expect_ok(a.t.error.empty() ? b.t.error : a.t.error, name);
+    }
+    {   // planted: both groups run the first group's code (no phase shift is fine), but one group skips its loads' wait
+        NoWait a(6, false), b(6, true);
+        eet::pipe::gemm_k_loop_pingpong(a, 6);
+        eet::pipe::gemm_k_loop_pingpong(b, 6);
+        a.finish("x"); b.finish("x");
+        Trace::check_across("x", a.t, b.t);
+        Trace::check_across("x", b.t, a.t);
+        expect_caught(a.t.error.empty() ? b.t.error : a.t.error, "two-group schedule whose waves never wait for their own tile loads");
     }
     for (int nt : {1, 2, 3, 4, 5, 8, 16, 33, 64}) {
         AttnRecorder r(nt);
