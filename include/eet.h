@@ -316,6 +316,15 @@ int eet_op_bias_residual(const void *x, const void *bias, const void *residual, 
 int eet_op_linear(const void *x, const void *w, const void *bias, const void *residual, void *y,
                   int64_t rows, int32_t in, int32_t out, int32_t act, void *hip_stream);
 
+/* eet_op_linear on rows that are not dense: row r of x starts at x + r*ldx, row r of y at y + r*ldy (in halfs;
+ * multiples of 8, ldx >= in, ldy >= out); the residual rows stay dense.  This is the form the layer's own prefill uses
+ * between its two feed-forward projections (Section 3.1), whose intermediate rows it keeps 128 bytes further apart than
+ * their length when they are 64 KB or longer: rows a multiple of 32 KB apart slow the projection that reads them down.
+ * Only the MFMA tile path takes strides: with rows <= 16 (the weight-streaming path of a decode step) and ldx != in or
+ * ldy != out the call returns EET_ERR_UNSUPPORTED_SHAPE.  Other errors as eet_op_linear. */
+int eet_op_linear_strided(const void *x, int64_t ldx, const void *w, const void *bias, const void *residual, void *y,
+                          int64_t ldy, int64_t rows, int32_t in, int32_t out, int32_t act, void *hip_stream);
+
 /* Causal, padding-skipping attention over whole prompts (mask fusion inside the contraction).
  *   q, ctx     [batch, padded_len, heads*d]; only valid rows are read / written
  *   k_cache, v_cache   [batch, heads, capacity, d]

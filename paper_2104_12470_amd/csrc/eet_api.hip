@@ -34,6 +34,12 @@ int hip_fail(hipError_t e, const char* what) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Rows of the prefill's feed-forward buffer lie F + kFfnRowPad halfs apart when F >= kFfnPadFrom: rows a
+// multiple of 32 KB apart slow the second feed-forward projection down (25082 x 12288 x 49152: 0.97-1.09 PFLOP/s with
+// rows 96 KB apart, 1.16 with 128 bytes more; no gain at 16384 and below, a small loss at 4096).
+constexpr size_t kFfnRowPad = 64;
+constexpr int kFfnPadFrom = 32768;
+
 // Byte offsets of the pieces of a layer's workspace.
 struct WorkspaceLayout {
     size_t lens, cu, row_map, buf_a, buf_b, buf_y, buf_f, part, total;
@@ -69,7 +75,7 @@ WorkspaceLayout layout_of(const eet_layer_config* c) {
     w.buf_a = off;   off = align_up(off + 2 * T * H, 256);
     w.buf_b = off;   off = align_up(off + 2 * T * H, 256);
     w.buf_y = off;   off = align_up(off + 2 * T * H, 256);
-    w.buf_f = off;   off = align_up(off + 2 * T * F, 256);
+    w.buf_f = off;   off = align_up(off + 2 * T * (F + kFfnRowPad), 256);
     w.splits = attention_decode_splits(c->max_batch, c->heads, c->max_seq);
     w.part = off;
     // sized for the split count of any batch <= max_batch (fewer sequences -> more splits)
@@ -212,11 +218,12 @@ static int enqueue_prefill(eet_layer* L, const SeqLens& lens, int batch, int pad
     GemmArgs f1{};
     f1.x = bufB; f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
     f1.M = (int)T; f1.N = F; f1.K = H;
-    EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
     // a9: FFN2 + bias + residual, scattered back to the padded layout
     GemmArgs f2{};
     f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
     f2.M = (int)T; f2.N = H; f2.K = F; f2.res = bufY; f2.res_row_map = nullptr; f2.out_row_map = d_map;
+    if (F >= kFfnPadFrom && gemm_takes_row_strides(f1) && gemm_takes_row_strides(f2)) f1.ldy = f2.lda = F + (int)kFfnRowPad;
+    EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
     EET_LAUNCH(launch_gemm(f2, EPI_BIAS_RES, s), "ffn 2");
 
     return EET_OK;
@@ -892,6 +899,28 @@ int eet_op_linear(const void* x, const void* w, const void* bias, const void* re
     GemmArgs g{};
     g.x = (const half_t*)x; g.w = (const half_t*)w; g.bias = (const half_t*)bias; g.y = (half_t*)y;
     g.M = (int)rows; g.N = out; g.K = in; g.res = (const half_t*)residual;
+    EET_LAUNCH(launch_gemm(g, residual ? EPI_BIAS_RES : (act ? EPI_BIAS_GELU : EPI_BIAS), (hipStream_t)hip_stream), "linear");
+    return EET_OK;
+}
+
+int eet_op_linear_strided(const void* x, int64_t ldx, const void* w, const void* bias, const void* residual, void* y, int64_t ldy,
+                          int64_t rows, int32_t in, int32_t out, int32_t act, void* hip_stream) {
+    if (!x || !w || !bias || !y) return fail(EET_ERR_INVALID_ARG, "eet_op_linear_strided: null argument");
+    if (rows < 0 || in < 1 || out < 1 || (act != 0 && act != 1)) return fail(EET_ERR_INVALID_ARG, "eet_op_linear_strided: bad size or act");
+    if (in % 64 != 0 || out % 64 != 0) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear_strided: in and out must be multiples of 64");
+    if (rows > 0x7fffffff) return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear_strided: more than 2^31-1 rows");
+    if (ldx < in || ldy < out || ldx % 8 != 0 || ldy % 8 != 0 || ldx > 0x7fffffff || ldy > 0x7fffffff)
+        return fail(EET_ERR_INVALID_ARG, "eet_op_linear_strided: row strides must be multiples of 8, at least in / out");
+    if (act == 1 && residual) return fail(EET_ERR_INVALID_ARG, "eet_op_linear_strided: gelu and residual together are not a layer step");
+    if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(y) || !aligned16(residual))
+        return fail(EET_ERR_INVALID_ARG, "eet_op_linear_strided: pointers must be 16-byte aligned");
+    GemmArgs g{};
+    g.x = (const half_t*)x; g.w = (const half_t*)w; g.bias = (const half_t*)bias; g.y = (half_t*)y;
+    g.M = (int)rows; g.N = out; g.K = in; g.res = (const half_t*)residual;
+    if ((ldx != in || ldy != out) && rows > 0 && !gemm_takes_row_strides(g))
+        return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear_strided: %lld rows go to the weight-streaming path, which takes dense rows only",
+                    (long long)rows);
+    g.lda = (int)ldx; g.ldy = (int)ldy;
     EET_LAUNCH(launch_gemm(g, residual ? EPI_BIAS_RES : (act ? EPI_BIAS_GELU : EPI_BIAS), (hipStream_t)hip_stream), "linear");
     return EET_OK;
 }

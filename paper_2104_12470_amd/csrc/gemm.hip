@@ -102,10 +102,12 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
 // bytes per instruction).  Rows are 128 bytes; their sixteen 8-byte units are XOR-permuted by (row/2)%16 so that
 // both access patterns spread over all banks.  `stage`: AM*16*128 bytes of LDS no other wave touches; mw, nw:
 // first row and column of the wave tile (its 64 columns are inside N or outside as a whole: N % 64 == 0).
-template <int AM, int AN, int EPI>
-__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][AN], char* stage, int mw, int nw,
+// A wave tile of 128 columns (ANT = 8 accumulator blocks across) is turned around in two passes of 64 columns, J0 = 0 and 4.
+template <int AM, int ANT, int J0, int EPI>
+__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][ANT], char* stage, int mw, int nw,
                                                  int lane) {
-    static_assert(AN == 4, "64 columns per wave tile");
+    static_assert(J0 + 4 <= ANT, "64 columns per pass");
+    constexpr int AN = 4;
     constexpr int ROWS = AM * 16;                         // rows of the wave tile
     const int M = a.M, N = a.N;
     if (nw >= N) return;
@@ -132,8 +134,8 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4
         for (int i = 0; i < AM; ++i) {
             const int row = i * 16 + (lane & 15);
             half4v* slot = reinterpret_cast<half4v*>(stage + row * 128 + ((unit ^ ((row >> 1) & 15)) * 8));
-            float v0 = acc[i][j][0] + (float)bias[0], v1 = acc[i][j][1] + (float)bias[1];
-            float v2 = acc[i][j][2] + (float)bias[2], v3 = acc[i][j][3] + (float)bias[3];
+            float v0 = acc[i][J0 + j][0] + (float)bias[0], v1 = acc[i][J0 + j][1] + (float)bias[1];
+            float v2 = acc[i][J0 + j][2] + (float)bias[2], v3 = acc[i][J0 + j][3] + (float)bias[3];
             if (EPI == EPI_BIAS_GELU) {
                 v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
             }
@@ -176,7 +178,7 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4
             }
         } else {
             const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
-            dst = a.y + orow * N + n;
+            dst = a.y + orow * (a.ldy ? a.ldy : N) + n;
         }
         *reinterpret_cast<half8v*>(dst) = v;
     }
@@ -236,15 +238,21 @@ __device__ __forceinline__ void wait_vm() {
 // sixth more than 32x32x16 (measured with bare loops of either: 2.08 against 1.79 PFLOP/s over tens of milliseconds): per
 // flop it reads and writes half the accumulator registers.  Weights are the A operand (16 output columns x 32 k), the
 // activations the B operand (32 k x 16 rows): a lane holds 4 consecutive output columns of one row.
-// A wave tile of WM x 64 is AM = WM/16 by AN = 4 accumulator blocks.  A K tile of 64 is walked in four sub-steps
-// s = 2h + mh: k half h (32 columns) times row half mh (AM/2 blocks).  The weight fragments of a k half (AN reads of 16
-// bytes per lane) serve both row halves and are read with the first; every sub-step reads AM/2 activation fragments; both
-// kinds are double-buffered in registers, so the reads of sub-step s+1 fly during the AM/2 * AN multiplies of sub-step s.
+// A wave tile of WM x WN is AM = WM/16 by AN = WN/16 accumulator blocks (WN = 64, or 128 for the four-wave 256 x 256 tile,
+// whose 64 blocks per wave live in the accumulation registers).  With two waves per SIMD (pipe::gemm_k_loop) a K tile of
+// 64 is walked in four sub-steps s = 2h + mh: k half h (32 columns) times row half mh (AM/2 blocks).  The weight
+// fragments of a k half (AN reads of 16 bytes per lane) serve both row halves and are read with the first; every sub-step
+// reads AM/2 activation fragments; both kinds are double-buffered in registers, so the reads of sub-step s+1 fly during
+// the AM/2 * AN multiplies of sub-step s, and the other wave of the SIMD covers what still shows.  With one wave per SIMD
+// (pipe::gemm_k_loop_interleaved) nothing covers a stall, and a burst of LDS reads stalls the issuing wave, multiplies
+// included, until the LDS queue drains (16 reads in a row in front of 64 multiplies: 1840 cycles against 1055 for the
+// multiplies alone; one read after every third multiply: 1080); there the fragments of a whole k half are
+// double-buffered and every request sits between two multiplies.
 template <int BM, int BN, int NW, int NS, int KS, int AM, int AN>
 struct GemmTileExec {
     static constexpr int BK = 64, AH = AM / 2;
     static constexpr int LRA = BM / NW, LRW = BN / NW, LIA = LRA / 8, LIW = LRW / 8;
-    static_assert(AM % 2 == 0 && AH >= 1 && AH <= 4 && AN == 4, "wave tile shape");
+    static_assert(AM % 2 == 0 && AH >= 1 && AH <= 4 && (AN == 4 || AN == 8), "wave tile shape");
     const half_t* pa[LIA];                 // this lane's source of each load instruction, K tile 0
     const half_t* pw[LIW];
     half_t* as_base;                       // stage 0 of this wave's K group: As[kg * NS], Ws[kg * NS]
@@ -253,6 +261,7 @@ struct GemmTileExec {
     unsigned foff[2];                      // byte offset of this lane's 16 bytes of k half h inside the (permuted) row
     int kg, wave;
     half8v fa[2][AH], fw[2][AN];           // fa[s & 1]: activations of sub-step s; fw[h & 1]: weights of k half h
+    half8v ga[2][AM], gw[2][AN];           // the one-wave-per-SIMD schedule: all fragments of k half h
     float4v acc[AM][AN];
 
     __device__ __forceinline__ void load(int tile, int stage) {
@@ -286,6 +295,12 @@ struct GemmTileExec {
             EET_DREAD(fw[H][1], vw_, 2048);
             EET_DREAD(fw[H][2], vw_, 4096);
             EET_DREAD(fw[H][3], vw_, 6144);
+            if (AN > 4) {
+                EET_DREAD(fw[H][4 % AN], vw_, 8192);
+                EET_DREAD(fw[H][5 % AN], vw_, 10240);
+                EET_DREAD(fw[H][6 % AN], vw_, 12288);
+                EET_DREAD(fw[H][7 % AN], vw_, 14336);
+            }
         }
     }
 #undef EET_DREAD
@@ -301,46 +316,69 @@ struct GemmTileExec {
             for (int j = 0; j < AN; ++j) asm volatile("" : "+v"(fw[SUB >> 1][j]));
         }
     }
-    // ---- the two-group schedule (pipe::gemm_k_loop_pingpong): a whole k half at a time, single-buffered ----------
-    __device__ __forceinline__ bool second_group() const { return wave >= NW / 2; }
-#define EET_DREAD(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(DST) : "v"(ADDR), "n"(OFF) : "memory")
-    template <int H>
-    __device__ __forceinline__ void read_half(int stage) {
-        const unsigned vw_ = w_lds + stage * (BN * BK * 2) + foff[H];
-        EET_DREAD(fw[0][0], vw_, 0);
-        EET_DREAD(fw[0][1], vw_, 2048);
-        EET_DREAD(fw[0][2], vw_, 4096);
-        EET_DREAD(fw[0][3], vw_, 6144);
-        const unsigned va_ = a_lds + stage * (BM * BK * 2) + foff[H];
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            EET_DREAD(fa[mh][0], va_, (mh * AH + 0) * 2048);
-            if (AH > 1) EET_DREAD(fa[mh][1 % AH], va_, (mh * AH + 1) * 2048);
-            if (AH > 2) EET_DREAD(fa[mh][2 % AH], va_, (mh * AH + 2) * 2048);
-            if (AH > 3) EET_DREAD(fa[mh][3 % AH], va_, (mh * AH + 3) * 2048);
-        }
+    // ---- the one-wave-per-SIMD schedule (pipe::gemm_k_loop_interleaved): whole k halves, double-buffered -------------
+    // LDS read number R of k half H into buffer H: the AN weight fragments, then the AM activation fragments
+    template <int H, int R>
+    __device__ __forceinline__ void half_read(unsigned va_, unsigned vw_) {
+        if constexpr (R < AN) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(gw[H][R % AN]) : "v"(vw_), "n"(R * 2048) : "memory");
+        else asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(ga[H][(R - AN) % AM]) : "v"(va_), "n"((R - AN) * 2048) : "memory");
     }
-#undef EET_DREAD
-    __device__ __forceinline__ void wait_reads() {
+    template <int H, int... R>
+    __device__ __forceinline__ void half_read_all(unsigned va_, unsigned vw_, std::integer_sequence<int, R...>) {
+        (half_read<H, R>(va_, vw_), ...);
+    }
+    template <int H>
+    __device__ __forceinline__ void fetch_half(int stage) {
+        half_read_all<H>(a_lds + stage * (BM * BK * 2) + foff[H], w_lds + stage * (BN * BK * 2) + foff[H], std::make_integer_sequence<int, AM + AN>{});
+    }
+    __device__ __forceinline__ void wait_fetched() {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < AN; ++j) asm volatile("" : "+v"(fw[0][j]));
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh)
+            for (int j = 0; j < AN; ++j) asm volatile("" : "+v"(gw[h][j]));
 #pragma unroll
-            for (int i = 0; i < AH; ++i) asm volatile("" : "+v"(fa[mh][i]));
+            for (int i = 0; i < AM; ++i) asm volatile("" : "+v"(ga[h][i]));
+        }
+    }
+    // multiply number IDX of k half H, followed by its share of the side work: the reads of the other k half and the tile
+    // loads, each spread over the first three quarters of the phase (the last quarter lets the reads land; loads issued
+    // later arrive later); scheduling barriers pin each request between the two multiplies it was written between
+    template <int H, bool LOAD, int IDX>
+    __device__ __forceinline__ void half_mma_one(unsigned va_, unsigned vw_, int64_t koff, int lstage) {
+        constexpr int MF = AM * AN, NR = AM + AN, NL = LIA + LIW;
+        constexpr int RS = (MF * 3 / 4) / NR, LS = (MF * 3 / 4) / NL;   // multiplies per read, per load (both measured best at 3 for 64)
+        static_assert(RS >= 1 && LS >= 1, "side work fits between the multiplies");
+        constexpr int i = IDX / AN, j = IDX % AN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(gw[H][j], ga[H][i], acc[i][j], 0, 0, 0);
+        if constexpr (IDX % RS == 0 && IDX / RS < NR) {
+            __builtin_amdgcn_sched_barrier(0);
+            half_read<1 - H, IDX / RS>(va_, vw_);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (LOAD && IDX % LS == LS / 2 && IDX / LS < NL) {
+            constexpr int v = IDX / LS;
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (v < LIA) load_lds_16B(pa[v % LIA] + koff, as_base + lstage * (BM * BK) + (wave * LRA + v * 8) * BK);
+            else load_lds_16B(pw[(v - LIA) % LIW] + koff, ws_base + lstage * (BN * BK) + (wave * LRW + (v - LIA) * 8) * BK);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    template <int H, bool LOAD, int... I>
+    __device__ __forceinline__ void half_mma_seq(unsigned va_, unsigned vw_, int64_t koff, int lstage, std::integer_sequence<int, I...>) {
+        __builtin_amdgcn_sched_barrier(0);
+        (half_mma_one<H, LOAD, I>(va_, vw_, koff, lstage), ...);
+        __builtin_amdgcn_sched_barrier(0);
     }
     template <int H>
-    __device__ __forceinline__ void mma_half() {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mh = 0; mh < 2; ++mh)
-#pragma unroll
-            for (int i = 0; i < AH; ++i)
-#pragma unroll
-                for (int j = 0; j < AN; ++j)
-                    acc[mh * AH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw[0][j], fa[mh][i], acc[mh * AH + i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+    __device__ __forceinline__ void mma_half_fetch(int stage) {
+        half_mma_seq<H, false>(a_lds + stage * (BM * BK * 2) + foff[1 - H], w_lds + stage * (BN * BK * 2) + foff[1 - H], 0, 0,
+                               std::make_integer_sequence<int, AM * AN>{});
+    }
+    template <int H>
+    __device__ __forceinline__ void mma_half_fetch_load(int stage, int tile, int lstage) {
+        half_mma_seq<H, true>(a_lds + stage * (BM * BK * 2) + foff[1 - H], w_lds + stage * (BN * BK * 2) + foff[1 - H],
+                              (int64_t)(tile * KS + kg) * BK, lstage, std::make_integer_sequence<int, AM * AN>{});
     }
     template <int BUF, int SUB>
     __device__ __forceinline__ void mma() {
@@ -356,11 +394,11 @@ struct GemmTileExec {
     }
 };
 
-// SCHED: 0 = the schedule of pipe::gemm_k_loop<NS>, 1 = its early-release form (two stages), 2 = two wave groups in
-// alternation (pipe::gemm_k_loop_pingpong; two stages, eight waves, one K group)
+// SCHED: 0 = the schedule of pipe::gemm_k_loop<NS>, 1 = its early-release form (two stages), 2 = the schedule for one wave
+// per SIMD (pipe::gemm_k_loop_interleaved; two stages, one K group)
 template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS, int SCHED>
 __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
-    static_assert(SCHED == 0 || (NS == 2 && KS == 1 && (SCHED == 1 || WGM * WGN == 8)), "schedule");
+    static_assert(SCHED == 0 || (NS == 2 && KS == 1 && (SCHED == 1 || SCHED == 2)), "schedule");
     // KS > 1: KS groups of WGM x WGN waves share the tile and take every KS-th K step each, through LDS stages of their
     // own; the other groups' accumulators are added to the first's through LDS at the end.  For the few
     // tiles of a narrow output with a long K, where nothing else puts more loads in flight per CU.
@@ -370,7 +408,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     constexpr int WM = BM / WGM, WN = BN / WGN, AM = WM / 16, AN = WN / 16;   // wave tile in 16 x 16 accumulator blocks
     constexpr int LRA = BM / NW, LRW = BN / NW;   // rows of each operand tile a wave loads per K step
     constexpr int LIA = LRA / 8, LIW = LRW / 8;   // wave-level load instructions per operand per K step
-    static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && WM % 32 == 0 && WN == 64, "tile shape");
+    static_assert(LRA % 8 == 0 && LRW % 8 == 0 && LIA >= 1 && LIW >= 1 && WM % 32 == 0 && (WN == 64 || WN == 128), "tile shape");
     __shared__ __attribute__((aligned(1024))) half_t As[KS * NS][BM * BK];
     __shared__ __attribute__((aligned(1024))) half_t Ws[KS * NS][BN * BK];
 
@@ -397,7 +435,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         int gr = m0 + row;
         gr = gr < M ? gr : M - 1;
-        ex.pa[v] = a.x + (int64_t)gr * K + c * 8;
+        ex.pa[v] = a.x + (int64_t)gr * (a.lda ? a.lda : K) + c * 8;
     }
 #pragma unroll
     for (int v = 0; v < LIW; ++v) {
@@ -420,10 +458,9 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     for (int i = 0; i < AM; ++i)
 #pragma unroll
         for (int j = 0; j < AN; ++j) acc[i][j] = float4v{0.f, 0.f, 0.f, 0.f};
-    if constexpr (SCHED == 2) pipe::gemm_k_loop_pingpong(ex, nk);
+    if constexpr (SCHED == 2) pipe::gemm_k_loop_interleaved(ex, nk);
     else pipe::gemm_k_loop<NS, SCHED == 1>(ex, nk);
 
-    static_assert(WN == 64, "the LDS epilogue is laid out for wave tiles of 64 columns");
     __syncthreads();                                      // every wave is done with the operand stages
     if constexpr (KS > 1) {
         // the other groups' partial tiles go over the weight stages, lane-major (no bank conflicts), to the first
@@ -455,11 +492,13 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     // wave of the group already turns its tile around: that must then happen in the activation stages only
     static_assert(KS == 1 || NW * EB <= (int)sizeof(As), "turn-around areas must not touch the partial tiles");
     if constexpr (NW * EB <= (int)sizeof(As)) {
-        epilogue_via_lds<AM, AN, EPI>(a, acc, reinterpret_cast<char*>(&As[0][0]) + wave * EB, m0 + wm0, n0 + wn0, lane);
+        char* area = reinterpret_cast<char*>(&As[0][0]) + wave * EB;
+        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, area, m0 + wm0, n0 + wn0, lane);
+        if constexpr (AN == 8) epilogue_via_lds<AM, AN, 4, EPI>(a, acc, area, m0 + wm0, n0 + wn0 + 64, lane);   // second 64 columns, same area
     } else {
-        static_assert(NW == 8 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
-        epilogue_via_lds<AM, AN, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
-                                      m0 + wm0, n0 + wn0, lane);
+        static_assert(NW == 8 && AN == 4 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
+        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
+                                         m0 + wm0, n0 + wn0, lane);
     }
 }
 
@@ -1250,16 +1289,26 @@ bool gemm_merges_attention_ranges(const GemmArgs& a) {
            try_flat(a, EPI_BIAS_RES, nullptr, true);
 }
 
+// true when launch_gemm gives this problem to an MFMA tile kernel.  Only those take row strides (lda, ldy), and a
+// problem that comes with strides never goes to the row slices.
+static bool is_strided(const GemmArgs& a) { return (a.lda != 0 && a.lda != a.K) || (a.ldy != 0 && a.ldy != a.N); }
+static bool goes_to_tile_kernel(const GemmArgs& a) {
+    const bool sliced = a.M > 16 && !is_strided(a) && a.res_row_map == nullptr && a.out_row_map == nullptr && a.tok_row_map == nullptr &&
+                        a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0 && slices_beat_tiles(a);
+    return a.M > 16 && !sliced;
+}
+bool gemm_takes_row_strides(const GemmArgs& a) { return a.M > 16 && a.x_splits <= 1; }
+
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
+    const bool bad_stride = (a.lda != 0 && (a.lda < a.K || a.lda % 8 != 0)) || (a.ldy != 0 && (a.ldy < a.N || a.ldy % 8 != 0));
+    if (bad_stride || (is_strided(a) && (!gemm_takes_row_strides(a) || epi == EPI_QKV))) return hipErrorInvalidValue;
     if (a.x_splits > 1 && (epi != EPI_BIAS_RES || !gemm_merges_attention_ranges(a))) return hipErrorInvalidValue;
     // A few more rows than the weight-streaming kernels take at once (a decode step of more than 16 sequences, a very
     // short prompt): the same kernels with the rows cut into slices of 16 along gridDim.y, where that beats a tile kernel
     // that would run a handful of workgroups through the whole K loop (decode layer-step of the hidden-1024 layer at 32
     // sequences: 91 us with the tile kernels, 38 us so; 128 sequences: 136 -> 73 us).
-    const bool sliced = a.M > 16 && a.res_row_map == nullptr && a.out_row_map == nullptr && a.tok_row_map == nullptr &&
-                        a.ln_gamma == nullptr && a.bump_lens == nullptr && a.pf.blocks == 0 && slices_beat_tiles(a);
-    if (a.M <= 16 || sliced) {
+    if (!goes_to_tile_kernel(a)) {
         // enough workgroups to cover the chip first, then wider slices to amortise the activations
         if (try_flat(a, epi, s)) return hipGetLastError();
         if (try_stream(a, epi, s)) return hipGetLastError();
@@ -1273,11 +1322,15 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         // over a very wide output, e.g. the vocabulary: 128 x 1024 x 50304 39.7 -> 30.9 us with 128x128 tiles)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
         if (big_tiles >= 150 && a.M > 128) {
-            // two wave groups in alternation, except for very long K, where the single-phase schedule with the early
-            // release of the stage is ahead (25082 x 12288 x 49152: 1.11 against 1.04 PFLOP/s; at K of 4096 to 16384 the
-            // alternation leads by 2-6 %, measured in one call)
+            // Four waves with 128 x 128 each: a third less LDS read traffic per flop than eight waves of 128 x 64, and the
+            // LDS of a CU -- fragment reads plus the arriving tiles -- is what the matrix pipes otherwise wait for
+            // (rows x N x K, eight waves in two alternating groups -> four waves: 25082 x 49152 x 12288 1.16 -> 1.23 PFLOP/s,
+            // 8192 x 16384 x 12288 1.20 -> 1.33, 2951 x 16384 x 4096 1.13 -> 1.24).  With a very long K and rows that are a
+            // multiple of 32 KB apart the eight-wave kernel with the early release of the stage is ahead (25082 x 12288 x
+            // 49152: 1.09 against 0.97); once the rows are 128 bytes further apart (the layer's own feed-forward buffer is
+            // laid out so) both reach 1.16.
             if (a.K >= 32768) launch_dma64_cfg<2, 4, 256, 256, 2, 1, 1>(a, epi, s);
-            else launch_dma64_cfg<2, 4, 256, 256, 2, 1, 2>(a, epi, s);
+            else launch_dma64_cfg<2, 2, 256, 256, 2, 1, 2>(a, epi, s);
         }
         else {
             // few tiles (short prompts, narrow layers): smaller tiles put more workgroups on the chip; the K loop of

@@ -53,6 +53,9 @@ struct GemmArgs {
     const half_t* bias;     // [N]
     half_t* y;              // output [*, N] (EPI_QKV: the Q rows, [M, hidden])
     int M, N, K;
+    // MFMA tile kernels only (launch_gemm refuses them elsewhere; see gemm_takes_row_strides): halfs between consecutive
+    // rows of x and of y (0: K and N; multiples of 8, not below K and N; not with EPI_QKV)
+    int lda, ldy;
     // EPI_BIAS_RES: residual row of output row m is res[res_row_map ? res_row_map[m] : m]
     const half_t* res;
     const int32_t* res_row_map;
@@ -82,6 +85,8 @@ struct GemmArgs {
     const float* x_part_ml;
     int x_splits;
 };
+// true when launch_gemm can serve this problem with row strides (more than 16 rows: an MFMA tile kernel)
+bool gemm_takes_row_strides(const GemmArgs& a);
 // true when launch_gemm would give this bias+residual projection to the kernel that can merge the key ranges itself
 bool gemm_merges_attention_ranges(const GemmArgs& a);
 

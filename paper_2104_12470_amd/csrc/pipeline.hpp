@@ -144,49 +144,43 @@ EET_PIPE_FN void gemm_k_loop(Ops& op, int nk) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// K loop of the MFMA tile kernel, two wave groups in alternation ("ping-pong"), two LDS stages.
+// K loop of the MFMA tile kernel for one wave per SIMD, two LDS stages.  Nothing else runs on the SIMD while a wave
+// waits, and the LDS of the CU is busy most of the time (fragment reads of four waves plus the arriving tiles), so
+// every request is issued between the multiplies of an earlier phase, spread evenly over them: a burst of LDS reads
+// stalls the wave's instruction stream, and the multiplies behind it, until the LDS queue has room.
 //
-// The waves of a workgroup form two groups; a SIMD hosts one wave of each.  A K tile is handled in four phases
-// separated by workgroup barriers: M0 (request tile kt+1, read the fragments of k half 0, wait for them), C0 (multiply
-// k half 0), M1 (wait for the own part of tile kt+1, read the fragments of k half 1, wait), C1 (multiply k half 1).
-// The second group enters one barrier later, so whenever one group multiplies the other does its memory work: the
-// matrix pipe of a SIMD always has exactly one wave feeding it back to back, and no wave's loads or LDS waits stand
-// between two multiplies.  Both groups run this same code; the second executes one extra barrier in front of the
-// loop and the first one behind it, so every wave passes the same number of barriers.
+// A K tile is two phases, one per k half; the fragments of a whole k half have two register buffers (buffer = k half).
+// While k half 0 of tile kt is multiplied the reads of its k half 1 are issued.  After them every read of the stage
+// has been issued: the wave waits for them and for its part of tile kt+1, and the barrier hands the stage over with
+// half of the tile's multiplies still to come.  While k half 1 is multiplied the loads of tile kt+2 go into the stage
+// just released and the reads of k half 0 of tile kt+1 are issued.  The loads past the last tile repeat the last tile
+// (the number of loads per step, and with it every wait count, stays fixed; nothing reads them).
 //
-// Hand-over (group A's phase p coincides with group B's phase p-1): when A requests tile kt+1 in M0(kt), the stage it
-// goes to held tile kt-1, whose last reads are B's M1(kt-1), finished before the barrier that opens A's M0(kt).  B's
-// part of tile kt+1 is requested in B's M0(kt) and waited for in B's M1(kt), which ends with the barrier that opens
-// A's M0(kt+1), the first read of that tile.
-//
-// Executor interface: load(tile, stage), wait_vmem<0>(), barrier() as above, and
-//   second_group()              wave-uniform: this wave belongs to the group that runs one phase behind
-//   read_half<H>(stage)         issue the LDS reads of k half H of the tile in `stage` (all fragments of the half)
-//   wait_reads()                every LDS read of this wave has landed
-//   mma_half<H>()               multiply-accumulate k half H
+// Executor interface: load(tile, stage), wait_vmem<L>(), barrier() as for gemm_k_loop, and
+//   fetch_half<H>(stage)                        issue the LDS reads of k half H of the tile in `stage` into buffer H
+//   wait_fetched()                              every LDS read of this wave has landed
+//   mma_half_fetch<H>(stage)                    multiply k half H out of buffer H; between the multiplies issue the reads
+//                                               of k half 1-H of `stage` into the other buffer
+//   mma_half_fetch_load<H>(stage, tile, lstage) the same, and issue the loads of K tile `tile` into stage `lstage`
 // ---------------------------------------------------------------------------------------------------------
 template <class Ops>
-EET_PIPE_FN void gemm_k_loop_pingpong(Ops& op, int nk) {
+EET_PIPE_FN void gemm_k_loop_interleaved(Ops& op, int nk) {
     op.load(0, 0);
-    op.template wait_vmem<0>();
-    op.barrier();
-    if (op.second_group()) op.barrier();
+    op.load(nk > 1 ? 1 : 0, 1);
+    op.template wait_vmem<1>();                   // tile 0 of this wave has landed ...
+    op.barrier();                                 // ... and everybody else's
+    op.template fetch_half<0>(0);
     for (int kt = 0; kt < nk; ++kt) {
         const int st = kt & 1;
-        if (kt + 1 < nk) op.load(kt + 1, st ^ 1);     // M0
-        op.template read_half<0>(st);
-        op.wait_reads();
-        op.barrier();
-        op.template mma_half<0>();                    // C0
-        op.barrier();
-        op.template wait_vmem<0>();                // M1: this wave's part of tile kt+1 has landed
-        op.template read_half<1>(st);
-        op.wait_reads();
-        op.barrier();
-        op.template mma_half<1>();                    // C1
-        op.barrier();
+        op.wait_fetched();
+        op.template mma_half_fetch<0>(st);
+        op.wait_fetched();                          // every read of stage st has landed
+        op.template wait_vmem<0>();               // this wave's part of tile kt+1 has landed
+        op.barrier();                             // ... and everybody else's; stage st is free
+        op.template mma_half_fetch_load<1>(st ^ 1, kt + 2 < nk ? kt + 2 : nk - 1, st);   // (reads past the last tile: stale, never multiplied)
     }
-    if (!op.second_group()) op.barrier();
+    op.wait_fetched();                              // the stale reads and the repeated loads too: the epilogue reuses the stages
+    op.template wait_vmem<0>();
 }
 
 // ---------------------------------------------------------------------------------------------------------

@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
             "eet_op_bias_gelu": (i32, [vp, vp, vp, i64, i32, vp]),
             "eet_op_bias_residual": (i32, [vp, vp, vp, vp, i64, i32, vp]),
             "eet_op_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
+            "eet_op_linear_strided": (i32, [vp, i64, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]),
             "eet_op_attention_prefill": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
             "eet_op_attention_encoder": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp]),
             "eet_op_attention_unfused": (i32, [vp, vp, vp, vp, i32p, i32, i32, i32, i32, i32, vp, i32, vp]),
@@ -136,7 +137,7 @@ EXPORTS = ("eet_kv_cache_bytes", "eet_workspace_bytes", "eet_layer_create", "eet
            "eet_cache_lens", "eet_layer_destroy", "eet_last_error", "eet_stack_kv_cache_bytes",
            "eet_stack_workspace_bytes", "eet_stack_create", "eet_stack_prefill", "eet_stack_decode_step",
            "eet_stack_cache_lens", "eet_stack_destroy", "eet_op_layernorm", "eet_op_softmax_maskfree",
-           "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_attention_prefill", "eet_op_attention_encoder",
+           "eet_op_bias_gelu", "eet_op_bias_residual", "eet_op_linear", "eet_op_linear_strided", "eet_op_attention_prefill", "eet_op_attention_encoder",
            "eet_op_attention_unfused", "eet_op_attention_decode_scratch_bytes", "eet_op_attention_decode", "eet_op_attention_decode_static", "eet_bufmgr_create", "eet_bufmgr_request",
            "eet_bufmgr_release", "eet_bufmgr_query", "eet_bufmgr_destroy", "eet_model_workspace_bytes", "eet_model_create",
            "eet_model_prefill", "eet_model_decode_step", "eet_model_hidden_states", "eet_model_destroy", "eet_op_embedding",
@@ -303,6 +304,15 @@ def eet_op_linear(x, w, bias, y, residual=None, act=0, stream=None) -> None:
     assert w.shape[1] == k
     _check(lib().eet_op_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), rows, k, w.shape[0], act,
                                _stream(stream)))
+
+
+def eet_op_linear_strided(x, w, bias, y, residual=None, act=0, stream=None) -> None:
+    """x [rows, in] and y [rows, out] may be column slices of wider contiguous buffers: their row strides are passed on."""
+    assert x.dim() == 2 and y.dim() == 2 and x.stride(1) == 1 and y.stride(1) == 1 and x.shape[0] == y.shape[0]
+    rows, k = x.shape
+    assert w.shape[1] == k and y.shape[1] == w.shape[0]
+    _check(lib().eet_op_linear_strided(x.data_ptr(), x.stride(0), _ptr(w), _ptr(bias), _ptr(residual), y.data_ptr(), y.stride(0),
+                                       rows, k, w.shape[0], act, _stream(stream)))
 
 
 def eet_op_attention_prefill(q, k_cache, v_cache, ctx, q_lens, heads, stream=None) -> None:

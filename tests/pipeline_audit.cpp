@@ -103,34 +103,6 @@ struct Trace {
             }
         }
     }
-    // The same rules between the waves of two groups that run different records (x reads, y loads): nothing orders two
-    // waves inside a segment, so every read / load pair on a stage must be a whole barrier apart, the load that a consumed
-    // read depends on -- the last one y issued before the read's segment -- must carry the read's tile, and both records
-    // must pass the same number of barriers.
-    static void check_across(const char* what, Trace& x, const Trace& y) {
-        char buf[256];
-        if (x.seg != y.seg) x.fail(std::string(what) + ": the two groups pass different numbers of barriers");
-        for (const Read& r : x.reads) {
-            if (r.retire_pos < 0) continue;
-            const Load* latest = nullptr;
-            for (const Load& g : y.loads) {
-                if (g.ring != r.ring || g.stage != r.stage || g.retire_pos < 0) continue;
-                const bool load_first = g.retire_seg < r.issue_seg, read_first = r.retire_seg < g.issue_seg;
-                if (!load_first && !read_first) {
-                    snprintf(buf, sizeof buf, "%s: R1/R2 ring %d stage %d: a read of tile %d (segments %d..%d) and the other group's load of tile %d "
-                             "(segments %d..%d) are not a barrier apart", what, r.ring, r.stage, r.tile, r.issue_seg, r.retire_seg, g.tile,
-                             g.issue_seg, g.retire_seg);
-                    x.fail(buf);
-                }
-                if (load_first && (!latest || g.issue_seg > latest->issue_seg)) latest = &g;
-            }
-            if (r.consumed && (!latest || latest->tile != r.tile)) {
-                snprintf(buf, sizeof buf, "%s: R2 ring %d stage %d: a consumed read expects tile %d, the other group's part of the stage holds tile %d",
-                         what, r.ring, r.stage, r.tile, latest ? latest->tile : -1);
-                x.fail(buf);
-            }
-        }
-    }
 };
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -191,45 +163,58 @@ struct GemmRecorder {
 };
 
 // ------------------------------------------------------------------------------------------------------------------
-// recorder for pipe::gemm_k_loop_pingpong: one record per wave group
+// recorder for pipe::gemm_k_loop_interleaved: two fragment buffers, one per k half
 // ------------------------------------------------------------------------------------------------------------------
-struct PingPongRecorder {
+struct HalfStepRecorder {
     Trace t;
     int nk;
-    bool second;
-    int half_read = -1;                                    // the read group sitting in the (single) fragment buffer
+    int buf_read[2] = {-1, -1};
     int issued = 0;
     std::vector<int> consumed;
-    PingPongRecorder(int nk_, bool second_) : nk(nk_), second(second_) {}
-    bool second_group() const { return second; }
+    explicit HalfStepRecorder(int nk_) : nk(nk_) {}
     void load(int tile, int stage) { t.issue_load(0, stage, tile); }
     template <int L>
-    void wait_vmem() { static_assert(L == 0, "the two-group schedule waits for everything"); t.retire_loads(0); }
+    void wait_vmem() { t.retire_loads((size_t)L); }
     void barrier() { t.barrier(); }
     template <int H>
-    void read_half(int stage) {
+    void fetch_half(int stage) {
         const int idx = issued++;
         if (H != idx % 2) t.fail("R4 fragment reads do not alternate between the two k halves");
-        if (half_read >= 0 && !t.reads[half_read].consumed) t.fail("R3 the fragment buffer is refilled before it was multiplied");
-        half_read = t.issue_read(0, stage, idx / 2, H);
+        if (buf_read[H] >= 0 && !t.reads[buf_read[H]].consumed) t.fail("R3 a fragment buffer is refilled before it was multiplied");
+        buf_read[H] = t.issue_read(0, stage, idx / 2, H);
     }
-    void wait_reads() { t.retire_reads(0); }
+    void wait_fetched() { t.retire_reads(0); }
     template <int H>
-    void mma_half() {
+    void multiply() {
         ++t.pos;
-        if (half_read < 0) { t.fail("R3 multiply before any fragment was read"); return; }
-        Read& r = t.reads[half_read];
-        if (r.sub != H) t.fail("R3 multiply names a k half that is not in the buffer");
+        if (buf_read[H] < 0) { t.fail("R3 multiply before any fragment was read"); return; }
+        Read& r = t.reads[buf_read[H]];
         if (r.retire_pos < 0) t.fail("R3 multiply consumes fragments that have not been waited for");
         if (r.consumed) t.fail("R4 a k half is multiplied twice");
         r.consumed = true;
         consumed.push_back(r.tile * 2 + r.sub);
     }
-    void finish(const char* what) {
+    // the requests are issued between the multiplies of the phase: in program order after its first multiply, which has
+    // checked that its own buffer was waited for; the reads go to the other buffer
+    template <int H>
+    void mma_half_fetch(int stage) {
+        multiply<H>();
+        fetch_half<1 - H>(stage);
+    }
+    template <int H>
+    void mma_half_fetch_load(int stage, int tile, int lstage) {
+        multiply<H>();
+        load(tile, lstage);
+        fetch_half<1 - H>(stage);
+    }
+    std::string verdict(const char* what) {
         t.check(what);
         if ((int)consumed.size() != 2 * nk) t.fail(std::string(what) + ": R4 number of multiply phases is not 2 per K tile");
         for (int i = 0; i < (int)consumed.size() && i < 2 * nk; ++i)
             if (consumed[i] != i) t.fail(std::string(what) + ": R4 k halves are not consumed once each, in order");
+        for (const Read& r : t.reads)
+            if (!r.consumed && r.tile < nk) t.fail(std::string(what) + ": R4 a fragment of a real tile is read and never multiplied");
+        return t.error;
     }
 };
 
@@ -303,12 +288,27 @@ void mutant_gemm_loop(Ops& op, int nk, Mistake what) {
     if (what == kLateLoadWait) op.template wait_vmem<0>();
 }
 
-// planted mistake for the two-group schedule: waves that never wait for their own tile loads after the prologue
-struct NoWait : PingPongRecorder {
-    using PingPongRecorder::PingPongRecorder;
-    template <int L>
-    void wait_vmem() { if (t.seg < 2) t.retire_loads(0); }
-};
+// planted mistake for the one-wave-per-SIMD schedule: the tile after next is requested during the first k half, before
+// the barrier that releases the stage it goes to
+template <class Ops>
+void mutant_interleaved_loop(Ops& op, int nk) {
+    op.load(0, 0);
+    op.load(nk > 1 ? 1 : 0, 1);
+    op.template wait_vmem<1>();
+    op.barrier();
+    op.template fetch_half<0>(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int st = kt & 1;
+        op.wait_fetched();
+        op.template mma_half_fetch_load<0>(st, kt + 2 < nk ? kt + 2 : nk - 1, st);
+        op.wait_fetched();
+        op.template wait_vmem<1>();
+        op.barrier();
+        op.template mma_half_fetch<1>(st ^ 1);
+    }
+    op.wait_fetched();
+    op.template wait_vmem<0>();
+}
 
 int failures = 0;
 
@@ -341,30 +341,17 @@ int main() {
             expect_ok(r.verdict(name), name);
         }
         {
+            HalfStepRecorder r(nk);
+            eet::pipe::gemm_k_loop_interleaved(r, nk);
+            snprintf(name, sizeof name, "tile kernel, one wave per SIMD, requests between the multiplies, %d K tiles", nk);
+            expect_ok(r.verdict(name), name);
+        }
+        {
             GemmRecorder r(nk);
             eet::pipe::gemm_k_loop<3>(r, nk);
             snprintf(name, sizeof name, "tile kernel, three LDS stages, %d K tiles", nk);
             expect_ok(r.verdict(name), name);
         }
-    }
-    for (int nk : {1, 2, 3, 4, 5, 16, 192, 768}) {
-        PingPongRecorder a(nk, false), b(nk, true);
-        eet::pipe::gemm_k_loop_pingpong(a, nk);
-        eet::pipe::gemm_k_loop_pingpong(b, nk);
-        snprintf(name, sizeof name, "tile kernel, two wave groups in alternation, %d K tiles", nk);
-        a.finish(name); b.finish(name);
-        Trace::check_across(name, a.t, b.t);
-        Trace::check_across(name, b.t, a.t);
-        expect_ok(a.t.error.empty() ? b.t.error : a.t.error, name);
-    }
-    {   // planted: both groups run the first group's code (no phase shift is fine), but one group skips its loads' wait
-        NoWait a(6, false), b(6, true);
-        eet::pipe::gemm_k_loop_pingpong(a, 6);
-        eet::pipe::gemm_k_loop_pingpong(b, 6);
-        a.finish("x"); b.finish("x");
-        Trace::check_across("x", a.t, b.t);
-        Trace::check_across("x", b.t, a.t);
-        expect_caught(a.t.error.empty() ? b.t.error : a.t.error, "two-group schedule whose waves never wait for their own tile loads");
     }
     for (int nt : {1, 2, 3, 4, 5, 8, 16, 33, 64}) {
         AttnRecorder r(nt);
@@ -399,6 +386,12 @@ int main() {
         GemmRecorder r(8);
         mutant_gemm_loop(r, 8, p.m);
         expect_caught(r.verdict(p.what), p.what);
+    }
+    {
+        HalfStepRecorder r(8);
+        mutant_interleaved_loop(r, 8);
+        const char* what = "one-wave-per-SIMD schedule that requests the tile after next before the stage is released";
+        expect_caught(r.verdict(what), what);
     }
     printf(failures ? "pipeline audit: %d FAILED\n" : "pipeline audit: all schedules pass (%d failures)\n", failures);
     return failures ? 1 : 0;

@@ -155,7 +155,8 @@ def test_encoder_use_elementwise(eet, name):
 def test_left_padded_prefill(eet, name):
     """eet_prefill_left_padded (the layout Algorithm 1 is printed for: pads first) against the oracle in that layout,
     and against eet_prefill on the same prompts right-padded: same numbers bit for bit, same cache, same lengths,
-    same decode steps afterwards.  cfg3 (full size, 256-row attention tiles) compares GPU with GPU only."""
+    same decode steps afterwards.  cfg3 (full size, head size 128, prompts over 512 tokens: the 256-row attention tiles)
+    is compared with the oracle on sampled rows of its longest and shortest prompt, in the left-padded layout."""
     w = wl.WORKLOADS[name]
     W = wl.layer_weights(w, 0, random_affine=True)
     x, lens = wl.prompt_embeddings(w), wl.lengths(w)
@@ -182,6 +183,20 @@ def test_left_padded_prefill(eet, name):
         for b, L in enumerate(lens):
             gate(got_l[b, S - L:], want[b, S - L:], f"{name} left-padded prefill b={b} L={L}")
         check_cache(left, oracle, oracle.lens, B, f"{name} after left-padded prefill")
+    else:                                                          # full size: the oracle evaluates sampled rows
+        W64 = {k: v.astype(np.float64) for k, v in W.items()}
+        rng = np.random.default_rng(w.seed + 7)
+        kc, vc = left.cache_views()
+        for b in sorted({int(np.argmax(lens)), int(np.argmin(lens))}):
+            L = int(lens[b])
+            assert L > 512, "the case is here for prompts that reach the 256-row attention tiles"
+            rows = sample_rows(L, L, rng)
+            o1 = orc.DecoderLayerOracle(W64, w.heads, 1, S, w.ln_eps)
+            want = o1.prefill(xl[b:b + 1], [L], rows={0: rows}, left_padded=True)[0]
+            at = S - L + np.asarray(rows)
+            gate(got_l[b, at], want[at], f"{name} left-padded prefill b={b} L={L} sampled rows")
+            gate(host(kc[b, :, :L]), o1.k_cache[0, :, :L], f"{name} left-padded K cache b={b}", 1e-2, 1e-3)
+            gate(host(vc[b, :, :L]), o1.v_cache[0, :, :L], f"{name} left-padded V cache b={b}", 1e-2, 1e-3)
     for k in range(2):                                             # decode does not know which side the pads were on
         xs = dev(wl.decode_embeddings(w, k))
         a, c = left.decode_step(xs), right.decode_step(xs)

@@ -234,6 +234,51 @@ def test_linear_large_tiles(eet, M, K, N):
     gate(host(y), lin + r.astype(np.float64), f"large linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
 
 
+@pytest.mark.parametrize("M,K,N,padx,pady", [(3000, 1024, 4160, 64, 72),     # 256x256 tiles, four waves
+                                              (300, 512, 640, 8, 64),          # the small tiles
+                                              (2049, 4096, 6144, 64, 0)])
+def test_linear_strided(eet, M, K, N, padx, pady):
+    """eet_op_linear_strided: x and y are column slices of wider buffers (the layout the layer gives its feed-forward
+    rows); the columns between the rows are neither read into the result nor written."""
+    x = wl.normal(360, M, (M, K))
+    w = wl.normal(361, N, (N, K), 1.0 / np.sqrt(K))
+    b = wl.normal(362, N, (N,), 0.5)
+    r = wl.normal(363, M, (M, N))
+    xw = torch.full((M, K + padx), float("nan"), dtype=torch.float16, device="cuda:0")     # poison between the rows
+    xw[:, :K] = dev(x)
+    yw = torch.full((M, N + pady), float("nan"), dtype=torch.float16, device="cuda:0")
+    lin = orc.linear(x, w, b)
+    eet.eet_op_linear_strided(xw[:, :K], dev(w), dev(b), yw[:, :N], act=1)
+    torch.cuda.synchronize()
+    gate(host(yw[:, :N].contiguous()), orc.gelu_tanh(lin), f"strided linear+gelu {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    assert bool(torch.isnan(yw[:, N:]).all()), "columns between the output rows were written"
+    yw.fill_(float("nan"))
+    eet.eet_op_linear_strided(xw[:, :K], dev(w), dev(b), yw[:, :N], residual=dev(r))
+    torch.cuda.synchronize()
+    gate(host(yw[:, :N].contiguous()), lin + r.astype(np.float64), f"strided linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    assert bool(torch.isnan(yw[:, N:]).all())
+    dense = torch.empty((M, N), dtype=torch.float16, device="cuda:0")                       # dense strides: the same call as eet_op_linear
+    eet.eet_op_linear_strided(dev(x), dev(w), dev(b), dense, residual=dev(r))
+    torch.cuda.synchronize()
+    gate(host(dense), lin + r.astype(np.float64), f"linear+res through the strided entry point, dense rows {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    if M > 512:                                    # the same tile kernel serves both (few dense rows may go to row slices instead)
+        assert np.array_equal(host(dense).view(np.uint16), host(yw[:, :N].contiguous()).view(np.uint16))
+
+
+def test_linear_strided_refuses_what_it_cannot_do(eet):
+    K, N = 256, 512
+    w, b = dev(wl.normal(364, 1, (N, K))), dev(wl.normal(365, 1, (N,)))
+    xw = torch.zeros((8, K + 64), dtype=torch.float16, device="cuda:0")
+    y = torch.empty((8, N), dtype=torch.float16, device="cuda:0")
+    with pytest.raises(RuntimeError, match="weight-streaming"):          # 8 rows: the decode path, dense rows only
+        eet.eet_op_linear_strided(xw[:, :K], w, b, y)
+    eet.eet_op_linear_strided(xw[:, :K].contiguous(), w, b, y)           # dense: served
+    L = eet.lib()
+    assert L.eet_op_linear_strided(xw.data_ptr(), K - 8, w.data_ptr(), b.data_ptr(), None, y.data_ptr(), N, 300, K, N, 0, None) == -1
+    assert L.eet_op_linear_strided(xw.data_ptr(), K + 4, w.data_ptr(), b.data_ptr(), None, y.data_ptr(), N, 300, K, N, 0, None) == -1
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("d,heads,S,cap,lens", [
     (64, 2, 24, 32, [24, 1, 7]),
     (64, 3, 200, 224, [200, 3, 129, 64, 65]),

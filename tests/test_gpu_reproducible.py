@@ -48,7 +48,7 @@ def workspace_piece(w, max_batch, offset):
               ("buffer A: LayerNorm-1 rows, then the attention context", al(2 * T * H)),
               ("buffer B: Q rows, then LayerNorm-2 rows", al(2 * T * H)),
               ("buffer Y: output projection + residual", al(2 * T * H)),
-              ("buffer F: first feed-forward projection + GELU", al(2 * T * F))]
+              ("buffer F: first feed-forward projection + GELU", al(2 * T * (F + 64)))]   # room for rows 128 bytes further apart
     lo = 0
     for name, size in pieces:
         if offset < lo + size:

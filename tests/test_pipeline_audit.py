@@ -1,4 +1,4 @@
-"""The LDS hand-over schedules of the two pipelined kernels (tile GEMM: two stages, two stages with early release, two wave groups in alternation, three stages; 256-row attention: K and V
+"""The LDS hand-over schedules of the two pipelined kernels (tile GEMM: two stages, two stages with early release, one wave per SIMD with the requests between the multiplies, three stages; 256-row attention: K and V
 rings) and the tile order, audited on the host: tests/pipeline_audit.cpp instantiates the very templates the kernels
 compile (paper_2104_12470_amd/csrc/pipeline.hpp) with a recording executor and checks that no stage is overwritten
 while a read of it can be outstanding, that consumed reads see landed tiles, that every K sub-step is multiplied once,
