@@ -454,6 +454,33 @@ def test_attention_decode_with_one_range_per_pair(eet, d, heads, cap, n_keys, pe
 
 
 @pytest.mark.parametrize("d,heads,cap,n_keys", [
+    (64, 64, 256, [0, 5, 0]),           # 192 pairs: one key range per pair
+    (128, 2, 4224, [0, 4224, -3]),      # few pairs: the key range is split and merged by the combine kernel
+])
+def test_attention_decode_of_a_sequence_without_keys_is_zero(eet, d, heads, cap, n_keys):
+    """n_keys[b] < 1 lives on the device and cannot be refused by the host: the context rows of such a sequence are
+    defined as zeros (not NaN), the other sequences do not notice."""
+    B = len(n_keys)
+    q = wl.normal(520 + d, 1, (B, heads, d))
+    kc = wl.normal(520 + d, 2, (B, heads, cap, d))
+    vc = wl.normal(520 + d, 3, (B, heads, cap, d))
+    seen = [max(n, 0) for n in n_keys]
+    live = [b for b in range(B) if seen[b] > 0]
+    want = orc.attention_decode(q[live], kc[live], vc[live], [seen[b] for b in live])
+    scratch = torch.empty(eet.eet_op_attention_decode_scratch_bytes(B, heads, d, cap), dtype=torch.uint8, device="cuda:0")
+    scratch.fill_(0xFF)                                   # NaN patterns where partial results will land
+    ctx = torch.full((B, heads * d), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_attention_decode(dev(q.reshape(B, heads * d)), dev(kc), dev(vc), ctx, dev(np.asarray(n_keys, np.int32)), scratch)
+    torch.cuda.synchronize()
+    got = host(ctx).reshape(B, heads, d)
+    for i, b in enumerate(live):
+        gate(got[b], want[i], f"attention decode beside sequences without keys, d={d} b={b}", OP_MAX, OP_MEAN)
+    for b in range(B):
+        if seen[b] == 0:
+            assert np.all(got[b] == 0), f"sequence {b} has no key: its context must be zeros"
+
+
+@pytest.mark.parametrize("d,heads,cap,n_keys", [
     (64, 4, 600, [1, 17, 600]),
     (128, 4, 600, [600, 16, 33]),
     (64, 2, 2048, [2048, 100]),        # several key ranges per (sequence, head), one of them empty for the short one
