@@ -974,7 +974,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 // Same data path as gemm_flat (whole-line loads, MFMA layout made in wave-private LDS staging
 // areas, no barrier inside the K loop), but K is a loop and the activations do not fit in LDS:
 //   * a workgroup of 4 waves owns 16*NF output columns; groups of UQ = 4 units (256 K values,
-//     512 contiguous bytes of every weight row) are dealt round-robin to the waves;
+//     512 contiguous bytes of every weight row; 2 units with NF = 3, for the registers) are dealt
+//     round-robin to the waves;
 //   * a wave loads, per group, NF*UQ*2 instructions of weights and UQ*XH of activations (the
 //     16 x 64 activation unit has the shape of a weight unit and takes the same road through the
 //     staging areas; XH = 1 when M <= 8), for group i+1 before group i is consumed (two register
@@ -987,7 +988,7 @@ constexpr int kStreamStagedUnits = 2;
 template <int NF, int EPI, int XH, bool SL>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     if (SL) take_row_slice<EPI>(a);
-    constexpr int UQ = 4;                                   // units per group
+    constexpr int UQ = NF >= 3 ? 2 : 4;                     // units per group (three column blocks: half as many, for the registers)
     constexpr int SU = kStreamStagedUnits;                  // units staged at a time
     constexpr int AREAS = SU * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
     extern __shared__ __attribute__((aligned(16))) unsigned char stream_smem[];
@@ -1253,6 +1254,17 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
     if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
+    // More than 8 rows: a workgroup pulls twice the activation lines out of L2, as many as weight lines when it owns 16
+    // columns, and the stream slows down with every distinct activation line (12288 x 49152: 208 us at 1 row, 211 at
+    // 8, 222 at 9, 246 at 16).  48 columns per workgroup cut that to a third: 246 -> 209 us, 12288 x 12288 60 -> 50 us,
+    // 36864 x 12288 179 -> 166 us, 49152 x 12288 226 -> 219 us (16 rows each).  Taken where 48 divides N and the
+    // workgroups fill the CUs evenly (N = 12288: exactly one per CU).  Sharing the activation lines between the waves of
+    // a workgroup through the CU's vector cache instead (waves side by side in N, all walking the same K) changed nothing.
+    const int wg48 = a.N % 48 == 0 ? a.N / 48 : 0;
+    if (a.M > 8 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {
+        launch_stream<3, 2>(a, epi, s);
+        return true;
+    }
     const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU
     if (a.M <= 8) {
         if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
