@@ -988,7 +988,7 @@ constexpr int kStreamStagedUnits = 2;
 template <int NF, int EPI, int XH, bool SL>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     if (SL) take_row_slice<EPI>(a);
-    constexpr int UQ = NF >= 3 ? 2 : 4;                     // units per group (three column blocks: half as many, for the registers)
+    constexpr int UQ = NF >= 3 ? 2 : 4;                     // units per group (three or four column blocks: half as many, for the registers)
     constexpr int SU = kStreamStagedUnits;                  // units staged at a time
     constexpr int AREAS = SU * (NF + 1);                    // staging areas per wave (16 x 144 bytes each)
     extern __shared__ __attribute__((aligned(16))) unsigned char stream_smem[];
@@ -1254,15 +1254,21 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
 static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
     if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
-    // More than 8 rows: a workgroup pulls twice the activation lines out of L2, as many as weight lines when it owns 16
+    // With 16 rows a workgroup pulls as many activation lines out of L2 as weight lines when it owns 16
     // columns, and the stream slows down with every distinct activation line (12288 x 49152: 208 us at 1 row, 211 at
     // 8, 222 at 9, 246 at 16).  48 columns per workgroup cut that to a third: 246 -> 209 us, 12288 x 12288 60 -> 50 us,
     // 36864 x 12288 179 -> 166 us, 49152 x 12288 226 -> 219 us (16 rows each).  Taken where 48 divides N and the
     // workgroups fill the CUs evenly (N = 12288: exactly one per CU).  Sharing the activation lines between the waves of
     // a workgroup through the CU's vector cache instead (waves side by side in N, all walking the same K) changed nothing.
     const int wg48 = a.N % 48 == 0 ? a.N / 48 : 0;
-    if (a.M > 8 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {
-        launch_stream<3, 2>(a, epi, s);
+    if (a.M > 1 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {   // (2 to 8 rows: 12288 x 4096 19.3 -> 18.1 us, 36864 x 12288 174 -> 162 us)
+        if (a.M > 8) launch_stream<3, 2>(a, epi, s);
+        else launch_stream<3, 1>(a, epi, s);
+        return true;
+    }
+    const int wg64 = a.N % 64 == 0 ? a.N / 64 : 0;             // N without a factor of 3: 64 columns (16 rows: 16384 x 4096 25.1 -> 23.0 us,
+    if (a.M > 8 && wg64 >= 256 && (wg64 % 256 == 0 || wg64 >= 1024)) {   // 32768 x 8192 129 -> 114 us; nothing to gain at 4 rows)
+        launch_stream<4, 2>(a, epi, s);
         return true;
     }
     const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU

@@ -216,6 +216,26 @@ def test_linear(eet, M, K, N):
     gate(host(y), lin + r.astype(np.float64), f"linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
 
 
+@pytest.mark.parametrize("M,K,N", [(16, 512, 12288), (9, 256, 12288), (5, 768, 12288), (2, 256, 49152),   # 48 columns per workgroup
+                                   (16, 512, 16384), (11, 256, 65536),                                     # 64 columns per workgroup
+                                   (40, 256, 12288)])                                                      # the same in row slices
+def test_linear_weight_stream_with_wide_workgroups(eet, M, K, N):
+    """Decode-sized rows over outputs wide enough for the weight-streaming kernel to give a workgroup 48 or 64 columns."""
+    x = wl.normal(370, M, (M, K))
+    w = wl.normal(371, N, (N, K), 1.0 / np.sqrt(K))
+    b = wl.normal(372, N, (N,), 0.5)
+    r = wl.normal(373, M, (M, N))
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+    lin = orc.linear(x, w, b)
+    eet.eet_op_linear(dev(x), dev(w), dev(b), y, act=1)
+    torch.cuda.synchronize()
+    gate(host(y), orc.gelu_tanh(lin), f"wide-workgroup stream linear+gelu {M}x{K}x{N}", OP_MAX, OP_MEAN)
+    y.fill_(float("nan"))
+    eet.eet_op_linear(dev(x), dev(w), dev(b), y, residual=dev(r))
+    torch.cuda.synchronize()
+    gate(host(y), lin + r.astype(np.float64), f"wide-workgroup stream linear+res {M}x{K}x{N}", OP_MAX, OP_MEAN)
+
+
 @pytest.mark.parametrize("M,K,N", [(3000, 1024, 4160), (4099, 192, 3136), (2049, 4096, 6144)])
 def test_linear_large_tiles(eet, M, K, N):
     """Shapes that take the 256x256 direct-to-LDS tile kernel, with ragged row and column tails."""
