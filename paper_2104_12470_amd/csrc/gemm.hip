@@ -8,7 +8,7 @@
 // Kernels:
 //   gemm_mfma_dma64  prefill (M = valid tokens of the batch, packed) and decode steps of many sequences: 256x256 tiles
 //                    for the large problems, 128x128, 128x64 and 64x64 when there are few; direct global->LDS loads,
-//                    v_mfma_f32_32x32x16_f16; bound by the matrix cores.
+//                    v_mfma_f32_16x16x32_f16; bound by the matrix cores.
 //   gemm_flat        decode (M <= 16 rows), small layers: one memory round trip, few instructions.
 //   gemm_stream      decode, large layers: every weight is read from HBM exactly once per step, so
 //                    the kernel is a weight stream; v_mfma_f32_16x16x32_f16 does the 16-row contraction.
