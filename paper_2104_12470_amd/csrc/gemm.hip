@@ -103,26 +103,81 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, float
 // both access patterns spread over all banks.  `stage`: AM*16*128 bytes of LDS no other wave touches; mw, nw:
 // first row and column of the wave tile (its 64 columns are inside N or outside as a whole: N % 64 == 0).
 // A wave tile of 128 columns (ANT = 8 accumulator blocks across) is turned around in two passes of 64 columns, J0 = 0 and 4.
-template <int AM, int ANT, int J0, int EPI>
-__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][ANT], char* stage, int mw, int nw,
-                                                 int lane) {
+// Row bookkeeping of a wave tile's whole-line accesses (lane -> row it*8 + lane/8 of the tile, it = 0 .. AM*2-1), looked up
+// once for both 64-column passes and with every lookup in flight together: r0 = output row (EPI_QKV: the sequence
+// whose cache the row's K and V go to), r1 = residual row (EPI_QKV: the cache slot; negative or >= max_seq: dropped).
+// Rows past M repeat row M-1; they are never stored.
+template <int AM, int EPI>
+__device__ __forceinline__ void epilogue_rows(const GemmArgs& a, int mw, int lane, int (&r0)[AM * 2], int (&r1)[AM * 2]) {
+    const int r8 = lane >> 3;
+    int m[AM * 2];
+#pragma unroll
+    for (int it = 0; it < AM * 2; ++it) {
+        m[it] = mw + it * 8 + r8;
+        m[it] = m[it] < a.M ? m[it] : a.M - 1;
+    }
+    if constexpr (EPI == EPI_QKV) {
+        if (a.tok_row_map) {                             // prefill: token -> (sequence, position)
+            int tok[AM * 2];
+#pragma unroll
+            for (int it = 0; it < AM * 2; ++it) tok[it] = a.tok_row_map[m[it]];
+#pragma unroll
+            for (int it = 0; it < AM * 2; ++it) {
+                r0[it] = tok[it] / a.S;
+                r1[it] = tok[it] - r0[it] * a.S;
+            }
+            if (a.left_pad) {                            // pads lead: token 0 of the sequence is at row S - L_b
+                int len[AM * 2];
+#pragma unroll
+                for (int it = 0; it < AM * 2; ++it) len[it] = a.lens[r0[it]];
+#pragma unroll
+                for (int it = 0; it < AM * 2; ++it) r1[it] -= a.S - len[it];
+            }
+        } else {                                         // decode: the new token goes to slot n_b
+#pragma unroll
+            for (int it = 0; it < AM * 2; ++it) {
+                r0[it] = m[it];
+                r1[it] = a.lens[m[it]];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < AM * 2; ++it) {
+            r0[it] = a.out_row_map ? a.out_row_map[m[it]] : m[it];
+            r1[it] = (EPI == EPI_BIAS_RES && a.res_row_map) ? a.res_row_map[m[it]] : m[it];
+        }
+    }
+}
+
+// The residual rows under 64 columns of a wave tile, as whole lines (16-byte chunk lane%8 of each row): every request is
+// issued before anything waits for one, so the tile costs one trip to memory instead of one per group of rows
+// (8192 x 16384 x 2048 with a residual: 634 -> 552 us; 25082 x 12288 x 12288: 6.56 -> 6.37 ms).
+template <int AM>
+__device__ __forceinline__ void epilogue_request_residual(const GemmArgs& a, half8v (&rv)[AM * 2], const int (&rrow)[AM * 2], int nw, int lane) {
+    if (nw >= a.N) return;
+    const int c8 = lane & 7;
+#pragma unroll
+    for (int it = 0; it < AM * 2; ++it) rv[it] = *reinterpret_cast<const half8v*>(a.res + (int64_t)rrow[it] * a.N + nw + c8 * 8);
+}
+
+template <int AM, int ANT, int J0, int EPI, int RV>
+__device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][ANT], const half8v (&rv)[RV],
+                                                 const int (&r0)[AM * 2], const int (&r1)[AM * 2], char* stage, int mw, int nw, int lane) {
     static_assert(J0 + 4 <= ANT, "64 columns per pass");
+    static_assert(EPI != EPI_BIAS_RES || RV == AM * 2, "the residual lines of the pass, from epilogue_request_residual");
     constexpr int AN = 4;
     constexpr int ROWS = AM * 16;                         // rows of the wave tile
     const int M = a.M, N = a.N;
     if (nw >= N) return;
     const int r8 = lane >> 3, c8 = lane & 7;              // whole-line pattern: row it*8 + r8, 16-byte chunk c8
-    if (EPI == EPI_BIAS_RES) {
-#pragma unroll 4
+    if constexpr (EPI == EPI_BIAS_RES) {
+#pragma unroll
         for (int it = 0; it < ROWS / 8; ++it) {
-            const int row = it * 8 + r8, m = mw + row;
-            if (m < M) {
-                const int64_t rr = a.res_row_map ? (int64_t)a.res_row_map[m] : (int64_t)m;
-                half8v v = *reinterpret_cast<const half8v*>(a.res + rr * N + nw + c8 * 8);
-                const int sw = (row >> 1) & 15;
-                if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
-                *reinterpret_cast<half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16)) = v;
-            }
+            const int row = it * 8 + r8;
+            half8v v = rv[it];
+            const int sw = (row >> 1) & 15;
+            if (sw & 1) v = __builtin_shufflevector(v, v, 4, 5, 6, 7, 0, 1, 2, 3);
+            *reinterpret_cast<half8v*>(stage + row * 128 + ((c8 ^ (sw >> 1)) * 16)) = v;
         }
     }
     // arithmetic on the accumulators: acc[i][j][0..3] = row i*16 + lane%16, columns j*16 + (lane/16)*4 ..+4
@@ -147,7 +202,7 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4
         }
     }
     // whole lines out
-#pragma unroll 4
+#pragma unroll
     for (int it = 0; it < ROWS / 8; ++it) {
         const int row = it * 8 + r8, m = mw + row;
         if (m >= M) continue;
@@ -162,23 +217,13 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4
             if (which == 0) {
                 dst = a.y + (int64_t)m * a.hidden + c;
             } else {
-                int b_, pos;
-                if (a.tok_row_map) {                     // prefill: token -> (sequence, position)
-                    const int tok = a.tok_row_map[m];
-                    b_ = tok / a.S;
-                    pos = tok - b_ * a.S;
-                    if (a.left_pad) pos -= a.S - a.lens[b_];   // pads lead: token 0 of the sequence is at row S - L_b
-                } else {                                 // decode: the new token goes to slot n_b
-                    b_ = m;
-                    pos = a.lens[m];
-                }
+                const int b_ = r0[it], pos = r1[it];
                 if (pos < 0 || pos >= a.max_seq) continue;   // see epilogue_apply: never outside the sequence's slots
                 const int g = c / a.d, dd = c - g * a.d;
                 dst = (which == 1 ? a.k_cache : a.v_cache) + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd;
             }
         } else {
-            const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
-            dst = a.y + orow * (a.ldy ? a.ldy : N) + n;
+            dst = a.y + (int64_t)r0[it] * (a.ldy ? a.ldy : N) + n;
         }
         *reinterpret_cast<half8v*>(dst) = v;
     }
@@ -488,16 +533,25 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
                     for (int r = 0; r < 4; ++r) acc[i][j][r] += red[g * (NW * PT) + ((i * AN + j) * 4 + r) * 64];
     }
     constexpr int EB = WM * 128;                           // bytes of a wave's turn-around area
+    // row lookups and residual lines of the wave tile: all requested here, consumed by the passes below
+    int er0[AM * 2], er1[AM * 2];
+    epilogue_rows<AM, EPI>(a, m0 + wm0, lane, er0, er1);
+    constexpr int RV = EPI == EPI_BIAS_RES ? AM * 2 : 1;
+    half8v rv0[RV], rv1[AN == 8 ? RV : 1];
+    if constexpr (EPI == EPI_BIAS_RES) {
+        epilogue_request_residual<AM>(a, rv0, er1, n0 + wn0, lane);
+        if constexpr (AN == 8) epilogue_request_residual<AM>(a, rv1, er1, n0 + wn0 + 64, lane);
+    }
     // with K groups the partial tiles above sit in the weight stages and group 0 may still be summing them while a faster
     // wave of the group already turns its tile around: that must then happen in the activation stages only
     static_assert(KS == 1 || NW * EB <= (int)sizeof(As), "turn-around areas must not touch the partial tiles");
     if constexpr (NW * EB <= (int)sizeof(As)) {
         char* area = reinterpret_cast<char*>(&As[0][0]) + wave * EB;
-        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, area, m0 + wm0, n0 + wn0, lane);
-        if constexpr (AN == 8) epilogue_via_lds<AM, AN, 4, EPI>(a, acc, area, m0 + wm0, n0 + wn0 + 64, lane);   // second 64 columns, same area
+        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, rv0, er0, er1, area, m0 + wm0, n0 + wn0, lane);
+        if constexpr (AN == 8) epilogue_via_lds<AM, AN, 4, EPI>(a, acc, rv1, er0, er1, area, m0 + wm0, n0 + wn0 + 64, lane);   // second 64 columns, same area
     } else {
         static_assert(NW == 8 && AN == 4 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
-        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
+        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, rv0, er0, er1, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
                                          m0 + wm0, n0 + wn0, lane);
     }
 }
