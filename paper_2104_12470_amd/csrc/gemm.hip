@@ -1082,9 +1082,17 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     const char* wbase = reinterpret_cast<const char*>(a.w) + (size_t)n0 * K * 2;
     const char* xbase = reinterpret_cast<const char*>(a.x);
 
+    // Workgroups start their walk over K in eight different places (workgroups are dealt round-robin to the eight XCDs, so
+    // blockIdx.x / 8 counts inside an XCD) instead of all reading the same K offset of their rows, and of the shared
+    // activation rows, at the same time (rows x N x K: 16 x 36864 x 12288 166 -> 157 us, 16 x 49152 x 12288 218 -> 208,
+    // 16 x 12288 x 12288 50.4 -> 47.6, 4 x 4096 x 16384 28.0 -> 21.9, 4 x 16384 x 4096 22.6 -> 21.0; K = 49152 unchanged;
+    // two phases were slower than one, thirty-two slower at K = 49152).  Only the order of a column's sum depends on it.
+    const int phase = (int)((((unsigned)blockIdx.x >> 3) & 7u) * (unsigned)ngroups) >> 3;
     half8v wA[UQ][NF][2], xA[UQ][XH], wB[UQ][NF][2], xB[UQ][XH];
     auto request = [&](half8v (&wr)[UQ][NF][2], half8v (&xr)[UQ][XH], int g) {
         g = g < ngroups ? g : ngroups - 1;                    // look-ahead past the end: a valid group, never consumed
+        g += phase;                                           // this workgroup's walk starts `phase` groups into K and wraps
+        g = g >= ngroups ? g - ngroups : g;
         const char* wg = wbase + (size_t)g * (UQ * 128);
         const char* xg = xbase + (size_t)g * (UQ * 128);
 #pragma unroll
