@@ -1379,6 +1379,40 @@ static bool goes_to_tile_kernel(const GemmArgs& a) {
 }
 bool gemm_takes_row_strides(const GemmArgs& a) { return a.M > 16 && a.x_splits <= 1; }
 
+// The same problem without its first m0 rows (not for EPI_QKV, whose decode form takes the sequence from the row number).
+static GemmArgs rows_from(const GemmArgs& a, int m0) {
+    GemmArgs r = a;
+    r.M = a.M - m0;
+    r.x = a.x + (size_t)m0 * (a.lda ? a.lda : a.K);
+    if (a.out_row_map) r.out_row_map = a.out_row_map + m0;
+    else r.y = a.y + (size_t)m0 * (a.ldy ? a.ldy : a.N);
+    if (a.res) {
+        if (a.res_row_map) r.res_row_map = a.res_row_map + m0;
+        else r.res = a.res + (size_t)m0 * a.N;
+    }
+    return r;
+}
+
+// One workgroup of the large-tile kernels fills a CU, so the tiles run in rounds of 256 and a launch pays for whole
+// rounds: a last round that is a third full takes as long as a full one (measured longer: 25082 x 12288 x 49152, 18.4
+// rounds, 26.3 ms; 24576 rows, 18 rounds, 24.6 ms).  Where a number of row tiles gives whole rounds and leaves few enough
+// rows for the small-tile kernels (below 150 large tiles, which they serve at about 0.6 of the large tiles' rate), the
+// launch is cut there: 24576 rows + 506 rows 24.6 + 0.85 ms.  Returns the rows of the first part, 0 for no cut.
+static int rows_in_whole_rounds(const GemmArgs& a, Epilogue epi, int big_tiles) {
+    constexpr int kCUs = 256;
+    if (epi == EPI_QKV || big_tiles < 2 * kCUs || big_tiles % kCUs == 0) return 0;
+    const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
+    for (int c = tm - 1; c >= 1; --c) {
+        const int rest = (tm - c) * tn;                   // large tiles' worth of rows left over
+        if (rest >= 150) break;
+        if ((c * tn) % kCUs != 0) continue;
+        if (a.M - c * 256 <= 16) return 0;                 // the rest would be a decode-sized problem: other kernels, no row strides
+        const int rounds_saved = (big_tiles + kCUs - 1) / kCUs - c * tn / kCUs;
+        return rest / (0.6 * kCUs) < rounds_saved - 0.1 ? c * 256 : 0;
+    }
+    return 0;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     if (a.M <= 0) return hipSuccess;
     const bool bad_stride = (a.lda != 0 && (a.lda < a.K || a.lda % 8 != 0)) || (a.ldy != 0 && (a.ldy < a.N || a.ldy % 8 != 0));
@@ -1401,6 +1435,14 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         // never for at most 128 rows, where half of every large tile would be idle (a decode step of many sequences
         // over a very wide output, e.g. the vocabulary: 128 x 1024 x 50304 39.7 -> 30.9 us with 128x128 tiles)
         const int big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+        if (int m_whole = rows_in_whole_rounds(a, epi, big_tiles)) {
+            // whole rounds of large tiles first, then the last few hundred rows as a problem of their own (small tiles)
+            GemmArgs head = a;
+            head.M = m_whole;
+            hipError_t e = launch_gemm(head, epi, s);
+            if (e != hipSuccess) return e;
+            return launch_gemm(rows_from(a, m_whole), epi, s);
+        }
         if (big_tiles >= 150 && a.M > 128) {
             // Four waves with 128 x 128 each: a third less LDS read traffic per flop than eight waves of 128 x 64, and the
             // LDS of a CU -- fragment reads plus the arriving tiles -- is what the matrix pipes otherwise wait for
