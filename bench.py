@@ -286,6 +286,8 @@ def _kernel_candidates(stack, torch, eet, reps, full=True):
             (eet.eet_op_linear if x.is_contiguous() and y.is_contiguous() else eet.eet_op_linear_strided)(
                 x, wts[wkey], wts[bkey], y, residual=residual, act=act)
         ms = time_launches(torch, run, max(4, min(reps, 24)), replays=2)
+        # one operator call: one launch of the tile kernel, or two where the library cuts the rows into whole rounds of
+        # large tiles plus a small-tile rest (the duration is the call's, the kernel trace lists the two launches)
         out.append({"kernel": f"prefill {name} (MFMA tile kernel, {T} x {n_out} x {n_in})", "bound": "mfma",
                     "work": 2.0 * T * n_out * n_in, "ms": ms, "launches": nl})
     prefill_projection("FFN-1 projection + bias + GELU", "w_fc1", "b_fc1", xp, yp, F, H, act=1)
