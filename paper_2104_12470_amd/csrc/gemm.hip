@@ -1323,7 +1323,7 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // workgroups fill the CUs evenly (N = 12288: exactly one per CU).  Sharing the activation lines between the waves of
     // a workgroup through the CU's vector cache instead (waves side by side in N, all walking the same K) changed nothing.
     const int wg48 = a.N % 48 == 0 ? a.N / 48 : 0;
-    if (a.M > 1 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {   // (2 to 8 rows: 12288 x 4096 19.3 -> 18.1 us, 36864 x 12288 174 -> 162 us)
+    if (a.M > 4 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {   // (8 rows: 49152 x 12288 209 -> 205 us; 4 rows: 12288 x 4096 16.7 -> 17.8 the other way, 2 rows: no difference)
         if (a.M > 8) launch_stream<3, 2>(a, epi, s);
         else launch_stream<3, 1>(a, epi, s);
         return true;
@@ -1333,12 +1333,12 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         launch_stream<4, 2>(a, epi, s);
         return true;
     }
-    const bool wide = a.N / 32 >= 1024;                       // 32 columns per workgroup once that still leaves four workgroups per CU
-    if (a.M <= 8) {
-        if (wide) launch_stream<2, 1>(a, epi, s); else launch_stream<1, 1>(a, epi, s);
-    } else {
-        if (wide) launch_stream<2, 2>(a, epi, s); else launch_stream<1, 2>(a, epi, s);
-    }
+    // Up to 8 rows otherwise 16 columns per workgroup whatever N is (32 columns, once the rule for wide outputs, lost since the
+    // workgroups walk K in phases: 1 row, 36864 x 12288 168 -> 153 us, 49152 x 12288 214 -> 201, 65536 x 4096 99 -> 88;
+    // 4 and 8 rows, 32768 x 8192 101 -> 93); more rows and a wide output that takes neither 48 nor 64: 32 columns.
+    if (a.M <= 8) launch_stream<1, 1>(a, epi, s);
+    else if (a.N / 32 >= 1024) launch_stream<2, 2>(a, epi, s);
+    else launch_stream<1, 2>(a, epi, s);
     return true;
 }
 
