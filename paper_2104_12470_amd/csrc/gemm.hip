@@ -1451,7 +1451,10 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             // multiple of 32 KB apart the eight-wave kernel with the early release of the stage is ahead (25082 x 12288 x
             // 49152: 1.09 against 0.97); once the rows are 128 bytes further apart (the layer's own feed-forward buffer is
             // laid out so) both reach 1.16.
-            if (a.K >= 32768) launch_dma64_cfg<2, 4, 256, 256, 2, 1, 1>(a, epi, s);
+            // (that comparison was on 18.4 rounds of tiles.  On whole rounds -- which is what the cut above leaves of such a
+            // launch -- the four waves are ahead at this K too: 24576 x 12288 x 49152 24.7 -> 23.7 ms, 4096 rows 3.97 -> 3.82;
+            // on part-filled rounds the eight waves stay ahead: 3000 x 4096 x 32768 0.80 against 0.87 ms.)
+            if (a.K >= 32768 && big_tiles % 256 != 0) launch_dma64_cfg<2, 4, 256, 256, 2, 1, 1>(a, epi, s);
             else launch_dma64_cfg<2, 2, 256, 256, 2, 1, 2>(a, epi, s);
         }
         else {
