@@ -1379,11 +1379,17 @@ static bool goes_to_tile_kernel(const GemmArgs& a) {
 }
 bool gemm_takes_row_strides(const GemmArgs& a) { return a.M > 16 && a.x_splits <= 1; }
 
-// The same problem without its first m0 rows (not for EPI_QKV, whose decode form takes the sequence from the row number).
-static GemmArgs rows_from(const GemmArgs& a, int m0) {
+// The same problem without its first m0 rows (EPI_QKV: the prefill form, whose rows carry their sequence and position in
+// tok_row_map; the decode form takes the sequence from the row number and is never cut).
+static GemmArgs rows_from(const GemmArgs& a, Epilogue epi, int m0) {
     GemmArgs r = a;
     r.M = a.M - m0;
     r.x = a.x + (size_t)m0 * (a.lda ? a.lda : a.K);
+    if (epi == EPI_QKV) {
+        r.y = a.y + (size_t)m0 * a.hidden;
+        r.tok_row_map = a.tok_row_map + m0;
+        return r;
+    }
     if (a.out_row_map) r.out_row_map = a.out_row_map + m0;
     else r.y = a.y + (size_t)m0 * (a.ldy ? a.ldy : a.N);
     if (a.res) {
@@ -1393,22 +1399,24 @@ static GemmArgs rows_from(const GemmArgs& a, int m0) {
     return r;
 }
 
-// One workgroup of the large-tile kernels fills a CU, so the tiles run in rounds of 256 and a launch pays for whole
-// rounds: a last round that is a third full takes as long as a full one (measured longer: 25082 x 12288 x 49152, 18.4
-// rounds, 26.3 ms; 24576 rows, 18 rounds, 24.6 ms).  Where a number of row tiles gives whole rounds and leaves few enough
-// rows for the small-tile kernels (below 150 large tiles, which they serve at about 0.6 of the large tiles' rate), the
-// launch is cut there: 24576 rows + 506 rows 24.6 + 0.85 ms.  Returns the rows of the first part, 0 for no cut.
+// One workgroup of the large-tile kernels fills a CU, so the tiles run in rounds of 256, and a launch whose last round is
+// part-filled pays for more than that round: 25082 x 12288 x 49152 (18.4 rounds) 26.3 ms, 24832 rows (18.2 rounds) 26.35 ms,
+// 24576 rows (18 rounds) 24.6 ms; 25082 x 36864 x 12288 (55.1 rounds) 19.1 ms, 24576 rows (54 rounds) 18.2 ms.  Where some
+// number of row tiles gives whole rounds and leaves at most 8 row tiles, the launch is cut there and the rest is a launch
+// of its own: small tiles below 150 large tiles' worth of rows (about 0.6 of the large tiles' rate: 506 x 12288 x 49152
+// 0.85 ms), else large tiles again (506 x 36864 x 12288 0.58 ms, 506 x 49152 x 12288 0.63 ms).  Returns the rows of the
+// first part, 0 for no cut.
 static int rows_in_whole_rounds(const GemmArgs& a, Epilogue epi, int big_tiles) {
     constexpr int kCUs = 256;
-    if (epi == EPI_QKV || big_tiles < 2 * kCUs || big_tiles % kCUs == 0) return 0;
+    if ((epi == EPI_QKV && a.tok_row_map == nullptr) || big_tiles < 2 * kCUs || big_tiles % kCUs == 0) return 0;
     const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
-    for (int c = tm - 1; c >= 1; --c) {
-        const int rest = (tm - c) * tn;                   // large tiles' worth of rows left over
-        if (rest >= 150) break;
+    for (int c = tm - 1; c >= 1 && c >= tm - 8; --c) {
         if ((c * tn) % kCUs != 0) continue;
         if (a.M - c * 256 <= 16) return 0;                 // the rest would be a decode-sized problem: other kernels, no row strides
-        const int rounds_saved = (big_tiles + kCUs - 1) / kCUs - c * tn / kCUs;
-        return rest / (0.6 * kCUs) < rounds_saved - 0.1 ? c * 256 : 0;
+        const int rest = (tm - c) * tn;                   // large tiles' worth of rows left over
+        const double rest_rounds = rest < 150 ? rest / (0.6 * kCUs) : (double)((rest + kCUs - 1) / kCUs);
+        const double rounds_now = (big_tiles + kCUs - 1) / kCUs - c * tn / kCUs + 0.27;   // what the part-filled round costs on top
+        return rest_rounds + 0.1 < rounds_now ? c * 256 : 0;
     }
     return 0;
 }
@@ -1441,7 +1449,7 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             head.M = m_whole;
             hipError_t e = launch_gemm(head, epi, s);
             if (e != hipSuccess) return e;
-            return launch_gemm(rows_from(a, m_whole), epi, s);
+            return launch_gemm(rows_from(a, epi, m_whole), epi, s);
         }
         if (big_tiles >= 150 && a.M > 128) {
             // Four waves with 128 x 128 each: a third less LDS read traffic per flop than eight waves of 128 x 64, and the

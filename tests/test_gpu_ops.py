@@ -257,7 +257,8 @@ def test_linear_large_tiles(eet, M, K, N):
 @pytest.mark.parametrize("M,K,N,padx,pady", [(3000, 1024, 4160, 64, 72),     # 256x256 tiles, four waves
                                               (300, 512, 640, 8, 64),          # the small tiles
                                               (2049, 4096, 6144, 64, 0),
-                                              (8492, 256, 4096, 64, 72)])      # 544 large tiles: two whole rounds of 8192 rows, then 300 rows on small tiles
+                                              (8492, 256, 4096, 64, 72),       # 544 large tiles: two whole rounds of 8192 rows, then 300 rows on small tiles
+                                              (2648, 256, 16384, 64, 0)])      # 704 large tiles: two whole rounds of 2048 rows, then 600 rows on large tiles again
 def test_linear_strided(eet, M, K, N, padx, pady):
     """eet_op_linear_strided: x and y are column slices of wider buffers (the layout the layer gives its feed-forward
     rows); the columns between the rows are neither read into the result nor written."""
