@@ -227,6 +227,15 @@ def _kernel_candidates(stack, torch, eet, reps, full=True):
     d = H // w.heads
     T = sum(stack.lens)
     out = []
+    # What a decode step of the real pass moves between two uses of the same operand: every layer's weights and visible
+    # K/V once.  An operator-level launch that cycled over less than that (one layer whose output projection is 300 MB,
+    # replayed back to back) would find its operand in the 256 MB memory-side cache, which the pass does not: such
+    # records cycle over copies of their operand until the cycle is as large as the pass's (capped at 2 GB).
+    step_bytes = nl * (2.0 * (4 * H * H + 2 * H * F) + 4.0 * H * sum(L + w.decode_steps // 2 for L in stack.lens))
+
+    def n_copies(bytes_per_launch):
+        want = min(step_bytes, 2.0e9)
+        return max(1, int(-(-want // (nl * bytes_per_launch))))
     if w.decode_steps:
         # (1) decode attention: K and V of every visible slot read once, q read, ctx written
         ks = sorted({0, w.decode_steps // 4, w.decode_steps // 2, 3 * w.decode_steps // 4, w.decode_steps - 1})
@@ -238,16 +247,21 @@ def _kernel_candidates(stack, torch, eet, reps, full=True):
         ctx = torch.empty_like(q)
         st = {"i": 0}
 
+        caches = [stack.cache_views(i) for i in range(nl)]
+        for _ in range(n_copies(sum(bytes_k) / len(bytes_k)) - 1):
+            caches += [(kc.clone(), vc.clone()) for kc, vc in caches[:nl]]
+
         def run_attn():
             i = st["i"]
             st["i"] += 1
-            kc, vc = stack.cache_views(i % nl)
-            eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // nl) % len(ks)], scratch)
-        n = nl * len(ks)
+            kc, vc = caches[i % len(caches)]
+            eet.eet_op_attention_decode(q, kc, vc, ctx, nkeys[(i // len(caches)) % len(ks)], scratch)
+        n = len(caches) * len(ks)
         ms = time_launches(torch, run_attn, n * max(1, reps // n))
         out.append({"kernel": f"attn_decode<{d}, 4> (+ attn_decode_combine when the key range is split): decode attention over the K/V cache",
                     "bound": "hbm", "work": sum(bytes_k) / len(bytes_k), "ms": ms,
                     "launches": w.decode_steps * nl})
+        del caches
         # (2) decode projections (weight stream) that have an operator-level twin: FFN-2 + bias +
         # residual and the attention output projection + bias + residual.  (The QKV and FFN-1
         # launches of small layers carry a fused LayerNorm and exist only inside the layer call.)
@@ -256,12 +270,15 @@ def _kernel_candidates(stack, torch, eet, reps, full=True):
             r = torch.randn(B, n_out, device="cuda:0").half()
             y = torch.empty(B, n_out, device="cuda:0", dtype=torch.float16)
             st2 = {"i": 0}
+            mats = [(stack.weights(i)[wkey], stack.weights(i)[bkey]) for i in range(nl)]
+            for _ in range(n_copies(2.0 * n_out * n_in) - 1):
+                mats += [(m.clone(), b_) for m, b_ in mats[:nl]]
 
             def run():
-                wts = stack.weights(st2["i"] % nl)
+                m, b_ = mats[st2["i"] % len(mats)]
                 st2["i"] += 1
-                eet.eet_op_linear(x, wts[wkey], wts[bkey], y, residual=r)
-            ms = time_launches(torch, run, nl * max(1, reps // nl))
+                eet.eet_op_linear(x, m, b_, y, residual=r)
+            ms = time_launches(torch, run, len(mats) * max(1, reps // len(mats)))
             out.append({"kernel": f"decode {name} + bias + residual (weight stream, M = {B} rows)", "bound": "hbm",
                         "work": 2.0 * (n_out * n_in + B * n_in + n_out + 2 * B * n_out), "ms": ms,
                         "launches": w.decode_steps * nl})
