@@ -297,12 +297,18 @@ def _kernel_candidates(stack, torch, eet, reps, full=True):
     st3 = {"i": 0}
 
     def prefill_projection(name, wkey, bkey, x, y, n_out, n_in, act=0, residual=None):
+        # a pass uses each weight matrix of a prefill once, with a whole decode phase before its next use: the record
+        # cycles over copies (1 GB of them) so that the matrix comes from HBM here too
+        mats = [(stack.weights(i)[wkey], stack.weights(i)[bkey]) for i in range(nl)]
+        for _ in range(max(1, int(-(-1.0e9 // (nl * 2.0 * n_out * n_in)))) - 1):
+            mats += [(m.clone(), b_) for m, b_ in mats[:nl]]
+
         def run():
-            wts = stack.weights(st3["i"] % nl)
+            m, b_ = mats[st3["i"] % len(mats)]
             st3["i"] += 1
             (eet.eet_op_linear if x.is_contiguous() and y.is_contiguous() else eet.eet_op_linear_strided)(
-                x, wts[wkey], wts[bkey], y, residual=residual, act=act)
-        ms = time_launches(torch, run, max(4, min(reps, 24)), replays=2)
+                x, m, b_, y, residual=residual, act=act)
+        ms = time_launches(torch, run, max(4, min(reps, 24), len(mats)), replays=2)
         # one operator call: one launch of the tile kernel, or two where the library cuts the rows into whole rounds of
         # large tiles plus a small-tile rest (the duration is the call's, the kernel trace lists the two launches)
         out.append({"kernel": f"prefill {name} (MFMA tile kernel, {T} x {n_out} x {n_in})", "bound": "mfma",
