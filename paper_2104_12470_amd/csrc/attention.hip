@@ -935,9 +935,30 @@ __global__ __launch_bounds__(256) void attn_decode_combine(AttnDecodeArgs a) {
     const int splits = a.splits;
     const float* ml = a.part_ml + bh * splits * 2;
     const float* pa = a.part_acc + bh * splits * D + dd;
+    float Lsum = 0.f, A = 0.f;
+    if (splits <= MAXS) {                                // the usual case: everything in one trip to memory
+        float mv[MAXS], lv[MAXS], av[MAXS];
+#pragma unroll
+        for (int u = 0; u < MAXS; ++u) {
+            const int s = u < splits ? u : splits - 1;
+            mv[u] = ml[s * 2];
+            lv[u] = ml[s * 2 + 1];
+            av[u] = pa[s * D];
+        }
+        float M = mv[0];                                 // an empty range reports the finite kEmpty and a zero sum (clamped slots repeat the last range)
+#pragma unroll
+        for (int u = 1; u < MAXS; ++u) M = fmaxf(M, mv[u]);
+#pragma unroll
+        for (int u = 0; u < MAXS; ++u) {
+            const float sc = u < splits ? exp2f(mv[u] - M) : 0.f;
+            Lsum += lv[u] * sc;
+            A += av[u] * sc;
+        }
+        a.ctx[bh * D + dd] = (half_t)(Lsum > 0.f ? A / Lsum : 0.f);
+        return;
+    }
     float M = -INFINITY;
     for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[s * 2]);     // an empty range reports the finite kEmpty and a zero sum
-    float Lsum = 0.f, A = 0.f;
     for (int s0 = 0; s0 < splits; s0 += MAXS) {
         float mv[MAXS], lv[MAXS], av[MAXS];
 #pragma unroll
