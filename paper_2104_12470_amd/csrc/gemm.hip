@@ -47,8 +47,8 @@ __device__ __forceinline__ void epilogue_fetch(const GemmArgs& a, int m, int n, 
 }
 
 template <int EPI>
-__device__ __forceinline__ void epilogue_apply(const GemmArgs& a, int m, int n, float v0, float v1, float v2, float v3,
-                                               const EpiOperands& e) {
+__device__ __forceinline__ half4v epilogue_apply(const GemmArgs& a, int m, int n, float v0, float v1, float v2, float v3,
+                                                 const EpiOperands& e) {   // returns the four values as stored
     v0 += (float)e.bias[0]; v1 += (float)e.bias[1]; v2 += (float)e.bias[2]; v3 += (float)e.bias[3];
     if (EPI == EPI_BIAS_GELU) {
         v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); v2 = gelu_tanh(v2); v3 = gelu_tanh(v3);
@@ -73,15 +73,16 @@ __device__ __forceinline__ void epilogue_apply(const GemmArgs& a, int m, int n, 
                 b_ = m;
                 pos = e.pos;
             }
-            if (pos < 0 || pos >= a.max_seq) return;   // device-side lengths advanced past the capacity (replays the host never saw): drop, never write outside the slots
+            if (pos < 0 || pos >= a.max_seq) return o;   // device-side lengths advanced past the capacity (replays the host never saw): drop, never write outside the slots
             const int g = c / a.d, dd = c - g * a.d;
             half_t* cache = which == 1 ? a.k_cache : a.v_cache;
             *reinterpret_cast<half4v*>(cache + (((int64_t)b_ * a.heads + g) * a.max_seq + pos) * a.d + dd) = o;
         }
-        return;
+        return o;
     }
     const int64_t orow = a.out_row_map ? (int64_t)a.out_row_map[m] : (int64_t)m;
     *reinterpret_cast<half4v*>(a.y + orow * a.N + n) = o;
+    return o;
 }
 
 template <int EPI>
@@ -1037,10 +1038,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 //     vector arithmetic at all; a group is staged two units at a time, which keeps the staging
 //     space small enough for two workgroups per CU;
 //   * the four partial tiles are summed through LDS once, at the end.
+//
+// LNS hands the statistics of the LayerNorm between two such projections from one launch to the next (GemmArgs::
+// row_stats_*), so that a decode step of a large layer has no LayerNorm launch between its output projection and its first
+// feed-forward projection:
+//   LNS = 1 (bias + residual): the threads that write the 16 x 16*NF outputs also leave, per row, the mean and the sum of
+//           squared deviations of the workgroup's columns of the rounded output;
+//   LNS = 2: the workgroup first merges the producer's groups (equal sizes, so group means average; squared deviations add
+//           up with the spread of the group means, taken relative to the first group's mean) into mean and 1/std per row,
+//           while its first weights are in flight, and normalises every activation vector (three fused multiply-adds per
+//           element) before it is staged for the matrix instructions.
 constexpr int kStreamStagedUnits = 2;
+constexpr int kStreamStatsLds = 1024;                       // bytes behind the staging areas: the merged row statistics (LNS = 2)
 
-template <int NF, int EPI, int XH, bool SL>
+template <int NF, int EPI, int XH, bool SL, int LNS = 0>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
+    static_assert(LNS == 0 || !SL, "row statistics: at most 16 rows, one slice");
+    static_assert(LNS != 1 || EPI == EPI_BIAS_RES, "the producer of row statistics is a bias + residual projection");
     if (SL) take_row_slice<EPI>(a);
     constexpr int UQ = NF >= 3 ? 2 : 4;                     // units per group (three or four column blocks: half as many, for the registers)
     constexpr int SU = kStreamStagedUnits;                  // units staged at a time
@@ -1088,8 +1102,26 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     // 16 x 12288 x 12288 50.4 -> 47.6, 4 x 4096 x 16384 28.0 -> 21.9, 4 x 16384 x 4096 22.6 -> 21.0; K = 49152 unchanged;
     // two phases were slower than one, thirty-two slower at K = 49152).  Only the order of a column's sum depends on it.
     const int phase = (int)((((unsigned)blockIdx.x >> 3) & 7u) * (unsigned)ngroups) >> 3;
-    half8v wA[UQ][NF][2], xA[UQ][XH], wB[UQ][NF][2], xB[UQ][XH];
-    auto request = [&](half8v (&wr)[UQ][NF][2], half8v (&xr)[UQ][XH], int g) {
+    // LNS = 2: the producer's row statistics; thread t takes row t%16 and every 16th group from t/16 on, 16 groups at a time.
+    // The first 16 (all of them up to 256 groups) are requested before anything else: loads return in issue order.
+    constexpr int kStatBatch = 16;
+    float2v stat[LNS == 2 ? kStatBatch : 1];
+    float stat0 = 0.f;                                       // the first group's mean of this thread's row
+    const float2v* stat_src = reinterpret_cast<const float2v*>(a.row_stats_in) + (tid & 15);
+    auto request_stats = [&](int u0) {
+#pragma unroll
+        for (int u = 0; u < kStatBatch; ++u) {
+            const int grp = (tid >> 4) + 16 * (u0 + u);
+            if (grp < a.row_stats_groups) stat[u] = stat_src[grp * 16];
+        }
+    };
+    if constexpr (LNS == 2) {
+        stat0 = stat_src[0][0];
+        request_stats(0);
+    }
+    constexpr int GB = LNS == 2 ? UQ : 1;
+    half8v wA[UQ][NF][2], xA[UQ][XH], wB[UQ][NF][2], xB[UQ][XH], gA[GB], bA[GB], gB[GB], bB[GB];
+    auto request = [&](half8v (&wr)[UQ][NF][2], half8v (&xr)[UQ][XH], half8v (&gr)[GB], half8v (&br)[GB], int g) {
         g = g < ngroups ? g : ngroups - 1;                    // look-ahead past the end: a valid group, never consumed
         g += phase;                                           // this workgroup's walk starts `phase` groups into K and wraps
         g = g >= ngroups ? g - ngroups : g;
@@ -1097,6 +1129,10 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
         const char* xg = xbase + (size_t)g * (UQ * 128);
 #pragma unroll
         for (int q = 0; q < UQ; ++q) {
+            if constexpr (LNS == 2) {                         // gamma and beta of the 8 columns this lane holds of unit q
+                gr[q] = *reinterpret_cast<const half8v*>(reinterpret_cast<const char*>(a.ln_gamma) + (size_t)g * (UQ * 128) + q * 128 + wchunk * 16);
+                br[q] = *reinterpret_cast<const half8v*>(reinterpret_cast<const char*>(a.ln_beta) + (size_t)g * (UQ * 128) + q * 128 + wchunk * 16);
+            }
 #pragma unroll
             for (int h = 0; h < XH; ++h) xr[q][h] = *reinterpret_cast<const half8v*>(xg + xoff[h] + q * 128);
 #pragma unroll
@@ -1110,15 +1146,26 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
     for (int f = 0; f < NF; ++f) acc[f] = float4v{0.f, 0.f, 0.f, 0.f};
     const uint32_t st_w = (uint32_t)(wrow * kFlatStageRow + wchunk * 8);     // staging write (halves)
     const uint32_t st_r = (uint32_t)(fr * kFlatStageRow + G * 8);            // staging read
-    auto consume = [&](const half8v (&wr)[UQ][NF][2], const half8v (&xr)[UQ][XH]) {
+    float ln_mu[XH], ln_rs[XH];                               // LNS = 2: mean and 1/std of this lane's activation rows
+    auto consume = [&](const half8v (&wr)[UQ][NF][2], const half8v (&xr)[UQ][XH], const half8v (&gr)[GB], const half8v (&br)[GB]) {
         // area (j*(NF+1) + 0) holds the activation unit j of the round, areas +1.. its weight units
 #pragma unroll
         for (int q0 = 0; q0 < UQ; q0 += SU) {
 #pragma unroll
             for (int j = 0; j < SU; ++j) {
 #pragma unroll
-                for (int h = 0; h < XH; ++h)
-                    *reinterpret_cast<half8v*>(&wst[st_w + ((j * (NF + 1)) * 16 + 8 * h) * kFlatStageRow]) = xr[q0 + j][h];
+                for (int h = 0; h < XH; ++h) {
+                    half8v xv = xr[q0 + j][h];
+                    if constexpr (LNS == 2) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float sc = __builtin_fmaf((float)gr[q0 + j][e], ln_rs[h], 0.f);
+                            const float sh = __builtin_fmaf(-ln_mu[h], sc, (float)br[q0 + j][e]);
+                            xv[e] = (half_t)__builtin_fmaf((float)xv[e], sc, sh);
+                        }
+                    }
+                    *reinterpret_cast<half8v*>(&wst[st_w + ((j * (NF + 1)) * 16 + 8 * h) * kFlatStageRow]) = xv;
+                }
 #pragma unroll
                 for (int f = 0; f < NF; ++f)
 #pragma unroll
@@ -1142,17 +1189,66 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
         }
     };
     int g = wave;
+    if (g < ngroups) request(wA, xA, gA, bA, g);
+    if constexpr (LNS == 2) {
+        // merge the groups: with q the first group's mean, A = sum(mean_g - q), B = sum((mean_g - q)^2), C = sum(M2_g);
+        // mean = q + A/G, sum of squared deviations = C + cols * (B - A^2/G)
+        float* sm = reinterpret_cast<float*>(stream_smem + 4 * AREAS * 16 * kFlatStageRow * 2);   // [4 waves][16 rows][3], then mean[16], 1/std[16]
+        float A = 0.f, B = 0.f, C = 0.f;
+        for (int u0 = 0; 16 * u0 < a.row_stats_groups; u0 += kStatBatch) {
+            if (u0 > 0) request_stats(u0);                    // more than 256 groups: further trips, behind the first weights
+#pragma unroll
+            for (int u = 0; u < kStatBatch; ++u) {
+                if ((tid >> 4) + 16 * (u0 + u) < a.row_stats_groups) {
+                    const float dm = stat[u][0] - stat0;
+                    A += dm;
+                    B = __builtin_fmaf(dm, dm, B);
+                    C += stat[u][1];
+                }
+            }
+        }
+        A += __shfl_xor(A, 16, kWave); B += __shfl_xor(B, 16, kWave); C += __shfl_xor(C, 16, kWave);
+        A += __shfl_xor(A, 32, kWave); B += __shfl_xor(B, 32, kWave); C += __shfl_xor(C, 32, kWave);
+        if (lane < 16) {
+            sm[(wave * 16 + lane) * 3 + 0] = A;
+            sm[(wave * 16 + lane) * 3 + 1] = B;
+            sm[(wave * 16 + lane) * 3 + 2] = C;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // LDS only: the weight loads stay in flight across the barrier
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (tid < 16) {
+            float At = 0.f, Bt = 0.f, Ct = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                At += sm[(w * 16 + tid) * 3 + 0];
+                Bt += sm[(w * 16 + tid) * 3 + 1];
+                Ct += sm[(w * 16 + tid) * 3 + 2];
+            }
+            const float G = (float)a.row_stats_groups, cols = (float)a.row_stats_cols;
+            const float m2 = Ct + cols * fmaxf(Bt - At * At / G, 0.f);
+            sm[192 + tid] = stat0 + At / G;
+            sm[208 + tid] = rsqrtf(m2 / (G * cols) + a.ln_eps);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int h = 0; h < XH; ++h) {
+            ln_mu[h] = sm[192 + 8 * h + wrow];
+            ln_rs[h] = sm[208 + 8 * h + wrow];
+        }
+    }
     if (g < ngroups) {
-        request(wA, xA, g);
         while (true) {
-            request(wB, xB, g + 4);
+            request(wB, xB, gB, bB, g + 4);
             __builtin_amdgcn_sched_barrier(0);                // keep the look-ahead loads ahead of the arithmetic
-            consume(wA, xA);
+            consume(wA, xA, gA, bA);
             g += 4;
             if (g >= ngroups) break;
-            request(wA, xA, g + 4);
+            request(wA, xA, gA, bA, g + 4);
             __builtin_amdgcn_sched_barrier(0);
-            consume(wB, xB);
+            consume(wB, xB, gB, bB);
             g += 4;
             if (g >= ngroups) break;
         }
@@ -1172,7 +1268,37 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
             const float4v pw = *reinterpret_cast<const float4v*>(rp + w * RT);
             v[0] += pw[0]; v[1] += pw[1]; v[2] += pw[2]; v[3] += pw[3];
         }
-        epilogue_apply<EPI>(a, eml, en, v[0], v[1], v[2], v[3], eo);
+        const half4v o = epilogue_apply<EPI>(a, eml, en, v[0], v[1], v[2], v[3], eo);
+        if constexpr (LNS == 1) {                             // this thread's four rounded outputs: mean and squared deviations
+            const float o0 = (float)o[0], o1 = (float)o[1], o2 = (float)o[2], o3 = (float)o[3];
+            const float mt = 0.25f * ((o0 + o1) + (o2 + o3));
+            const float d0 = o0 - mt, d1 = o1 - mt, d2 = o2 - mt, d3 = o3 - mt;
+            float* sp = red + 4 * RT + tid * 2;               // behind the four waves' partial tiles
+            sp[0] = mt;
+            sp[1] = (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+        }
+    }
+    if constexpr (LNS == 1) {
+        static_assert((4 * RT + 256 * 2) * 4 <= 4 * AREAS * 16 * kFlatStageRow * 2, "statistics behind the partial tiles, inside the staging space");
+        __syncthreads();
+        // the first of a row's 4*NF threads merges them (equal sizes: means average, squared deviations add up with the
+        // spread of the means) and writes the row's pair for this workgroup
+        if (writer && tid % (4 * NF) == 0) {
+            const float* sp = red + 4 * RT + tid * 2;
+            float ms = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4 * NF; ++t) ms += sp[2 * t];
+            const float mg = ms * (1.0f / (4 * NF));
+            float m2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4 * NF; ++t) {
+                const float dm = sp[2 * t] - mg;
+                m2 += sp[2 * t + 1] + 4.0f * dm * dm;
+            }
+            float* dst = a.row_stats_out + ((size_t)blockIdx.x * 16 + eml) * 2;
+            dst[0] = mg;
+            dst[1] = m2;
+        }
     }
 }
 
@@ -1290,6 +1416,12 @@ static bool try_flat(const GemmArgs& a, Epilogue epi, hipStream_t s, bool ask_on
     return true;
 }
 
+// LNS (see gemm_stream): 1 = leave row statistics (bias + residual), 2 = normalise the activations from them
+static bool leaves_row_stats(const GemmArgs& a, Epilogue epi) { return a.row_stats_out != nullptr && epi == EPI_BIAS_RES && a.M <= 16; }
+static bool takes_row_stats(const GemmArgs& a, Epilogue epi) {
+    return a.row_stats_in != nullptr && a.ln_gamma != nullptr && epi == EPI_BIAS_GELU && a.M <= 16 && a.row_stats_groups >= 1 && a.row_stats_cols >= 1;
+}
+
 template <int NF, int XH>
 static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int lds = 4 * kStreamStagedUnits * (NF + 1) * 16 * kFlatStageRow * 2;
@@ -1305,6 +1437,14 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         return;
     }
     const dim3 grid(a.N / (16 * NF));
+    if (leaves_row_stats(a, epi)) {
+        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false, 1>, a, grid, block, lds, s);
+        return;
+    }
+    if (takes_row_stats(a, epi)) {
+        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false, 2>, a, grid, block, lds + kStreamStatsLds, s);
+        return;
+    }
     switch (epi) {
         case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH, false>, a, grid, block, lds, s); break;
         case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false>, a, grid, block, lds, s); break;
@@ -1312,10 +1452,12 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH, false>, a, grid, block, lds, s); break;
     }
 }
-// true when the streaming kernel took the problem: K a multiple of 256, whole column tiles, no LayerNorm
-static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-    if (a.ln_gamma != nullptr || a.K % 256 != 0 || a.N % 32 != 0) return false;
-    if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return false;   // 32-bit lane offsets
+
+// Blocks of 16 columns the streaming kernel gives a workgroup for this problem; 0: not its problem (K a multiple of 256,
+// whole column tiles, and no LayerNorm unless its statistics come with the call).
+static int stream_column_blocks(const GemmArgs& a, Epilogue epi) {
+    if ((a.ln_gamma != nullptr && !takes_row_stats(a, epi)) || a.K % 256 != 0 || a.N % 32 != 0) return 0;
+    if ((int64_t)a.M * a.K * 2 >= ((int64_t)1 << 31) || (int64_t)32 * a.K * 2 >= ((int64_t)1 << 31)) return 0;   // 32-bit lane offsets
     // With 16 rows a workgroup pulls as many activation lines out of L2 as weight lines when it owns 16
     // columns, and the stream slows down with every distinct activation line (12288 x 49152: 208 us at 1 row, 211 at
     // 8, 222 at 9, 246 at 16).  48 columns per workgroup cut that to a third: 246 -> 209 us, 12288 x 12288 60 -> 50 us,
@@ -1323,22 +1465,27 @@ static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // workgroups fill the CUs evenly (N = 12288: exactly one per CU).  Sharing the activation lines between the waves of
     // a workgroup through the CU's vector cache instead (waves side by side in N, all walking the same K) changed nothing.
     const int wg48 = a.N % 48 == 0 ? a.N / 48 : 0;
-    if (a.M > 4 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) {   // (8 rows: 49152 x 12288 209 -> 205 us; 4 rows: 12288 x 4096 16.7 -> 17.8 the other way, 2 rows: no difference)
-        if (a.M > 8) launch_stream<3, 2>(a, epi, s);
-        else launch_stream<3, 1>(a, epi, s);
-        return true;
-    }
+    if (a.M > 4 && wg48 >= 256 && (wg48 % 256 == 0 || wg48 >= 1024)) return 3;   // (8 rows: 49152 x 12288 209 -> 205 us; 4 rows: 12288 x 4096 16.7 -> 17.8 the other way, 2 rows: no difference)
     const int wg64 = a.N % 64 == 0 ? a.N / 64 : 0;             // N without a factor of 3: 64 columns (16 rows: 16384 x 4096 25.1 -> 23.0 us,
-    if (a.M > 8 && wg64 >= 256 && (wg64 % 256 == 0 || wg64 >= 1024)) {   // 32768 x 8192 129 -> 114 us; nothing to gain at 4 rows)
-        launch_stream<4, 2>(a, epi, s);
-        return true;
-    }
+    if (a.M > 8 && wg64 >= 256 && (wg64 % 256 == 0 || wg64 >= 1024)) return 4;   // 32768 x 8192 129 -> 114 us; nothing to gain at 4 rows)
     // Up to 8 rows otherwise 16 columns per workgroup whatever N is (32 columns, once the rule for wide outputs, lost since the
     // workgroups walk K in phases: 1 row, 36864 x 12288 168 -> 153 us, 49152 x 12288 214 -> 201, 65536 x 4096 99 -> 88;
     // 4 and 8 rows, 32768 x 8192 101 -> 93); more rows and a wide output that takes neither 48 nor 64: 32 columns.
-    if (a.M <= 8) launch_stream<1, 1>(a, epi, s);
-    else if (a.N / 32 >= 1024) launch_stream<2, 2>(a, epi, s);
-    else launch_stream<1, 2>(a, epi, s);
+    if (a.M <= 8) return 1;
+    return a.N / 32 >= 1024 ? 2 : 1;
+}
+
+// true when the streaming kernel took the problem
+static bool try_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+    const int nf = stream_column_blocks(a, epi);
+    if (nf == 0) return false;
+    const bool few = a.M <= 8;                                // at most 8 rows: one half of the activation unit
+    switch (nf) {
+        case 1: if (few) launch_stream<1, 1>(a, epi, s); else launch_stream<1, 2>(a, epi, s); break;
+        case 2: launch_stream<2, 2>(a, epi, s); break;
+        case 3: if (few) launch_stream<3, 1>(a, epi, s); else launch_stream<3, 2>(a, epi, s); break;
+        default: launch_stream<4, 2>(a, epi, s); break;
+    }
     return true;
 }
 
@@ -1362,6 +1509,25 @@ static bool slices_beat_tiles(const GemmArgs& a) {
     const double k_loop = (a.K / 64) * (k_split ? 0.23 : 0.33) * (wg64 > 768.0 ? wg64 / 768.0 : 1.0);
     const double est_tiles = 3.0 + (w_mb / 3.0 > k_loop ? w_mb / 3.0 : k_loop);
     return est_slices < est_tiles;
+}
+
+bool gemm_hands_row_stats(const GemmArgs& producer, const GemmArgs& consumer, Epilogue consumer_epi, int& groups, int& cols) {
+    GemmArgs p = producer, c = consumer;
+    p.row_stats_out = reinterpret_cast<float*>(16);              // any non-null value: only asked, never launched
+    c.row_stats_in = reinterpret_cast<const float*>(16);
+    c.row_stats_groups = c.row_stats_cols = 1;
+    if (p.M < 1 || p.M > 16 || c.M != p.M || c.K != p.N || c.ln_gamma == nullptr || p.ln_gamma != nullptr || p.x_splits > 1) return false;
+    if (try_flat(p, EPI_BIAS_RES, nullptr, true) || try_flat(c, consumer_epi, nullptr, true)) return false;
+    const int nf = stream_column_blocks(p, EPI_BIAS_RES), nfc = takes_row_stats(c, consumer_epi) ? stream_column_blocks(c, consumer_epi) : 0;
+    if (nf == 0 || p.N % (16 * nf) != 0 || nfc == 0) return false;
+    // Every workgroup of the consumer merges the producer's groups before its first multiply: that pays where a workgroup
+    // then streams a megabyte of weights or more and one trip brings all groups (hidden 12288 at 16 rows: 48 columns x 24 KB
+    // each, 256 groups: 826 -> 818 us per step); with short-lived workgroups the launch it saves is cheaper (hidden 4096
+    // at 4 rows, 16 columns x 8 KB each: 106.7 -> 108.7 us per step; hidden 12288 at 1 row, 768 groups: 638 -> 652 us).
+    if ((int64_t)16 * nfc * c.K * 2 < (1 << 20) || p.N / (16 * nf) > 256) return false;
+    groups = p.N / (16 * nf);
+    cols = 16 * nf;
+    return true;
 }
 
 bool gemm_merges_attention_ranges(const GemmArgs& a) {
@@ -1426,6 +1592,10 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const bool bad_stride = (a.lda != 0 && (a.lda < a.K || a.lda % 8 != 0)) || (a.ldy != 0 && (a.ldy < a.N || a.ldy % 8 != 0));
     if (bad_stride || (is_strided(a) && (!gemm_takes_row_strides(a) || epi == EPI_QKV))) return hipErrorInvalidValue;
     if (a.x_splits > 1 && (epi != EPI_BIAS_RES || !gemm_merges_attention_ranges(a))) return hipErrorInvalidValue;
+    // row statistics are between two launches of the weight-streaming kernel: asked for anywhere else, refuse
+    if (a.row_stats_out != nullptr && !(leaves_row_stats(a, epi) && !try_flat(a, epi, nullptr, true) && stream_column_blocks(a, epi) != 0 &&
+                                        a.N % (16 * stream_column_blocks(a, epi)) == 0)) return hipErrorInvalidValue;
+    if (a.row_stats_in != nullptr && !(takes_row_stats(a, epi) && !try_flat(a, epi, nullptr, true) && stream_column_blocks(a, epi) != 0)) return hipErrorInvalidValue;
     // A few more rows than the weight-streaming kernels take at once (a decode step of more than 16 sequences, a very
     // short prompt): the same kernels with the rows cut into slices of 16 along gridDim.y, where that beats a tile kernel
     // that would run a handful of workgroups through the whole K loop (decode layer-step of the hidden-1024 layer at 32

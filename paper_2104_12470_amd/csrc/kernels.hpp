@@ -84,7 +84,19 @@ struct GemmArgs {
     const float* x_part_acc;
     const float* x_part_ml;
     int x_splits;
+    // gemm_stream with at most 16 rows only: the statistics of a LayerNorm handed from the projection that writes a row
+    // (EPI_BIAS_RES, row_stats_out != nullptr) to the projection that normalises it (ln_gamma != nullptr, row_stats_in !=
+    // nullptr), so that no launch stands between the two.  Every workgroup of the producer also writes, per row, the mean
+    // and the sum of squared deviations of its own columns of the rounded output: row_stats_out[(group*16 + row)*2 ..+2].
+    // The consumer merges the row_stats_groups groups of row_stats_cols columns each into mean and 1/std per row and
+    // normalises the activation rows on their way to the matrix instructions; its x is the producer's output as it is.
+    float* row_stats_out;
+    const float* row_stats_in;
+    int row_stats_groups, row_stats_cols;
 };
+// For a bias+residual projection that launch_gemm would give to gemm_stream and that then can leave row statistics for
+// `consumer` (which gemm_stream must take too): the layout of row_stats_out (workgroups, columns per workgroup); else false.
+bool gemm_hands_row_stats(const GemmArgs& producer, const GemmArgs& consumer, Epilogue consumer_epi, int& groups, int& cols);
 // true when launch_gemm can serve this problem with row strides (more than 16 rows: an MFMA tile kernel)
 bool gemm_takes_row_strides(const GemmArgs& a);
 // true when launch_gemm would give this bias+residual projection to the kernel that can merge the key ranges itself

@@ -298,15 +298,19 @@ def test_replays_the_host_never_saw_stay_inside_the_slots(eet, name, lens):
     layer.close()
 
 
-@pytest.mark.parametrize("name", ["small64", "cfg2-2seq", "h2048"])
+@pytest.mark.parametrize("name", ["small64", "cfg2-2seq", "h2048", "h12288"])
 def test_inputs_with_a_common_offset_and_an_outlier_channel(eet, name):
     """Hidden states as real models have them: every row shifted by a common offset of several standard deviations and
     one channel (the first: the pivot of the LayerNorm statistics fused into the decode projections) ten times larger
     than the rest.  Prefill (row-kernel LayerNorm) and decode steps (LayerNorm fused into the small-layer kernel for
-    the first two, row kernel + weight-streaming kernel for the hidden-2048 layer) against the oracle."""
+    the first two, row kernel + weight-streaming kernel for the hidden-2048 layer; in the hidden-12288 layer of 5
+    sequences the output projection hands the statistics of the second LayerNorm to the first feed-forward projection,
+    both weight streams) against the oracle."""
     from dataclasses import replace
     if name == "h2048":
         w = wl.Workload("h2048", 29, 2048, 16, 8192, 1, 3, 24, 8, 24, 3, 32)
+    elif name == "h12288":
+        w = wl.Workload("h12288", 31, 12288, 96, 12288, 1, 5, 24, 8, 24, 3, 32, sigma_w=0.006)
     else:
         w = wl.WORKLOADS["small64"] if name == "small64" else replace(wl.WORKLOADS["cfg2"], batch=2, decode_steps=3)
     W = wl.layer_weights(w, 0, True)
