@@ -23,17 +23,37 @@ namespace eet {
 namespace pipe {
 
 // ---------------------------------------------------------------------------------------------------------
-// Tile order of the MFMA tile kernel.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
-// XCD x is given a contiguous range of a tile sequence in which any 32 consecutive tiles (one per CU of the XCD)
-// form a block of 8 row-tiles x 4 column-tiles: 12 operand panels are shared by 32 tiles.  Every workgroup
-// index in [0, tiles_m * tiles_n) maps to a different tile (checked on the host for all small grids).
+// Tile order of the MFMA tile kernel.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): workgroup
+// pid runs on XCD pid % 8 and is the (pid / 8)-th there; with one workgroup per CU (the 256 x 256 tiles) the 32 CUs of
+// an XCD work on 32 consecutive workgroups of theirs at a time.  Every workgroup index in [0, tiles_m * tiles_n) maps to
+// a different tile (checked on the host for all small grids and the large ones in use).
+//   * Whole rounds of 256 tiles, from two rounds on, both tile counts multiples of 16: round r is one super-block of
+//     16 x 16 tiles (row-major over the super-blocks, so consecutive rounds keep their 16 row tiles), of which XCD x takes
+//     the 8 x 4 block at (x / 4, x % 4).  The chip then reads 32 operand panels per round instead of the 96 of eight
+//     unrelated blocks, and an XCD shares its 12 with its neighbours through the memory-side cache (rows x N x K:
+//     24576 x 49152 x 12288 23.9 -> 21.35 ms, 24576 x 36864 x 12288 17.67 -> 16.05, 24576 x 12288 x 12288 6.00 -> 5.58,
+//     24576 x 12288 x 49152 23.3 -> 22.5, 8192 x 16384 x 12288 2.51 -> 2.43; nothing lost at 3 or 4 rounds).
+//   * Whole rounds, 16 rounds or more, other tile counts: block k of 32 consecutive positions of the sequence below goes
+//     to XCD k % 8, so the XCDs work side by side on one group of 8 row tiles (about two thirds of the gain above on the
+//     same shapes; with few rounds it loses: 4096 x 12288 x 12288 0.92 -> 0.97 ms).
+//   * Otherwise XCD x is given a contiguous range of a tile sequence in which any 32 consecutive tiles form a block of
+//     8 row-tiles x 4 column-tiles: 12 operand panels are shared by 32 tiles.
 // ---------------------------------------------------------------------------------------------------------
 EET_PIPE_FN void tile_of_block(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
     constexpr int GM = 8;
     const int nb = tiles_m * tiles_n;
     const int xcd = pid & 7, local = pid >> 3;
+    const bool whole_rounds = (nb & 255) == 0;
+    if (whole_rounds && nb >= 512 && (tiles_m & 15) == 0 && (tiles_n & 15) == 0) {
+        const int sb = local >> 5, w = local & 31, sbn_count = tiles_n >> 4;
+        const int sbm = sb / sbn_count, sbn = sb - sbm * sbn_count;
+        tile_m = sbm * 16 + (xcd >> 2) * 8 + (w & 7);
+        tile_n = sbn * 16 + (xcd & 3) * 4 + (w >> 3);
+        return;
+    }
     const int q = nb >> 3, rem = nb & 7;
-    const int t = xcd * q + (xcd < rem ? xcd : rem) + local;   // position in the sequence
+    int t = xcd * q + (xcd < rem ? xcd : rem) + local;         // position in the sequence
+    if (whole_rounds && nb >= 4096) t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
     const int per_group = GM * tiles_n;
     const int grp = t / per_group, in_grp = t - grp * per_group;
     const int gm0 = grp * GM;

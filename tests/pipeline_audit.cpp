@@ -359,7 +359,7 @@ int main() {
         snprintf(name, sizeof name, "256-row attention, K and V rings of three stages, %d key tiles", nt);
         expect_ok(r.verdict(name), name);
     }
-    {   // the tile order visits every tile exactly once, for every grid up to 40 x 40 tiles and a few large ones
+    {   // the tile order visits every tile exactly once, for every grid up to 40 x 40 tiles and a few large ones (all three orders)
         int bad = 0;
         auto check_grid = [&](int tm, int tn) {
             std::vector<int> seen((size_t)tm * tn, 0);
@@ -373,7 +373,8 @@ int main() {
         };
         for (int tm = 1; tm <= 40; ++tm)
             for (int tn = 1; tn <= 40; ++tn) check_grid(tm, tn);
-        check_grid(96, 192); check_grid(96, 48); check_grid(13, 16); check_grid(97, 193); check_grid(1, 1000); check_grid(1000, 1);
+        check_grid(96, 192); check_grid(96, 48); check_grid(96, 144); check_grid(13, 16); check_grid(97, 193); check_grid(1, 1000); check_grid(1000, 1);
+        check_grid(40, 128); check_grid(8, 512); check_grid(24, 192); check_grid(100, 64); check_grid(16, 48); check_grid(32, 64);   // whole rounds with and without multiples of 16
         expect_ok(bad ? "tile order: some workgroup index maps outside the grid or two map to one tile" : "", "tile order is a bijection");
     }
     const struct { Mistake m; const char* what; } planted[] = {
