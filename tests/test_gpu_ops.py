@@ -287,6 +287,25 @@ def test_linear_strided(eet, M, K, N, padx, pady):
         assert np.array_equal(host(dense).view(np.uint16), host(yw[:, :N].contiguous()).view(np.uint16))
 
 
+@pytest.mark.parametrize("M,K,N,what", [(8192, 128, 4096, "32 x 16 tiles in two rounds: one 16 x 16 super-block per round"),
+                                        (6144, 64, 49152, "24 x 192 tiles in 18 rounds: eight blocks of one row group side by side")])
+def test_linear_tile_orders_of_whole_rounds(eet, M, K, N, what):
+    """Whole rounds of 256 x 256 tiles are handed to the XCDs in orders of their own: every output element is still written
+    exactly once with the right value (sampled rows against the oracle, the first and last rows of tiles among them; the
+    whole output finite, i.e. written)."""
+    x = wl.normal(380, M, (M, K))
+    w = wl.normal(381, N, (N, K), 1.0 / np.sqrt(K))
+    b = wl.normal(382, N, (N,), 0.5)
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+    eet.eet_op_linear(dev(x), dev(w), dev(b), y)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y).all()), "some tile was not written"
+    rng = np.random.default_rng(M + N)
+    rows = sorted({0, 255, 256, 2047, 2048, 4095, 4096, M - 257, M - 256, M - 1} | {int(v) for v in rng.integers(0, M, 54)})
+    want = orc.linear(x[rows], w, b)
+    gate(host(y[rows]), want, f"linear {M}x{K}x{N} ({what})", OP_MAX, OP_MEAN)
+
+
 def test_linear_strided_refuses_what_it_cannot_do(eet):
     K, N = 256, 512
     w, b = dev(wl.normal(364, 1, (N, K))), dev(wl.normal(365, 1, (N,)))
