@@ -1568,15 +1568,16 @@ static GemmArgs rows_from(const GemmArgs& a, Epilogue epi, int m0) {
 // One workgroup of the large-tile kernels fills a CU, so the tiles run in rounds of 256, and a launch whose last round is
 // part-filled pays for more than that round: 25082 x 12288 x 49152 (18.4 rounds) 26.3 ms, 24832 rows (18.2 rounds) 26.35 ms,
 // 24576 rows (18 rounds) 24.6 ms; 25082 x 36864 x 12288 (55.1 rounds) 19.1 ms, 24576 rows (54 rounds) 18.2 ms.  Where some
-// number of row tiles gives whole rounds and leaves at most 8 row tiles, the launch is cut there and the rest is a launch
+// number of row tiles gives whole rounds and leaves at most 16 row tiles, the launch is cut there and the rest is a launch
 // of its own: small tiles below 150 large tiles' worth of rows (about 0.6 of the large tiles' rate: 506 x 12288 x 49152
 // 0.85 ms), else large tiles again (506 x 36864 x 12288 0.58 ms, 506 x 49152 x 12288 0.63 ms).  Returns the rows of the
-// first part, 0 for no cut.
+// first part, 0 for no cut.  The whole rounds are also what the tile order that lets the XCDs share operand panels
+// needs (pipe::tile_of_block): 20000 x 12288 x 12288, 14.8 rounds, 4.92 ms as one launch.
 static int rows_in_whole_rounds(const GemmArgs& a, Epilogue epi, int big_tiles) {
     constexpr int kCUs = 256;
     if ((epi == EPI_QKV && a.tok_row_map == nullptr) || big_tiles < 2 * kCUs || big_tiles % kCUs == 0) return 0;
     const int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
-    for (int c = tm - 1; c >= 1 && c >= tm - 8; --c) {
+    for (int c = tm - 1; c >= 1 && c >= tm - 16; --c) {
         if ((c * tn) % kCUs != 0) continue;
         if (a.M - c * 256 <= 16) return 0;                 // the rest would be a decode-sized problem: other kernels, no row strides
         const int rest = (tm - c) * tn;                   // large tiles' worth of rows left over
