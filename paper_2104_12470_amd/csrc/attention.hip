@@ -775,7 +775,9 @@ __device__ __forceinline__ float dpp_f(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
 }
 
-template <int D, int NW>
+// NT: K and V rows are loaded with the non-temporal hint (AttnDecodeArgs::read_once); a template parameter because the
+// compiler merges the arms of a branch whose loads differ in nothing but the hint, and drops it.
+template <int D, int NW, bool NT>
 __global__ __launch_bounds__(NW * 64) void attn_decode(AttnDecodeArgs a) {
     constexpr int LPK = D / 8;           // lanes per key row (8 or 16)
     constexpr int KPI = 64 / LPK;        // key rows per load instruction (8 or 4)
@@ -818,8 +820,13 @@ __global__ __launch_bounds__(NW * 64) void attn_decode(AttnDecodeArgs a) {
             int row = j0 + u * KPI + kslot;
             row = row < c1 ? row : c1 - 1;                // weight zero in consume()
             const uint32_t off = (uint32_t)row * (uint32_t)(D * 2) + lane_off;
-            kf[u] = *reinterpret_cast<const half8v*>(kbase + off);
-            vf[u] = *reinterpret_cast<const half8v*>(vbase + off);
+            if constexpr (NT) {
+                kf[u] = load_once(reinterpret_cast<const half8v*>(kbase + off));
+                vf[u] = load_once(reinterpret_cast<const half8v*>(vbase + off));
+            } else {
+                kf[u] = *reinterpret_cast<const half8v*>(kbase + off);
+                vf[u] = *reinterpret_cast<const half8v*>(vbase + off);
+            }
         }
     };
     auto consume = [&](const half8v (&kf)[U], const half8v (&vf)[U], int j0) {
@@ -997,8 +1004,13 @@ size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits) {
 
 hipError_t launch_attention_decode(const AttnDecodeArgs& a, hipStream_t s) {
     const dim3 grid(a.splits, a.heads, a.batch), block(256);
-    if (a.d == 128) hipLaunchKernelGGL((attn_decode<128, 4>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((attn_decode<64, 4>), grid, block, 0, s, a);
+    if (a.d == 128) {
+        if (a.read_once) hipLaunchKernelGGL((attn_decode<128, 4, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((attn_decode<128, 4, false>), grid, block, 0, s, a);
+    } else {
+        if (a.read_once) hipLaunchKernelGGL((attn_decode<64, 4, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((attn_decode<64, 4, false>), grid, block, 0, s, a);
+    }
     if (a.splits > 1 && !a.leave_ranges) {
         const int pairs = a.batch * a.heads;
         if (a.d == 128) hipLaunchKernelGGL(attn_decode_combine<128>, dim3((pairs + 1) / 2), dim3(256), 0, s, a);

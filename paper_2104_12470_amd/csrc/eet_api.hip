@@ -37,6 +37,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Rows of the prefill's feed-forward buffer lie F + kFfnRowPad halfs apart when F >= kFfnPadFrom: rows a
 // multiple of 32 KB apart slow the second feed-forward projection down (25082 x 12288 x 49152: 0.97-1.09 PFLOP/s with
 // rows 96 KB apart, 1.16 with 128 bytes more; no gain at 16384 and below, a small loss at 4096).
+// The operator entry points do not know what else runs between two of their calls: an operand of this size or more
+// (weights of a projection, the K/V capacity of a decode attention) is taken to come from HBM every time and is read with
+// the non-temporal hint; the layer, stack and model entry points decide from what a whole decode step moves.
+constexpr size_t kReadOnceOperandBytes = (size_t)64 << 20;
 constexpr size_t kFfnRowPad = 64;
 constexpr int kFfnPadFrom = 32768;
 
@@ -103,6 +107,7 @@ struct eet_layer {
     char* ws;
     int d;
     int batch;                         // batch of the last prefill, 0 = none yet
+    int stack_layers;                  // layers whose decode steps run between two steps of this one (1: a layer on its own)
     int32_t host_lens[EET_MAX_BATCH];  // host mirror of the device cache lengths (capacity checks only)
 };
 
@@ -323,6 +328,17 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     // that consume them (each workgroup recomputes the row statistics of the <= 16 token rows).
     // Measured break-even is near 16 MB of FFN-1 weights; larger layers keep the separate row kernel.
     const bool fuse_ln = B <= 16 && (size_t)F * H * sizeof(half_t) <= ((size_t)16 << 20);
+    // What a decode step moves between two uses of the same weight or cache row: every layer's weights and visible K/V
+    // once.  More than the memory-side cache holds: nothing survives there until the next step, and the read-once operands
+    // are loaded with the non-temporal hint (a tenth faster from HBM).  Less (hidden 2048 on its own: 150 MB): the step
+    // lives in that cache, which the hint would only disturb (6.68 -> 6.75 ms for 128 steps).
+    size_t visible = 0;
+    for (int b = 0; b < B; ++b) visible += (size_t)L->host_lens[b] + 1;
+    const size_t step_bytes = (size_t)(L->stack_layers > 0 ? L->stack_layers : 1) *
+                              (2 * ((size_t)4 * H * H + (size_t)2 * H * F) + (size_t)4 * H * visible);
+    // (not for the small layers whose idle workgroups pull the next launches' operands into that cache: PrefetchArgs below;
+    // the hint on the consumer's loads undoes that: 24 hidden-1024 layers 320.7 -> 330.4 ms for 512 steps)
+    const int once = (step_bytes > kMemorySideCacheBytes && !fuse_ln) ? 1 : 0;
     // The same small layers leave CUs idle in every launch: extra workgroups of the two launches with the fewest
     // workgroups pull operands of later launches towards the memory-side cache (PrefetchArgs).  `next`: the layer
     // whose step follows this one (the next layer of a stack, or this layer's own next step).  Measured on the
@@ -344,12 +360,12 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     g.x = qkv_in; g.w = (const half_t*)L->w.w_qkv; g.bias = (const half_t*)L->w.b_qkv; g.y = bufB;
     g.M = B; g.N = 3 * H; g.K = H;
     g.k_cache = kc; g.v_cache = vc; g.tok_row_map = nullptr; g.lens = d_lens;   // new token -> slot n_b
-    g.S = 1; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq;
+    g.S = 1; g.hidden = H; g.heads = c.heads; g.d = L->d; g.max_seq = c.max_seq; g.read_once = once;
     if (fuse_ln) { g.ln_gamma = (const half_t*)L->w.ln1_g; g.ln_beta = (const half_t*)L->w.ln1_b; g.ln_eps = c.ln_eps; }
     EET_LAUNCH(launch_gemm(g, EPI_QKV, s), "qkv projection");
     AttnDecodeArgs at{};
     at.q = bufB; at.ctx = bufA; at.k_cache = kc; at.v_cache = vc; at.lens = d_lens; at.len_bias = 1;
-    at.batch = B; at.heads = c.heads; at.d = L->d; at.capacity = c.max_seq;
+    at.batch = B; at.heads = c.heads; at.d = L->d; at.capacity = c.max_seq; at.read_once = once;
     at.splits = attention_decode_splits(B, c.heads, c.max_seq);
     at.part_acc = reinterpret_cast<float*>(L->ws + L->lay.part);
     at.part_ml = at.part_acc + (size_t)B * c.heads * at.splits * L->d;
@@ -357,7 +373,7 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     // n_b in this step (cache append, attention) is already ordered before it on the stream
     GemmArgs o{};
     o.x = bufA; o.w = (const half_t*)L->w.w_o; o.bias = (const half_t*)L->w.b_o; o.y = bufY;
-    o.M = B; o.N = H; o.K = H; o.res = x;
+    o.M = B; o.N = H; o.K = H; o.res = x; o.read_once = once;
     o.heads = c.heads; o.d = L->d;
     // With the key range split (few (sequence, head) pairs) the ranges need merging.  Where the output projection goes to
     // the small-layer kernel, that kernel merges them while it loads its activations, and the merge launch (4 us, the
@@ -379,7 +395,7 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     // hidden 4096's 107).
     GemmArgs f1{};
     f1.w = (const half_t*)L->w.w_fc1; f1.bias = (const half_t*)L->w.b_fc1; f1.y = bufF;
-    f1.M = B; f1.N = F; f1.K = H;
+    f1.M = B; f1.N = F; f1.K = H; f1.read_once = once;
     bool hand_stats = false;
     if (!fuse_ln && bump_in_gemm) {
         GemmArgs probe = f1;
@@ -406,7 +422,7 @@ static int enqueue_decode(eet_layer* L, const void* tokens, void* out, void* kv_
     EET_LAUNCH(launch_gemm(f1, EPI_BIAS_GELU, s), "ffn 1");
     GemmArgs f2{};
     f2.x = bufF; f2.w = (const half_t*)L->w.w_fc2; f2.bias = (const half_t*)L->w.b_fc2; f2.y = static_cast<half_t*>(out);
-    f2.M = B; f2.N = H; f2.K = F; f2.res = bufY;
+    f2.M = B; f2.N = H; f2.K = F; f2.res = bufY; f2.read_once = once;
     if (prefetch && next != nullptr) {                    // during FFN-2 (128 workgroups): the QKV matrix and the K/V rows of the step that follows
         f2.pf.lin[0] = next->w.w_qkv; f2.pf.lin_lines[0] = lines((size_t)3 * H * H * 2);
         f2.pf.k_cache = static_cast<const half_t*>(next_kv);
@@ -534,6 +550,7 @@ int eet_stack_create(const eet_layer_config* cfg, int32_t n_layers, const eet_la
             eet_stack_destroy(st);
             return rc;
         }
+        st->layers[l]->stack_layers = n_layers;
     }
     st->cfg = *cfg;
     st->ws = static_cast<char*>(workspace);
@@ -922,6 +939,7 @@ int eet_op_linear(const void* x, const void* w, const void* bias, const void* re
     GemmArgs g{};
     g.x = (const half_t*)x; g.w = (const half_t*)w; g.bias = (const half_t*)bias; g.y = (half_t*)y;
     g.M = (int)rows; g.N = out; g.K = in; g.res = (const half_t*)residual;
+    g.read_once = (size_t)out * in * sizeof(half_t) >= kReadOnceOperandBytes;
     EET_LAUNCH(launch_gemm(g, residual ? EPI_BIAS_RES : (act ? EPI_BIAS_GELU : EPI_BIAS), (hipStream_t)hip_stream), "linear");
     return EET_OK;
 }
@@ -944,6 +962,7 @@ int eet_op_linear_strided(const void* x, int64_t ldx, const void* w, const void*
         return fail(EET_ERR_UNSUPPORTED_SHAPE, "eet_op_linear_strided: %lld rows go to the weight-streaming path, which takes dense rows only",
                     (long long)rows);
     g.lda = (int)ldx; g.ldy = (int)ldy;
+    g.read_once = (size_t)out * in * sizeof(half_t) >= kReadOnceOperandBytes;
     EET_LAUNCH(launch_gemm(g, residual ? EPI_BIAS_RES : (act ? EPI_BIAS_GELU : EPI_BIAS), (hipStream_t)hip_stream), "linear");
     return EET_OK;
 }
@@ -1107,6 +1126,7 @@ int eet_op_attention_decode(const void* q, const void* k_cache, const void* v_ca
     AttnDecodeArgs a{};
     a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
     a.lens = n_keys; a.len_bias = 0; a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity;
+    a.read_once = (size_t)4 * batch * heads * d * capacity >= kReadOnceOperandBytes;
     a.splits = attention_decode_splits(batch, heads, capacity);
     a.part_acc = (float*)scratch;
     a.part_ml = a.part_acc + (size_t)batch * heads * a.splits * d;
@@ -1164,6 +1184,7 @@ extern "C" int eet_op_attention_decode_static(const void* q, const void* k_cache
     AttnDecodeArgs a{};
     a.q = (const half_t*)q; a.ctx = (half_t*)ctx; a.k_cache = (const half_t*)k_cache; a.v_cache = (const half_t*)v_cache;
     a.lens = n_keys; a.len_bias = 0; a.batch = batch; a.heads = heads; a.d = d; a.capacity = capacity;
+    a.read_once = (size_t)4 * batch * heads * d * capacity >= kReadOnceOperandBytes;
     a.splits = splits;
     // every slot the merge reads is written by the attention launch in front of it: nothing has to start at zero
     a.part_acc = static_cast<float*>(ptr);

@@ -1048,11 +1048,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat(GemmArgs a) {
 //           up with the spread of the group means, taken relative to the first group's mean) into mean and 1/std per row,
 //           while its first weights are in flight, and normalises every activation vector (three fused multiply-adds per
 //           element) before it is staged for the matrix instructions.
+// NT: the weights are loaded with the non-temporal hint (GemmArgs::read_once).  A template parameter, not a branch: the compiler
+// merges the two arms of a branch whose loads differ in nothing but the hint, and drops it.
 constexpr int kStreamStagedUnits = 2;
 constexpr int kStreamStatsLds = 1024;                       // bytes behind the staging areas: the merged row statistics (LNS = 2)
 
-template <int NF, int EPI, int XH, bool SL, int LNS = 0>
+template <int NF, int EPI, int XH, bool SL, int LNS = 0, bool NT = false>
 __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
+    static_assert(!NT || !SL, "row slices read the weights once from memory and then from the caches: plain loads");
     static_assert(LNS == 0 || !SL, "row statistics: at most 16 rows, one slice");
     static_assert(LNS != 1 || EPI == EPI_BIAS_RES, "the producer of row statistics is a bias + residual projection");
     if (SL) take_row_slice<EPI>(a);
@@ -1135,11 +1138,16 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
             }
 #pragma unroll
             for (int h = 0; h < XH; ++h) xr[q][h] = *reinterpret_cast<const half8v*>(xg + xoff[h] + q * 128);
+        }
+#pragma unroll
+        for (int q = 0; q < UQ; ++q)
 #pragma unroll
             for (int f = 0; f < NF; ++f)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) wr[q][f][h] = *reinterpret_cast<const half8v*>(wg + woff[f][h] + q * 128);
-        }
+                for (int h = 0; h < 2; ++h) {
+                    const half8v* src = reinterpret_cast<const half8v*>(wg + woff[f][h] + q * 128);
+                    if constexpr (NT) wr[q][f][h] = load_once(src); else wr[q][f][h] = *src;
+                }
     };
     float4v acc[NF];
 #pragma unroll
@@ -1422,6 +1430,25 @@ static bool takes_row_stats(const GemmArgs& a, Epilogue epi) {
     return a.row_stats_in != nullptr && a.ln_gamma != nullptr && epi == EPI_BIAS_GELU && a.M <= 16 && a.row_stats_groups >= 1 && a.row_stats_cols >= 1;
 }
 
+// at most 16 rows: one slice, with or without the non-temporal hint on the weights
+template <int NF, int XH, bool NT>
+static void launch_stream_rows(const GemmArgs& a, Epilogue epi, dim3 grid, dim3 block, int lds, hipStream_t s) {
+    if (leaves_row_stats(a, epi)) {
+        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false, 1, NT>, a, grid, block, lds, s);
+        return;
+    }
+    if (takes_row_stats(a, epi)) {
+        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false, 2, NT>, a, grid, block, lds + kStreamStatsLds, s);
+        return;
+    }
+    switch (epi) {
+        case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH, false, 0, NT>, a, grid, block, lds, s); break;
+        case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false, 0, NT>, a, grid, block, lds, s); break;
+        case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false, 0, NT>, a, grid, block, lds, s); break;
+        case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH, false, 0, NT>, a, grid, block, lds, s); break;
+    }
+}
+
 template <int NF, int XH>
 static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int lds = 4 * kStreamStagedUnits * (NF + 1) * 16 * kFlatStageRow * 2;
@@ -1437,20 +1464,8 @@ static void launch_stream(const GemmArgs& a, Epilogue epi, hipStream_t s) {
         return;
     }
     const dim3 grid(a.N / (16 * NF));
-    if (leaves_row_stats(a, epi)) {
-        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false, 1>, a, grid, block, lds, s);
-        return;
-    }
-    if (takes_row_stats(a, epi)) {
-        launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false, 2>, a, grid, block, lds + kStreamStatsLds, s);
-        return;
-    }
-    switch (epi) {
-        case EPI_BIAS: launch_flat_kernel(gemm_stream<NF, EPI_BIAS, XH, false>, a, grid, block, lds, s); break;
-        case EPI_BIAS_GELU: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_GELU, XH, false>, a, grid, block, lds, s); break;
-        case EPI_BIAS_RES: launch_flat_kernel(gemm_stream<NF, EPI_BIAS_RES, XH, false>, a, grid, block, lds, s); break;
-        case EPI_QKV: launch_flat_kernel(gemm_stream<NF, EPI_QKV, XH, false>, a, grid, block, lds, s); break;
-    }
+    if (a.read_once) launch_stream_rows<NF, XH, true>(a, epi, grid, block, lds, s);
+    else launch_stream_rows<NF, XH, false>(a, epi, grid, block, lds, s);
 }
 
 // Blocks of 16 columns the streaming kernel gives a workgroup for this problem; 0: not its problem (K a multiple of 256,

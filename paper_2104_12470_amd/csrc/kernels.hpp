@@ -93,7 +93,14 @@ struct GemmArgs {
     float* row_stats_out;
     const float* row_stats_in;
     int row_stats_groups, row_stats_cols;
+    // gemm_stream only: 1 = the weights are read with the non-temporal hint (common.hpp: load_once).  Right when nothing
+    // could keep them cached until their next use anyway (a decode step that moves more than the memory-side cache holds);
+    // wrong for a layer small enough to live in that cache from step to step, which the hint would keep out of it.
+    int read_once;
 };
+// the memory-side cache of the part: what a decode step must exceed, in bytes moved between two uses of an operand, before
+// its read-once operands are loaded with the non-temporal hint
+constexpr size_t kMemorySideCacheBytes = (size_t)256 << 20;
 // For a bias+residual projection that launch_gemm would give to gemm_stream and that then can leave row statistics for
 // `consumer` (which gemm_stream must take too): the layout of row_stats_out (workgroups, columns per workgroup); else false.
 bool gemm_hands_row_stats(const GemmArgs& producer, const GemmArgs& consumer, Epilogue consumer_epi, int& groups, int& cols);
@@ -136,6 +143,7 @@ struct AttnDecodeArgs {
     float* part_acc;        // [batch*heads*splits, d]   (splits > 1)
     float* part_ml;         // [batch*heads*splits, 2]
     int leave_ranges;       // 1: no merge launch, the projection that follows merges the ranges (GemmArgs::x_splits)
+    int read_once;          // 1: K/V rows loaded with the non-temporal hint (see GemmArgs::read_once)
 };
 int attention_decode_splits(int batch, int heads, int capacity);
 size_t attention_decode_scratch_bytes(int batch, int heads, int d, int splits);
