@@ -161,7 +161,7 @@ __device__ __forceinline__ void epilogue_request_residual(const GemmArgs& a, hal
     for (int it = 0; it < AM * 2; ++it) rv[it] = *reinterpret_cast<const half8v*>(a.res + (int64_t)rrow[it] * a.N + nw + c8 * 8);
 }
 
-template <int AM, int ANT, int J0, int EPI, int RV>
+template <int AM, int ANT, int J0, int EPI, bool NTS, int RV>
 __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4v (&acc)[AM][ANT], const half8v (&rv)[RV],
                                                  const int (&r0)[AM * 2], const int (&r1)[AM * 2], char* stage, int mw, int nw, int lane) {
     static_assert(J0 + 4 <= ANT, "64 columns per pass");
@@ -226,7 +226,8 @@ __device__ __forceinline__ void epilogue_via_lds(const GemmArgs& a, const float4
         } else {
             dst = a.y + (int64_t)r0[it] * (a.ldy ? a.ldy : N) + n;
         }
-        *reinterpret_cast<half8v*>(dst) = v;
+        if constexpr (NTS) __builtin_nontemporal_store(v, reinterpret_cast<half8v*>(dst));   // an output too large to stay cached for its reader
+        else *reinterpret_cast<half8v*>(dst) = v;
     }
 }
 
@@ -442,7 +443,9 @@ struct GemmTileExec {
 
 // SCHED: 0 = the schedule of pipe::gemm_k_loop<NS>, 1 = its early-release form (two stages), 2 = the schedule for one wave
 // per SIMD (pipe::gemm_k_loop_interleaved; two stages, one K group)
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS, int SCHED>
+// NTS: the output is stored with the non-temporal hint (outputs of 256 MB and more, which no cache keeps for their reader:
+// 24576 x 49152 x 12288 21.70 -> 21.53 ms, 24576 x 12288 x 12288 5.69 -> 5.59, 8192 x 16384 x 12288 2.436 -> 2.393).
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS, int KS, int SCHED, bool NTS = false>
 __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a, int tiles_m, int tiles_n) {
     static_assert(SCHED == 0 || (NS == 2 && KS == 1 && (SCHED == 1 || SCHED == 2)), "schedule");
     // KS > 1: KS groups of WGM x WGN waves share the tile and take every KS-th K step each, through LDS stages of their
@@ -548,11 +551,11 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64) void gemm_mfma_dma64(GemmArgs a,
     static_assert(KS == 1 || NW * EB <= (int)sizeof(As), "turn-around areas must not touch the partial tiles");
     if constexpr (NW * EB <= (int)sizeof(As)) {
         char* area = reinterpret_cast<char*>(&As[0][0]) + wave * EB;
-        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, rv0, er0, er1, area, m0 + wm0, n0 + wn0, lane);
-        if constexpr (AN == 8) epilogue_via_lds<AM, AN, 4, EPI>(a, acc, rv1, er0, er1, area, m0 + wm0, n0 + wn0 + 64, lane);   // second 64 columns, same area
+        epilogue_via_lds<AM, AN, 0, EPI, NTS>(a, acc, rv0, er0, er1, area, m0 + wm0, n0 + wn0, lane);
+        if constexpr (AN == 8) epilogue_via_lds<AM, AN, 4, EPI, NTS>(a, acc, rv1, er0, er1, area, m0 + wm0, n0 + wn0 + 64, lane);   // second 64 columns, same area
     } else {
         static_assert(NW == 8 && AN == 4 && 4 * EB <= (int)sizeof(As) && 4 * EB <= (int)sizeof(Ws), "turn-around areas");
-        epilogue_via_lds<AM, AN, 0, EPI>(a, acc, rv0, er0, er1, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
+        epilogue_via_lds<AM, AN, 0, EPI, NTS>(a, acc, rv0, er0, er1, reinterpret_cast<char*>(wave < 4 ? &As[0][0] : &Ws[0][0]) + (wave & 3) * EB,
                                          m0 + wm0, n0 + wn0, lane);
     }
 }
@@ -1313,15 +1316,15 @@ __global__ __launch_bounds__(256) void gemm_stream(GemmArgs a) {
 // --------------------------------------------------------------------------------------------
 // dispatch
 // --------------------------------------------------------------------------------------------
-template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2, int KS = 1, int SCHED = 0>
+template <int WGM, int WGN, int BM = 256, int BN = 256, int NS = 2, int KS = 1, int SCHED = 0, bool NTS = false>
 static void launch_dma64_cfg(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * KS * 64);
     switch (epi) {
-        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
-        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS, KS, SCHED>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS, NS, KS, SCHED, NTS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_GELU, NS, KS, SCHED, NTS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_BIAS_RES, NS, KS, SCHED, NTS>), grid, block, 0, s, a, tm, tn); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemm_mfma_dma64<BM, BN, WGM, WGN, EPI_QKV, NS, KS, SCHED, NTS>), grid, block, 0, s, a, tm, tn); break;
     }
 }
 
@@ -1649,6 +1652,7 @@ hipError_t launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s) {
             // launch -- the four waves are ahead at this K too: 24576 x 12288 x 49152 24.7 -> 23.7 ms, 4096 rows 3.97 -> 3.82;
             // on part-filled rounds the eight waves stay ahead: 3000 x 4096 x 32768 0.80 against 0.87 ms.)
             if (a.K >= 32768 && big_tiles % 256 != 0) launch_dma64_cfg<2, 4, 256, 256, 2, 1, 1>(a, epi, s);
+            else if ((size_t)a.M * a.N * sizeof(half_t) >= kMemorySideCacheBytes) launch_dma64_cfg<2, 2, 256, 256, 2, 1, 2, true>(a, epi, s);
             else launch_dma64_cfg<2, 2, 256, 256, 2, 1, 2>(a, epi, s);
         }
         else {
