@@ -350,6 +350,38 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
         assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_prefill_in_chunks_of_pairs(eet, causal):
+    """More K/V than the memory-side cache holds (9 prompts x 40 heads, 285 MB): the launch takes the (sequence, head)
+    pairs in chunks (here 48 of 360: a ragged last chunk).  Sampled queries of every sequence, all heads, against the
+    oracle; rows that no workgroup may write keep their fill."""
+    d, heads, S = 128, 40, 2048
+    lens = [2048, 1024, 1025, 1791, 1793, 1536, 2047, 1280, 1777]
+    B, H = len(lens), heads * d
+    assert sum(lens) * H * 4 > 256 << 20
+    q = wl.normal(431, 1, (B, S, heads, d))
+    k = wl.normal(431, 2, (B, S, heads, d))
+    v = wl.normal(431, 3, (B, S, heads, d))
+    kc = torch.full((B, heads, S, d), float("nan"), dtype=torch.float16, device="cuda:0")
+    vc = torch.full((B, heads, S, d), float("nan"), dtype=torch.float16, device="cuda:0")
+    for b, L in enumerate(lens):
+        kc[b, :, :L] = dev(k[b, :L]).permute(1, 0, 2)
+        vc[b, :, :L] = dev(v[b, :L]).permute(1, 0, 2)
+    ctx = torch.full((B, S, H), 7.0, dtype=torch.float16, device="cuda:0")
+    op = eet.eet_op_attention_prefill if causal else eet.eet_op_attention_encoder
+    op(dev(q.reshape(B, S, H)), kc, vc, ctx, lens, heads)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(432)
+    for b, L in enumerate(lens):
+        assert bool((ctx[b, L:] == 7.0).all())                    # pad rows are not written by the op
+        Kb = np.ascontiguousarray(np.asarray(k[b, :L], np.float64).transpose(1, 0, 2))
+        Vb = np.ascontiguousarray(np.asarray(v[b, :L], np.float64).transpose(1, 0, 2))
+        rows = sorted({0, 255, 256, L - 257, L - 1} | {int(t) for t in rng.integers(0, L, 4)})
+        want = np.stack([orc.attend(np.asarray(q[b, t], np.float64), Kb, Vb, t + 1 if causal else L) for t in rows])
+        got = host(ctx[b, rows]).reshape(len(rows), heads, d)
+        gate(got, want, f"attention prefill in chunks b={b} L={L} causal={causal}", OP_MAX, OP_MEAN)
+
+
 @pytest.mark.parametrize("d,heads,S,cap,lens", [
     (128, 2, 1100, 1104, [1100, 700]),        # 256-row kernel
     (128, 2, 500, 512, [500, 257]),           # 128-row kernel, heads of 128
