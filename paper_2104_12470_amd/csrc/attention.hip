@@ -30,6 +30,23 @@ constexpr float kLog2e = 1.4426950408889634f;
 // CAUSAL = false is the encoder's window (Section 4, Bert layer): padding skip only, no sequence
 // mask; every query tile then walks all key tiles of its sequence and only the last tile compares
 // key indices (against L_b).
+// The (sequence, head) pairs and their query tiles over the workgroups of a prefill launch: the tiles of a pair on one
+// XCD (workgroups are dealt round-robin to the 8 XCDs; the chunk size is a multiple of 8), whose L2 then holds its K/V,
+// and within a chunk of pairs the longest tiles of all its pairs first, then the next longest ... (the best balance).
+// grid = (pairs, tiles) is one chunk; chunk_pairs != 0, grid = (chunks * chunk_pairs * chunk_tiles), takes the pairs
+// chunk after chunk, so that the K/V of the pairs in flight stays in the memory-side cache from one tile of a pair to its
+// next.  false: a pad workgroup of the last chunk.
+__device__ __forceinline__ bool prefill_pair_and_tile(const AttnPrefillArgs& a, int& pair, int& tile) {
+    pair = blockIdx.x;
+    tile = (int)gridDim.y - 1 - (int)blockIdx.y;
+    if (a.chunk_pairs != 0) {
+        const int per = a.chunk_pairs * a.chunk_tiles, c = blockIdx.x / per, r = blockIdx.x - c * per;
+        pair = c * a.chunk_pairs + r % a.chunk_pairs;
+        tile = a.chunk_tiles - 1 - r / a.chunk_pairs;
+    }
+    return pair < a.batch * a.heads;
+}
+
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLens lens) {
     constexpr int BQ = 128, BKV = 64;
@@ -41,11 +58,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill(AttnPrefillArgs a, SeqLen
     __shared__ __attribute__((aligned(16))) half_t Ks[BKV * LDKS];
     __shared__ __attribute__((aligned(16))) half_t Vt[D * LDVT];
 
-    // grid = ((sequence, head) pairs, query tiles): the tiles are dispatched longest first over all pairs, and the
-    // tiles of a pair land on one XCD (workgroups are dealt round-robin to the 8 XCDs), whose L2 then holds its K/V
-    const int b = blockIdx.x / a.heads, g = blockIdx.x % a.heads;
+    int pair, tile;
+    if (!prefill_pair_and_tile(a, pair, tile)) return;
+    const int b = pair / a.heads, g = pair % a.heads;
     const int L = lens.len[b];
-    const int i0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * BQ;
+    const int i0 = tile * BQ;
     if (i0 >= L) return;                                          // pad queries are never visited
     int row0 = b * a.S;
     if (a.packed) {
@@ -317,18 +334,8 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
     __shared__ __attribute__((aligned(1024))) char Ks[3][TILEB];
     __shared__ __attribute__((aligned(1024))) char Vs[3][TILEB];
 
-    // The (sequence, head) pairs and their query tiles over the workgroups: the tiles of a pair on one XCD (workgroups
-    // are dealt round-robin to the 8 XCDs, chunk_pairs is a multiple of 8), and within a chunk of pairs the longest tiles
-    // of all its pairs first, then the next longest ... (the best balance).  grid = (pairs, tiles) is one chunk;
-    // chunk_pairs != 0, grid = (chunks * chunk_pairs * chunk_tiles), takes the pairs chunk after chunk, so that the K/V of
-    // the pairs in flight stays in the memory-side cache from one tile of a pair to its next.
-    int pair = blockIdx.x, tile = (int)gridDim.y - 1 - (int)blockIdx.y;
-    if (a.chunk_pairs != 0) {
-        const int per = a.chunk_pairs * a.chunk_tiles, c = blockIdx.x / per, r = blockIdx.x - c * per;
-        pair = c * a.chunk_pairs + r % a.chunk_pairs;
-        tile = a.chunk_tiles - 1 - r / a.chunk_pairs;
-        if (pair >= a.batch * a.heads) return;
-    }
+    int pair, tile;
+    if (!prefill_pair_and_tile(a, pair, tile)) return;
     const int b = pair / a.heads, g = pair % a.heads;
     const int L = lens.len[b];
     const int i0 = tile * BQ;
@@ -580,8 +587,8 @@ __global__ __launch_bounds__(512) void attn_prefill_wide(AttnPrefillArgs a, SeqL
         }
 }
 
-// K/V of the pairs of one chunk of attn_prefill_wide's grid (at least 32 pairs: four per XCD)
-constexpr size_t kChunkKvBytes = (size_t)40 << 20;
+// K/V of the pairs of one chunk of a prefill launch (16 to 48 pairs: two to six per XCD)
+constexpr size_t kChunkKvBytes = (size_t)64 << 20;
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s) {
     // 256-row kernel for heads of 128 and prompts beyond 512 tokens (measured, one call: equal to the 128-row kernel
     // from 512 to 1024 tokens, 15-20 % ahead from 2048 on, 6-15 % behind up to 512, where twice as many workgroups
@@ -590,35 +597,37 @@ hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& len
     const bool wide = a.d == 128 && a.max_len > 512;
     const int bq = wide ? 256 : 128;
     const dim3 grid(a.heads * a.batch, (a.max_len + bq - 1) / bq), block(wide ? 512 : 256);
+    // In chunks of pairs once the K/V of the launch is more than the memory-side cache holds: with the tiles of all
+    // pairs in turn, a pair's K/V then comes from HBM again for every one of its tiles (16 prompts of 1024-2048
+    // tokens, 96 heads: 6.3 GB fetched for 1.2 GB of K/V and 0.6 GB of Q).  TFLOP/s by pairs per chunk, one call
+    // (none / 8 / 16 / 32 / 48 / 96 / 192): those prompts 577-604 / 622 / 680 / 703 / 689 / 677 / 669; 16 prompts of
+    // 2048-4096 tokens, 32 heads 711-734 / 811 / 824 / 848 / 831 / 820 / 806; 16 of 512-1024 tokens, 96 heads 414-448
+    // / 378 / 470 / 504 / 498 / 508 / 494; 4 prompts of 8192-16384 tokens, 32 heads (none / 8 / 16 / 32 / 64) 922 / 1011 /
+    // 1013 / 997 / 950; the 128-row kernel (none / 8 / 16 / 32 / 48 / 96): 128 prompts of 256-512 tokens, 32 heads of 64
+    // 222-260 / 262 / 296 / 306 / 307 / 308, 16 of 1024-2048 tokens, 64 heads of 64 492-538 / 576 / 594 / 601 / 593 / 580;
+    // below the cache's size chunks gain nothing (4 prompts of 1024-2048 tokens, 96 heads, 303 MB:
+    // 601-645 / 590 / 651 / 672 / 684 / 685 / 663; 167 MB: 640-705 / 556 / 639 / 696 / 691 / 692 / 712).
+    AttnPrefillArgs w = a;
+    size_t kv_bytes = 0;
+    for (int b = 0; b < a.batch; ++b) kv_bytes += (size_t)lens.len[b] * a.heads * a.d * 2 * sizeof(half_t);
+    const int pairs = (int)grid.x;
+    int chunk = 0;
+    if (kv_bytes > kMemorySideCacheBytes) {
+        chunk = (int)(kChunkKvBytes / (kv_bytes / pairs)) / 8 * 8;
+        chunk = chunk < 16 ? 16 : chunk > 48 ? 48 : chunk;
+    }
+    w.chunk_pairs = chunk >= pairs ? 0 : chunk;
+    w.chunk_tiles = (int)grid.y;
+    const dim3 wgrid = w.chunk_pairs ? dim3((pairs + chunk - 1) / chunk * chunk * grid.y) : grid;
     if (wide) {
-        // In chunks of pairs once the K/V of the launch is more than the memory-side cache holds: with the tiles of all
-        // pairs in turn, a pair's K/V then comes from HBM again for every one of its tiles (16 prompts of 1024-2048
-        // tokens, 96 heads: 6.3 GB fetched for 1.2 GB of K/V and 0.6 GB of Q).  TFLOP/s by pairs per chunk, one call
-        // (none / 8 / 16 / 32 / 48 / 96 / 192): those prompts 577-604 / 622 / 680 / 703 / 689 / 677 / 669; 16 prompts of
-        // 2048-4096 tokens, 32 heads 711-734 / 811 / 824 / 848 / 831 / 820 / 806; 16 of 512-1024 tokens, 96 heads 414-448
-        // / 378 / 470 / 504 / 498 / 508 / 494; below the cache's size chunks gain nothing (4 prompts of 1024-2048
-        // tokens, 96 heads, 303 MB: 601-645 / 590 / 651 / 672 / 684 / 685 / 663; 167 MB: 640-705 / 556 / 639 / 696 / 691 /
-        // 692 / 712).
-        AttnPrefillArgs w = a;
-        size_t kv_bytes = 0;
-        for (int b = 0; b < a.batch; ++b) kv_bytes += (size_t)lens.len[b] * a.heads * a.d * 2 * sizeof(half_t);
-        const int pairs = (int)grid.x;
-        int chunk = 0;
-        if (kv_bytes > kMemorySideCacheBytes) {
-            chunk = (int)(kChunkKvBytes / (kv_bytes / pairs)) / 8 * 8;
-            chunk = chunk < 32 ? 32 : chunk;
-        }
-        w.chunk_pairs = chunk >= pairs ? 0 : chunk;
-        w.chunk_tiles = (int)grid.y;
-        const dim3 wgrid = w.chunk_pairs ? dim3((pairs + chunk - 1) / chunk * chunk * grid.y) : grid;
         if (a.causal) hipLaunchKernelGGL((attn_prefill_wide<128, true>), wgrid, block, 0, s, w, lens);
         else hipLaunchKernelGGL((attn_prefill_wide<128, false>), wgrid, block, 0, s, w, lens);
     } else if (a.causal) {
-        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, true>), grid, block, 0, s, a, lens);
-        else hipLaunchKernelGGL((attn_prefill<64, true>), grid, block, 0, s, a, lens);
+        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, true>), wgrid, block, 0, s, w, lens);
+        else hipLaunchKernelGGL((attn_prefill<64, true>), wgrid, block, 0, s, w, lens);
     } else {
-        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, false>), grid, block, 0, s, a, lens);
-        else hipLaunchKernelGGL((attn_prefill<64, false>), grid, block, 0, s, a, lens);
+        if (a.d == 128) hipLaunchKernelGGL((attn_prefill<128, false>), wgrid, block, 0, s, w, lens);
+        else hipLaunchKernelGGL((attn_prefill<64, false>), wgrid, block, 0, s, w, lens);
     }
     return hipGetLastError();
 }

@@ -124,7 +124,7 @@ struct AttnPrefillArgs {
     int S;                  // padded length (row stride between sequences when not packed)
     int max_len;            // max over lens (sizes the grid)
     int causal;             // 1: query i sees keys 0..i; 0: every valid query sees all L_b keys (encoder)
-    int chunk_pairs, chunk_tiles;   // set by the launcher (callers leave 0): see the grid order of attn_prefill_wide
+    int chunk_pairs, chunk_tiles;   // set by the launcher (callers leave 0): the grid order of the prefill kernels
 };
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, const SeqLens& lens, hipStream_t s);
 // Unfused form (causal, not packed, S a multiple of 8): raw scores q.k into scores[batch, heads, S, S] for the tiles

@@ -350,15 +350,18 @@ def test_attention_prefill(eet, d, heads, S, cap, lens):
         assert np.all(got[b, L:] == 7.0)                          # pad rows are not written by the op
 
 
-@pytest.mark.parametrize("causal", [True, False])
-def test_attention_prefill_in_chunks_of_pairs(eet, causal):
-    """More K/V than the memory-side cache holds (9 prompts x 40 heads, 285 MB): the launch takes the (sequence, head)
-    pairs in chunks (here 48 of 360: a ragged last chunk).  Sampled queries of every sequence, all heads, against the
-    oracle; rows that no workgroup may write keep their fill."""
-    d, heads, S = 128, 40, 2048
-    lens = [2048, 1024, 1025, 1791, 1793, 1536, 2047, 1280, 1777]
+@pytest.mark.parametrize("d,heads,lens,causal", [
+    (128, 40, [2048, 1024, 1025, 1791, 1793, 1536, 2047, 1280, 1777], True),      # 256-row kernel, 360 pairs in chunks of 48
+    (128, 40, [2048, 1024, 1025, 1791, 1793, 1536, 2047, 1280, 1777], False),
+    (64, 40, [2048, 1024, 1025, 1791, 1793, 1536, 2047, 1280, 1777, 2000, 1100, 1999, 1500, 1600, 1700, 1800, 1900, 1234, 1357, 1111], True),   # 128-row kernel, 800 pairs
+])
+def test_attention_prefill_in_chunks_of_pairs(eet, d, heads, lens, causal):
+    """More K/V than the memory-side cache holds (285 and 330 MB): the launch takes the (sequence, head) pairs in chunks
+    of 48, the last one ragged.  Sampled queries of every sequence, all heads, against the oracle; rows that no workgroup
+    may write keep their fill."""
+    S = 2048
     B, H = len(lens), heads * d
-    assert sum(lens) * H * 4 > 256 << 20
+    assert sum(lens) * H * 4 > 256 << 20 and (B * heads) % 48 != 0
     q = wl.normal(431, 1, (B, S, heads, d))
     k = wl.normal(431, 2, (B, S, heads, d))
     v = wl.normal(431, 3, (B, S, heads, d))
