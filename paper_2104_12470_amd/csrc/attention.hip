@@ -8,7 +8,6 @@
 // unbounded (the goal of Section 2.2) and the S x S buffer of Section 3.2 is not needed.
 //
 // K/V cache layout: [batch][heads][capacity][d] fp16, slot t = token t of the sequence.
-#include <cstdlib>
 #include <type_traits>
 #include "kernels.hpp"
 #include "pipeline.hpp"
